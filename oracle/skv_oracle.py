@@ -1,0 +1,311 @@
+"""CPU float64 oracle for attention over a low-rank projected KV cache.
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain statement of what
+the GPU library must compute.  It may be imported by the tests, by the smoke
+check and by the benchmark's CPU-baseline leg, and by nothing else: the
+product path never calls it and shares no code, table or constant with it.
+
+Everything below is the paper's definition written out with numpy float64:
+
+  * compression            K_down = K P_K, V_down = V P_V      (Sec. 2.1, Eq. 1)
+  * reconstruction         K_tilde = K_down P_K^T, same for V  (Sec. 2.1 Eq. 2; Sec. 3.2 Eq. 7)
+  * per-head attention     softmax(Q K^T / sqrt(d_h)) V        (App. A.1, Eq. 18)
+  * grouped-query heads    Eq. 18 per query head, several query heads
+                           reading one KV head                 (App. A.1)
+  * cache-size ratio       CR = (r_K + r_V) / (2 d_h)          (Sec. 2.1, Eq. 3)
+  * sequential budgeted rank selection                         (Sec. 3.5, Eqs. 15-17; App. B, Alg. 2)
+
+Readings taken where the paper is silent (all listed in the design notes):
+the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
+mean is subtracted before projecting; query head h reads KV head h // G with
+G = H_Q / H_KV; the cache stores bf16 (round to nearest, ties to even, one
+rounding straight from the float64 sum); the decode query attends rows
+[0, n_ctx) of the cache, its own freshly appended row included.
+
+bf16 tensors cross this module's boundary as numpy uint16 bit patterns so
+that oracle and GPU consume identical bytes.
+
+Pins (tests/test_oracle_*.py): full rank with a square orthogonal basis equals
+uncompressed attention computed by an independent brute force; P^T P = I and
+P P^T P = P; invariance under a rotation of the basis inside its span;
+in-span inputs are reproduced exactly; n = 1 and uniform-score closed forms;
+the definition form equals the factored form; a pure-Python brute force on a
+tiny case; the library scaled-dot-product routine when P = I; the paper's
+printed 16 GB cache-size example; budget invariants and an exhaustive check
+of the greedy selector.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+# --------------------------------------------------------------------------
+# bf16 <-> float64 (own helpers; storage precision per the reading above)
+# --------------------------------------------------------------------------
+
+
+def bf16_bits_to_f64(bits) -> np.ndarray:
+    """Exact value of each bf16 bit pattern (uint16) as float64."""
+    b = np.asarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("bf16 bit patterns must be uint16")
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x) -> np.ndarray:
+    """Round float64 to bf16 (8 significant bits, float32 exponent range),
+    nearest-even, in ONE rounding; returns uint16 bit patterns.  Finite inputs."""
+    x = np.asarray(x, dtype=np.float64)
+    if not np.all(np.isfinite(x)):
+        raise ValueError("oracle rounding is defined for finite values only")
+    mant, expo = np.frexp(x)                    # x = mant * 2**expo, 0.5 <= |mant| < 1
+    e = expo - 1                                # x = (1.f) * 2**e
+    e = np.maximum(e, -126)                     # below 2**-126: subnormal spacing
+    quantum = np.ldexp(1.0, e - 7)              # spacing of bf16 numbers in that binade
+    r = np.rint(x / quantum) * quantum          # rint = round half to even; exact in f64
+    r = np.where(np.abs(r) >= 2.0 ** 128, np.copysign(np.inf, r), r)
+    f32 = r.astype(np.float32)                  # exact: r has <= 8 significant bits
+    out = (f32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+    # keep the sign of a negative zero produced by rounding a tiny negative value
+    neg_zero = (r == 0.0) & np.signbit(x)
+    return np.where(neg_zero, np.uint16(0x8000), out).astype(np.uint16)
+
+
+def round_to_bf16(x) -> np.ndarray:
+    """float64 -> nearest bf16 value, returned as float64."""
+    return bf16_bits_to_f64(f64_to_bf16_bits(x))
+
+
+# --------------------------------------------------------------------------
+# Sec. 2.1: compression, reconstruction, cache ratio
+# --------------------------------------------------------------------------
+
+
+def compress(X: np.ndarray, P: np.ndarray) -> np.ndarray:
+    """X_down = X P (Eq. 1).  X: [n, d_h], P: [d_h, r] -> [n, r]."""
+    return np.asarray(X, np.float64) @ np.asarray(P, np.float64)
+
+
+def reconstruct(X_down: np.ndarray, P: np.ndarray) -> np.ndarray:
+    """X_tilde = X_down P^T (Eq. 2 / Eq. 7).  [n, r], [d_h, r] -> [n, d_h]."""
+    return np.asarray(X_down, np.float64) @ np.asarray(P, np.float64).T
+
+
+def compression_ratio(r_k: int, r_v: int, d_h: int) -> float:
+    """CR = (r_K + r_V) / (2 d_h) (Eq. 3); also the cost c(r_K, r_V) of App. B."""
+    return (r_k + r_v) / (2.0 * d_h)
+
+
+def kv_cache_bytes(n_layers: int, n_kv_heads: int, n_ctx: int, batch: int,
+                   r_k: int, r_v: int, bytes_per_elem: int = 2) -> int:
+    """Bytes held by a cache that stores r_K + r_V numbers per token, KV head,
+    layer and sequence.  With r_K = r_V = d_h this is the uncompressed cache of
+    the introduction's example."""
+    return n_layers * n_kv_heads * n_ctx * batch * (r_k + r_v) * bytes_per_elem
+
+
+# --------------------------------------------------------------------------
+# App. A.1: attention of one query against one head's keys and values
+# --------------------------------------------------------------------------
+
+
+def attention_single_query(q: np.ndarray, K: np.ndarray, V: np.ndarray,
+                           scale: float) -> np.ndarray:
+    """softmax(q K^T * scale) V for a single query row (Eq. 18, decode case).
+    Two-pass textbook softmax: subtract the maximum, exponentiate, normalise."""
+    s = (K @ q) * scale                         # [n]
+    s = s - np.max(s)
+    w = np.exp(s)
+    p = w / np.sum(w)
+    return p @ V                                # [d_h]
+
+
+# --------------------------------------------------------------------------
+# One decoder layer's compressed cache
+# --------------------------------------------------------------------------
+
+
+@dataclass
+class OracleLayer:
+    """Plain container: shapes, bases and the compressed cache of one layer.
+
+    p_k, p_v:  float64 [n_bases, d_h, r]; n_bases is n_kv_heads (one basis per
+               KV head) or 1 (a single basis shared by all heads, the paper's
+               choice for keys in Sec. 3.3 "Head sharing").
+    k_cache, v_cache: float64 [batch, n_kv_heads, capacity, r]; in "bf16"
+               storage every entry is a bf16-representable value.
+    """
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    r_k: int
+    r_v: int
+    capacity: int
+    p_k: np.ndarray
+    p_v: np.ndarray
+    k_cache: np.ndarray
+    v_cache: np.ndarray
+    store: str = "bf16"
+
+    def basis_k(self, h: int) -> np.ndarray:
+        return self.p_k[h if self.p_k.shape[0] > 1 else 0]
+
+    def basis_v(self, h: int) -> np.ndarray:
+        return self.p_v[h if self.p_v.shape[0] > 1 else 0]
+
+
+def new_layer(batch, n_q_heads, n_kv_heads, head_dim, p_k, p_v, capacity,
+              store="bf16", fill=0.0) -> OracleLayer:
+    p_k = np.asarray(p_k, np.float64)
+    p_v = np.asarray(p_v, np.float64)
+    if n_q_heads % n_kv_heads:
+        raise ValueError("n_q_heads must be a multiple of n_kv_heads")
+    if p_k.shape[1] != head_dim or p_v.shape[1] != head_dim:
+        raise ValueError("bases must be [n_bases, head_dim, r]")
+    if p_k.shape[0] not in (1, n_kv_heads) or p_v.shape[0] not in (1, n_kv_heads):
+        raise ValueError("one basis per KV head, or one shared basis")
+    if store not in ("bf16", "f64"):
+        raise ValueError("store must be 'bf16' or 'f64'")
+    r_k, r_v = p_k.shape[2], p_v.shape[2]
+    return OracleLayer(
+        batch, n_q_heads, n_kv_heads, head_dim, r_k, r_v, capacity, p_k, p_v,
+        np.full((batch, n_kv_heads, capacity, r_k), fill, np.float64),
+        np.full((batch, n_kv_heads, capacity, r_v), fill, np.float64), store)
+
+
+def project_append(layer: OracleLayer, k_new: np.ndarray, v_new: np.ndarray,
+                   cur_len: int) -> None:
+    """Project T new tokens and store them at rows [cur_len, cur_len + T).
+
+    k_new, v_new: float64 [batch, T, n_kv_heads, head_dim] (exact values of
+    the caller's bf16 inputs).  Each stored number is the float64 sum of
+    Eq. 1, rounded once to bf16 when the layer stores bf16.  Rows outside the
+    written range are left untouched."""
+    k_new = np.asarray(k_new, np.float64)
+    v_new = np.asarray(v_new, np.float64)
+    B, T, H, d = k_new.shape
+    if (B, H, d) != (layer.batch, layer.n_kv_heads, layer.head_dim) or v_new.shape != k_new.shape:
+        raise ValueError("new keys/values must be [batch, T, n_kv_heads, head_dim]")
+    if cur_len < 0 or cur_len + T > layer.capacity:
+        raise ValueError("append exceeds capacity")
+    for b in range(B):
+        for h in range(H):
+            kd = compress(k_new[b, :, h, :], layer.basis_k(h))
+            vd = compress(v_new[b, :, h, :], layer.basis_v(h))
+            if layer.store == "bf16":
+                kd, vd = round_to_bf16(kd), round_to_bf16(vd)
+            layer.k_cache[b, h, cur_len:cur_len + T, :] = kd
+            layer.v_cache[b, h, cur_len:cur_len + T, :] = vd
+
+
+def decode_attention(layer: OracleLayer, q: np.ndarray, n_ctx: int,
+                     scale: float | None = None, heads=None) -> np.ndarray:
+    """Definition form of one decode step (Sec. 3.2 Eq. 7 inside App. A.1 Eq. 18).
+
+    q: float64 [batch, n_q_heads, head_dim].  For every sequence b and query
+    head h: rebuild the full-width keys and values of KV head h // G from rows
+    [0, n_ctx) of the cache, then apply single-query softmax attention with
+    scale 1/sqrt(head_dim) unless another scale is given.  Returns float64
+    [batch, n_q_heads, head_dim]; `heads`, if given, is an iterable of
+    (b, h) pairs to compute (all other rows are NaN)."""
+    q = np.asarray(q, np.float64)
+    if q.shape != (layer.batch, layer.n_q_heads, layer.head_dim):
+        raise ValueError("q must be [batch, n_q_heads, head_dim]")
+    if not 1 <= n_ctx <= layer.capacity:
+        raise ValueError("n_ctx out of range")
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.full(q.shape, np.nan, np.float64)
+    wanted = None if heads is None else set((int(b), int(h)) for b, h in heads)
+    for b in range(layer.batch):
+        for kv in range(layer.n_kv_heads):
+            hs = [h for h in range(kv * G, (kv + 1) * G)
+                  if wanted is None or (b, h) in wanted]
+            if not hs:
+                continue
+            K_tilde = reconstruct(layer.k_cache[b, kv, :n_ctx, :], layer.basis_k(kv))
+            V_tilde = reconstruct(layer.v_cache[b, kv, :n_ctx, :], layer.basis_v(kv))
+            for h in hs:
+                out[b, h] = attention_single_query(q[b, h], K_tilde, V_tilde, scale)
+    return out
+
+
+def decode_attention_factored(layer: OracleLayer, q: np.ndarray, n_ctx: int,
+                              scale: float | None = None) -> np.ndarray:
+    """The algebraically equal factored form, kept only to be tested against
+    decode_attention: (q P_K) K_down^T for the scores, mix the rank-r_V rows,
+    lift with P_V^T.  Not used as a parity reference."""
+    q = np.asarray(q, np.float64)
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.empty(q.shape, np.float64)
+    for b in range(layer.batch):
+        for h in range(layer.n_q_heads):
+            kv = h // G
+            q_low = q[b, h] @ layer.basis_k(kv)                   # [r_K]
+            s = (layer.k_cache[b, kv, :n_ctx, :] @ q_low) * scale
+            w = np.exp(s - np.max(s))
+            p = w / np.sum(w)
+            a_low = p @ layer.v_cache[b, kv, :n_ctx, :]           # [r_V]
+            out[b, h] = layer.basis_v(kv) @ a_low                 # [d_h]
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.5 / App. B Alg. 2: sequential budgeted rank selection
+# --------------------------------------------------------------------------
+
+
+def layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, delta):
+    """Greedy per-layer choice of (r_K, r_V) under a cache budget.
+
+    delta[l][i][j] is the layer-output error of layer l at ranks
+    (cand_k[i], cand_v[j]); the surfaces are inputs (evaluating them needs the
+    model).  Follows Alg. 2: B_1 = L*rho; for l = 1..L the per-layer allowance
+    is tau_l = B_l / (L - l + 1); among pairs with cost (r_K+r_V)/(2 d_h) <=
+    tau_l take the smallest error; then B_{l+1} = B_l - cost.
+
+    Readings: the allowance uses Alg. 2's denominator (the main text's Eq. 15
+    prints L-(l+1), which would not give tau_1 = rho).  Feasibility is tested
+    in integer rank units, (r_K+r_V)*(L-l+1) <= 2*d_h*B_l*(1+1e-12).  Equal
+    errors: lower cost, then larger r_V, then first in candidate order.  If no
+    pair fits, the cheapest pair is taken (ties: lower error) and the run
+    continues with a negative balance; `feasible` is then False.
+
+    Returns (r_k list, r_v list, achieved mean ratio, feasible)."""
+    delta = np.asarray(delta, np.float64)
+    cand_k = [int(r) for r in cand_k]
+    cand_v = [int(r) for r in cand_v]
+    if delta.shape != (n_layers, len(cand_k), len(cand_v)):
+        raise ValueError("delta must be [n_layers, n_k, n_v]")
+    units = 2.0 * head_dim * n_layers * rho      # budget in rank units: 2 d_h B_l
+    feasible = True
+    rk_out, rv_out = [], []
+    for l in range(n_layers):
+        remaining_layers = n_layers - l          # L - l + 1 with l counted from 1
+        best = None
+        for i, rk in enumerate(cand_k):
+            for j, rv in enumerate(cand_v):
+                cost = rk + rv
+                if cost * remaining_layers <= units * (1.0 + 1e-12):
+                    key = (delta[l, i, j], cost, -rv, i * len(cand_v) + j)
+                    if best is None or key < best[0]:
+                        best = (key, rk, rv)
+        if best is None:
+            feasible = False
+            for i, rk in enumerate(cand_k):
+                for j, rv in enumerate(cand_v):
+                    key = (rk + rv, delta[l, i, j], -rv, i * len(cand_v) + j)
+                    if best is None or key < best[0]:
+                        best = (key, rk, rv)
+        _, rk, rv = best
+        rk_out.append(rk)
+        rv_out.append(rv)
+        units -= rk + rv
+    achieved = sum(a + b for a, b in zip(rk_out, rv_out)) / (2.0 * head_dim * n_layers)
+    return rk_out, rv_out, achieved, feasible
