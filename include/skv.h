@@ -1,0 +1,188 @@
+/*
+ * skv -- decode attention over a KV cache stored as rank-r projections onto
+ * orthonormal bases, for AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only.  Every pointer marked "device" is GPU
+ * memory owned by the caller; "host" is ordinary process memory.  The library
+ * owns no memory, keeps no state between calls, never allocates and never
+ * synchronises: GPU work is enqueued on the hipStream_t passed as `stream`
+ * (NULL = the default stream) and the call returns at once.  All arguments are
+ * checked on the host before anything is launched; when a call returns an
+ * error nothing has been written.  The return value is the only error channel.
+ *
+ * Notation follows the paper: d_h = head_dim, r_K / r_V = ranks of the key and
+ * value bases P_K, P_V (d_h x r, orthonormal columns), H_Q query heads, H_KV
+ * KV heads, G = H_Q / H_KV query heads per KV head, n = tokens in the cache.
+ *
+ * All bf16 data is IEEE-style bfloat16 (upper half of a float32), 2 bytes.
+ */
+#ifndef SKV_H
+#define SKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SKV_OK = 0,
+  SKV_ERR_NULL = 1,      /* a required pointer is NULL                                   */
+  SKV_ERR_SHAPE = 2,     /* head_dim != 128, batch < 1, H_Q not a multiple of H_KV,
+                            G not in {1,2,4,8}, T < 0, bad strides, bad split count      */
+  SKV_ERR_RANK = 3,      /* a rank is not a multiple of 16 in [16, 128]                  */
+  SKV_ERR_CAPACITY = 4,  /* cur_len + T > capacity, n_ctx < 1 or n_ctx > capacity        */
+  SKV_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned, or a stride is not
+                            a multiple of 8 elements                                     */
+  SKV_ERR_WORKSPACE = 6, /* workspace smaller than the call needs                        */
+  SKV_ERR_BUDGET = 7,    /* skv_layer_ranks: some layer had no affordable rank pair
+                            (outputs are still filled, see there)                        */
+  SKV_ERR_HIP = 8        /* a launch failed; hipGetLastError() has the detail            */
+} skv_status;
+
+#define SKV_HEAD_DIM 128
+#define SKV_MAX_SPLITS 256
+
+/*
+ * One decoder layer's compressed cache (Sec. 2.1: K_down = K P_K stored in place
+ * of K, V_down = V P_V in place of V; ranks differ per layer, Sec. 3.5).
+ * Plain data, filled and owned by the caller.
+ *
+ *   k_cache  device bf16 [batch][n_kv_heads][capacity][r_k], row-major, rows packed
+ *   v_cache  device bf16 [batch][n_kv_heads][capacity][r_v]
+ *   p_k      device bf16 [n_bases][head_dim][r_k] row-major
+ *   p_v      device bf16 [n_bases][head_dim][r_v] row-major
+ *   p_k_head_stride / p_v_head_stride: elements between consecutive KV heads'
+ *            bases.  0 means one basis shared by every head (the paper shares
+ *            the key basis across heads and keeps value bases per head,
+ *            Sec. 3.3 "Head sharing"); otherwise at least head_dim * r.
+ * The bf16 numbers stored in p_k / p_v are the basis: nothing re-orthonormalises.
+ */
+typedef struct {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim;
+  int32_t r_k, r_v;
+  int64_t capacity;
+  void* k_cache;
+  void* v_cache;
+  const void* p_k;
+  const void* p_v;
+  int64_t p_k_head_stride;
+  int64_t p_v_head_stride;
+} skv_layer;
+
+/*
+ * Compression of new tokens (Sec. 2.1 Eq. 1; Sec. 3.2: the compressed tensors
+ * are what is cached).  For every sequence b, KV head h and new token t < T:
+ *     k_cache[b][h][cur_len + t][:] = bf16( k_new[b][t][h][:] . P_K[h] )
+ *     v_cache[b][h][cur_len + t][:] = bf16( v_new[b][t][h][:] . P_V[h] )
+ * with float32 accumulation over head_dim and one round-to-nearest-even to bf16.
+ * No mean is subtracted.  Rows outside [cur_len, cur_len + T) are not touched.
+ *
+ *   k_new, v_new  device bf16, element (b,t,h,i) at
+ *                 b*stride_b + t*stride_t + h*stride_h + i  (strides in elements,
+ *                 each a multiple of 8; the head_dim axis is contiguous)
+ *   T             number of new tokens per sequence (0 is a no-op)
+ *   cur_len       tokens already in the cache (the caller tracks it)
+ * Errors: NULL, SHAPE, RANK, CAPACITY, ALIGN, HIP.
+ */
+skv_status skv_project_append(const skv_layer* layer,
+                              const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                              int32_t T, int64_t cur_len, void* stream);
+
+/*
+ * One decode step of attention with the reconstructed cache (App. A.1 Eq. 18
+ * applied per query head to K~ = K_down P_K^T and V~ = V_down P_V^T, Sec. 3.2
+ * Eq. 7).  For every sequence b and query head h, with kv = h / G:
+ *     out[b][h][:] = softmax_j( scale * <q[b][h], K~[b][kv][j]> ) . V~[b][kv][0:n_ctx]
+ * over cache rows j in [0, n_ctx).  The library evaluates the algebraically
+ * equal factored form ((q P_K) against K_down, mix V_down, lift with P_V^T)
+ * with float32 arithmetic and a split of the context into independent ranges
+ * merged in a fixed order, so results are deterministic run to run.
+ *
+ *   q          device bf16 [batch][n_q_heads][head_dim]
+ *   out        device float32 [batch][n_q_heads][head_dim]
+ *   n_ctx      rows of the cache to attend, 1 <= n_ctx <= capacity (the same for
+ *              every sequence); rows >= n_ctx are never read
+ *   scale      softmax scale; <= 0 selects 1/sqrt(head_dim) -- the ORIGINAL head
+ *              dimension of Eq. 18, not the rank
+ *   workspace  device scratch of at least skv_decode_workspace_bytes(); contents
+ *              on entry are irrelevant; two calls that may overlap in time need
+ *              separate workspaces
+ * Errors: NULL, SHAPE, RANK, CAPACITY, ALIGN, WORKSPACE, HIP.
+ */
+skv_status skv_decode_attention(const skv_layer* layer, const void* q, void* out,
+                                int64_t n_ctx, float scale,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace that skv_decode_attention / skv_decode_partial need for
+ * this layer at any n_ctx <= capacity and any split count <= SKV_MAX_SPLITS.
+ * Returns 0 if the layer's shape is invalid. */
+size_t skv_decode_workspace_bytes(const skv_layer* layer);
+
+/* The number of context ranges skv_decode_attention uses for this shape
+ * (1..SKV_MAX_SPLITS); 0 if the arguments are invalid. */
+int32_t skv_decode_default_splits(const skv_layer* layer, int64_t n_ctx);
+
+/*
+ * The two stages of skv_decode_attention, exposed so that a caller can time or
+ * schedule them separately; calling them back to back on one stream with the
+ * same workspace and n_splits is exactly skv_decode_attention.
+ *
+ * skv_decode_partial: query projection, scores, online softmax and value mix
+ * over each of n_splits context ranges; writes per (b, h, range) the running
+ * maximum, the normaliser and the un-normalised rank-r_V mix into workspace.
+ * n_splits <= 0 selects skv_decode_default_splits(); a value larger than the
+ * context allows is an error (SHAPE).
+ *
+ * skv_decode_combine: merges the ranges (softmax is invariant to the split:
+ * rescale each range by exp(m_range - m), add) in range order, divides by the
+ * normaliser and lifts with P_V^T into out.
+ */
+skv_status skv_decode_partial(const skv_layer* layer, const void* q,
+                              int64_t n_ctx, float scale, int32_t n_splits,
+                              void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_decode_combine(const skv_layer* layer, void* out, int32_t n_splits,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sequential budgeted rank selection (Sec. 3.5 Eqs. 15-17; App. B Alg. 2).
+ * Host only; touches no GPU.  delta is host float64 [n_layers][n_k][n_v]
+ * row-major: the layer-output error of layer l at ranks (cand_k[i], cand_v[j]).
+ * The surfaces are inputs -- producing them needs the model -- so the
+ * dependence of later surfaces on earlier choices is the caller's business.
+ *
+ * B_1 = n_layers * rho.  For l = 1..n_layers: allowance tau_l = B_l/(L-l+1)
+ * (Alg. 2's form; it gives tau_1 = rho); among pairs whose cost
+ * (r_K + r_V)/(2 head_dim) does not exceed tau_l the smallest delta wins;
+ * B_{l+1} = B_l - cost.  Feasibility is tested in integer rank units with a
+ * relative slack of 1e-12.  Ties in delta: lower cost, then larger r_V, then
+ * the earlier (i, j).  If no pair is affordable the cheapest pair is taken
+ * (ties: lower delta), selection continues, and the call finally returns
+ * SKV_ERR_BUDGET with all outputs filled.
+ *
+ *   r_k_out, r_v_out  host int32 [n_layers]
+ *   achieved_ratio    host, may be NULL: sum(r_K + r_V) / (2 head_dim n_layers)
+ * Candidate ranks may be any positive integers <= head_dim (selection is
+ * arithmetic only; what the kernels accept is a separate matter).
+ * Errors: NULL, SHAPE (n_layers, n_k, n_v < 1; head_dim < 1; rho <= 0; a
+ * candidate outside [1, head_dim]; a NaN in delta), BUDGET.
+ */
+skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho,
+                           const int32_t* cand_k, int32_t n_k,
+                           const int32_t* cand_v, int32_t n_v,
+                           const double* delta,
+                           int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio);
+
+/* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
+ * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
+size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);
+
+/* Static, human-readable name of a status code. */
+const char* skv_status_string(skv_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKV_H */

@@ -1,0 +1,206 @@
+"""ctypes binding of the C-ABI library declared in include/skv.h.
+
+Argument marshalling only: every step of the path runs in the library's
+kernels.  PyTorch tensors supply device memory and the current stream.  The
+shared library must have been built (python -m paper_2601_21686_amd.build);
+if it is missing, loading raises -- there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libskv.so")
+
+SKV_OK = 0
+SKV_ERR_NULL, SKV_ERR_SHAPE, SKV_ERR_RANK, SKV_ERR_CAPACITY = 1, 2, 3, 4
+SKV_ERR_ALIGN, SKV_ERR_WORKSPACE, SKV_ERR_BUDGET, SKV_ERR_HIP = 5, 6, 7, 8
+SKV_HEAD_DIM = 128
+SKV_MAX_SPLITS = 256
+
+EXPORTS = (
+    "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
+    "skv_decode_default_splits", "skv_decode_partial", "skv_decode_combine",
+    "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
+)
+
+
+class SkvError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+class skv_layer(C.Structure):
+    _fields_ = [
+        ("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("r_k", C.c_int32), ("r_v", C.c_int32),
+        ("capacity", C.c_int64),
+        ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
+        ("p_k", C.c_void_p), ("p_v", C.c_void_p),
+        ("p_k_head_stride", C.c_int64), ("p_v_head_stride", C.c_int64),
+    ]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Opens libskv.so once and declares every prototype."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2601_21686_amd.build`")
+    L = C.CDLL(LIB_PATH)
+    LP = C.POINTER(skv_layer)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.skv_project_append.argtypes = [LP, vp, vp, i64, i64, i64, i32, i64, vp]
+    L.skv_project_append.restype = C.c_int
+    L.skv_decode_attention.argtypes = [LP, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_decode_attention.restype = C.c_int
+    L.skv_decode_workspace_bytes.argtypes = [LP]
+    L.skv_decode_workspace_bytes.restype = sz
+    L.skv_decode_default_splits.argtypes = [LP, i64]
+    L.skv_decode_default_splits.restype = i32
+    L.skv_decode_partial.argtypes = [LP, vp, i64, C.c_float, i32, vp, sz, vp]
+    L.skv_decode_partial.restype = C.c_int
+    L.skv_decode_combine.argtypes = [LP, vp, i32, vp, sz, vp]
+    L.skv_decode_combine.restype = C.c_int
+    L.skv_layer_ranks.argtypes = [i32, i32, C.c_double, C.POINTER(i32), i32, C.POINTER(i32), i32,
+                                  C.POINTER(C.c_double), C.POINTER(i32), C.POINTER(i32),
+                                  C.POINTER(C.c_double)]
+    L.skv_layer_ranks.restype = C.c_int
+    L.skv_cache_bytes.argtypes = [LP, i64]
+    L.skv_cache_bytes.restype = sz
+    L.skv_status_string.argtypes = [C.c_int]
+    L.skv_status_string.restype = C.c_char_p
+    _lib = L
+    return L
+
+
+def status_string(code: int) -> str:
+    return lib().skv_status_string(int(code)).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != SKV_OK:
+        raise SkvError(code, where)
+
+
+def _stream_ptr(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+class Layer:
+    """One decoder layer's compressed cache: device tensors plus the C struct.
+
+    p_k, p_v: bf16 CUDA tensors [n_bases, 128, r]; n_bases = n_kv_heads, or 1
+    for a basis shared by all heads.  The cache tensors are allocated here
+    (uninitialised) unless passed in.
+    """
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, capacity,
+                 k_cache=None, v_cache=None, head_dim=SKV_HEAD_DIM):
+        dev = p_k.device
+        assert p_k.dtype == torch.bfloat16 and p_v.dtype == torch.bfloat16
+        assert p_k.is_contiguous() and p_v.is_contiguous()
+        self.batch, self.n_q_heads, self.n_kv_heads = int(batch), int(n_q_heads), int(n_kv_heads)
+        self.head_dim, self.capacity = int(head_dim), int(capacity)
+        self.r_k, self.r_v = int(p_k.shape[2]), int(p_v.shape[2])
+        self.p_k, self.p_v = p_k, p_v
+        if k_cache is None:
+            k_cache = torch.empty((batch, n_kv_heads, capacity, self.r_k), dtype=torch.bfloat16, device=dev)
+        if v_cache is None:
+            v_cache = torch.empty((batch, n_kv_heads, capacity, self.r_v), dtype=torch.bfloat16, device=dev)
+        assert k_cache.is_contiguous() and v_cache.is_contiguous()
+        self.k_cache, self.v_cache = k_cache, v_cache
+        self.c = skv_layer(
+            self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.r_k, self.r_v,
+            self.capacity, k_cache.data_ptr(), v_cache.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
+            0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
+            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+        self._ws = None
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            n = skv_decode_workspace_bytes(self)
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.p_k.device)
+        return self._ws
+
+
+def _ref(layer):
+    return C.byref(layer.c if isinstance(layer, Layer) else layer)
+
+
+# ---- the C ABI, same names -------------------------------------------------
+
+
+def skv_project_append(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int, stream=None) -> None:
+    """k_new, v_new: bf16 [batch, T, n_kv_heads, 128], last axis contiguous."""
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
+    _check(lib().skv_project_append(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                    int(k_new.shape[1]), int(cur_len), _stream_ptr(stream)),
+           "skv_project_append")
+
+
+def skv_decode_workspace_bytes(layer) -> int:
+    return int(lib().skv_decode_workspace_bytes(_ref(layer)))
+
+
+def skv_decode_default_splits(layer, n_ctx: int) -> int:
+    return int(lib().skv_decode_default_splits(_ref(layer), int(n_ctx)))
+
+
+def skv_decode_attention(layer, q: torch.Tensor, out: torch.Tensor, n_ctx: int, scale: float = 0.0,
+                         workspace: torch.Tensor | None = None, stream=None) -> None:
+    """q: bf16 [batch, n_q_heads, 128]; out: float32 of the same shape."""
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_attention(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx),
+                                      float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                      _stream_ptr(stream)), "skv_decode_attention")
+
+
+def skv_decode_partial(layer, q: torch.Tensor, n_ctx: int, scale: float = 0.0, n_splits: int = 0,
+                       workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_partial(_ref(layer), q.data_ptr(), int(n_ctx), float(scale), int(n_splits),
+                                    ws.data_ptr(), ws.numel() * ws.element_size(),
+                                    _stream_ptr(stream)), "skv_decode_partial")
+
+
+def skv_decode_combine(layer, out: torch.Tensor, n_splits: int, workspace: torch.Tensor | None = None,
+                       stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_combine(_ref(layer), out.data_ptr(), int(n_splits), ws.data_ptr(),
+                                    ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_combine")
+
+
+def skv_cache_bytes(layer, n_tokens: int) -> int:
+    return int(lib().skv_cache_bytes(_ref(layer), int(n_tokens)))
+
+
+def skv_layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, delta):
+    """Returns (r_k list, r_v list, achieved ratio, feasible flag).  Host only."""
+    import numpy as np
+    ck = (C.c_int32 * len(cand_k))(*[int(x) for x in cand_k])
+    cv = (C.c_int32 * len(cand_v))(*[int(x) for x in cand_v])
+    d = np.ascontiguousarray(np.asarray(delta, dtype=np.float64))
+    if d.shape != (n_layers, len(cand_k), len(cand_v)):
+        raise ValueError("delta must be [n_layers, n_k, n_v]")
+    rk = (C.c_int32 * n_layers)()
+    rv = (C.c_int32 * n_layers)()
+    ach = C.c_double(0.0)
+    code = lib().skv_layer_ranks(n_layers, head_dim, float(rho), ck, len(cand_k), cv, len(cand_v),
+                                 d.ctypes.data_as(C.POINTER(C.c_double)), rk, rv, C.byref(ach))
+    if code not in (SKV_OK, SKV_ERR_BUDGET):
+        raise SkvError(code, "skv_layer_ranks")
+    return list(rk), list(rv), float(ach.value), code == SKV_OK

@@ -1,0 +1,76 @@
+"""Compiles the HIP sources into paper_2601_21686_amd/libskv.so for gfx950.
+
+Run as `python -m paper_2601_21686_amd.build` (or through
+__graft_entry__.build()).  hipcc cross-compiles without a GPU.
+"""
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
+OUT = os.path.join(PKG, "libskv.so")
+BUILD_DIR = os.path.join(ROOT, "_build")
+
+KEY_RANKS = (16, 32, 48, 64, 80, 96, 112, 128)
+
+# Packed-FP32 instruction selection is switched off for all device code.
+DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
+          "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
+
+
+def _hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found")
+    return exe
+
+
+def _jobs():
+    jobs = [("skv_host.o", [os.path.join(CSRC, "skv_host.cpp")], []),
+            ("skv_decode_combine.o", ["-x", "hip", os.path.join(CSRC, "skv_decode_combine.hip")], DEVICE_FLAGS),
+            ("skv_append.o", ["-x", "hip", os.path.join(CSRC, "skv_append.hip")], DEVICE_FLAGS)]
+    for rk in KEY_RANKS:
+        jobs.append((f"skv_decode_partial_rk{rk}.o",
+                     ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}"],
+                     DEVICE_FLAGS))
+    return jobs
+
+
+def build(verbose: bool = True, workers: int | None = None) -> str:
+    hipcc = _hipcc()
+    os.makedirs(BUILD_DIR, exist_ok=True)
+    workers = workers or min(8, os.cpu_count() or 1)
+
+    def compile_one(job):
+        obj, src_args, extra = job
+        out = os.path.join(BUILD_DIR, obj)
+        cmd = [hipcc, "-c", *COMMON, *extra, *src_args, "-o", out]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"compile failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
+        if verbose:
+            err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
+            print(f"[build] {obj}" + (f"\n{err}" if err else ""), flush=True)
+        return out
+
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        objs = list(ex.map(compile_one, _jobs()))
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT, *objs]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"link failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
+    if verbose:
+        print(f"[build] linked {OUT}", flush=True)
+    return OUT
+
+
+if __name__ == "__main__":
+    build()
+    sys.exit(0)

@@ -1,0 +1,165 @@
+// Compression of new keys and values and their placement in the cache
+// (Sec. 2.1 Eq. 1: K_down = K P_K, V_down = V P_V; Sec. 3.2: these compressed
+// tensors are what gets cached).
+//
+// Two kernels.  A chunk of tokens is a dense [tokens x 128] . [128 x r]
+// contraction per KV head and runs on the matrix cores (MFMA 16x16x32 bf16,
+// float32 accumulate).  A handful of tokens (a decode step appends one per
+// sequence) is a matrix-vector product and runs on the vector ALUs.
+// Both round the float32 sum to bf16 once, to nearest even.
+#include "skv_internal.h"
+
+namespace skv {
+namespace {
+
+constexpr int D = SKV_HEAD_DIM;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// float32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// ---------------------------------------------------------------------------
+// Few tokens: one workgroup per (sequence, token, KV head); threads 0..127
+// produce key channels, 128..255 value channels.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void append_vector_kernel(const AppendParams p) {
+  __shared__ float x_s[2][D];
+  const int tid = threadIdx.x;
+  const int idx = blockIdx.x;                    // (b * T + t) * H_KV + h
+  const int h = idx % p.n_kv_heads;
+  const int bt = idx / p.n_kv_heads;
+  const int t = bt % p.T;
+  const int b = bt / p.T;
+  const int which = tid >> 7;                    // 0: keys, 1: values
+  const int c = tid & 127;
+  const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)h * p.stride_h;
+  x_s[which][c] = bf16_to_f32((which ? p.v_new : p.k_new)[src + c]);
+  __syncthreads();
+  const int r = which ? p.r_v : p.r_k;
+  if (c >= r) return;
+  const uint16_t* basis = which ? p.p_v + (int64_t)h * p.p_v_head_stride
+                                : p.p_k + (int64_t)h * p.p_k_head_stride;
+  float a = 0.f;
+#pragma unroll 8
+  for (int d = 0; d < D; ++d) a = fmaf(x_s[which][d], bf16_to_f32(basis[d * r + c]), a);
+  uint16_t* cache = which ? p.v_cache : p.k_cache;
+  const int64_t row = ((int64_t)b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
+  cache[row * r + c] = (uint16_t)f32_to_bf16_bits(a);
+}
+
+// ---------------------------------------------------------------------------
+// Chunk of tokens on the matrix cores.
+//
+// Per (KV head, key-or-value) the product is computed transposed,
+// C^T[channel][token] = sum_d P[d][channel] * X[token][d], so that each lane of
+// the 16x16 result tile ends up with 4 consecutive channels of one token and
+// can store them as one 8-byte piece of the cache row.
+//   A operand (16 channels x 32 d): from the basis, staged transposed in LDS
+//   B operand (32 d x 16 tokens):   straight from global, 16 bytes per lane
+// v_mfma_f32_16x16x32_bf16 operand layout: lane L supplies A[L%16][8*(L/16)..+7]
+// and B[8*(L/16)..+7][L%16]; result register v of lane L is C[4*(L/16)+v][L%16].
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTilesPerWave = 4;                 // 16-token tiles per wave
+constexpr int kTokensPerWg = 4 * kTilesPerWave * 16;
+constexpr int kLdsPitch = D + 8;                 // bf16 elements; keeps 16-byte reads conflict-free
+
+__global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t pt_s[SKV_HEAD_DIM * kLdsPitch];   // [channel][d]
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int h = blockIdx.y;
+  const int which = blockIdx.z;                  // 0: keys, 1: values
+  const int r = which ? p.r_v : p.r_k;
+  const uint16_t* basis = which ? p.p_v + (int64_t)h * p.p_v_head_stride
+                                : p.p_k + (int64_t)h * p.p_k_head_stride;
+  const uint16_t* x = which ? p.v_new : p.k_new;
+  uint16_t* cache = which ? p.v_cache : p.k_cache;
+
+  // basis [d][c] -> LDS [c][d]
+  const int c8n = r >> 3;
+  for (int i = tid; i < D * c8n; i += 256) {
+    const int d = i / c8n, c8 = i % c8n;
+    const uint4 v = *reinterpret_cast<const uint4*>(basis + d * r + c8 * 8);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      pt_s[(c8 * 8 + 2 * e) * kLdsPitch + d] = (uint16_t)(w[e] & 0xffffu);
+      pt_s[(c8 * 8 + 2 * e + 1) * kLdsPitch + d] = (uint16_t)(w[e] >> 16);
+    }
+  }
+  __syncthreads();
+
+  const int M = p.batch * p.T;                   // token rows of this head
+  const int m0 = blockIdx.x * kTokensPerWg + wave * (kTilesPerWave * 16);
+  if (m0 >= M) return;
+
+  const int lrow = lane & 15;
+  const int lk = lane >> 4;
+
+  bf16x8 bfrag[kTilesPerWave][4];
+  int64_t dst_row[kTilesPerWave];
+  bool valid[kTilesPerWave];
+#pragma unroll
+  for (int nt = 0; nt < kTilesPerWave; ++nt) {
+    const int tok = m0 + nt * 16 + lrow;
+    valid[nt] = tok < M;
+    const int tc = valid[nt] ? tok : M - 1;
+    const int b = tc / p.T, t = tc % p.T;
+    const uint16_t* src = x + (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)h * p.stride_h;
+    dst_row[nt] = ((int64_t)b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      bfrag[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + ks * 32 + lk * 8));
+  }
+
+  for (int mt = 0; mt < (r >> 4); ++mt) {
+    f32x4 acc[kTilesPerWave];
+#pragma unroll
+    for (int nt = 0; nt < kTilesPerWave; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8 a = __builtin_bit_cast(
+          bf16x8, *reinterpret_cast<const uint4*>(&pt_s[(mt * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
+#pragma unroll
+      for (int nt = 0; nt < kTilesPerWave; ++nt)
+        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfrag[nt][ks], acc[nt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int nt = 0; nt < kTilesPerWave; ++nt) {
+      if (!valid[nt]) continue;
+      uint2 o;
+      o.x = f32_to_bf16_bits(acc[nt][0]) | (f32_to_bf16_bits(acc[nt][1]) << 16);
+      o.y = f32_to_bf16_bits(acc[nt][2]) | (f32_to_bf16_bits(acc[nt][3]) << 16);
+      *reinterpret_cast<uint2*>(cache + dst_row[nt] * r + mt * 16 + lk * 4) = o;
+    }
+  }
+}
+
+constexpr int kVectorPathMaxRows = 64;           // batch * T at or below this: vector kernel
+
+}  // namespace
+
+hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
+  const int64_t rows = (int64_t)p.batch * p.T;
+  if (rows <= kVectorPathMaxRows) {
+    const dim3 grid((unsigned)(rows * p.n_kv_heads));
+    hipLaunchKernelGGL(append_vector_kernel, grid, dim3(256), 0, stream, p);
+  } else {
+    const dim3 grid((unsigned)((rows + kTokensPerWg - 1) / kTokensPerWg), (unsigned)p.n_kv_heads, 2u);
+    hipLaunchKernelGGL(append_mfma_kernel, grid, dim3(256), 0, stream, p);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace skv

@@ -1,0 +1,330 @@
+// Host layer of the C ABI: argument checks, launch planning, rank selection.
+// No device code here.
+#include <cmath>
+#include <cstdint>
+#include <limits>
+
+#include "skv_internal.h"
+
+namespace skv {
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; }
+
+// Workgroups the decode launch aims for: a few per compute unit on a 256-CU
+// part, so that short contexts still spread over the chip.
+constexpr int kTargetWorkgroups = 2048;
+
+skv_status check_layer(const skv_layer* L) {
+  if (!L) return SKV_ERR_NULL;
+  if (!L->k_cache || !L->v_cache || !L->p_k || !L->p_v) return SKV_ERR_NULL;
+  if (L->head_dim != SKV_HEAD_DIM) return SKV_ERR_SHAPE;
+  if (L->batch < 1 || L->n_kv_heads < 1 || L->n_q_heads < 1) return SKV_ERR_SHAPE;
+  if (L->n_q_heads % L->n_kv_heads) return SKV_ERR_SHAPE;
+  const int g = L->n_q_heads / L->n_kv_heads;
+  if (!(g == 1 || g == 2 || g == 4 || g == 8)) return SKV_ERR_SHAPE;
+  if ((int64_t)L->batch * L->n_q_heads > (1 << 20)) return SKV_ERR_SHAPE;
+  if (!rank_ok(L->r_k) || !rank_ok(L->r_v)) return SKV_ERR_RANK;
+  if (L->capacity < 1 || L->capacity > std::numeric_limits<int32_t>::max()) return SKV_ERR_CAPACITY;
+  const int64_t sk = L->p_k_head_stride, sv = L->p_v_head_stride;
+  if (sk != 0 && sk < (int64_t)SKV_HEAD_DIM * L->r_k) return SKV_ERR_SHAPE;
+  if (sv != 0 && sv < (int64_t)SKV_HEAD_DIM * L->r_v) return SKV_ERR_SHAPE;
+  if ((sk % 8) || (sv % 8)) return SKV_ERR_ALIGN;
+  if (!aligned16(L->k_cache) || !aligned16(L->v_cache) || !aligned16(L->p_k) || !aligned16(L->p_v))
+    return SKV_ERR_ALIGN;
+  return SKV_OK;
+}
+
+size_t workspace_need(const skv_layer* L, int32_t n_splits) {
+  return (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)(L->r_v + 2) * sizeof(float);
+}
+
+void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, int32_t chunk,
+                        void* workspace) {
+  p->k_cache = static_cast<const uint32_t*>(L->k_cache);
+  p->v_cache = static_cast<const uint32_t*>(L->v_cache);
+  p->p_k = static_cast<const uint16_t*>(L->p_k);
+  p->p_v = static_cast<const uint16_t*>(L->p_v);
+  p->q = nullptr;
+  p->out = nullptr;
+  p->capacity = L->capacity;
+  p->p_k_head_stride = L->p_k_head_stride;
+  p->p_v_head_stride = L->p_v_head_stride;
+  p->batch = L->batch;
+  p->n_q_heads = L->n_q_heads;
+  p->n_kv_heads = L->n_kv_heads;
+  p->group = L->n_q_heads / L->n_kv_heads;
+  p->r_k = L->r_k;
+  p->r_v = L->r_v;
+  p->n_ctx = 0;
+  p->n_splits = n_splits;
+  p->chunk = chunk;
+  p->scale_log2e = 0.f;
+  float* ws = static_cast<float*>(workspace);
+  p->part_acc = ws;
+  p->part_ml = ws + (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)L->r_v;
+}
+
+decode_partial_launcher partial_launcher_for(int r_k) {
+  switch (r_k) {
+    case 16: return launch_decode_partial_rk16;
+    case 32: return launch_decode_partial_rk32;
+    case 48: return launch_decode_partial_rk48;
+    case 64: return launch_decode_partial_rk64;
+    case 80: return launch_decode_partial_rk80;
+    case 96: return launch_decode_partial_rk96;
+    case 112: return launch_decode_partial_rk112;
+    case 128: return launch_decode_partial_rk128;
+  }
+  return nullptr;
+}
+
+skv_status check_decode_common(const skv_layer* L, int32_t n_splits, const void* workspace,
+                               size_t workspace_bytes) {
+  if (!workspace) return SKV_ERR_NULL;
+  if (!aligned16(workspace)) return SKV_ERR_ALIGN;
+  if (n_splits < 1 || n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
+  if (workspace_bytes < workspace_need(L, n_splits)) return SKV_ERR_WORKSPACE;
+  return SKV_OK;
+}
+
+}  // namespace
+
+bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx, int32_t want,
+                 int32_t* n_splits, int32_t* chunk) {
+  if (n_ctx < 1) return false;
+  const int64_t tiles = (n_ctx + kChunkQuantum - 1) / kChunkQuantum;
+  int64_t s;
+  if (want > 0) {
+    if (want > SKV_MAX_SPLITS) return false;
+    s = want;
+  } else {
+    const int64_t columns = (int64_t)batch * n_kv_heads * (group / heads_per_pass(group));
+    s = kTargetWorkgroups / (columns > 0 ? columns : 1);
+    if (s < 1) s = 1;
+    if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
+    if (s > tiles) s = tiles;
+  }
+  const int64_t tiles_per_split = (tiles + s - 1) / s;
+  const int64_t c = tiles_per_split * kChunkQuantum;
+  if (c > std::numeric_limits<int32_t>::max()) return false;
+  if (want <= 0) s = (n_ctx + c - 1) / c;   // drop ranges that would be empty
+  *n_splits = (int32_t)s;
+  *chunk = (int32_t)c;
+  return true;
+}
+
+}  // namespace skv
+
+using namespace skv;
+
+extern "C" {
+
+const char* skv_status_string(skv_status s) {
+  switch (s) {
+    case SKV_OK: return "SKV_OK";
+    case SKV_ERR_NULL: return "SKV_ERR_NULL";
+    case SKV_ERR_SHAPE: return "SKV_ERR_SHAPE";
+    case SKV_ERR_RANK: return "SKV_ERR_RANK";
+    case SKV_ERR_CAPACITY: return "SKV_ERR_CAPACITY";
+    case SKV_ERR_ALIGN: return "SKV_ERR_ALIGN";
+    case SKV_ERR_WORKSPACE: return "SKV_ERR_WORKSPACE";
+    case SKV_ERR_BUDGET: return "SKV_ERR_BUDGET";
+    case SKV_ERR_HIP: return "SKV_ERR_HIP";
+  }
+  return "SKV_ERR_UNKNOWN";
+}
+
+size_t skv_cache_bytes(const skv_layer* L, int64_t n_tokens) {
+  if (!L || n_tokens < 0) return 0;
+  return (size_t)L->batch * L->n_kv_heads * (size_t)n_tokens * (size_t)(L->r_k + L->r_v) * 2u;
+}
+
+size_t skv_decode_workspace_bytes(const skv_layer* L) {
+  if (check_layer(L) != SKV_OK) return 0;
+  return workspace_need(L, SKV_MAX_SPLITS);
+}
+
+int32_t skv_decode_default_splits(const skv_layer* L, int64_t n_ctx) {
+  if (check_layer(L) != SKV_OK) return 0;
+  if (n_ctx < 1 || n_ctx > L->capacity) return 0;
+  int32_t s = 0, c = 0;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, &c)) return 0;
+  return s;
+}
+
+skv_status skv_decode_partial(const skv_layer* L, const void* q, int64_t n_ctx, float scale,
+                              int32_t n_splits, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+  skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (!q) return SKV_ERR_NULL;
+  if (!aligned16(q)) return SKV_ERR_ALIGN;
+  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
+  if (n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
+  if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
+  int32_t s = 0, chunk = 0;
+  const int group = L->n_q_heads / L->n_kv_heads;
+  if (!plan_splits(L->batch, L->n_kv_heads, group, n_ctx, n_splits, &s, &chunk)) return SKV_ERR_SHAPE;
+  st = check_decode_common(L, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+
+  DecodeParams p;
+  fill_decode_params(L, &p, s, chunk, workspace);
+  p.q = static_cast<const uint16_t*>(q);
+  p.n_ctx = (int32_t)n_ctx;
+  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
+  p.scale_log2e = (float)(sc * 1.4426950408889634);
+  decode_partial_launcher launch = partial_launcher_for(L->r_k);
+  if (!launch) return SKV_ERR_RANK;
+  if (launch(L->r_v, heads_per_pass(group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_decode_combine(const skv_layer* L, void* out, int32_t n_splits, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (!out) return SKV_ERR_NULL;
+  if (!aligned16(out)) return SKV_ERR_ALIGN;
+  st = check_decode_common(L, n_splits, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams p;
+  fill_decode_params(L, &p, n_splits, 0, workspace);
+  p.out = static_cast<float*>(out);
+  if (launch_decode_combine(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_decode_attention(const skv_layer* L, const void* q, void* out, int64_t n_ctx,
+                                float scale, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  // Check everything both stages need before the first launch, so that an
+  // error never leaves half the work enqueued.
+  skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (!q || !out || !workspace) return SKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return SKV_ERR_ALIGN;
+  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
+  const int32_t s = skv_decode_default_splits(L, n_ctx);
+  if (s < 1) return SKV_ERR_SHAPE;
+  st = check_decode_common(L, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  st = skv_decode_partial(L, q, n_ctx, scale, s, workspace, workspace_bytes, stream);
+  if (st != SKV_OK) return st;
+  return skv_decode_combine(L, out, s, workspace, workspace_bytes, stream);
+}
+
+skv_status skv_project_append(const skv_layer* L, const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                              int64_t cur_len, void* stream) {
+  skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (T < 0) return SKV_ERR_SHAPE;
+  if (cur_len < 0 || cur_len + (int64_t)T > L->capacity) return SKV_ERR_CAPACITY;
+  if (T == 0) return SKV_OK;
+  if (!k_new || !v_new) return SKV_ERR_NULL;
+  if (stride_b < 0 || stride_t < 0 || stride_h < 0) return SKV_ERR_SHAPE;
+  if ((int64_t)L->batch * T > std::numeric_limits<int32_t>::max()) return SKV_ERR_SHAPE;
+  if ((stride_b % 8) || (stride_t % 8) || (stride_h % 8)) return SKV_ERR_ALIGN;
+  if (!aligned16(k_new) || !aligned16(v_new)) return SKV_ERR_ALIGN;
+
+  AppendParams p;
+  p.k_cache = static_cast<uint16_t*>(L->k_cache);
+  p.v_cache = static_cast<uint16_t*>(L->v_cache);
+  p.p_k = static_cast<const uint16_t*>(L->p_k);
+  p.p_v = static_cast<const uint16_t*>(L->p_v);
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.capacity = L->capacity;
+  p.p_k_head_stride = L->p_k_head_stride;
+  p.p_v_head_stride = L->p_v_head_stride;
+  p.stride_b = stride_b;
+  p.stride_t = stride_t;
+  p.stride_h = stride_h;
+  p.cur_len = cur_len;
+  p.batch = L->batch;
+  p.n_kv_heads = L->n_kv_heads;
+  p.r_k = L->r_k;
+  p.r_v = L->r_v;
+  p.T = T;
+  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho, const int32_t* cand_k,
+                           int32_t n_k, const int32_t* cand_v, int32_t n_v, const double* delta,
+                           int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio) {
+  if (!cand_k || !cand_v || !delta || !r_k_out || !r_v_out) return SKV_ERR_NULL;
+  if (n_layers < 1 || n_k < 1 || n_v < 1 || head_dim < 1) return SKV_ERR_SHAPE;
+  if (!(rho > 0.0) || std::isinf(rho)) return SKV_ERR_SHAPE;
+  for (int i = 0; i < n_k; ++i)
+    if (cand_k[i] < 1 || cand_k[i] > head_dim) return SKV_ERR_SHAPE;
+  for (int j = 0; j < n_v; ++j)
+    if (cand_v[j] < 1 || cand_v[j] > head_dim) return SKV_ERR_SHAPE;
+  const int64_t total = (int64_t)n_layers * n_k * n_v;
+  for (int64_t i = 0; i < total; ++i)
+    if (delta[i] != delta[i]) return SKV_ERR_SHAPE;
+
+  // Budget carried in rank units (2 * head_dim * B_l) so that costs are integers.
+  double units = 2.0 * (double)head_dim * (double)n_layers * rho;
+  bool all_feasible = true;
+  int64_t spent = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    const double remaining = (double)(n_layers - l);
+    const double* surf = delta + (int64_t)l * n_k * n_v;
+    int bi = -1, bj = -1;
+    // pass 1: affordable pairs, ordered by (delta, cost, larger r_V, position)
+    for (int i = 0; i < n_k; ++i) {
+      for (int j = 0; j < n_v; ++j) {
+        const int cost = cand_k[i] + cand_v[j];
+        if ((double)cost * remaining > units * (1.0 + 1e-12)) continue;
+        bool better;
+        if (bi < 0) {
+          better = true;
+        } else {
+          const double d0 = surf[bi * n_v + bj], d1 = surf[i * n_v + j];
+          const int c0 = cand_k[bi] + cand_v[bj];
+          if (d1 != d0) better = d1 < d0;
+          else if (cost != c0) better = cost < c0;
+          else if (cand_v[j] != cand_v[bj]) better = cand_v[j] > cand_v[bj];
+          else better = false;
+        }
+        if (better) { bi = i; bj = j; }
+      }
+    }
+    if (bi < 0) {
+      // pass 2: nothing fits -- cheapest pair, ordered by (cost, delta, larger r_V, position)
+      all_feasible = false;
+      for (int i = 0; i < n_k; ++i) {
+        for (int j = 0; j < n_v; ++j) {
+          const int cost = cand_k[i] + cand_v[j];
+          bool better;
+          if (bi < 0) {
+            better = true;
+          } else {
+            const double d0 = surf[bi * n_v + bj], d1 = surf[i * n_v + j];
+            const int c0 = cand_k[bi] + cand_v[bj];
+            if (cost != c0) better = cost < c0;
+            else if (d1 != d0) better = d1 < d0;
+            else if (cand_v[j] != cand_v[bj]) better = cand_v[j] > cand_v[bj];
+            else better = false;
+          }
+          if (better) { bi = i; bj = j; }
+        }
+      }
+    }
+    r_k_out[l] = cand_k[bi];
+    r_v_out[l] = cand_v[bj];
+    units -= (double)(cand_k[bi] + cand_v[bj]);
+    spent += cand_k[bi] + cand_v[bj];
+  }
+  if (achieved_ratio) *achieved_ratio = (double)spent / (2.0 * (double)head_dim * (double)n_layers);
+  return all_feasible ? SKV_OK : SKV_ERR_BUDGET;
+}
+
+}  // extern "C"

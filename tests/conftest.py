@@ -1,4 +1,5 @@
 import os
+import shutil
 import sys
 
 import pytest
@@ -10,6 +11,16 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_present():
+    """Tests load the library that is built; they build it only if there is none."""
+    from paper_2601_21686_amd import binding
+    if not os.path.exists(binding.LIB_PATH) and (shutil.which("hipcc") or os.path.exists("/opt/rocm/bin/hipcc")):
+        from paper_2601_21686_amd import build
+        build.build(verbose=False)
+    yield
 
 
 @pytest.fixture(scope="session")

@@ -1,0 +1,156 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the
+header declares, rejects bad arguments before launching anything, and its
+host-only rank selection agrees with the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import skv_oracle as O
+from paper_2601_21686_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libskv.so not built")
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "skv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(skv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert B.status_string(0) == "SKV_OK"
+    assert B.status_string(B.SKV_ERR_RANK) == "SKV_ERR_RANK"
+    assert B.status_string(99) == "SKV_ERR_UNKNOWN"
+
+
+FAKE = 0x10000  # non-null, 16-byte aligned; never dereferenced because validation fails first
+
+
+def _layer(**kw):
+    d = dict(batch=4, n_q_heads=32, n_kv_heads=8, head_dim=128, r_k=64, r_v=64, capacity=1024,
+             k_cache=FAKE, v_cache=FAKE, p_k=FAKE, p_v=FAKE,
+             p_k_head_stride=128 * 64, p_v_head_stride=128 * 64)
+    d.update(kw)
+    return B.skv_layer(**d)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(k_cache=None), B.SKV_ERR_NULL),
+    (dict(p_v=None), B.SKV_ERR_NULL),
+    (dict(head_dim=64), B.SKV_ERR_SHAPE),
+    (dict(batch=0), B.SKV_ERR_SHAPE),
+    (dict(n_q_heads=30), B.SKV_ERR_SHAPE),
+    (dict(n_q_heads=24), B.SKV_ERR_SHAPE),          # G = 3
+    (dict(r_k=0), B.SKV_ERR_RANK),
+    (dict(r_k=72), B.SKV_ERR_RANK),
+    (dict(r_v=144), B.SKV_ERR_RANK),
+    (dict(capacity=0), B.SKV_ERR_CAPACITY),
+    (dict(p_k_head_stride=100), B.SKV_ERR_SHAPE),
+    (dict(p_v_head_stride=128 * 64 + 4), B.SKV_ERR_ALIGN),
+    (dict(k_cache=FAKE + 8), B.SKV_ERR_ALIGN),
+])
+def test_bad_layers_are_rejected_by_every_entry_point(kw, code):
+    lib = B.lib()
+    L = _layer(**kw)
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == code
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 0, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_combine(C.byref(L), FAKE, 1, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_workspace_bytes(C.byref(L)) == 0
+    assert lib.skv_decode_default_splits(C.byref(L), 16) == 0
+
+
+def test_bad_call_arguments_are_rejected():
+    lib = B.lib()
+    L = _layer()
+    ws = lib.skv_decode_workspace_bytes(C.byref(L))
+    assert ws == 4 * 32 * 256 * 66 * 4
+    assert lib.skv_cache_bytes(C.byref(L), 1000) == 4 * 8 * 1000 * 128 * 2
+    # append
+    assert lib.skv_project_append(None, FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_project_append(C.byref(L), None, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1024, 128, -1, 0, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 2, 1023, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, -1, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1020, 128, 1, 0, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_project_append(C.byref(L), FAKE + 2, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_project_append(C.byref(L), FAKE, FAKE, -8, 1024, 128, 1, 0, None) == B.SKV_ERR_SHAPE
+    # T = 0 is a no-op that needs no input pointers
+    assert lib.skv_project_append(C.byref(L), None, None, 0, 0, 0, 0, 1024, None) == B.SKV_OK
+    # decode
+    assert lib.skv_decode_attention(C.byref(L), None, FAKE, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert lib.skv_decode_attention(C.byref(L), FAKE, None, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, None, ws, None) == B.SKV_ERR_NULL
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 0, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 1025, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, 8, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE + 4, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 257, FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, float("nan"), 1, FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 4, FAKE, 4 * 32 * 4 * 66 * 4 - 1, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_combine(C.byref(L), FAKE, 0, FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_combine(C.byref(L), FAKE, 257, FAKE, ws, None) == B.SKV_ERR_SHAPE
+
+
+def test_default_split_plan():
+    lib = B.lib()
+    L = _layer(capacity=1 << 20)
+    # 32 (b, kv) columns -> 64 ranges at long context; never more ranges than 256-token tiles
+    assert lib.skv_decode_default_splits(C.byref(L), 32768) == 64
+    assert lib.skv_decode_default_splits(C.byref(L), 1) == 1
+    assert lib.skv_decode_default_splits(C.byref(L), 257) == 2
+    assert lib.skv_decode_default_splits(C.byref(L), 1 << 20) == 64
+    for n in (1, 255, 256, 257, 1000, 5000, 32767, 32768, 32769, 131072):
+        s = lib.skv_decode_default_splits(C.byref(L), n)
+        assert 1 <= s <= 256
+
+
+def test_layer_ranks_matches_oracle_on_random_surfaces():
+    rng = np.random.default_rng(0)
+    for trial in range(300):
+        L = int(rng.integers(1, 12))
+        d = 128
+        ck = sorted(rng.choice([16, 32, 48, 64, 80, 96, 112, 128], size=int(rng.integers(1, 6)), replace=False).tolist())
+        cv = sorted(rng.choice([16, 32, 48, 64, 80, 96, 112, 128], size=int(rng.integers(1, 6)), replace=False).tolist())
+        rho = float(rng.choice([0.3, 0.5, 0.55, 0.6, 0.7, 0.75, 0.8, 0.9, 1.0]))
+        if trial % 3 == 0:
+            delta = rng.integers(0, 4, size=(L, len(ck), len(cv))).astype(float)   # ties
+        else:
+            delta = rng.uniform(0, 1, size=(L, len(ck), len(cv)))
+        want = O.layer_ranks(L, d, rho, ck, cv, delta)
+        got = B.skv_layer_ranks(L, d, rho, ck, cv, delta)
+        assert got[0] == want[0] and got[1] == want[1]
+        assert got[2] == want[2] and got[3] == want[3]
+
+
+def test_layer_ranks_argument_errors():
+    lib = B.lib()
+    i32 = C.c_int32
+    ck = (i32 * 2)(64, 128)
+    bad = (i32 * 2)(64, 256)
+    delta = (C.c_double * 8)(*([0.5] * 8))
+    nan = (C.c_double * 8)(*([float("nan")] * 8))
+    rk, rv = (i32 * 2)(), (i32 * 2)()
+    f = lib.skv_layer_ranks
+    assert f(2, 128, 0.8, ck, 2, ck, 2, delta, rk, rv, None) == B.SKV_OK
+    assert f(0, 128, 0.8, ck, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_SHAPE
+    assert f(2, 128, 0.0, ck, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_SHAPE
+    assert f(2, 128, 0.8, bad, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_SHAPE
+    assert f(2, 128, 0.8, ck, 2, ck, 2, nan, rk, rv, None) == B.SKV_ERR_SHAPE
+    assert f(2, 128, 0.8, None, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_NULL
+    assert f(2, 128, 0.8, ck, 2, ck, 2, delta, None, rv, None) == B.SKV_ERR_NULL
+    assert f(2, 128, 0.3, ck, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_BUDGET
+    assert list(rk) == [64, 64] and list(rv) == [64, 64]

@@ -1,0 +1,115 @@
+"""GPU parity of decode attention against the float64 oracle, element by
+element, on sizes the oracle finishes in seconds.  Both sides read the same
+cache bytes (written by the oracle's own append)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_21686_amd import binding as B
+from _helpers import TOL, Pair, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _filled_pair(seed, batch, hq, hkv, r_k, r_v, n, capacity=None, **kw):
+    P = Pair(seed, batch, hq, hkv, r_k, r_v, capacity or n, **kw)
+    k, v = P.raw_kv(seed, n, device="cpu")
+    P.oracle_append(k, v, 0)
+    P.upload_oracle_cache(n)
+    return P
+
+
+@pytest.mark.parametrize("r_k,r_v", [(64, 64), (16, 16), (32, 48), (48, 80), (80, 32), (96, 112),
+                                      (112, 96), (128, 128), (64, 96), (16, 128), (128, 16)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4)])
+def test_decode_matches_oracle_across_ranks(r_k, r_v, hq, hkv):
+    n = 1500                                        # several tiles and a ragged tail
+    P = _filled_pair(("ranks", r_k, r_v, hq), 2, hq, hkv, r_k, r_v, n)
+    q = P.queries(1)
+    want = P.oracle_decode(q, n)
+    got = P.gpu_decode(q, n)
+    assert vec_rel_err(got, want) <= TOL
+
+
+@pytest.mark.parametrize("group", [1, 2, 4, 8])
+def test_decode_head_grouping(group):
+    hkv = 2
+    P = _filled_pair(("group", group), 2, hkv * group, hkv, 64, 64, 777)
+    q = P.queries(2)
+    assert vec_rel_err(P.gpu_decode(q, 777), P.oracle_decode(q, 777)) <= TOL
+
+
+@pytest.mark.parametrize("n_ctx", [1, 2, 7, 8, 9, 31, 32, 33, 127, 128, 129, 255, 256, 257, 511, 513, 1024])
+def test_decode_context_lengths_and_unread_tail(n_ctx):
+    cap = 1100
+    P = _filled_pair(("ctx",), 1, 8, 2, 64, 64, cap)
+    # rows beyond n_ctx hold NaN: they must never influence the result
+    nan = torch.full((1,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.gpu.k_cache[:, :, n_ctx:] = nan
+    P.gpu.v_cache[:, :, n_ctx:] = nan
+    q = P.queries(3)
+    got = P.gpu_decode(q, n_ctx)
+    assert np.all(np.isfinite(got))
+    assert vec_rel_err(got, P.oracle_decode(q, n_ctx)) <= TOL
+
+
+@pytest.mark.parametrize("n_splits", [1, 2, 3, 5, 8, 64, 256])
+def test_explicit_split_counts_including_empty_ranges(n_splits):
+    n = 2000
+    P = _filled_pair(("splits",), 2, 8, 2, 48, 80, n)
+    q = P.queries(4)
+    out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
+    B.skv_decode_partial(P.gpu, q, n, 0.0, n_splits)
+    B.skv_decode_combine(P.gpu, out, n_splits)
+    torch.cuda.synchronize()
+    assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n)) <= TOL
+
+
+def test_shared_key_basis_and_custom_scale():
+    n = 900
+    P = _filled_pair(("shared",), 2, 8, 4, 64, 96, n, shared_k=True)
+    assert P.gpu.c.p_k_head_stride == 0
+    q = P.queries(5)
+    for scale in (0.0, 0.05, 0.3):
+        want = P.oracle_decode(q, n, scale if scale > 0 else None)
+        assert vec_rel_err(P.gpu_decode(q, n, scale), want) <= TOL
+
+
+def test_peaked_softmax_with_large_scores():
+    # one key aligned with the query: the softmax is dominated by a single row
+    n = 1200
+    P = _filled_pair(("peaked",), 1, 4, 1, 64, 64, n)
+    q = P.queries(6)
+    want = P.oracle_decode(q, n, 4.0)
+    got = P.gpu_decode(q, n, 4.0)
+    assert vec_rel_err(got, want) <= TOL
+
+
+def test_decode_is_deterministic_and_stage_calls_equal_the_fused_call():
+    n = 3000
+    P = _filled_pair(("det",), 2, 8, 2, 64, 64, n)
+    q = P.queries(7)
+    a = P.gpu_decode(q, n)
+    b = P.gpu_decode(q, n)
+    assert np.array_equal(a, b)
+    s = B.skv_decode_default_splits(P.gpu, n)
+    out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
+    B.skv_decode_partial(P.gpu, q, n, 0.0, s)
+    B.skv_decode_combine(P.gpu, out, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), a)
+
+
+def test_errors_leave_output_untouched():
+    P = _filled_pair(("err",), 1, 4, 1, 64, 64, 64)
+    q = P.queries(8)
+    out = torch.full((1, 4, 128), 7.0, dtype=torch.float32, device="cuda")
+    with pytest.raises(B.SkvError) as e:
+        B.skv_decode_attention(P.gpu, q, out, 65)
+    assert e.value.code == B.SKV_ERR_CAPACITY
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.SkvError) as e:
+        B.skv_decode_attention(P.gpu, q, out, 64, 0.0, small)
+    assert e.value.code == B.SKV_ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert torch.all(out == 7.0)
