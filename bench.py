@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the compressed-KV decode path on one MI355X.
+
+One "step" is one pass of the whole hot path for one new token per sequence:
+project the new key/value onto P_K / P_V and append them to the bf16 compressed
+cache, then decode attention over the whole cache (query projection, scores,
+online softmax, value mix, split merge, lift).  Every layer of the workload is
+visited once per step.  Inputs are seeded and synthetic and already resident in
+HBM when the clock starts.
+
+Prints ONE JSON line.  `value` is algorithmic compressed-cache bytes per second
+for the whole step (GB/s); tokens/s is reported beside it.  `roofline` is the
+decode range kernel alone, timed with events on the launch stream.
+`cpu_baseline` is the float64 oracle timed on the host for one decode step of
+the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+METRIC = "compressed-KV decode attention: achieved HBM GB/s + tokens/s at b4/32K"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="b4_ctx32k_r64")
+    ap.add_argument("--splits", type=int, default=0, help="context ranges for the roofline leg (0 = library default)")
+    ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
+    ap.add_argument("--mode", choices=("bench", "kernel", "copy"), default="bench",
+                    help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
+                         "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters")
+    return ap.parse_args()
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch of the decode range kernel, from the committed counter summary."""
+    path = os.path.join(ROOT, "profiles", f"decode_partial_{workload}_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    with open(path) as f:
+        for line in f:
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                vals[k.strip()] = v.strip()
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus {args.gpus} is not supported. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2601_21686_amd import binding as B
+    from paper_2601_21686_amd import synth
+
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2601_21686_amd import build
+        build.build(verbose=False)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    if args.mode == "copy":
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "copy", "bytes_read_per_launch": 1 << 30, "bytes_written_per_launch": 1 << 30,
+                          "launches": 5}))
+        return
+
+    wl = synth.WORKLOADS[args.workload]
+    K, W = args.steps, args.warmup
+    if args.mode == "kernel":
+        K, W = 1, 0
+    Bt, HQ, HKV, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+    if wl.r_k:
+        ranks_k, ranks_v = [wl.r_k] * wl.n_layers, [wl.r_v] * wl.n_layers
+    else:
+        ranks_k, ranks_v = synth.layer_rank_draw(synth.stable_seed(wl.name, "ranks"), wl.n_layers)
+
+    # The first timed step attends exactly wl.n_ctx tokens.
+    n0 = wl.n_ctx - 1 - W
+    cap = wl.n_ctx + K + 8
+    assert n0 >= 1
+
+    layers, scales = [], []
+    for li in range(wl.n_layers):
+        _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, li, "pk"), HKV, d, ranks_k[li])
+        _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, li, "pv"), HKV, d, ranks_v[li])
+        layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
+        scales.append((synth.channel_scales(synth.stable_seed(wl.name, li, "sk"), HKV, d),
+                       synth.channel_scales(synth.stable_seed(wl.name, li, "sv"), HKV, d)))
+
+    # Prefill the caches through the library's own append (chunks on the matrix cores).
+    CH = 4096
+    for li, L in enumerate(layers):
+        for c0 in range(0, n0, CH):
+            t = min(CH, n0 - c0)
+            k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
+            v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
+            B.skv_project_append(L, k, v, c0)
+    torch.cuda.synchronize()
+
+    # Per-step inputs: one new token per sequence and layer, one query per head.
+    n_steps_total = W + K
+    new_k = [synth.kv_activations(synth.stable_seed(wl.name, li, "nk"), Bt, n_steps_total, HKV, d, scales[li][0], dev)
+             for li in range(wl.n_layers)]
+    new_v = [synth.kv_activations(synth.stable_seed(wl.name, li, "nv"), Bt, n_steps_total, HKV, d, scales[li][1], dev)
+             for li in range(wl.n_layers)]
+    qs = torch.stack([synth.queries(synth.stable_seed(wl.name, "q", s), Bt, HQ * wl.n_layers, d, dev)
+                      .view(Bt, wl.n_layers, HQ, d).transpose(0, 1).contiguous() for s in range(n_steps_total)])
+    outs = torch.empty((n_steps_total, wl.n_layers, Bt, HQ, d), dtype=torch.float32, device=dev)
+    ws = torch.empty(max(B.skv_decode_workspace_bytes(L) for L in layers), dtype=torch.uint8, device=dev)
+
+    def step(s: int):
+        cur = n0 + s
+        for li, L in enumerate(layers):
+            B.skv_project_append(L, new_k[li][:, s:s + 1], new_v[li][:, s:s + 1], cur)
+            B.skv_decode_attention(L, qs[s, li], outs[s, li], cur + 1, 0.0, ws)
+
+    for s in range(W):
+        step(s)
+    torch.cuda.synchronize()
+
+    use_graph = not args.no_graph and args.mode == "bench"
+    if use_graph:
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                for s in range(W, W + K):
+                    step(s)
+        torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps ------------------------------------------------
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if use_graph:
+        g.replay()
+    else:
+        for s in range(W, W + K):
+            step(s)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    ms_per_step = elapsed * 1e3 / K
+
+    # algorithmic compressed-cache bytes read by the K timed steps
+    bytes_steps = 0
+    for s in range(W, W + K):
+        n_ctx = n0 + s + 1
+        for li in range(wl.n_layers):
+            bytes_steps += Bt * HKV * n_ctx * (ranks_k[li] + ranks_v[li]) * 2
+    gbps = bytes_steps / elapsed / 1e9
+    tokens_per_s = Bt * K / elapsed
+
+    # ---- roofline leg: the decode range kernel alone, events on the launch stream --------
+    # single layer: that layer; a stack: the layer with the median rank sum
+    li_big = sorted(range(wl.n_layers), key=lambda i: ranks_k[i] + ranks_v[i])[wl.n_layers // 2]
+    Lr = layers[li_big]
+    n_roof = wl.n_ctx
+    splits = args.splits if args.splits > 0 else B.skv_decode_default_splits(Lr, n_roof)
+    for _ in range(10):
+        B.skv_decode_partial(Lr, qs[0, li_big], n_roof, 0.0, splits, ws)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.kernel_iters):
+        B.skv_decode_partial(Lr, qs[0, li_big], n_roof, 0.0, splits, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    kern_ms = e0.elapsed_time(e1) / args.kernel_iters
+    # algorithmic bytes of one launch: every cache row once per KV head, the bases, the
+    # queries in, the per-range partial results out
+    rk, rv = ranks_k[li_big], ranks_v[li_big]
+    kern_bytes = (Bt * HKV * n_roof * (rk + rv) * 2 + HKV * d * rk * 2 + Bt * HQ * d * 2
+                  + Bt * HQ * splits * (rv + 2) * 4)
+    achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
+
+    result = {
+        "metric": METRIC,
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "tokens_per_s": round(tokens_per_s, 1),
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": Bt, "n_q_heads": HQ, "n_kv_heads": HKV, "head_dim": d,
+                   "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
+                   "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
+                   "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
+                   "cache": "bf16", "step": "append 1 token/sequence + decode attention, every layer",
+                   "launch": "hip graph replay" if use_graph else "per-call launches"},
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": read_traffic(wl.name), "bytes_per_launch": kern_bytes,
+                     "us_per_launch": round(kern_ms * 1e3, 3), "n_ctx": n_roof, "r_k": rk, "r_v": rv,
+                     "splits": splits},
+    }
+
+    # ---- CPU baseline: the float64 oracle, one decode step of the same workload ----------
+    if not args.no_cpu_baseline and args.mode == "bench":
+        from oracle import skv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        f64 = lambda t: O.bf16_bits_to_f64(synth.torch_bf16_to_bits(t))
+        li = 0
+        s_chk = W + K - 1                                  # the last timed step
+        n_chk = n0 + s_chk + 1
+        ora = O.new_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v), n_chk, store="bf16")
+        for c0 in range(0, n0, CH):                        # same seeded raw inputs as the GPU prefill
+            t = min(CH, n0 - c0)
+            k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
+            v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
+            O.project_append(ora, f64(k), f64(v), c0)
+        O.project_append(ora, f64(new_k[li][:, :s_chk + 1]), f64(new_v[li][:, :s_chk + 1]), n0)
+        # bounded sample: the last timed steps, newest first, for about 12 s of host time
+        budget_s, spent, errs, cpu_bytes, n_done = 12.0, 0.0, [], 0, 0
+        for s_i in range(s_chk, W - 1, -1):
+            n_i = n0 + s_i + 1
+            qh = f64(qs[s_i, li])
+            tb = time.perf_counter()
+            want = O.decode_attention(ora, qh, n_i)
+            spent += time.perf_counter() - tb
+            got = outs[s_i, li].cpu().numpy().astype(np.float64)
+            errs.append(float(np.max(np.max(np.abs(got - want), axis=-1) / np.max(np.abs(want), axis=-1))))
+            cpu_bytes += Bt * HKV * n_i * (ranks_k[li] + ranks_v[li]) * 2
+            n_done += 1
+            if spent >= budget_s:
+                break
+        result["cpu_baseline"] = {
+            "value": round(cpu_bytes / spent / 1e9, 4), "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "tokens_per_s": round(Bt * n_done / spent / wl.n_layers, 3),
+            "sample": f"decode attention of layer 0 for the last {n_done} timed steps (n_ctx {n0 + s_chk + 2 - n_done}.."
+                      f"{n_chk}), all {Bt} sequences x {HQ} query heads, float64 definition form, {spent:.2f} s of host time",
+        }
+        result["parity"] = {"max_rel_err_vs_oracle": max(errs), "tolerance": 2e-3,
+                            "checked": f"layer 0, last {n_done} timed steps, {Bt} sequences x {HQ} heads each"}
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
