@@ -116,7 +116,7 @@ skv_status skv_decode_attention(const skv_layer* layer, const void* q, void* out
                                 int64_t n_ctx, float scale,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace that skv_decode_attention / skv_decode_partial need for
+/* Bytes of workspace that skv_decode_attention, skv_decode_step and the stages need for
  * this layer at any n_ctx <= capacity and any split count <= SKV_MAX_SPLITS.
  * Returns 0 if the layer's shape is invalid. */
 size_t skv_decode_workspace_bytes(const skv_layer* layer);
@@ -126,22 +126,46 @@ size_t skv_decode_workspace_bytes(const skv_layer* layer);
 int32_t skv_decode_default_splits(const skv_layer* layer, int64_t n_ctx);
 
 /*
- * The two stages of skv_decode_attention, exposed so that a caller can time or
- * schedule them separately; calling them back to back on one stream with the
- * same workspace and n_splits is exactly skv_decode_attention.
+ * One whole decode step for T new tokens per sequence (T = 1 in a serving
+ * loop): exactly skv_project_append(k_new, v_new, T, cur_len) followed by
+ * skv_decode_attention(q, out, n_ctx = cur_len + T), i.e. the query attends
+ * the freshly appended rows too (Sec. 3.2: attention always sees the
+ * reconstructed, compressed forms).  Doing both in one call lets the library
+ * project new keys, new values and queries in a single small launch ahead of
+ * the streaming kernel.  Arguments and errors as for the two calls.
+ */
+skv_status skv_decode_step(const skv_layer* layer,
+                           const void* k_new, const void* v_new,
+                           int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                           int32_t T, int64_t cur_len,
+                           const void* q, void* out, float scale,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The three stages of skv_decode_attention, exposed so that a caller can time
+ * or schedule them separately; calling them back to back on one stream with
+ * the same workspace and n_splits is exactly skv_decode_attention.
  *
- * skv_decode_partial: query projection, scores, online softmax and value mix
- * over each of n_splits context ranges; writes per (b, h, range) the running
- * maximum, the normaliser and the un-normalised rank-r_V mix into workspace.
- * n_splits <= 0 selects skv_decode_default_splits(); a value larger than the
- * context allows is an error (SHAPE).
+ * skv_decode_project_query: q~ = (q P_K) * scale for every query head, with the
+ * key basis of the head's KV group (projecting the keys induces the same
+ * projection of the query inside q K~^T, Sec. 2.1 Eq. 2 and Sec. 2.2); kept in
+ * float32 in the workspace.
+ *
+ * skv_decode_partial: scores of the projected queries against K_down, online
+ * softmax and value mix over each of n_splits context ranges; writes per
+ * (b, h, range) the running maximum, the normaliser and the un-normalised
+ * rank-r_V mix into the workspace.  n_splits <= 0 selects
+ * skv_decode_default_splits(); any value up to SKV_MAX_SPLITS is honoured
+ * (ranges beyond the context are empty).
  *
  * skv_decode_combine: merges the ranges (softmax is invariant to the split:
  * rescale each range by exp(m_range - m), add) in range order, divides by the
- * normaliser and lifts with P_V^T into out.
+ * normaliser and lifts with P_V^T into out.  n_splits must be the count the
+ * partial stage used.
  */
-skv_status skv_decode_partial(const skv_layer* layer, const void* q,
-                              int64_t n_ctx, float scale, int32_t n_splits,
+skv_status skv_decode_project_query(const skv_layer* layer, const void* q, float scale,
+                                    void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_decode_partial(const skv_layer* layer, int64_t n_ctx, int32_t n_splits,
                               void* workspace, size_t workspace_bytes, void* stream);
 skv_status skv_decode_combine(const skv_layer* layer, void* out, int32_t n_splits,
                               void* workspace, size_t workspace_bytes, void* stream);

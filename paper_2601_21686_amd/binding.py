@@ -23,7 +23,8 @@ SKV_MAX_SPLITS = 256
 
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
-    "skv_decode_default_splits", "skv_decode_partial", "skv_decode_combine",
+    "skv_decode_default_splits", "skv_decode_step", "skv_decode_project_query",
+    "skv_decode_partial", "skv_decode_combine",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
 )
 
@@ -67,7 +68,11 @@ def lib() -> C.CDLL:
     L.skv_decode_workspace_bytes.restype = sz
     L.skv_decode_default_splits.argtypes = [LP, i64]
     L.skv_decode_default_splits.restype = i32
-    L.skv_decode_partial.argtypes = [LP, vp, i64, C.c_float, i32, vp, sz, vp]
+    L.skv_decode_step.argtypes = [LP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_decode_step.restype = C.c_int
+    L.skv_decode_project_query.argtypes = [LP, vp, C.c_float, vp, sz, vp]
+    L.skv_decode_project_query.restype = C.c_int
+    L.skv_decode_partial.argtypes = [LP, i64, i32, vp, sz, vp]
     L.skv_decode_partial.restype = C.c_int
     L.skv_decode_combine.argtypes = [LP, vp, i32, vp, sz, vp]
     L.skv_decode_combine.restype = C.c_int
@@ -168,12 +173,34 @@ def skv_decode_attention(layer, q: torch.Tensor, out: torch.Tensor, n_ctx: int, 
                                       _stream_ptr(stream)), "skv_decode_attention")
 
 
-def skv_decode_partial(layer, q: torch.Tensor, n_ctx: int, scale: float = 0.0, n_splits: int = 0,
-                       workspace: torch.Tensor | None = None, stream=None) -> None:
+def skv_decode_step(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int, q: torch.Tensor,
+                    out: torch.Tensor, scale: float = 0.0, workspace: torch.Tensor | None = None,
+                    stream=None) -> None:
+    """Append k_new/v_new ([batch, T, n_kv_heads, 128]) at cur_len, then attend cur_len + T rows."""
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_decode_partial(_ref(layer), q.data_ptr(), int(n_ctx), float(scale), int(n_splits),
-                                    ws.data_ptr(), ws.numel() * ws.element_size(),
-                                    _stream_ptr(stream)), "skv_decode_partial")
+    _check(lib().skv_decode_step(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                 int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
+                                 float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                 _stream_ptr(stream)), "skv_decode_step")
+
+
+def skv_decode_project_query(layer, q: torch.Tensor, scale: float = 0.0,
+                             workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_project_query(_ref(layer), q.data_ptr(), float(scale), ws.data_ptr(),
+                                          ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_project_query")
+
+
+def skv_decode_partial(layer, n_ctx: int, n_splits: int = 0, workspace: torch.Tensor | None = None,
+                       stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_partial(_ref(layer), int(n_ctx), int(n_splits), ws.data_ptr(),
+                                    ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_partial")
 
 
 def skv_decode_combine(layer, out: torch.Tensor, n_splits: int, workspace: torch.Tensor | None = None,

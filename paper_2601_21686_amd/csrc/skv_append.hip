@@ -2,56 +2,18 @@
 // (Sec. 2.1 Eq. 1: K_down = K P_K, V_down = V P_V; Sec. 3.2: these compressed
 // tensors are what gets cached).
 //
-// Two kernels.  A chunk of tokens is a dense [tokens x 128] . [128 x r]
-// contraction per KV head and runs on the matrix cores (MFMA 16x16x32 bf16,
-// float32 accumulate).  A handful of tokens (a decode step appends one per
-// sequence) is a matrix-vector product and runs on the vector ALUs.
-// Both round the float32 sum to bf16 once, to nearest even.
+// A chunk of tokens is a dense [tokens x 128] . [128 x r] contraction per KV
+// head and runs on the matrix cores (MFMA 16x16x32 bf16, float32 accumulate);
+// this file holds that kernel.  A handful of tokens (a decode step appends one
+// per sequence) is a matrix-vector product and runs on the vector ALUs (see
+// skv_project.hip).  Both round the float32 sum to bf16 once, to nearest even.
+#include "skv_device_util.h"
 #include "skv_internal.h"
 
 namespace skv {
 namespace {
 
 constexpr int D = SKV_HEAD_DIM;
-
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
-
-// float32 -> bf16, round to nearest even (finite inputs; NaN stays NaN).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
-  uint32_t u = __float_as_uint(x);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-
-// ---------------------------------------------------------------------------
-// Few tokens: one workgroup per (sequence, token, KV head); threads 0..127
-// produce key channels, 128..255 value channels.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void append_vector_kernel(const AppendParams p) {
-  __shared__ float x_s[2][D];
-  const int tid = threadIdx.x;
-  const int idx = blockIdx.x;                    // (b * T + t) * H_KV + h
-  const int h = idx % p.n_kv_heads;
-  const int bt = idx / p.n_kv_heads;
-  const int t = bt % p.T;
-  const int b = bt / p.T;
-  const int which = tid >> 7;                    // 0: keys, 1: values
-  const int c = tid & 127;
-  const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)h * p.stride_h;
-  x_s[which][c] = bf16_to_f32((which ? p.v_new : p.k_new)[src + c]);
-  __syncthreads();
-  const int r = which ? p.r_v : p.r_k;
-  if (c >= r) return;
-  const uint16_t* basis = which ? p.p_v + (int64_t)h * p.p_v_head_stride
-                                : p.p_k + (int64_t)h * p.p_k_head_stride;
-  float a = 0.f;
-#pragma unroll 8
-  for (int d = 0; d < D; ++d) a = fmaf(x_s[which][d], bf16_to_f32(basis[d * r + c]), a);
-  uint16_t* cache = which ? p.v_cache : p.k_cache;
-  const int64_t row = ((int64_t)b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
-  cache[row * r + c] = (uint16_t)f32_to_bf16_bits(a);
-}
 
 // ---------------------------------------------------------------------------
 // Chunk of tokens on the matrix cores.
@@ -146,19 +108,13 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
   }
 }
 
-constexpr int kVectorPathMaxRows = 64;           // batch * T at or below this: vector kernel
-
 }  // namespace
 
 hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
   const int64_t rows = (int64_t)p.batch * p.T;
-  if (rows <= kVectorPathMaxRows) {
-    const dim3 grid((unsigned)(rows * p.n_kv_heads));
-    hipLaunchKernelGGL(append_vector_kernel, grid, dim3(256), 0, stream, p);
-  } else {
-    const dim3 grid((unsigned)((rows + kTokensPerWg - 1) / kTokensPerWg), (unsigned)p.n_kv_heads, 2u);
-    hipLaunchKernelGGL(append_mfma_kernel, grid, dim3(256), 0, stream, p);
-  }
+  if (rows <= kVectorAppendMaxRows) return launch_project(&p, nullptr, stream);
+  const dim3 grid((unsigned)((rows + kTokensPerWg - 1) / kTokensPerWg), (unsigned)p.n_kv_heads, 2u);
+  hipLaunchKernelGGL(append_mfma_kernel, grid, dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

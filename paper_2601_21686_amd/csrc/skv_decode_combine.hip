@@ -5,20 +5,26 @@
 // ranges: with m = max_s m_s,  l = sum_s l_s 2^(m_s - m),  a = sum_s a_s 2^(m_s - m)
 // the attention output in rank-r_V coordinates is a / l, and the output in
 // head_dim is (a / l) P_V^T  (Sec. 3.2 Eq. 7: V~ = V_down P_V^T, so
-// softmax(.) V~ = (softmax(.) V_down) P_V^T).  Sums run in range order, so the
-// result does not depend on scheduling.
+// softmax(.) V~ = (softmax(.) V_down) P_V^T).  Every sum runs in a fixed order,
+// so the result does not depend on scheduling.
+//
+// The kernel is a chain of small dependent steps, so its time is latency: every
+// global load it will need (its row of P_V, the range maxima, its share of the
+// partial mixes) is requested at the top, before the first wait.
+#include "skv_device_util.h"
 #include "skv_internal.h"
 
 namespace skv {
 namespace {
 
 constexpr int kCombineThreads = SKV_HEAD_DIM;   // one thread per output channel
-
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+constexpr int kPreload = 8;                     // partial-mix values per thread requested up front
+constexpr int kMlPerThread = SKV_MAX_SPLITS / kCombineThreads;
 
 __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const DecodeParams p) {
   __shared__ float w_s[SKV_MAX_SPLITS];          // 2^(m_s - m)
-  __shared__ float l_s[SKV_MAX_SPLITS];
+  __shared__ float lw_s[SKV_MAX_SPLITS];         // l_s 2^(m_s - m)
+  __shared__ float part_s[kCombineThreads];      // [range group][channel]
   __shared__ float a_s[SKV_HEAD_DIM];            // a / l, rank-r_V coordinates
   __shared__ float red_s[kCombineThreads / 64];
 
@@ -28,16 +34,38 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
   const int kv = h / p.group;
   const int S = p.n_splits;
   const int RV = p.r_v;
-  const float* ml = p.part_ml + (int64_t)bh * S * 2;
+  const float2* ml = reinterpret_cast<const float2*>(p.part_ml) + (int64_t)bh * S;
   const float* pa = p.part_acc + (int64_t)bh * S * RV;
 
-  float mloc = -3.0e38f;
-  for (int s = tid; s < S; s += kCombineThreads) {
-    const float ms = ml[2 * s];
-    w_s[s] = ms;
-    l_s[s] = ml[2 * s + 1];
-    mloc = fmaxf(mloc, ms);
+  // ---- every request first -----------------------------------------------------------------
+  const uint4* prow = reinterpret_cast<const uint4*>(p.p_v + (int64_t)kv * p.p_v_head_stride + (int64_t)tid * RV);
+  const int nc8 = RV >> 3;
+  uint4 pv[SKV_HEAD_DIM / 8];
+#pragma unroll
+  for (int k = 0; k < SKV_HEAD_DIM / 8; ++k)
+    if (k < nc8) pv[k] = prow[k];
+  float2 mlr[kMlPerThread];
+#pragma unroll
+  for (int k = 0; k < kMlPerThread; ++k) {
+    const int s = tid + k * kCombineThreads;
+    mlr[k] = s < S ? ml[s] : make_float2(-3.0e38f, 0.f);
   }
+  // thread -> (channel c, range group sg): group sg sums ranges sg, sg + NG, ...
+  const int ng = kCombineThreads / RV;
+  const int c = tid % RV;
+  const int sg = tid / RV;
+  const bool active = sg < ng;
+  float av[kPreload];
+#pragma unroll
+  for (int k = 0; k < kPreload; ++k) {
+    const int s = sg + k * ng;
+    av[k] = (active && s < S) ? pa[(int64_t)s * RV + c] : 0.f;
+  }
+
+  // ---- m = max_s m_s; weights ------------------------------------------------------------
+  float mloc = mlr[0].x;
+#pragma unroll
+  for (int k = 1; k < kMlPerThread; ++k) mloc = fmaxf(mloc, mlr[k].x);
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
   if ((tid & 63) == 0) red_s[tid >> 6] = mloc;
@@ -45,28 +73,48 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
   float m = red_s[0];
 #pragma unroll
   for (int w = 1; w < kCombineThreads / 64; ++w) m = fmaxf(m, red_s[w]);
-  for (int s = tid; s < S; s += kCombineThreads) w_s[s] = __builtin_amdgcn_exp2f(w_s[s] - m);
-  __syncthreads();
-
-  float l = 0.f;
-  for (int s = 0; s < S; ++s) l = fmaf(l_s[s], w_s[s], l);
-  if (tid < RV) {
-    float a = 0.f;
-    for (int s = 0; s < S; ++s) a = fmaf(pa[(int64_t)s * RV + tid], w_s[s], a);
-    a_s[tid] = a / l;
+#pragma unroll
+  for (int k = 0; k < kMlPerThread; ++k) {
+    const int s = tid + k * kCombineThreads;
+    if (s < S) {
+      const float w = __builtin_amdgcn_exp2f(mlr[k].x - m);
+      w_s[s] = w;
+      lw_s[s] = mlr[k].y * w;
+    }
   }
   __syncthreads();
 
-  // out[d] = sum_c a[c] * P_V[kv][d][c]
-  const uint4* prow = reinterpret_cast<const uint4*>(p.p_v + (int64_t)kv * p.p_v_head_stride + (int64_t)tid * RV);
-  float o = 0.f;
-  for (int c8 = 0; c8 < RV / 8; ++c8) {
-    const uint4 v = prow[c8];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  // ---- a[c] = sum_s a_s[c] w_s: per range group, then over groups; l = sum_s l_s w_s -----------
+  float a = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      o = fmaf(a_s[c8 * 8 + 2 * i], __uint_as_float(w[i] << 16), o);
-      o = fmaf(a_s[c8 * 8 + 2 * i + 1], __uint_as_float(w[i] & 0xffff0000u), o);
+  for (int k = 0; k < kPreload; ++k) {
+    const int s = sg + k * ng;
+    if (active && s < S) a = fmaf(av[k], w_s[s], a);
+  }
+  if (active)
+    for (int s = sg + kPreload * ng; s < S; s += ng) a = fmaf(pa[(int64_t)s * RV + c], w_s[s], a);
+  if (active) part_s[sg * RV + c] = a;
+  float l = 0.f;
+  for (int s = 0; s < S; ++s) l += lw_s[s];
+  __syncthreads();
+  if (tid < RV) {
+    float t = part_s[tid];
+    for (int g = 1; g < ng; ++g) t += part_s[g * RV + tid];
+    a_s[tid] = t / l;
+  }
+  __syncthreads();
+
+  // ---- out[d] = sum_c a[c] * P_V[kv][d][c] --------------------------------------------------
+  float o = 0.f;
+#pragma unroll
+  for (int k = 0; k < SKV_HEAD_DIM / 8; ++k) {
+    if (k < nc8) {
+      const uint32_t w[4] = {pv[k].x, pv[k].y, pv[k].z, pv[k].w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        o = fmaf(a_s[k * 8 + 2 * i], bf16_lo(w[i]), o);
+        o = fmaf(a_s[k * 8 + 2 * i + 1], bf16_hi(w[i]), o);
+      }
     }
   }
   p.out[(int64_t)bh * SKV_HEAD_DIM + tid] = o;

@@ -1,5 +1,5 @@
-// Split-context decode attention over the compressed cache: query projection,
-// scores, online softmax and value mix for one context range of one KV head.
+// Split-context decode attention over the compressed cache: scores, online
+// softmax and value mix for one context range of one KV head.
 //
 // This file is compiled once per key rank (-DSKV_RK=16,32,...,128); each
 // object holds the kernels for that r_K and every r_V in {16,...,128} and
@@ -7,8 +7,8 @@
 //
 // What is computed (App. A.1 Eq. 18 on the reconstructed cache of Sec. 3.2
 // Eq. 7, in the factored form q K~^T = (q P_K) K_down^T,
-// softmax(.) V~ = (softmax(.) V_down) P_V^T):
-//   q~[g]   = (q[g] . P_K) * scale * log2(e)               per query head g of the group
+// softmax(.) V~ = (softmax(.) V_down) P_V^T), given
+//   q~[g]   = (q[g] . P_K) * scale * log2(e)               per query head g of the group:
 //   s[g][j] = <q~[g], K_down[j]>                            j in this range
 //   m, l, a = running max, normaliser and sum_j 2^(s_j - m) V_down[j]
 // written per (sequence, query head, range) for the combine kernel.
@@ -19,8 +19,11 @@
 // the first 128 bytes of the row and the j-th eighth of the rest, which keeps
 // every load a 4..16-byte piece that is contiguous across the octet.  A
 // 64-lane wave therefore covers 8 consecutive rows per load, U loads deep.
-// Scores are reduced across the octet with DPP adds (no LDS); each octet runs
-// its own online-softmax stream and streams are merged once at the end.
+// Scores are reduced across the octet with DPP adds (no LDS); the two quads of
+// an octet each finish half of the query heads; each octet runs its own
+// online-softmax stream and streams are merged once at the end.
+// The projected query q~ comes from the projection kernel (skv_project.hip).
+#include "skv_device_util.h"
 #include "skv_internal.h"
 
 #ifndef SKV_RK
@@ -32,9 +35,6 @@ namespace {
 
 constexpr float kNegBig = -1.0e30f;   // "no score seen yet"; finite so that differences stay finite
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // How the r channels of a row are dealt to the 8 lanes of an octet.
@@ -55,22 +55,31 @@ struct RowMap {
   }
 };
 
+#ifndef SKV_NT
+#define SKV_NT 1                 // non-temporal (streaming) loads of the cache
+#endif
+#if SKV_NT
+#define SKV_LOAD(p) __builtin_nontemporal_load(p)
+#else
+#define SKV_LOAD(p) (*(p))
+#endif
+
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int N>
 __device__ __forceinline__ void load_dwords(const uint32_t* p, uint32_t* w) {
   if constexpr (N == 1) {
-    w[0] = __builtin_nontemporal_load(p);
+    w[0] = SKV_LOAD(p);
   } else if constexpr (N == 2) {
-    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(p));
+    const u32x2 v = SKV_LOAD(reinterpret_cast<const u32x2*>(p));
     w[0] = v.x; w[1] = v.y;
   } else if constexpr (N == 3) {
-    w[0] = __builtin_nontemporal_load(p);
-    w[1] = __builtin_nontemporal_load(p + 1);
-    w[2] = __builtin_nontemporal_load(p + 2);
+    w[0] = SKV_LOAD(p);
+    w[1] = SKV_LOAD(p + 1);
+    w[2] = SKV_LOAD(p + 2);
   } else if constexpr (N == 4) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    const u32x4 v = SKV_LOAD(reinterpret_cast<const u32x4*>(p));
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   }
 }
@@ -104,90 +113,172 @@ __device__ __forceinline__ float octet_sum(float x) {
   return x;
 }
 
-// Rows in flight per lane: about 16 dwords of keys and of values.
+// Build-time tunables (defaults are the measured best on MI355X).
+#ifndef SKV_DW_IN_FLIGHT
+#define SKV_DW_IN_FLIGHT 8       // dwords of keys (and of values) one lane requests per tile
+#endif
+#ifndef SKV_PIPELINE
+#define SKV_PIPELINE 1           // tiles requested ahead of the one being computed on (0 = none)
+#endif
+
+// Rows per lane and tile: about SKV_DW_IN_FLIGHT dwords of keys and of values.
 template <int RK, int RV>
 struct Depth {
   static constexpr int kMaxDw = RowMap<RK>::DPL > RowMap<RV>::DPL ? RowMap<RK>::DPL : RowMap<RV>::DPL;
-  static constexpr int U = kMaxDw <= 2 ? 8 : (kMaxDw <= 4 ? 4 : 2);
+  static constexpr int kRaw = SKV_DW_IN_FLIGHT / kMaxDw;
+  static constexpr int U = kRaw < 1 ? 1 : (kRaw > 8 ? 8 : kRaw);
 };
 
-// One pass over 8*U rows of a wave.  row0 is this lane's first row; the lane's
-// rows are row0 + 8u.  With MASKED, rows >= t_end are ignored (their loads are
-// redirected to row t_end-1 so that nothing outside [0, n_ctx) is ever read).
-template <int RK, int RV, int GT, int U, bool MASKED>
-__device__ __forceinline__ void process_rows(const uint32_t* __restrict__ kbase,
-                                             const uint32_t* __restrict__ vbase, int row0, int t_end,
-                                             int j, const float (&qreg)[GT][RowMap<RK>::CPL],
-                                             float (&m)[GT], float (&l)[GT],
-                                             float (&acc)[GT][RowMap<RV>::CPL]) {
-  using KM = RowMap<RK>;
-  using VM = RowMap<RV>;
-  uint32_t kw[U][KM::DPL];
-  uint32_t vw[U][VM::DPL];
-  bool valid[U];
+// The raw cache words of one tile: U rows of keys and of values per lane.
+template <int RK, int RV, int U>
+struct TileRegs {
+  uint32_t kw[U][RowMap<RK>::DPL];
+  uint32_t vw[U][RowMap<RV>::DPL];
+};
+
+// Requests 8*U rows of a wave.  row0 is this lane's first row; the lane's rows
+// are row0 + 8u.  With MASKED, rows >= t_end are redirected to row t_end-1 so
+// that nothing outside [0, n_ctx) is ever read.
+template <int RK, int RV, int U, bool MASKED>
+__device__ __forceinline__ void issue_rows(const uint32_t* __restrict__ kbase,
+                                           const uint32_t* __restrict__ vbase, int row0, int t_end,
+                                           int j, TileRegs<RK, RV, U>& t) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int row = row0 + 8 * u;
-    valid[u] = true;
-    if constexpr (MASKED) {
-      valid[u] = row < t_end;
-      row = valid[u] ? row : t_end - 1;
-    }
-    load_row<RK>(kbase + (int64_t)row * KM::ROW_DW, j, kw[u]);
-    load_row<RV>(vbase + (int64_t)row * VM::ROW_DW, j, vw[u]);
+    if constexpr (MASKED) row = row < t_end ? row : t_end - 1;
+    load_row<RK>(kbase + (int64_t)row * RowMap<RK>::ROW_DW, j, t.kw[u]);
   }
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int row = row0 + 8 * u;
+    if constexpr (MASKED) row = row < t_end ? row : t_end - 1;
+    load_row<RV>(vbase + (int64_t)row * RowMap<RV>::ROW_DW, j, t.vw[u]);
+  }
+}
 
-  float s[U][GT];
+// How the query heads of a pass are shared inside an octet.  With two or more heads the two
+// quads of the octet split them: after the per-lane partial dot products every lane keeps the
+// partial sums of "its" half (HL heads) and hands the other half to its mirror lane (i <-> 7-i,
+// which sits in the other quad), so the cross-lane reduction, the running maximum, the
+// exponentials and the normaliser are computed for HL heads per lane instead of GT.  The mix
+// needs the weights of all GT heads; the other half comes from the mirror lane (i <-> 7-i),
+// which sits in the other quad.  Accumulator slot a < HL belongs to head qd*HL + a (this
+// lane's quad qd), slot HL + a to head (1-qd)*HL + a.
+template <int GT>
+struct HeadSplit {
+  static constexpr bool kSplit = GT >= 2;
+  static constexpr int HL = kSplit ? GT / 2 : GT;     // heads whose softmax this lane runs
+  __device__ static int head_of_slot(int slot, int qd) {
+    if (!kSplit) return slot;
+    return slot < HL ? qd * HL + slot : (1 - qd) * HL + (slot - HL);
+  }
+};
+
+// Scores, online softmax and value mix for the rows of one tile.
+//   qreg: projected queries in slot order (HeadSplit), this lane's channels
+//   m, l: running maximum (log2 units) and normaliser of this lane's HL heads
+//   acc:  un-normalised mixes, slot order
+template <int RK, int RV, int GT, int U, bool MASKED>
+__device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int row0, int t_end, int qd,
+                                             const float (&qreg)[GT][RowMap<RK>::CPL],
+                                             float (&m)[HeadSplit<GT>::HL], float (&l)[HeadSplit<GT>::HL],
+                                             float (&acc)[GT][RowMap<RV>::CPL]) {
+  using KM = RowMap<RK>;
+  using VM = RowMap<RV>;
+  using HS = HeadSplit<GT>;
+  constexpr int HL = HS::HL;
+#ifdef SKV_DIAG_READ_ONLY
+  {
+    uint32_t x = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+#pragma unroll
+      for (int i = 0; i < KM::DPL; ++i) x ^= t.kw[u][i];
+#pragma unroll
+      for (int i = 0; i < VM::DPL; ++i) x ^= t.vw[u][i];
+    }
+    acc[0][0] += __uint_as_float(x & 0x3fffffffu);
+    return;
+  }
+#endif
+  // per-lane partial dot products for all GT heads, then keep this quad's half and reduce
+  float s[U][HL];
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     float kf[KM::CPL];
-    unpack_row<RK>(kw[u], kf);
+    unpack_row<RK>(t.kw[u], kf);
+    float d[GT];                                 // slot order: see HeadSplit
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
-      float d = 0.f;
+      d[g] = 0.f;
 #pragma unroll
-      for (int i = 0; i < KM::CPL; ++i) d = fmaf(qreg[g][i], kf[i], d);
-      s[u][g] = d;
+      for (int i = 0; i < KM::CPL; ++i) d[g] = fmaf(qreg[g][i], kf[i], d[g]);
+    }
+#pragma unroll
+    for (int a = 0; a < HL; ++a) {
+      float x;
+      if constexpr (HS::kSplit) {
+        // slot HL+a of the mirror lane is the same head as slot a here: one add pairs the
+        // two quads, two more finish the sum inside the quad
+        x = d[a] + dpp_f32<0x141>(d[HL + a]);
+        x += dpp_f32<0xB1>(x);
+        x += dpp_f32<0x4E>(x);
+      } else {
+        x = octet_sum(d[a]);
+      }
+      if constexpr (MASKED) x = (row0 + 8 * u < t_end) ? x : kNegBig;
+      s[u][a] = x;
     }
   }
+
+  // online softmax of this lane's heads; the rescale of the accumulators is skipped unless
+  // some octet of the wave saw a new maximum (rare once the stream has warmed up)
+  float c[HL];
+  bool moved = false;
 #pragma unroll
-  for (int u = 0; u < U; ++u) {
+  for (int a = 0; a < HL; ++a) {
+    float mx = s[0][a];
 #pragma unroll
-    for (int g = 0; g < GT; ++g) {
-      float t = octet_sum(s[u][g]);
-      if constexpr (MASKED) t = valid[u] ? t : kNegBig;
-      s[u][g] = t;
+    for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][a]);
+    const float mn = fmaxf(m[a], mx);
+    moved = moved || (mn > m[a]);
+    c[a] = fast_exp2(m[a] - mn);             // exactly 1 when the maximum did not move
+    m[a] = mn;
+  }
+  if (__builtin_amdgcn_ballot_w64(moved) != 0) {
+#pragma unroll
+    for (int a = 0; a < HL; ++a) {
+      l[a] *= c[a];
+#pragma unroll
+      for (int i = 0; i < VM::CPL; ++i) acc[a][i] *= c[a];
+      if constexpr (HS::kSplit) {
+        const float cr = dpp_f32<0x141>(c[a]);   // the other quad's factor for its head
+#pragma unroll
+        for (int i = 0; i < VM::CPL; ++i) acc[HL + a][i] *= cr;
+      }
     }
   }
 
   float pw[U][GT];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    float mx = s[0][g];
-#pragma unroll
-    for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][g]);
-    if (mx > m[g]) {                       // rare once the stream has warmed up
-      const float c = fast_exp2(m[g] - mx);
-      l[g] *= c;
-#pragma unroll
-      for (int i = 0; i < VM::CPL; ++i) acc[g][i] *= c;
-      m[g] = mx;
-    }
+  for (int a = 0; a < HL; ++a) {
     float lsum = 0.f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float pv = fast_exp2(s[u][g] - m[g]);
-      if constexpr (MASKED) pv = valid[u] ? pv : 0.f;
-      pw[u][g] = pv;
+      float pv = fast_exp2(s[u][a] - m[a]);
+      if constexpr (MASKED) pv = (row0 + 8 * u < t_end) ? pv : 0.f;
+      pw[u][a] = pv;
+      if constexpr (HS::kSplit) pw[u][HL + a] = dpp_f32<0x141>(pv);
       lsum += pv;
     }
-    l[g] += lsum;
+    l[a] += lsum;
   }
 
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     float vf[VM::CPL];
-    unpack_row<RV>(vw[u], vf);
+    unpack_row<RV>(t.vw[u], vf);
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
 #pragma unroll
@@ -196,21 +287,21 @@ __device__ __forceinline__ void process_rows(const uint32_t* __restrict__ kbase,
   }
 }
 
+#ifdef SKV_WAVES_PER_EU
+#define SKV_OCCUPANCY_ATTR __attribute__((amdgpu_waves_per_eu(SKV_WAVES_PER_EU, SKV_WAVES_PER_EU)))
+#else
+#define SKV_OCCUPANCY_ATTR
+#endif
+
 template <int RK, int RV, int GT>
-__global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
+__global__ __launch_bounds__(kDecodeThreads) SKV_OCCUPANCY_ATTR void decode_partial_kernel(const DecodeParams p) {
   using KM = RowMap<RK>;
   using VM = RowMap<RV>;
   constexpr int U = Depth<RK, RV>::U;
   constexpr int ROWS_PER_WAVE = 8 * U;
   constexpr int ROWS_PER_WG = 4 * ROWS_PER_WAVE;
-  constexpr int D = SKV_HEAD_DIM;
-  constexpr int DSLICES = 8;                     // head_dim split 8 ways for the query projection
 
-  // LDS: query projection scratch, later reused for the cross-wave merge.
-  constexpr int kProjFloats = GT * D + DSLICES * GT * RK + GT * RK;
-  constexpr int kMergeFloats = 4 * GT * (RV + 2);
-  constexpr int kLdsFloats = kProjFloats > kMergeFloats ? kProjFloats : kMergeFloats;
-  __shared__ float lds[kLdsFloats];
+  __shared__ float red[4 * GT * (RV + 2)];       // cross-wave merge at the end of the range
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -227,113 +318,144 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   const int b = bkv / p.n_kv_heads;
   const int hq0 = kv * p.group + pass * GT;      // first query head of this pass
 
-  const int t0 = split * p.chunk;
-  const int t1 = min(t0 + p.chunk, p.n_ctx);
+  int t0, t1;
+  range_of_split(p.n_ctx, p.n_splits, split, &t0, &t1);
 
   float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
   float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;
   const int64_t head_step_acc = (int64_t)p.n_splits * RV;
   const int64_t head_step_ml = (int64_t)p.n_splits * 2;
 
-  if (t0 >= p.n_ctx) {
+  if (t0 >= t1) {
     // Empty range: the neutral element of the merge.
     for (int i = tid; i < GT * RV; i += kDecodeThreads) out_acc[(i / RV) * head_step_acc + (i % RV)] = 0.f;
     if (tid < GT) { out_ml[tid * head_step_ml] = kNegBig; out_ml[tid * head_step_ml + 1] = 0.f; }
     return;
   }
 
-  // ---- q~ = (q . P_K) * scale * log2(e) --------------------------------------------------
-  float* q_s = lds;                              // [GT][D]
-  float* part_s = lds + GT * D;                  // [DSLICES][GT][RK]
-  float* qt_s = part_s + DSLICES * GT * RK;      // [GT][RK]
-  const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
-  for (int i = tid; i < GT * D; i += kDecodeThreads) q_s[i] = bf16_to_f32(qptr[i]);
-  __syncthreads();
-  const uint16_t* pk = p.p_k + (int64_t)kv * p.p_k_head_stride;
-  for (int item = tid; item < RK * DSLICES; item += kDecodeThreads) {
-    const int c = item % RK;
-    const int ds = item / RK;
-    float a[GT];
-#pragma unroll
-    for (int g = 0; g < GT; ++g) a[g] = 0.f;
-#pragma unroll 4
-    for (int dd = 0; dd < D / DSLICES; ++dd) {
-      const int d = ds * (D / DSLICES) + dd;
-      const float w = bf16_to_f32(pk[d * RK + c]);
-#pragma unroll
-      for (int g = 0; g < GT; ++g) a[g] = fmaf(q_s[g * D + d], w, a[g]);
-    }
-#pragma unroll
-    for (int g = 0; g < GT; ++g) part_s[(ds * GT + g) * RK + c] = a[g];
-  }
-  __syncthreads();
-  for (int i = tid; i < GT * RK; i += kDecodeThreads) {
-    const int g = i / RK, c = i % RK;
-    float a = 0.f;
-#pragma unroll
-    for (int ds = 0; ds < DSLICES; ++ds) a += part_s[(ds * GT + g) * RK + c];
-    qt_s[i] = a * p.scale_log2e;
-  }
-  __syncthreads();
+  const uint32_t* kbase = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * KM::ROW_DW;
+  const uint32_t* vbase = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * VM::ROW_DW;
+  const int lane_row = wave * ROWS_PER_WAVE + oct;     // this lane's first row inside a tile
+  const int n_full = (t1 - t0) / ROWS_PER_WG;         // tiles with every row valid
+  using Tile = TileRegs<RK, RV, U>;
+  Tile ta;
+
+  // ---- this lane's slice of the projected queries (prepared by the projection kernel), in
+  //      slot order; requested first, the first tile of the range right behind it ---------------
   float qreg[GT][KM::CPL];
+#ifdef SKV_DIAG_NO_PROLOGUE
 #pragma unroll
   for (int g = 0; g < GT; ++g)
 #pragma unroll
-    for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = qt_s[g * RK + KM::chan(j, i)];
+    for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = 0.01f * (float)(g + i + j);
+#else
+  {
+    const float* qt = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const float* qh = qt + HeadSplit<GT>::head_of_slot(g, j >> 2) * RK;
+#pragma unroll
+      for (int i = 0; i < KM::CPL; i += 2) {
+        const float2 v = *reinterpret_cast<const float2*>(qh + KM::chan(j, i));
+        qreg[g][i] = v.x;
+        qreg[g][i + 1] = v.y;
+      }
+    }
+  }
+#endif
+  if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, t0 + lane_row, t1, j, ta);
 
   // ---- stream the range ---------------------------------------------------------------
-  const uint32_t* kbase = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * KM::ROW_DW;
-  const uint32_t* vbase = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * VM::ROW_DW;
-
-  float m[GT], l[GT], acc[GT][VM::CPL];
+  using HS = HeadSplit<GT>;
+  constexpr int HL = HS::HL;
+  const int qd = j >> 2;                         // which quad of the octet this lane is in
+  float m[HL], l[HL], acc[GT][VM::CPL];
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    m[g] = kNegBig;
-    l[g] = 0.f;
+  for (int a = 0; a < HL; ++a) {
+    m[a] = kNegBig;
+    l[a] = 0.f;
+  }
+#pragma unroll
+  for (int g = 0; g < GT; ++g)
 #pragma unroll
     for (int i = 0; i < VM::CPL; ++i) acc[g][i] = 0.f;
-  }
 
-  int base = t0;
-  for (; base + ROWS_PER_WG <= t1; base += ROWS_PER_WG)
-    process_rows<RK, RV, GT, U, false>(kbase, vbase, base + wave * ROWS_PER_WAVE + oct, t1, j, qreg, m, l, acc);
-  if (base < t1)
-    process_rows<RK, RV, GT, U, true>(kbase, vbase, base + wave * ROWS_PER_WAVE + oct, t1, j, qreg, m, l, acc);
+  // A ring of NBUF register tiles: while one is being consumed the next NBUF-1 are already on
+  // their way.  The steady-state loop issues unconditionally, so that the wait before each
+  // consume is exactly "everything older than the tiles requested since".
+  constexpr int NBUF = SKV_PIPELINE + 1;
+  static_assert(NBUF >= 2, "at least one tile is requested ahead");
+  if (n_full > 0) {
+    Tile ring[NBUF];
+    ring[0] = ta;                                   // tile 0 was requested before the projection
+#pragma unroll
+    for (int k = 1; k < NBUF - 1; ++k)
+      if (k < n_full) issue_rows<RK, RV, U, false>(kbase, vbase, t0 + k * ROWS_PER_WG + lane_row, t1, j, ring[k]);
+    int i = 0;
+    if constexpr (NBUF > 1) {
+      while (i + 2 * NBUF - 2 < n_full) {           // ring[k] holds tile i+k for k < NBUF-1
+#pragma unroll
+        for (int k = 0; k < NBUF; ++k) {
+          issue_rows<RK, RV, U, false>(kbase, vbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
+                                       ring[(k + NBUF - 1) % NBUF]);
+          consume_rows<RK, RV, GT, U, false>(ring[k], 0, t1, qd, qreg, m, l, acc);
+        }
+        i += NBUF;
+      }
+    }
+    // drain: fewer than 2*NBUF-1 tiles left; ring[k] holds tile i+k for k < NBUF-1 (where it exists)
+#pragma unroll
+    for (int k = 0; k < 2 * NBUF - 2 || k < 1; ++k) {
+      if (i + k < n_full) {
+        if (NBUF > 1 && i + k + NBUF - 1 < n_full)
+          issue_rows<RK, RV, U, false>(kbase, vbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
+                                       ring[(k + NBUF - 1) % NBUF]);
+        consume_rows<RK, RV, GT, U, false>(ring[k % NBUF], 0, t1, qd, qreg, m, l, acc);
+      }
+    }
+  }
+  if (t0 + n_full * ROWS_PER_WG < t1) {               // ragged tail of the range
+    const int row0 = t0 + n_full * ROWS_PER_WG + lane_row;
+    issue_rows<RK, RV, U, true>(kbase, vbase, row0, t1, j, ta);
+    consume_rows<RK, RV, GT, U, true>(ta, row0, t1, qd, qreg, m, l, acc);
+  }
 
   // ---- merge the 8 octet streams of the wave (lanes 8, 16, 32 apart) ---------------------
 #pragma unroll
-  for (int g = 0; g < GT; ++g) {
-    float mw = m[g];
+  for (int a = 0; a < HL; ++a) {
+    float mw = m[a];
     mw = fmaxf(mw, __shfl_xor(mw, 8));
     mw = fmaxf(mw, __shfl_xor(mw, 16));
     mw = fmaxf(mw, __shfl_xor(mw, 32));
-    const float f = fast_exp2(m[g] - mw);
-    float lg = l[g] * f;
+    const float f = fast_exp2(m[a] - mw);
+    float lg = l[a] * f;
     lg += __shfl_xor(lg, 8);
     lg += __shfl_xor(lg, 16);
     lg += __shfl_xor(lg, 32);
-    l[g] = lg;
-    m[g] = mw;
+    l[a] = lg;
+    m[a] = mw;
 #pragma unroll
-    for (int i = 0; i < VM::CPL; ++i) {
-      float a = acc[g][i] * f;
-      a += __shfl_xor(a, 8);
-      a += __shfl_xor(a, 16);
-      a += __shfl_xor(a, 32);
-      acc[g][i] = a;
+    for (int half = 0; half < (HS::kSplit ? 2 : 1); ++half) {
+      const float fh = half == 0 ? f : dpp_f32<0x141>(f);   // slot HL+a: the mirror lane's head
+#pragma unroll
+      for (int i = 0; i < VM::CPL; ++i) {
+        float x = acc[half * HL + a][i] * fh;
+        x += __shfl_xor(x, 8);
+        x += __shfl_xor(x, 16);
+        x += __shfl_xor(x, 32);
+        acc[half * HL + a][i] = x;
+      }
     }
   }
 
   // ---- merge the 4 waves through LDS, in wave order -----------------------------------
-  __syncthreads();                               // projection scratch no longer needed
-  float* red = lds;                              // [4][GT][RV + 2]
   if (oct == 0) {
 #pragma unroll
-    for (int g = 0; g < GT; ++g) {
-      float* r = red + (wave * GT + g) * (RV + 2);
+    for (int slot = 0; slot < GT; ++slot) {
+      float* r = red + (wave * GT + HS::head_of_slot(slot, qd)) * (RV + 2);
 #pragma unroll
-      for (int i = 0; i < VM::CPL; ++i) r[VM::chan(j, i)] = acc[g][i];
-      if (j == 0) { r[RV] = m[g]; r[RV + 1] = l[g]; }
+      for (int i = 0; i < VM::CPL; ++i) r[VM::chan(j, i)] = acc[slot][i];
+      if ((j & 3) == 0 && slot < HL) { r[RV] = m[slot]; r[RV + 1] = l[slot]; }
     }
   }
   __syncthreads();

@@ -14,9 +14,11 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; }
 
-// Workgroups the decode launch aims for: a few per compute unit on a 256-CU
-// part, so that short contexts still spread over the chip.
-constexpr int kTargetWorkgroups = 2048;
+// Workgroups the streaming launch aims for: two per compute unit of the 256-CU part.  Each
+// workgroup keeps enough loads in flight by itself (it requests a tile ahead), so more
+// workgroups only add per-workgroup start-up and merge cost; measured at batch 4 / 32K context,
+// 8 or 16 ranges per (sequence, KV head) are the fastest, 32 and 64 are slower.
+constexpr int kTargetWorkgroups = 512;
 
 skv_status check_layer(const skv_layer* L) {
   if (!L) return SKV_ERR_NULL;
@@ -38,12 +40,19 @@ skv_status check_layer(const skv_layer* L) {
   return SKV_OK;
 }
 
+size_t align256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+// Workspace layout (bytes): [projected queries][partial mixes][partial max/normaliser].  The
+// first block does not depend on the split count, so it can be filled before that is known.
+size_t qt_bytes(const skv_layer* L) {
+  return align256((size_t)L->batch * L->n_q_heads * (size_t)L->r_k * sizeof(float));
+}
 size_t workspace_need(const skv_layer* L, int32_t n_splits) {
-  return (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)(L->r_v + 2) * sizeof(float);
+  return qt_bytes(L) +
+         (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)(L->r_v + 2) * sizeof(float);
 }
 
-void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, int32_t chunk,
-                        void* workspace) {
+void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, void* workspace) {
   p->k_cache = static_cast<const uint32_t*>(L->k_cache);
   p->v_cache = static_cast<const uint32_t*>(L->v_cache);
   p->p_k = static_cast<const uint16_t*>(L->p_k);
@@ -61,11 +70,11 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, i
   p->r_v = L->r_v;
   p->n_ctx = 0;
   p->n_splits = n_splits;
-  p->chunk = chunk;
   p->scale_log2e = 0.f;
-  float* ws = static_cast<float*>(workspace);
-  p->part_acc = ws;
-  p->part_ml = ws + (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)L->r_v;
+  char* ws = static_cast<char*>(workspace);
+  p->qt = reinterpret_cast<float*>(ws);
+  p->part_acc = reinterpret_cast<float*>(ws + qt_bytes(L));
+  p->part_ml = p->part_acc + (size_t)L->batch * L->n_q_heads * (size_t)n_splits * (size_t)L->r_v;
 }
 
 decode_partial_launcher partial_launcher_for(int r_k) {
@@ -94,26 +103,20 @@ skv_status check_decode_common(const skv_layer* L, int32_t n_splits, const void*
 }  // namespace
 
 bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx, int32_t want,
-                 int32_t* n_splits, int32_t* chunk) {
-  if (n_ctx < 1) return false;
-  const int64_t tiles = (n_ctx + kChunkQuantum - 1) / kChunkQuantum;
-  int64_t s;
+                 int32_t* n_splits) {
+  if (n_ctx < 1 || n_ctx > std::numeric_limits<int32_t>::max() - kRangeQuantum) return false;
   if (want > 0) {
     if (want > SKV_MAX_SPLITS) return false;
-    s = want;
-  } else {
-    const int64_t columns = (int64_t)batch * n_kv_heads * (group / heads_per_pass(group));
-    s = kTargetWorkgroups / (columns > 0 ? columns : 1);
-    if (s < 1) s = 1;
-    if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
-    if (s > tiles) s = tiles;
+    *n_splits = want;
+    return true;
   }
-  const int64_t tiles_per_split = (tiles + s - 1) / s;
-  const int64_t c = tiles_per_split * kChunkQuantum;
-  if (c > std::numeric_limits<int32_t>::max()) return false;
-  if (want <= 0) s = (n_ctx + c - 1) / c;   // drop ranges that would be empty
+  const int64_t quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
+  const int64_t columns = (int64_t)batch * n_kv_heads * (group / heads_per_pass(group));
+  int64_t s = (kTargetWorkgroups + columns - 1) / (columns > 0 ? columns : 1);
+  if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
+  if (s > quanta) s = quanta;                 // never a range without rows
+  if (s < 1) s = 1;
   *n_splits = (int32_t)s;
-  *chunk = (int32_t)c;
   return true;
 }
 
@@ -151,77 +154,50 @@ size_t skv_decode_workspace_bytes(const skv_layer* L) {
 int32_t skv_decode_default_splits(const skv_layer* L, int64_t n_ctx) {
   if (check_layer(L) != SKV_OK) return 0;
   if (n_ctx < 1 || n_ctx > L->capacity) return 0;
-  int32_t s = 0, c = 0;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, &c)) return 0;
+  int32_t s = 0;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s)) return 0;
   return s;
 }
 
-skv_status skv_decode_partial(const skv_layer* L, const void* q, int64_t n_ctx, float scale,
-                              int32_t n_splits, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+}  // extern "C"
+
+namespace {
+
+// ---- checks (no side effects) ---------------------------------------------------------------
+
+skv_status check_query_stage(const skv_layer* L, const void* q, float scale, const void* workspace,
+                             size_t workspace_bytes) {
   skv_status st = check_layer(L);
   if (st != SKV_OK) return st;
-  if (!q) return SKV_ERR_NULL;
-  if (!aligned16(q)) return SKV_ERR_ALIGN;
-  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
-  if (n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
+  if (!q || !workspace) return SKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(workspace)) return SKV_ERR_ALIGN;
   if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
-  int32_t s = 0, chunk = 0;
-  const int group = L->n_q_heads / L->n_kv_heads;
-  if (!plan_splits(L->batch, L->n_kv_heads, group, n_ctx, n_splits, &s, &chunk)) return SKV_ERR_SHAPE;
-  st = check_decode_common(L, s, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-
-  DecodeParams p;
-  fill_decode_params(L, &p, s, chunk, workspace);
-  p.q = static_cast<const uint16_t*>(q);
-  p.n_ctx = (int32_t)n_ctx;
-  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
-  p.scale_log2e = (float)(sc * 1.4426950408889634);
-  decode_partial_launcher launch = partial_launcher_for(L->r_k);
-  if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, heads_per_pass(group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
-    return SKV_ERR_HIP;
+  if (workspace_bytes < workspace_need(L, 1)) return SKV_ERR_WORKSPACE;
   return SKV_OK;
 }
 
-skv_status skv_decode_combine(const skv_layer* L, void* out, int32_t n_splits, void* workspace,
-                              size_t workspace_bytes, void* stream) {
+skv_status check_partial_stage(const skv_layer* L, int64_t n_ctx, int32_t n_splits,
+                               const void* workspace, size_t workspace_bytes, int32_t* s_out) {
+  skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
+  if (n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, n_splits, s_out))
+    return SKV_ERR_SHAPE;
+  return check_decode_common(L, *s_out, workspace, workspace_bytes);
+}
+
+skv_status check_combine_stage(const skv_layer* L, const void* out, int32_t n_splits,
+                               const void* workspace, size_t workspace_bytes) {
   skv_status st = check_layer(L);
   if (st != SKV_OK) return st;
   if (!out) return SKV_ERR_NULL;
   if (!aligned16(out)) return SKV_ERR_ALIGN;
-  st = check_decode_common(L, n_splits, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  DecodeParams p;
-  fill_decode_params(L, &p, n_splits, 0, workspace);
-  p.out = static_cast<float*>(out);
-  if (launch_decode_combine(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  return SKV_OK;
+  return check_decode_common(L, n_splits, workspace, workspace_bytes);
 }
 
-skv_status skv_decode_attention(const skv_layer* L, const void* q, void* out, int64_t n_ctx,
-                                float scale, void* workspace, size_t workspace_bytes,
-                                void* stream) {
-  // Check everything both stages need before the first launch, so that an
-  // error never leaves half the work enqueued.
-  skv_status st = check_layer(L);
-  if (st != SKV_OK) return st;
-  if (!q || !out || !workspace) return SKV_ERR_NULL;
-  if (!aligned16(q) || !aligned16(out)) return SKV_ERR_ALIGN;
-  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
-  const int32_t s = skv_decode_default_splits(L, n_ctx);
-  if (s < 1) return SKV_ERR_SHAPE;
-  st = check_decode_common(L, s, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  st = skv_decode_partial(L, q, n_ctx, scale, s, workspace, workspace_bytes, stream);
-  if (st != SKV_OK) return st;
-  return skv_decode_combine(L, out, s, workspace, workspace_bytes, stream);
-}
-
-skv_status skv_project_append(const skv_layer* L, const void* k_new, const void* v_new,
-                              int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
-                              int64_t cur_len, void* stream) {
+skv_status check_append(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
+                        int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len) {
   skv_status st = check_layer(L);
   if (st != SKV_OK) return st;
   if (T < 0) return SKV_ERR_SHAPE;
@@ -229,31 +205,155 @@ skv_status skv_project_append(const skv_layer* L, const void* k_new, const void*
   if (T == 0) return SKV_OK;
   if (!k_new || !v_new) return SKV_ERR_NULL;
   if (stride_b < 0 || stride_t < 0 || stride_h < 0) return SKV_ERR_SHAPE;
-  if ((int64_t)L->batch * T > std::numeric_limits<int32_t>::max()) return SKV_ERR_SHAPE;
+  if ((int64_t)L->batch * T > std::numeric_limits<int32_t>::max() / 64) return SKV_ERR_SHAPE;
   if ((stride_b % 8) || (stride_t % 8) || (stride_h % 8)) return SKV_ERR_ALIGN;
   if (!aligned16(k_new) || !aligned16(v_new)) return SKV_ERR_ALIGN;
+  return SKV_OK;
+}
 
+// ---- parameter blocks ---------------------------------------------------------------------
+
+void fill_query_params(const skv_layer* L, DecodeParams* p, const void* q, float scale, void* workspace) {
+  fill_decode_params(L, p, 1, workspace);
+  p->q = static_cast<const uint16_t*>(q);
+  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
+  p->scale_log2e = (float)(sc * 1.4426950408889634);
+}
+
+void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, const void* v_new,
+                        int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                        int64_t cur_len) {
+  p->k_cache = static_cast<uint16_t*>(L->k_cache);
+  p->v_cache = static_cast<uint16_t*>(L->v_cache);
+  p->p_k = static_cast<const uint16_t*>(L->p_k);
+  p->p_v = static_cast<const uint16_t*>(L->p_v);
+  p->k_new = static_cast<const uint16_t*>(k_new);
+  p->v_new = static_cast<const uint16_t*>(v_new);
+  p->capacity = L->capacity;
+  p->p_k_head_stride = L->p_k_head_stride;
+  p->p_v_head_stride = L->p_v_head_stride;
+  p->stride_b = stride_b;
+  p->stride_t = stride_t;
+  p->stride_h = stride_h;
+  p->cur_len = cur_len;
+  p->batch = L->batch;
+  p->n_kv_heads = L->n_kv_heads;
+  p->r_k = L->r_k;
+  p->r_v = L->r_v;
+  p->T = T;
+}
+
+// ---- launches -----------------------------------------------------------------------------
+
+skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* workspace, void* stream) {
+  DecodeParams p;
+  fill_decode_params(L, &p, s, workspace);
+  p.n_ctx = (int32_t)n_ctx;
+  decode_partial_launcher launch = partial_launcher_for(L->r_k);
+  if (!launch) return SKV_ERR_RANK;
+  if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status run_combine(const skv_layer* L, void* out, int32_t s, void* workspace, void* stream) {
+  DecodeParams p;
+  fill_decode_params(L, &p, s, workspace);
+  p.out = static_cast<float*>(out);
+  if (launch_decode_combine(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+skv_status skv_decode_project_query(const skv_layer* L, const void* q, float scale, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+  const skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams p;
+  fill_query_params(L, &p, q, scale, workspace);
+  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_decode_partial(const skv_layer* L, int64_t n_ctx, int32_t n_splits, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int32_t s = 0;
+  const skv_status st = check_partial_stage(L, n_ctx, n_splits, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  return run_partial(L, n_ctx, s, workspace, stream);
+}
+
+skv_status skv_decode_combine(const skv_layer* L, void* out, int32_t n_splits, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  const skv_status st = check_combine_stage(L, out, n_splits, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, n_splits, workspace, stream);
+}
+
+skv_status skv_decode_attention(const skv_layer* L, const void* q, void* out, int64_t n_ctx,
+                                float scale, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  // Check everything the three stages need before the first launch, so that an error
+  // never leaves part of the work enqueued.
+  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams p;
+  fill_query_params(L, &p, q, scale, workspace);
+  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  st = run_partial(L, n_ctx, s, workspace, stream);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status skv_project_append(const skv_layer* L, const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                              int64_t cur_len, void* stream) {
+  const skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK || T == 0) return st;
   AppendParams p;
-  p.k_cache = static_cast<uint16_t*>(L->k_cache);
-  p.v_cache = static_cast<uint16_t*>(L->v_cache);
-  p.p_k = static_cast<const uint16_t*>(L->p_k);
-  p.p_v = static_cast<const uint16_t*>(L->p_v);
-  p.k_new = static_cast<const uint16_t*>(k_new);
-  p.v_new = static_cast<const uint16_t*>(v_new);
-  p.capacity = L->capacity;
-  p.p_k_head_stride = L->p_k_head_stride;
-  p.p_v_head_stride = L->p_v_head_stride;
-  p.stride_b = stride_b;
-  p.stride_t = stride_t;
-  p.stride_h = stride_h;
-  p.cur_len = cur_len;
-  p.batch = L->batch;
-  p.n_kv_heads = L->n_kv_heads;
-  p.r_k = L->r_k;
-  p.r_v = L->r_v;
-  p.T = T;
+  fill_append_params(L, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
   return SKV_OK;
+}
+
+skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_new,
+                           int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                           int64_t cur_len, const void* q, void* out, float scale, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK) return st;
+  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int64_t n_ctx = cur_len + T;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  DecodeParams qp;
+  fill_query_params(L, &qp, q, scale, workspace);
+  AppendParams ap;
+  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (T > 0 && (int64_t)L->batch * T <= kVectorAppendMaxRows) {
+    // the usual decode step: new keys, new values and queries projected by one small launch
+    if (launch_project(&ap, &qp, hs) != hipSuccess) return SKV_ERR_HIP;
+  } else {
+    if (T > 0 && launch_append(ap, hs) != hipSuccess) return SKV_ERR_HIP;
+    if (launch_project(nullptr, &qp, hs) != hipSuccess) return SKV_ERR_HIP;
+  }
+  st = run_partial(L, n_ctx, s, workspace, stream);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
 }
 
 skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho, const int32_t* cand_k,

@@ -17,6 +17,7 @@ struct DecodeParams {
   const uint16_t* q;
   float* part_acc;           // [batch][n_q_heads][n_splits][r_v]
   float* part_ml;            // [batch][n_q_heads][n_splits][2]  (max in log2 units, normaliser)
+  float* qt;                 // [batch][n_q_heads][r_k]: projected query times scale*log2(e)
   float* out;                // [batch][n_q_heads][128]
   int64_t capacity;
   int64_t p_k_head_stride;
@@ -25,7 +26,6 @@ struct DecodeParams {
   int32_t r_k, r_v;
   int32_t n_ctx;
   int32_t n_splits;
-  int32_t chunk;             // tokens per split (multiple of kChunkQuantum)
   float scale_log2e;         // softmax scale times log2(e)
 };
 
@@ -47,13 +47,27 @@ struct AppendParams {
   int32_t T;
 };
 
-constexpr int kChunkQuantum = 256;   // every split but the last covers a multiple of this many tokens
+// The context is cut into quanta of this many rows; a range is a run of whole quanta (the last
+// one may be ragged), and the ranges of a call differ by at most one quantum.
+constexpr int kRangeQuantum = 64;
 constexpr int kDecodeThreads = 256;
 
-// Chooses (n_splits, chunk) for a context of n_ctx tokens.  want <= 0: heuristic.
-// Returns false if `want` cannot be honoured.
+// Number of context ranges for n_ctx tokens.  want <= 0: heuristic.  Returns false if `want`
+// is out of range.
 bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx,
-                 int32_t want, int32_t* n_splits, int32_t* chunk);
+                 int32_t want, int32_t* n_splits);
+
+// Rows [t0, t1) of range `split` out of n_splits over n_ctx rows: whole quanta, dealt as evenly
+// as possible (the first `rem` ranges get one more); empty when t0 >= t1.
+__host__ __device__ inline void range_of_split(int n_ctx, int n_splits, int split, int* t0, int* t1) {
+  const int quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
+  const int q = quanta / n_splits, rem = quanta % n_splits;
+  const int first = split * q + (split < rem ? split : rem);
+  const int count = q + (split < rem ? 1 : 0);
+  *t0 = first * kRangeQuantum;
+  const int end = (first + count) * kRangeQuantum;
+  *t1 = end < n_ctx ? end : n_ctx;
+}
 
 // Heads of one KV group handled per workgroup pass (1, 2 or 4).
 inline int heads_per_pass(int group) { return group >= 4 ? 4 : group; }
@@ -72,5 +86,10 @@ hipError_t launch_decode_partial_rk128(int, int, const DecodeParams&, hipStream_
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);
+// Few-token appends (ap) and query projections (dp) in one launch; either may be null.
+hipError_t launch_project(const AppendParams* ap, const DecodeParams* dp, hipStream_t stream);
+
+// Token rows (batch * T) up to which an append runs as vector projections.
+constexpr int kVectorAppendMaxRows = 64;
 
 }  // namespace skv

@@ -67,7 +67,9 @@ def test_bad_layers_are_rejected_by_every_entry_point(kw, code):
     L = _layer(**kw)
     assert lib.skv_project_append(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == code
     assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, 1 << 30, None) == code
-    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 0, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, FAKE, FAKE, 0.0, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_project_query(C.byref(L), FAKE, 0.0, FAKE, 1 << 30, None) == code
+    assert lib.skv_decode_partial(C.byref(L), 16, 0, FAKE, 1 << 30, None) == code
     assert lib.skv_decode_combine(C.byref(L), FAKE, 1, FAKE, 1 << 30, None) == code
     assert lib.skv_decode_workspace_bytes(C.byref(L)) == 0
     assert lib.skv_decode_default_splits(C.byref(L), 16) == 0
@@ -77,7 +79,7 @@ def test_bad_call_arguments_are_rejected():
     lib = B.lib()
     L = _layer()
     ws = lib.skv_decode_workspace_bytes(C.byref(L))
-    assert ws == 4 * 32 * 256 * 66 * 4
+    assert ws == 4 * 32 * 64 * 4 + 4 * 32 * 256 * 66 * 4          # projected queries + partial results
     assert lib.skv_cache_bytes(C.byref(L), 1000) == 4 * 8 * 1000 * 128 * 2
     # append
     assert lib.skv_project_append(None, FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_NULL
@@ -98,9 +100,25 @@ def test_bad_call_arguments_are_rejected():
     assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 1025, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
     assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, 8, None) == B.SKV_ERR_WORKSPACE
     assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE + 4, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_ALIGN
-    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 257, FAKE, ws, None) == B.SKV_ERR_SHAPE
-    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, float("nan"), 1, FAKE, ws, None) == B.SKV_ERR_SHAPE
-    assert lib.skv_decode_partial(C.byref(L), FAKE, 16, 0.0, 4, FAKE, 4 * 32 * 4 * 66 * 4 - 1, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, float("inf"), FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_project_query(C.byref(L), None, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert lib.skv_decode_project_query(C.byref(L), FAKE, float("nan"), FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_project_query(C.byref(L), FAKE, 0.0, FAKE, 64, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_project_query(C.byref(L), FAKE + 4, 0.0, FAKE, ws, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_decode_partial(C.byref(L), 16, 257, FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_partial(C.byref(L), 0, 1, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    need4 = 4 * 32 * 64 * 4 + 4 * 32 * 4 * 66 * 4
+    assert lib.skv_decode_partial(C.byref(L), 16, 4, FAKE, need4 - 1, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_partial(C.byref(L), 16, 4, None, need4, None) == B.SKV_ERR_NULL
+    # the fused step checks the append and the decode arguments before anything runs
+    step = lib.skv_decode_step
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 1024, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert step(C.byref(L), None, FAKE, 8192, 1024, 128, 1, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, None, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, FAKE, None, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, 0, FAKE, FAKE, 0.0, FAKE, 100, None) == B.SKV_ERR_WORKSPACE
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1020, 128, 1, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_ALIGN
+    assert step(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 0, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY  # nothing to attend
     assert lib.skv_decode_combine(C.byref(L), FAKE, 0, FAKE, ws, None) == B.SKV_ERR_SHAPE
     assert lib.skv_decode_combine(C.byref(L), FAKE, 257, FAKE, ws, None) == B.SKV_ERR_SHAPE
 
@@ -108,14 +126,19 @@ def test_bad_call_arguments_are_rejected():
 def test_default_split_plan():
     lib = B.lib()
     L = _layer(capacity=1 << 20)
-    # 32 (b, kv) columns -> 64 ranges at long context; never more ranges than 256-token tiles
-    assert lib.skv_decode_default_splits(C.byref(L), 32768) == 64
+    # 32 (sequence, KV head) columns -> 16 ranges at long context (two workgroups per CU);
+    # never more ranges than 64-row quanta
+    assert lib.skv_decode_default_splits(C.byref(L), 32768) == 16
+    assert lib.skv_decode_default_splits(C.byref(L), 1 << 20) == 16
     assert lib.skv_decode_default_splits(C.byref(L), 1) == 1
-    assert lib.skv_decode_default_splits(C.byref(L), 257) == 2
-    assert lib.skv_decode_default_splits(C.byref(L), 1 << 20) == 64
-    for n in (1, 255, 256, 257, 1000, 5000, 32767, 32768, 32769, 131072):
-        s = lib.skv_decode_default_splits(C.byref(L), n)
-        assert 1 <= s <= 256
+    assert lib.skv_decode_default_splits(C.byref(L), 64) == 1
+    assert lib.skv_decode_default_splits(C.byref(L), 65) == 2
+    assert lib.skv_decode_default_splits(C.byref(L), 1000) == 16
+    mha = _layer(n_q_heads=32, n_kv_heads=32, batch=8, capacity=1 << 20)
+    assert lib.skv_decode_default_splits(C.byref(mha), 131072) == 2
+    one = _layer(batch=1, capacity=1 << 20)
+    assert lib.skv_decode_default_splits(C.byref(one), 1024) == 16
+    assert lib.skv_decode_default_splits(C.byref(one), 1 << 20) == 64
 
 
 def test_layer_ranks_matches_oracle_on_random_surfaces():

@@ -59,7 +59,8 @@ def test_explicit_split_counts_including_empty_ranges(n_splits):
     P = _filled_pair(("splits",), 2, 8, 2, 48, 80, n)
     q = P.queries(4)
     out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
-    B.skv_decode_partial(P.gpu, q, n, 0.0, n_splits)
+    B.skv_decode_project_query(P.gpu, q, 0.0)
+    B.skv_decode_partial(P.gpu, n, n_splits)
     B.skv_decode_combine(P.gpu, out, n_splits)
     torch.cuda.synchronize()
     assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n)) <= TOL
@@ -94,10 +95,17 @@ def test_decode_is_deterministic_and_stage_calls_equal_the_fused_call():
     assert np.array_equal(a, b)
     s = B.skv_decode_default_splits(P.gpu, n)
     out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
-    B.skv_decode_partial(P.gpu, q, n, 0.0, s)
+    B.skv_decode_project_query(P.gpu, q, 0.0)
+    B.skv_decode_partial(P.gpu, n, s)
     B.skv_decode_combine(P.gpu, out, s)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), a)
+    # a different split of the context gives the same result up to float32 rounding
+    for s2 in (1, 7):
+        B.skv_decode_partial(P.gpu, n, s2)
+        B.skv_decode_combine(P.gpu, out, s2)
+        torch.cuda.synchronize()
+        assert vec_rel_err(out.cpu().numpy(), a) < 1e-5
 
 
 def test_errors_leave_output_untouched():
@@ -113,3 +121,28 @@ def test_errors_leave_output_untouched():
     assert e.value.code == B.SKV_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert torch.all(out == 7.0)
+
+
+@pytest.mark.parametrize("batch,T,hq,hkv,r_k,r_v", [(4, 1, 8, 2, 64, 64), (2, 3, 4, 4, 48, 80), (1, 1, 16, 2, 32, 96),
+                                                    (3, 40, 8, 2, 64, 64)])
+def test_decode_step_equals_append_then_decode(batch, T, hq, hkv, r_k, r_v):
+    # the fused step (one projection launch for k, v and q) against the two separate calls, bit for bit,
+    # and against the oracle
+    n0 = 700
+    Pa = Pair(("step", batch, T, r_k), batch, hq, hkv, r_k, r_v, n0 + T)
+    Pb = Pair(("step", batch, T, r_k), batch, hq, hkv, r_k, r_v, n0 + T, oracle=False)
+    k0, v0 = Pa.raw_kv(1, n0)
+    for P in (Pa, Pb):
+        B.skv_project_append(P.gpu, k0, v0, 0)
+    Pa.oracle_append(k0.cpu(), v0.cpu(), 0)
+    k1, v1 = Pa.raw_kv(2, T)
+    q = Pa.queries(3)
+    out_a = torch.empty((batch, hq, 128), dtype=torch.float32, device="cuda")
+    B.skv_decode_step(Pa.gpu, k1, v1, n0, q, out_a)
+    B.skv_project_append(Pb.gpu, k1, v1, n0)
+    out_b = Pb.gpu_decode(q, n0 + T)
+    torch.cuda.synchronize()
+    assert torch.equal(Pa.gpu.k_cache, Pb.gpu.k_cache) and torch.equal(Pa.gpu.v_cache, Pb.gpu.v_cache)
+    assert np.array_equal(out_a.cpu().numpy(), out_b)
+    Pa.oracle_append(k1.cpu(), v1.cpu(), n0)
+    assert vec_rel_err(out_b, Pa.oracle_decode(q, n0 + T)) <= TOL

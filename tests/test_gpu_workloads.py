@@ -67,11 +67,34 @@ class Stack:
         while self.cur < n:
             self.append(min(CHUNK, n - self.cur), ("fill", self.cur))
 
-    def decode(self, tag):
+    def _queries(self, tag):
         wl = self.wl
         q = synth.queries(synth.stable_seed(wl.name, "q", tag), wl.batch, wl.n_q_heads * wl.n_layers, 128, "cuda")
         q = q.view(wl.batch, wl.n_layers, wl.n_q_heads, 128).transpose(0, 1).contiguous()
         out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, 128), dtype=torch.float32, device="cuda")
+        return q, out
+
+    def step(self, tag):
+        """One decode step through the fused entry point: append one seeded token per sequence, attend."""
+        wl = self.wl
+        q, out = self._queries(tag)
+        for li, L in enumerate(self.layers):
+            k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", tag), wl.batch, 1, wl.n_kv_heads, 128,
+                                     self.scales[li][0], "cuda")
+            v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", tag), wl.batch, 1, wl.n_kv_heads, 128,
+                                     self.scales[li][1], "cuda")
+            B.skv_decode_step(L, k, v, self.cur, q[li], out[li], 0.0, self.ws)
+            if li in self.sample_layers:
+                for b, kv in self.sample_streams:
+                    self.raw[(li, b, kv)][0].append(synth.torch_bf16_to_bits(k[b, :, kv]))
+                    self.raw[(li, b, kv)][1].append(synth.torch_bf16_to_bits(v[b, :, kv]))
+        self.cur += 1
+        torch.cuda.synchronize()
+        return q, out
+
+    def decode(self, tag):
+        wl = self.wl
+        q, out = self._queries(tag)
         for li, L in enumerate(self.layers):
             B.skv_decode_attention(L, q[li], out[li], self.cur, 0.0, self.ws)
         torch.cuda.synchronize()
@@ -123,8 +146,7 @@ def test_b4_ctx32k_r64_consecutive_decode_steps():
     S = Stack(wl, [0], [(0, 0), (1, 3), (2, 5), (3, 7)])
     S.fill_to(wl.n_ctx - steps)
     for s in range(steps):                                   # each step appends one token, then attends
-        S.append(1, ("step", s))
-        q, out = S.decode(s)
+        q, out = S.step(("step", s))
         if s in (0, steps // 2, steps - 1):
             print(f"b4_ctx32k_r64 step {s} n_ctx {S.cur} worst rel err", S.check(q, out), flush=True)
     assert S.cur == 32768
@@ -142,8 +164,7 @@ def test_b4_ctx32k_L32_mixed_ranks_stack():
             pick.append(li)
     S = Stack(wl, pick, [(0, 1), (3, 6)])
     S.fill_to(wl.n_ctx - 1)
-    S.append(1, "last")
-    q, out = S.decode(0)
+    q, out = S.step("last")                                  # one decode step over all 32 layers
     assert torch.all(torch.isfinite(out))
     print("b4_ctx32k_L32_mixed layers", pick, [(rk[i], rv[i]) for i in pick], "worst rel err", S.check(q, out), flush=True)
 
@@ -163,7 +184,6 @@ def test_b8_ctx128k_mha_r64_96():
     S = Stack(wl, [0], [(0, 0), (3, 17), (7, 31)])
     S.fill_to(wl.n_ctx - 2)
     for s in range(2):
-        S.append(1, ("step", s))
-        q, out = S.decode(s)
+        q, out = S.step(("step", s))
     assert S.cur == 131072
     print("b8_ctx128k_mha_r64_96 worst rel err", S.check(q, out), flush=True)
