@@ -40,9 +40,10 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
-    ap.add_argument("--mode", choices=("bench", "kernel", "copy"), default="bench",
+    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
-                         "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters")
+                         "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
+                         "append: the chunk append of the workload (projection on the matrix cores) alone")
     return ap.parse_args()
 
 
@@ -96,6 +97,35 @@ def main():
         return
 
     wl = synth.WORKLOADS[args.workload]
+    if args.mode == "append":
+        # the chunk append alone: T = the workload's chunk, written at the end of a cache holding n_ctx - T rows
+        T = max(wl.append_chunk, 256)
+        rk, rv = (wl.r_k or 64), (wl.r_v or 64)
+        _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pk"), wl.n_kv_heads, wl.head_dim, rk)
+        _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pv"), wl.n_kv_heads, wl.head_dim, rv)
+        L = B.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, pk.to(dev), pv.to(dev), wl.n_ctx)
+        sc = synth.channel_scales(synth.stable_seed(wl.name, 0, "sk"), wl.n_kv_heads, wl.head_dim)
+        k = synth.kv_activations(1, wl.batch, T, wl.n_kv_heads, wl.head_dim, sc, dev)
+        v = synth.kv_activations(2, wl.batch, T, wl.n_kv_heads, wl.head_dim, sc, dev)
+        for _ in range(3):
+            B.skv_project_append(L, k, v, wl.n_ctx - T)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        iters = max(1, args.kernel_iters // 10)
+        e0.record()
+        for _ in range(iters):
+            B.skv_project_append(L, k, v, wl.n_ctx - T)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / iters
+        nbytes = wl.batch * T * wl.n_kv_heads * (2 * wl.head_dim + rk + rv) * 2
+        flops = 2 * wl.batch * T * wl.n_kv_heads * wl.head_dim * (rk + rv)
+        print(json.dumps({"mode": "append", "workload": wl.name, "batch": wl.batch, "T": T, "r_k": rk, "r_v": rv,
+                          "us_per_launch": round(us, 2), "bytes_per_launch": nbytes, "flops_per_launch": flops,
+                          "achieved_GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                          "achieved_TFLOPs": round(flops / us / 1e6, 1), "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / 2500.0, 4),
+                          "launches": iters + 3}))
+        return
     K, W = args.steps, args.warmup
     if args.mode == "kernel":
         K, W = 1, 0

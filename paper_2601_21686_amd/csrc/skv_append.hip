@@ -29,10 +29,40 @@ constexpr int D = SKV_HEAD_DIM;
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTilesPerWave = 4;                 // 16-token tiles per wave
-constexpr int kTokensPerWg = 4 * kTilesPerWave * 16;
+// Two float32 -> packed bf16 pair with the hardware conversion (round to nearest even).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+constexpr int kTilesPerWave = 4;                 // 16-token tiles per wave and pass
+constexpr int kTokensPerWave = kTilesPerWave * 16;
+constexpr int kTokensPerWg = 4 * kTokensPerWave;
 constexpr int kLdsPitch = D + 8;                 // bf16 elements; keeps 16-byte reads conflict-free
+constexpr int kMaxBlocksPerHead = 32;            // workgroups per (KV head, key-or-value): each stages the
+                                                 // basis once and then walks over many token tiles
+
+// The 16-byte pieces of 64 token rows that one wave feeds to the matrix cores.
+struct TokenFrags {
+  bf16x8 b[kTilesPerWave][4];
+};
+
+__device__ __forceinline__ void load_token_frags(const AppendParams& p, const uint16_t* x, int h, int m0,
+                                                 int M, int lrow, int lk, TokenFrags& f) {
+#pragma unroll
+  for (int nt = 0; nt < kTilesPerWave; ++nt) {
+    const int tok = m0 + nt * 16 + lrow;
+    const int tc = tok < M ? tok : M - 1;        // rows past the end re-read the last row; never stored
+    const int b = tc / p.T, t = tc % p.T;
+    const uint16_t* src = x + (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)h * p.stride_h;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+      f.b[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + ks * 32 + lk * 8));
+  }
+}
 
 __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t pt_s[SKV_HEAD_DIM * kLdsPitch];   // [channel][d]
@@ -47,6 +77,15 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
                                 : p.p_k + (int64_t)h * p.p_k_head_stride;
   const uint16_t* x = which ? p.v_new : p.k_new;
   uint16_t* cache = which ? p.v_cache : p.k_cache;
+  const int M = p.batch * p.T;                   // token rows of this head
+  const int lrow = lane & 15;
+  const int lk = lane >> 4;
+  const int stride = gridDim.x * kTokensPerWg;
+
+  // the first tile is requested before the basis is staged
+  int m0 = blockIdx.x * kTokensPerWg + wave * kTokensPerWave;
+  TokenFrags cur, nxt;
+  if (m0 < M) load_token_frags(p, x, h, m0, M, lrow, lk, cur);
 
   // basis [d][c] -> LDS [c][d]
   const int c8n = r >> 3;
@@ -62,49 +101,43 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
   }
   __syncthreads();
 
-  const int M = p.batch * p.T;                   // token rows of this head
-  const int m0 = blockIdx.x * kTokensPerWg + wave * (kTilesPerWave * 16);
-  if (m0 >= M) return;
+  for (; m0 < M; m0 += stride) {
+    const int m_next = m0 + stride;
+    if (m_next < M) load_token_frags(p, x, h, m_next, M, lrow, lk, nxt);   // on its way while this tile computes
 
-  const int lrow = lane & 15;
-  const int lk = lane >> 4;
-
-  bf16x8 bfrag[kTilesPerWave][4];
-  int64_t dst_row[kTilesPerWave];
-  bool valid[kTilesPerWave];
-#pragma unroll
-  for (int nt = 0; nt < kTilesPerWave; ++nt) {
-    const int tok = m0 + nt * 16 + lrow;
-    valid[nt] = tok < M;
-    const int tc = valid[nt] ? tok : M - 1;
-    const int b = tc / p.T, t = tc % p.T;
-    const uint16_t* src = x + (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)h * p.stride_h;
-    dst_row[nt] = ((int64_t)b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-      bfrag[nt][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + ks * 32 + lk * 8));
-  }
-
-  for (int mt = 0; mt < (r >> 4); ++mt) {
-    f32x4 acc[kTilesPerWave];
-#pragma unroll
-    for (int nt = 0; nt < kTilesPerWave; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const bf16x8 a = __builtin_bit_cast(
-          bf16x8, *reinterpret_cast<const uint4*>(&pt_s[(mt * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
-#pragma unroll
-      for (int nt = 0; nt < kTilesPerWave; ++nt)
-        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bfrag[nt][ks], acc[nt], 0, 0, 0);
-    }
+    int64_t dst_row[kTilesPerWave];
+    bool valid[kTilesPerWave];
 #pragma unroll
     for (int nt = 0; nt < kTilesPerWave; ++nt) {
-      if (!valid[nt]) continue;
-      uint2 o;
-      o.x = f32_to_bf16_bits(acc[nt][0]) | (f32_to_bf16_bits(acc[nt][1]) << 16);
-      o.y = f32_to_bf16_bits(acc[nt][2]) | (f32_to_bf16_bits(acc[nt][3]) << 16);
-      *reinterpret_cast<uint2*>(cache + dst_row[nt] * r + mt * 16 + lk * 4) = o;
+      const int tok = m0 + nt * 16 + lrow;
+      valid[nt] = tok < M;
+      const int tc = valid[nt] ? tok : M - 1;
+      const int b = tc / p.T, t = tc % p.T;
+      dst_row[nt] = ((int64_t)b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
     }
+
+    for (int mt = 0; mt < (r >> 4); ++mt) {
+      f32x4 acc[kTilesPerWave];
+#pragma unroll
+      for (int nt = 0; nt < kTilesPerWave; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 a = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const uint4*>(&pt_s[(mt * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
+#pragma unroll
+        for (int nt = 0; nt < kTilesPerWave; ++nt)
+          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cur.b[nt][ks], acc[nt], 0, 0, 0);
+      }
+#pragma unroll
+      for (int nt = 0; nt < kTilesPerWave; ++nt) {
+        if (!valid[nt]) continue;
+        uint2 o;
+        o.x = pack_bf16x2(acc[nt][0], acc[nt][1]);
+        o.y = pack_bf16x2(acc[nt][2], acc[nt][3]);
+        *reinterpret_cast<uint2*>(cache + dst_row[nt] * r + mt * 16 + lk * 4) = o;
+      }
+    }
+    cur = nxt;
   }
 }
 
@@ -113,7 +146,9 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
 hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
   const int64_t rows = (int64_t)p.batch * p.T;
   if (rows <= kVectorAppendMaxRows) return launch_project(&p, nullptr, stream);
-  const dim3 grid((unsigned)((rows + kTokensPerWg - 1) / kTokensPerWg), (unsigned)p.n_kv_heads, 2u);
+  int64_t blocks = (rows + kTokensPerWg - 1) / kTokensPerWg;
+  if (blocks > kMaxBlocksPerHead) blocks = kMaxBlocksPerHead;
+  const dim3 grid((unsigned)blocks, (unsigned)p.n_kv_heads, 2u);
   hipLaunchKernelGGL(append_mfma_kernel, grid, dim3(256), 0, stream, p);
   return hipGetLastError();
 }

@@ -118,7 +118,7 @@ __device__ __forceinline__ float octet_sum(float x) {
 #define SKV_DW_IN_FLIGHT 8       // dwords of keys (and of values) one lane requests per tile
 #endif
 #ifndef SKV_PIPELINE
-#define SKV_PIPELINE 1           // tiles requested ahead of the one being computed on (0 = none)
+#define SKV_PIPELINE 1           // tiles requested ahead of the one being computed on (>= 1)
 #endif
 
 // Rows per lane and tile: about SKV_DW_IN_FLIGHT dwords of keys and of values.
@@ -188,20 +188,6 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
   using VM = RowMap<RV>;
   using HS = HeadSplit<GT>;
   constexpr int HL = HS::HL;
-#ifdef SKV_DIAG_READ_ONLY
-  {
-    uint32_t x = 0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-#pragma unroll
-      for (int i = 0; i < KM::DPL; ++i) x ^= t.kw[u][i];
-#pragma unroll
-      for (int i = 0; i < VM::DPL; ++i) x ^= t.vw[u][i];
-    }
-    acc[0][0] += __uint_as_float(x & 0x3fffffffu);
-    return;
-  }
-#endif
   // per-lane partial dot products for all GT heads, then keep this quad's half and reduce
   float s[U][HL];
 #pragma unroll
@@ -287,14 +273,8 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
   }
 }
 
-#ifdef SKV_WAVES_PER_EU
-#define SKV_OCCUPANCY_ATTR __attribute__((amdgpu_waves_per_eu(SKV_WAVES_PER_EU, SKV_WAVES_PER_EU)))
-#else
-#define SKV_OCCUPANCY_ATTR
-#endif
-
 template <int RK, int RV, int GT>
-__global__ __launch_bounds__(kDecodeThreads) SKV_OCCUPANCY_ATTR void decode_partial_kernel(const DecodeParams p) {
+__global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
   using KM = RowMap<RK>;
   using VM = RowMap<RV>;
   constexpr int U = Depth<RK, RV>::U;
@@ -343,12 +323,6 @@ __global__ __launch_bounds__(kDecodeThreads) SKV_OCCUPANCY_ATTR void decode_part
   // ---- this lane's slice of the projected queries (prepared by the projection kernel), in
   //      slot order; requested first, the first tile of the range right behind it ---------------
   float qreg[GT][KM::CPL];
-#ifdef SKV_DIAG_NO_PROLOGUE
-#pragma unroll
-  for (int g = 0; g < GT; ++g)
-#pragma unroll
-    for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = 0.01f * (float)(g + i + j);
-#else
   {
     const float* qt = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;
 #pragma unroll
@@ -362,7 +336,6 @@ __global__ __launch_bounds__(kDecodeThreads) SKV_OCCUPANCY_ATTR void decode_part
       }
     }
   }
-#endif
   if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, t0 + lane_row, t1, j, ta);
 
   // ---- stream the range ---------------------------------------------------------------
