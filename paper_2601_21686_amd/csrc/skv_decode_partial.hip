@@ -34,6 +34,7 @@ namespace skv {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;   // "no score seen yet"; finite so that differences stay finite
+constexpr float kRescaleSlack = 8.0f; // log2 units a score may exceed the softmax reference before it moves
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -56,7 +57,7 @@ struct RowMap {
 };
 
 #ifndef SKV_NT
-#define SKV_NT 1                 // non-temporal (streaming) loads of the cache
+#define SKV_NT 0                 // 1: non-temporal loads of the cache (measured slightly slower)
 #endif
 #if SKV_NT
 #define SKV_LOAD(p) __builtin_nontemporal_load(p)
@@ -177,7 +178,8 @@ struct HeadSplit {
 
 // Scores, online softmax and value mix for the rows of one tile.
 //   qreg: projected queries in slot order (HeadSplit), this lane's channels
-//   m, l: running maximum (log2 units) and normaliser of this lane's HL heads
+//   m, l: softmax reference (log2 units; within kRescaleSlack below the running maximum) and
+//         normaliser of this lane's HL heads
 //   acc:  un-normalised mixes, slot order
 template <int RK, int RV, int GT, int U, bool MASKED>
 __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int row0, int t_end, int qd,
@@ -218,8 +220,11 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
     }
   }
 
-  // online softmax of this lane's heads; the rescale of the accumulators is skipped unless
-  // some octet of the wave saw a new maximum (rare once the stream has warmed up)
+  // online softmax of this lane's heads.  The reference m only follows the running maximum when
+  // a score exceeds it by more than kRescaleSlack (weights then stay below 2^kRescaleSlack, far
+  // inside float32 range, and every sum is rescaled consistently, so the result is unchanged);
+  // after the first tile of a stream this almost never happens, and the rescale of the
+  // accumulators is skipped unless some octet of the wave needs it.
   float c[HL];
   bool moved = false;
 #pragma unroll
@@ -227,9 +232,10 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
     float mx = s[0][a];
 #pragma unroll
     for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][a]);
-    const float mn = fmaxf(m[a], mx);
-    moved = moved || (mn > m[a]);
-    c[a] = fast_exp2(m[a] - mn);             // exactly 1 when the maximum did not move
+    const bool jump = mx > m[a] + kRescaleSlack;
+    const float mn = jump ? mx : m[a];
+    moved = moved || jump;
+    c[a] = fast_exp2(m[a] - mn);             // exactly 1 when the reference stays
     m[a] = mn;
   }
   if (__builtin_amdgcn_ballot_w64(moved) != 0) {
