@@ -30,7 +30,8 @@ typedef enum {
   SKV_OK = 0,
   SKV_ERR_NULL = 1,      /* a required pointer is NULL                                   */
   SKV_ERR_SHAPE = 2,     /* head_dim != 128, batch < 1, H_Q not a multiple of H_KV,
-                            G not in {1,2,4,8}, T < 0, bad strides, bad split count      */
+                            G not in {1,2,4,8}, too many (sequence, KV head) pairs,
+                            T < 0, bad strides, bad split count                          */
   SKV_ERR_RANK = 3,      /* a rank is not a multiple of 16 in [16, 128]                  */
   SKV_ERR_CAPACITY = 4,  /* cur_len + T > capacity, n_ctx < 1 or n_ctx > capacity        */
   SKV_ERR_ALIGN = 5,     /* a device pointer is not 16-byte aligned, or a stride is not
@@ -124,6 +125,13 @@ size_t skv_decode_workspace_bytes(const skv_layer* layer);
 /* The number of context ranges skv_decode_attention uses for this shape
  * (1..SKV_MAX_SPLITS); 0 if the arguments are invalid. */
 int32_t skv_decode_default_splits(const skv_layer* layer, int64_t n_ctx);
+
+/* Rows [*first_row, *end_row) of the cache that context range `range` of `n_splits` covers
+ * when n_ctx rows are attended (host only).  Ranges are runs of whole 64-row quanta, dealt as
+ * evenly as possible; together they tile [0, n_ctx); a range may be empty.
+ * Errors: NULL, CAPACITY (n_ctx < 1), SHAPE (n_splits or range out of bounds). */
+skv_status skv_decode_range(int64_t n_ctx, int32_t n_splits, int32_t range,
+                            int64_t* first_row, int64_t* end_row);
 
 /*
  * One whole decode step for T new tokens per sequence (T = 1 in a serving

@@ -23,7 +23,7 @@ SKV_MAX_SPLITS = 256
 
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
-    "skv_decode_default_splits", "skv_decode_step", "skv_decode_project_query",
+    "skv_decode_default_splits", "skv_decode_range", "skv_decode_step", "skv_decode_project_query",
     "skv_decode_partial", "skv_decode_combine",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
 )
@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
     L.skv_decode_workspace_bytes.restype = sz
     L.skv_decode_default_splits.argtypes = [LP, i64]
     L.skv_decode_default_splits.restype = i32
+    L.skv_decode_range.argtypes = [i64, i32, i32, C.POINTER(i64), C.POINTER(i64)]
+    L.skv_decode_range.restype = C.c_int
     L.skv_decode_step.argtypes = [LP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_decode_step.restype = C.c_int
     L.skv_decode_project_query.argtypes = [LP, vp, C.c_float, vp, sz, vp]
@@ -162,6 +164,13 @@ def skv_decode_workspace_bytes(layer) -> int:
 
 def skv_decode_default_splits(layer, n_ctx: int) -> int:
     return int(lib().skv_decode_default_splits(_ref(layer), int(n_ctx)))
+
+
+def skv_decode_range(n_ctx: int, n_splits: int, rng: int):
+    """(first_row, end_row) of context range `rng` out of `n_splits` over n_ctx rows."""
+    a, b = C.c_int64(0), C.c_int64(0)
+    _check(lib().skv_decode_range(int(n_ctx), int(n_splits), int(rng), C.byref(a), C.byref(b)), "skv_decode_range")
+    return int(a.value), int(b.value)
 
 
 def skv_decode_attention(layer, q: torch.Tensor, out: torch.Tensor, n_ctx: int, scale: float = 0.0,

@@ -28,7 +28,8 @@ skv_status check_layer(const skv_layer* L) {
   if (L->n_q_heads % L->n_kv_heads) return SKV_ERR_SHAPE;
   const int g = L->n_q_heads / L->n_kv_heads;
   if (!(g == 1 || g == 2 || g == 4 || g == 8)) return SKV_ERR_SHAPE;
-  if ((int64_t)L->batch * L->n_q_heads > (1 << 20)) return SKV_ERR_SHAPE;
+  // one grid row per (sequence, KV head, pass) in the streaming launch: the grid's y limit
+  if ((int64_t)L->batch * L->n_kv_heads * (g / heads_per_pass(g)) > 65535) return SKV_ERR_SHAPE;
   if (!rank_ok(L->r_k) || !rank_ok(L->r_v)) return SKV_ERR_RANK;
   if (L->capacity < 1 || L->capacity > std::numeric_limits<int32_t>::max()) return SKV_ERR_CAPACITY;
   const int64_t sk = L->p_k_head_stride, sv = L->p_v_head_stride;
@@ -149,6 +150,19 @@ size_t skv_cache_bytes(const skv_layer* L, int64_t n_tokens) {
 size_t skv_decode_workspace_bytes(const skv_layer* L) {
   if (check_layer(L) != SKV_OK) return 0;
   return workspace_need(L, SKV_MAX_SPLITS);
+}
+
+skv_status skv_decode_range(int64_t n_ctx, int32_t n_splits, int32_t range, int64_t* first_row,
+                            int64_t* end_row) {
+  if (!first_row || !end_row) return SKV_ERR_NULL;
+  if (n_ctx < 1 || n_ctx > std::numeric_limits<int32_t>::max() - kRangeQuantum) return SKV_ERR_CAPACITY;
+  if (n_splits < 1 || n_splits > SKV_MAX_SPLITS || range < 0 || range >= n_splits) return SKV_ERR_SHAPE;
+  int t0 = 0, t1 = 0;
+  range_of_split((int)n_ctx, n_splits, range, &t0, &t1);
+  if (t0 > t1) t0 = t1;
+  *first_row = t0;
+  *end_row = t1;
+  return SKV_OK;
 }
 
 int32_t skv_decode_default_splits(const skv_layer* L, int64_t n_ctx) {

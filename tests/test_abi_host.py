@@ -54,6 +54,7 @@ def _layer(**kw):
     (dict(batch=0), B.SKV_ERR_SHAPE),
     (dict(n_q_heads=30), B.SKV_ERR_SHAPE),
     (dict(n_q_heads=24), B.SKV_ERR_SHAPE),          # G = 3
+    (dict(batch=10000), B.SKV_ERR_SHAPE),           # more (sequence, KV head) columns than a grid holds
     (dict(r_k=0), B.SKV_ERR_RANK),
     (dict(r_k=72), B.SKV_ERR_RANK),
     (dict(r_v=144), B.SKV_ERR_RANK),
@@ -139,6 +140,33 @@ def test_default_split_plan():
     one = _layer(batch=1, capacity=1 << 20)
     assert lib.skv_decode_default_splits(C.byref(one), 1024) == 16
     assert lib.skv_decode_default_splits(C.byref(one), 1 << 20) == 64
+
+
+def test_context_ranges_tile_the_context_evenly():
+    rng = np.random.default_rng(3)
+    cases = [(1, 1), (1, 256), (63, 4), (64, 2), (65, 2), (1000, 16), (32768, 16), (32831, 16), (131072, 2),
+             (100, 256), (4097, 7)] + [(int(rng.integers(1, 200000)), int(rng.integers(1, 257))) for _ in range(200)]
+    for n, s in cases:
+        spans = [B.skv_decode_range(n, s, i) for i in range(s)]
+        pos = 0
+        sizes = []
+        for a, b in spans:
+            assert a <= b
+            if a < b:
+                assert a == pos                    # contiguous, in order, no overlap
+                pos = b
+                sizes.append(b - a)
+        assert pos == n                            # complete
+        full = [x for x in sizes[:-1]]             # all but the ragged last one are whole quanta
+        assert all(x % 64 == 0 for x in full)
+        if len(sizes) > 1:
+            assert max(sizes) - min(sizes[:-1] or sizes) <= 64
+    lib = B.lib()
+    a, b = C.c_int64(), C.c_int64()
+    assert lib.skv_decode_range(0, 1, 0, C.byref(a), C.byref(b)) == B.SKV_ERR_CAPACITY
+    assert lib.skv_decode_range(10, 0, 0, C.byref(a), C.byref(b)) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_range(10, 4, 4, C.byref(a), C.byref(b)) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_range(10, 4, 0, None, C.byref(b)) == B.SKV_ERR_NULL
 
 
 def test_layer_ranks_matches_oracle_on_random_surfaces():
