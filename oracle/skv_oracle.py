@@ -14,6 +14,7 @@ Everything below is the paper's definition written out with numpy float64:
                            reading one KV head                 (App. A.1)
   * cache-size ratio       CR = (r_K + r_V) / (2 d_h)          (Sec. 2.1, Eq. 3)
   * sequential budgeted rank selection                         (Sec. 3.5, Eqs. 15-17; App. B, Alg. 2)
+  * asymmetric integer quantisation of the compressed cache    (Sec. 4.3; 8 bits, group 64)
 
 Readings taken where the paper is silent (all listed in the design notes):
 the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
@@ -32,7 +33,9 @@ in-span inputs are reproduced exactly; n = 1 and uniform-score closed forms;
 the definition form equals the factored form; a pure-Python brute force on a
 tiny case; the library scaled-dot-product routine when P = I; the paper's
 printed 16 GB cache-size example; budget invariants and an exhaustive check
-of the greedy selector.  No function here is "parity unpinned".
+of the greedy selector; for the quantiser: on-grid inputs are recovered exactly,
+the round-trip error bound, flat groups, library rounding, and the invariance
+of the output to the key zero point.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -309,3 +312,190 @@ def layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, delta)
         units -= rk + rv
     achieved = sum(a + b for a, b in zip(rk_out, rv_out)) / (2.0 * head_dim * n_layers)
     return rk_out, rv_out, achieved, feasible
+
+
+# --------------------------------------------------------------------------
+# Sec. 4.3: asymmetric integer quantisation of the compressed cache
+# --------------------------------------------------------------------------
+#
+# The paper applies asymmetric integer quantisation with group size 64 to the
+# compressed tensors: keys with group-wise scales shared across batch and
+# sequence positions within each KV head, values with token-wise group scales,
+# and reports 8 bits as essentially lossless.  Reading taken here:
+#   * a group is 64 consecutive channels of a rank-r row (the last group of a
+#     row may be shorter);
+#   * keys: one (scale, zero) pair per KV head and channel group, float32,
+#     fixed before any token is cached (a calibration result the caller brings);
+#   * values: one (scale, zero) pair per token and channel group, computed when
+#     the token is appended from that group's minimum and maximum, and stored
+#     next to the codes as two bf16 numbers;
+#   * code = clamp(round_half_even((x - zero) / scale), 0, 2^bits - 1),
+#     x_hat = code * scale + zero.
+# A code is an integer decided by floating point, so the decision is taken in
+# the precision the GPU kernel uses: float32 (IEEE subtraction and division)
+# on the float32-rounded projection.  Attention then runs, in float64, on the
+# dequantised rows exactly as on a bf16 cache.
+
+GROUP = 64
+
+
+def group_slices(r: int):
+    """Channel ranges of the quantisation groups of a rank-r row."""
+    return [slice(s, min(s + GROUP, r)) for s in range(0, r, GROUP)]
+
+
+def calibrate_static_range(y: np.ndarray, bits: int = 8):
+    """(scale, zero) float32 per channel group from sample rows y [n, r]:
+    zero = min, scale = (max - min) / (2^bits - 1); a flat group gets scale 1."""
+    y32 = np.asarray(y, np.float64).astype(np.float32)
+    levels = np.float32(2 ** bits - 1)
+    sc, zr = [], []
+    for g in group_slices(y32.shape[1]):
+        lo, hi = y32[:, g].min(), y32[:, g].max()
+        s = np.float32(hi - lo) / levels
+        sc.append(s if s > 0 else np.float32(1.0))
+        zr.append(lo)
+    return np.array(sc, np.float32), np.array(zr, np.float32)
+
+
+def quantize_static(y: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: int = 8) -> np.ndarray:
+    """Codes (uint8) of rows y [n, r] under fixed per-group (scale, zero) float32."""
+    y32 = np.asarray(y, np.float64).astype(np.float32)
+    out = np.empty(y32.shape, np.uint8)
+    top = np.float32(2 ** bits - 1)
+    for gi, g in enumerate(group_slices(y32.shape[1])):
+        t = (y32[:, g] - np.float32(zero[gi])) / np.float32(scale[gi])        # float32 throughout
+        out[:, g] = np.clip(np.rint(t), np.float32(0), top).astype(np.uint8)
+    return out
+
+
+def quantize_dynamic(y: np.ndarray, bits: int = 8):
+    """Per-row, per-group quantisation.  Returns (codes uint8 [n, r],
+    scale bits uint16 [n, n_groups], zero bits uint16 [n, n_groups]); scale and
+    zero are bf16: zero = bf16(min), scale = bf16((max - min) / (2^bits - 1)),
+    replaced by 1 when that is 0."""
+    y32 = np.asarray(y, np.float64).astype(np.float32)
+    n, r = y32.shape
+    groups = group_slices(r)
+    codes = np.empty((n, r), np.uint8)
+    sb = np.empty((n, len(groups)), np.uint16)
+    zb = np.empty((n, len(groups)), np.uint16)
+    levels = np.float32(2 ** bits - 1)
+    for gi, g in enumerate(groups):
+        lo = y32[:, g].min(axis=1)
+        hi = y32[:, g].max(axis=1)
+        s_bits = f64_to_bf16_bits(((hi - lo) / levels).astype(np.float64))     # float32 quotient, then bf16
+        s = bf16_bits_to_f64(s_bits).astype(np.float32)
+        flat = s == 0
+        s_bits = np.where(flat, np.uint16(0x3F80), s_bits)
+        s = np.where(flat, np.float32(1.0), s)
+        z_bits = f64_to_bf16_bits(lo.astype(np.float64))
+        z = bf16_bits_to_f64(z_bits).astype(np.float32)
+        t = (y32[:, g] - z[:, None]) / s[:, None]
+        codes[:, g] = np.clip(np.rint(t), np.float32(0), levels).astype(np.uint8)
+        sb[:, gi], zb[:, gi] = s_bits, z_bits
+    return codes, sb, zb
+
+
+def dequantize(codes: np.ndarray, scale: np.ndarray, zero: np.ndarray) -> np.ndarray:
+    """x_hat = code * scale + zero in float64.  scale, zero: per group, either
+    [n_groups] (static) or [n, n_groups] (per row), any float dtype."""
+    codes = np.asarray(codes)
+    out = np.empty(codes.shape, np.float64)
+    scale = np.asarray(scale, np.float64)
+    zero = np.asarray(zero, np.float64)
+    for gi, g in enumerate(group_slices(codes.shape[1])):
+        s = scale[..., gi]
+        z = zero[..., gi]
+        if s.ndim:
+            s, z = s[:, None], z[:, None]
+        out[:, g] = codes[:, g].astype(np.float64) * s + z
+    return out
+
+
+@dataclass
+class OracleQuantLayer:
+    """One layer's quantised compressed cache.
+    k_codes [batch, n_kv_heads, capacity, r_k] uint8 with static k_scale / k_zero
+    float32 [n_kv_heads, n_groups_k]; v_codes likewise with per-row bf16
+    v_scale_bits / v_zero_bits uint16 [batch, n_kv_heads, capacity, n_groups_v]."""
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    r_k: int
+    r_v: int
+    capacity: int
+    bits: int
+    p_k: np.ndarray
+    p_v: np.ndarray
+    k_scale: np.ndarray
+    k_zero: np.ndarray
+    k_codes: np.ndarray
+    v_codes: np.ndarray
+    v_scale_bits: np.ndarray
+    v_zero_bits: np.ndarray
+
+    def basis_k(self, h: int) -> np.ndarray:
+        return self.p_k[h if self.p_k.shape[0] > 1 else 0]
+
+    def basis_v(self, h: int) -> np.ndarray:
+        return self.p_v[h if self.p_v.shape[0] > 1 else 0]
+
+
+def new_quant_layer(batch, n_q_heads, n_kv_heads, head_dim, p_k, p_v, k_scale, k_zero, capacity,
+                    bits=8) -> OracleQuantLayer:
+    p_k, p_v = np.asarray(p_k, np.float64), np.asarray(p_v, np.float64)
+    r_k, r_v = p_k.shape[2], p_v.shape[2]
+    ngk, ngv = len(group_slices(r_k)), len(group_slices(r_v))
+    k_scale = np.asarray(k_scale, np.float32).reshape(n_kv_heads, ngk)
+    k_zero = np.asarray(k_zero, np.float32).reshape(n_kv_heads, ngk)
+    return OracleQuantLayer(
+        batch, n_q_heads, n_kv_heads, head_dim, r_k, r_v, capacity, bits, p_k, p_v, k_scale, k_zero,
+        np.zeros((batch, n_kv_heads, capacity, r_k), np.uint8),
+        np.zeros((batch, n_kv_heads, capacity, r_v), np.uint8),
+        np.full((batch, n_kv_heads, capacity, ngv), 0x3F80, np.uint16),
+        np.zeros((batch, n_kv_heads, capacity, ngv), np.uint16))
+
+
+def quant_project_append(layer: OracleQuantLayer, k_new: np.ndarray, v_new: np.ndarray, cur_len: int) -> None:
+    """Project T new tokens (Eq. 1, float64 sums), quantise, store at rows
+    [cur_len, cur_len + T)."""
+    k_new, v_new = np.asarray(k_new, np.float64), np.asarray(v_new, np.float64)
+    B, T, H, d = k_new.shape
+    if cur_len < 0 or cur_len + T > layer.capacity:
+        raise ValueError("append exceeds capacity")
+    for b in range(B):
+        for h in range(H):
+            kd = compress(k_new[b, :, h, :], layer.basis_k(h))
+            vd = compress(v_new[b, :, h, :], layer.basis_v(h))
+            layer.k_codes[b, h, cur_len:cur_len + T] = quantize_static(kd, layer.k_scale[h], layer.k_zero[h], layer.bits)
+            c, sb, zb = quantize_dynamic(vd, layer.bits)
+            layer.v_codes[b, h, cur_len:cur_len + T] = c
+            layer.v_scale_bits[b, h, cur_len:cur_len + T] = sb
+            layer.v_zero_bits[b, h, cur_len:cur_len + T] = zb
+
+
+def quant_decode_attention(layer: OracleQuantLayer, q: np.ndarray, n_ctx: int,
+                           scale: float | None = None, heads=None) -> np.ndarray:
+    """Eq. 18 per query head on K~ = dequant(K codes) P_K^T, V~ = dequant(V codes) P_V^T."""
+    q = np.asarray(q, np.float64)
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.full(q.shape, np.nan, np.float64)
+    wanted = None if heads is None else set((int(b), int(h)) for b, h in heads)
+    for b in range(layer.batch):
+        for kv in range(layer.n_kv_heads):
+            hs = [h for h in range(kv * G, (kv + 1) * G) if wanted is None or (b, h) in wanted]
+            if not hs:
+                continue
+            k_low = dequantize(layer.k_codes[b, kv, :n_ctx], layer.k_scale[kv], layer.k_zero[kv])
+            v_low = dequantize(layer.v_codes[b, kv, :n_ctx],
+                               bf16_bits_to_f64(layer.v_scale_bits[b, kv, :n_ctx]),
+                               bf16_bits_to_f64(layer.v_zero_bits[b, kv, :n_ctx]))
+            K_tilde = reconstruct(k_low, layer.basis_k(kv))
+            V_tilde = reconstruct(v_low, layer.basis_v(kv))
+            for h in hs:
+                out[b, h] = attention_single_query(q[b, h], K_tilde, V_tilde, scale)
+    return out

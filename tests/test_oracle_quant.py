@@ -1,0 +1,156 @@
+"""Pins for the oracle's integer quantisation of the compressed cache (Sec. 4.3):
+hand-computed codes, exact recovery of on-grid inputs, the round-trip error bound,
+flat groups, clamping, invariance of attention to the key zero point, and closeness
+of 8-bit attention to the unquantised result."""
+import numpy as np
+
+from oracle import skv_oracle as O
+from paper_2601_21686_amd import synth
+
+
+def test_groups_are_runs_of_64_channels():
+    assert O.group_slices(32) == [slice(0, 32)]
+    assert O.group_slices(64) == [slice(0, 64)]
+    assert O.group_slices(96) == [slice(0, 64), slice(64, 96)]
+    assert O.group_slices(128) == [slice(0, 64), slice(64, 128)]
+
+
+def test_static_codes_by_hand():
+    # scale 0.5, zero -1: x -> (x + 1) / 0.5, half-way cases go to the even code, out of range clamps
+    y = np.array([[-1.0, -0.75, -0.5, 0.0, 0.25, 0.75, 126.5, 200.0, -3.0, 0.126]])
+    want = np.array([[0, 0, 1, 2, 2, 4, 255, 255, 0, 2]], np.uint8)
+    #            (x+1)/.5 = 0, 0.5->0, 1, 2, 2.5->2, 3.5->4, 255, clamp, clamp, 2.252->2
+    got = O.quantize_static(y, np.array([0.5], np.float32), np.array([-1.0], np.float32))
+    assert np.array_equal(got, want)
+    back = O.dequantize(got, np.array([0.5]), np.array([-1.0]))
+    assert np.array_equal(back, want * 0.5 - 1.0)
+
+
+def test_static_on_grid_inputs_are_recovered_exactly_per_group():
+    rng = np.random.default_rng(0)
+    r = 96
+    scale = np.array([2.0 ** -5, 2.0 ** -3], np.float32)
+    zero = np.array([-3.0, 1.5], np.float32)
+    codes = rng.integers(0, 256, size=(40, r)).astype(np.uint8)
+    y = O.dequantize(codes, scale, zero)
+    assert np.array_equal(y[:, :64], codes[:, :64] * 2.0 ** -5 - 3.0)        # group 0 uses pair 0
+    assert np.array_equal(y[:, 64:], codes[:, 64:] * 2.0 ** -3 + 1.5)        # group 1 uses pair 1
+    assert np.array_equal(O.quantize_static(y, scale, zero), codes)
+
+
+def test_static_round_trip_error_is_half_a_step_inside_the_range():
+    rng = np.random.default_rng(1)
+    y = rng.uniform(-2.0, 3.0, size=(200, 128))
+    scale, zero = O.calibrate_static_range(y)
+    assert scale.shape == (2,) and np.allclose(zero, [y[:, :64].min(), y[:, 64:].min()], rtol=1e-6)
+    codes = O.quantize_static(y, scale, zero)
+    assert codes.min() == 0 and codes.max() == 255
+    back = O.dequantize(codes, scale, zero)
+    step = np.repeat(scale.astype(np.float64), 64)[None]
+    assert np.all(np.abs(back - y) <= step / 2 * (1 + 1e-4) + 1e-6)
+    # beyond the calibrated range values clamp to the ends
+    far = np.full((1, 128), 100.0)
+    assert np.all(O.quantize_static(far, scale, zero) == 255)
+    assert np.all(O.quantize_static(-far, scale, zero) == 0)
+
+
+def test_dynamic_quantisation_by_hand_and_flat_groups():
+    # group 0: values 0 .. 255/64 on a grid of 1/64: scale = 2^-6 exactly, zero = 0, codes = 64 * value
+    k = np.arange(64) * 4 % 256
+    row = np.concatenate([k / 64.0, np.full(32, 0.3)])[None]                # group 1 is flat
+    row[0, 5] = 255 / 64.0
+    row[0, 6] = 0.0
+    codes, sb, zb = O.quantize_dynamic(row)
+    assert O.bf16_bits_to_f64(sb)[0, 0] == 2.0 ** -6 and O.bf16_bits_to_f64(zb)[0, 0] == 0.0
+    assert np.array_equal(codes[0, :64], (row[0, :64] * 64).astype(np.uint8))
+    # flat group: scale falls back to 1, zero = bf16(0.3), all codes 0, and the value comes back as bf16(0.3)
+    assert O.bf16_bits_to_f64(sb)[0, 1] == 1.0
+    assert np.all(codes[0, 64:] == 0)
+    back = O.dequantize(codes, O.bf16_bits_to_f64(sb), O.bf16_bits_to_f64(zb))
+    assert np.array_equal(back[0, :64], row[0, :64])
+    assert np.all(back[0, 64:] == O.round_to_bf16(0.3))
+
+
+def test_dynamic_round_trip_error_bound_and_monotone_codes():
+    rng = np.random.default_rng(2)
+    y = rng.standard_normal((300, 128)) * np.exp(rng.uniform(-3, 3, (300, 1)))
+    codes, sb, zb = O.quantize_dynamic(y)
+    s = O.bf16_bits_to_f64(sb)
+    z = O.bf16_bits_to_f64(zb)
+    back = O.dequantize(codes, s, z)
+    y32 = y.astype(np.float32).astype(np.float64)
+    for gi, g in enumerate(O.group_slices(128)):
+        lo, hi = y32[:, g].min(1), y32[:, g].max(1)
+        # zero is bf16(lo), scale is bf16((hi-lo)/255): both within 2^-8 relative of the exact values
+        assert np.all(np.abs(z[:, gi] - lo) <= np.abs(lo) * 2.0 ** -8)
+        assert np.all(np.abs(s[:, gi] - (hi - lo) / 255) <= (hi - lo) / 255 * 2.0 ** -8 * 1.01)
+        # inside [z, z + 255 s] the error is half a step; outside, the overshoot adds to it
+        over = np.maximum(0, y32[:, g] - (z[:, gi] + 255 * s[:, gi])[:, None]) + np.maximum(0, z[:, gi][:, None] - y32[:, g])
+        assert np.all(np.abs(back[:, g] - y32[:, g]) <= s[:, gi][:, None] / 2 * (1 + 1e-4) + over + 1e-12)
+        # codes are monotone in the value
+        order = np.argsort(y32[:, g], axis=1)
+        sorted_codes = np.take_along_axis(codes[:, g].astype(int), order, axis=1)
+        assert np.all(np.diff(sorted_codes, axis=1) >= 0)
+        assert np.all(codes[:, g].min(1) <= 1) and np.all(codes[:, g].max(1) >= 250)   # the range is used
+
+
+def _quant_pair(rng, B, HQ, HKV, rk, rv, n):
+    d = 128
+    Pk64, Pk = synth.orthonormal_bases(1, HKV, d, rk)
+    Pv64, Pv = synth.orthonormal_bases(2, HKV, d, rv)
+    pk = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(Pk))
+    pv = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(Pv))
+    sk = synth.channel_scales(3, HKV, d)
+    K = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(synth.kv_activations(4, B, n, HKV, d, sk)))
+    V = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(synth.kv_activations(5, B, n, HKV, d, sk)))
+    ngk = len(O.group_slices(rk))
+    ks, kz = np.empty((HKV, ngk), np.float32), np.empty((HKV, ngk), np.float32)
+    for h in range(HKV):
+        ks[h], kz[h] = O.calibrate_static_range(np.concatenate([O.compress(K[b, :, h], pk[h]) for b in range(B)]))
+    Lq = O.new_quant_layer(B, HQ, HKV, d, pk, pv, ks, kz, n)
+    O.quant_project_append(Lq, K, V, 0)
+    Lb = O.new_layer(B, HQ, HKV, d, pk, pv, n, store="bf16")
+    O.project_append(Lb, K, V, 0)
+    q = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(synth.queries(6, B, HQ, d)))
+    return Lq, Lb, q
+
+
+def test_attention_does_not_depend_on_the_key_zero_point():
+    # a shift of a group's zero point adds the same constant to every score of a query: softmax removes it
+    rng = np.random.default_rng(3)
+    Lq, _, q = _quant_pair(rng, 1, 4, 2, 96, 64, 200)
+    a = O.quant_decode_attention(Lq, q, 200)
+    Lq.k_zero = Lq.k_zero + np.array([[0.7, -1.3], [2.0, 0.25]], np.float32)
+    b = O.quant_decode_attention(Lq, q, 200)
+    assert np.allclose(a, b, rtol=1e-10, atol=1e-12)
+    # the scale, in contrast, matters
+    Lq.k_scale = Lq.k_scale * np.float32(1.5)
+    assert not np.allclose(a, O.quant_decode_attention(Lq, q, 200), rtol=1e-3)
+
+
+def test_eight_bit_cache_stays_close_to_the_unquantised_cache():
+    rng = np.random.default_rng(4)
+    Lq, Lb, q = _quant_pair(rng, 2, 8, 2, 64, 64, 600)
+    a = O.quant_decode_attention(Lq, q, 600)
+    b = O.decode_attention(Lb, q, 600)
+    err = np.max(np.abs(a - b), axis=-1) / np.max(np.abs(b), axis=-1)
+    assert err.max() < 3e-2            # "essentially unchanged" at 8 bits (Sec. 4.3)
+    assert err.max() > 1e-6            # but it is a different cache
+
+
+def test_quant_append_places_rows_and_leaves_the_rest():
+    B, HKV, d, r, cap, T, cur = 2, 2, 128, 32, 10, 3, 4
+    P64, Pbf = synth.orthonormal_bases(9, HKV, d, r)
+    L = O.new_quant_layer(B, HKV, HKV, d, P64, P64, np.ones((HKV, 1)), np.zeros((HKV, 1)), cap)
+    L.k_codes[:] = 77
+    L.v_codes[:] = 78
+    rng = np.random.default_rng(5)
+    K = rng.standard_normal((B, T, HKV, d)) * 20
+    O.quant_project_append(L, K, K, cur)
+    rest = np.ones(cap, bool)
+    rest[cur:cur + T] = False
+    assert np.all(L.k_codes[:, :, rest] == 77) and np.all(L.v_codes[:, :, rest] == 78)
+    for b in range(B):
+        for h in range(HKV):
+            want = np.clip(np.rint((K[b, :, h] @ P64[h]).astype(np.float32)), 0, 255)
+            assert np.array_equal(L.k_codes[b, h, cur:cur + T], want.astype(np.uint8))
