@@ -179,6 +179,52 @@ skv_status skv_decode_combine(const skv_layer* layer, void* out, int32_t n_split
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ---- 8-bit quantised compressed cache (Sec. 4.3) --------------------------
+ * Asymmetric integer quantisation of the compressed rows, group size 64
+ * channels (the last group of a row may be shorter): code =
+ * clamp(round_half_even((x - zero) / scale), 0, 255), x_hat = code*scale + zero,
+ * decided in float32.  Keys use one (scale, zero) per KV head and channel group,
+ * fixed in advance and shared by every sequence and position (a calibration
+ * result the caller brings); values use one pair per token and channel group,
+ * computed from that group's minimum and maximum when the token is appended
+ * (zero = bf16(min), scale = bf16((max - min)/255), 1 for a flat group) and
+ * stored next to the codes.  Attention is Eq. 18 on K~ = K_hat P_K^T,
+ * V~ = V_hat P_V^T.  Ranks must be multiples of 32.
+ *
+ *   base.k_cache  device uint8 [batch][n_kv_heads][capacity][r_k]   (codes)
+ *   base.v_cache  device uint8 [batch][n_kv_heads][capacity][r_v]
+ *   k_scale, k_zero  device float32 [n_kv_heads][ceil(r_k/64)]
+ *   v_meta        device uint32 [batch][n_kv_heads][capacity][ceil(r_v/64)]:
+ *                 bf16 scale in the low half, bf16 zero in the high half
+ * Everything else (bases, strides, workspace, streams, errors) as for the bf16
+ * cache; workspace size is skv_decode_workspace_bytes(&q->base).  Appends of any
+ * T run as per-token projections (a matrix-core chunk path is not part of this
+ * variant).
+ */
+typedef struct {
+  skv_layer base;
+  const float* k_scale;
+  const float* k_zero;
+  void* v_meta;
+} skv_q8_layer;
+
+skv_status skv_q8_project_append(const skv_q8_layer* layer,
+                                 const void* k_new, const void* v_new,
+                                 int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                                 int32_t T, int64_t cur_len, void* stream);
+skv_status skv_q8_decode_attention(const skv_q8_layer* layer, const void* q, void* out,
+                                   int64_t n_ctx, float scale,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_q8_decode_step(const skv_q8_layer* layer,
+                              const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                              int32_t T, int64_t cur_len,
+                              const void* q, void* out, float scale,
+                              void* workspace, size_t workspace_bytes, void* stream);
+/* Bytes the quantised cache of one layer holds for n tokens (codes + value metadata). */
+size_t skv_q8_cache_bytes(const skv_q8_layer* layer, int64_t n_tokens);
+
+/*
  * Sequential budgeted rank selection (Sec. 3.5 Eqs. 15-17; App. B Alg. 2).
  * Host only; touches no GPU.  delta is host float64 [n_layers][n_k][n_v]
  * row-major: the layer-output error of layer l at ranks (cand_k[i], cand_v[j]).

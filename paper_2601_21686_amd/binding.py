@@ -26,6 +26,7 @@ EXPORTS = (
     "skv_decode_default_splits", "skv_decode_range", "skv_decode_step", "skv_decode_project_query",
     "skv_decode_partial", "skv_decode_combine",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
+    "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
 )
 
 
@@ -44,6 +45,10 @@ class skv_layer(C.Structure):
         ("p_k", C.c_void_p), ("p_v", C.c_void_p),
         ("p_k_head_stride", C.c_int64), ("p_v_head_stride", C.c_int64),
     ]
+
+
+class skv_q8_layer(C.Structure):
+    _fields_ = [("base", skv_layer), ("k_scale", C.c_void_p), ("k_zero", C.c_void_p), ("v_meta", C.c_void_p)]
 
 
 _lib = None
@@ -84,6 +89,15 @@ def lib() -> C.CDLL:
     L.skv_layer_ranks.restype = C.c_int
     L.skv_cache_bytes.argtypes = [LP, i64]
     L.skv_cache_bytes.restype = sz
+    QP = C.POINTER(skv_q8_layer)
+    L.skv_q8_project_append.argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp]
+    L.skv_q8_project_append.restype = C.c_int
+    L.skv_q8_decode_attention.argtypes = [QP, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_q8_decode_attention.restype = C.c_int
+    L.skv_q8_decode_step.argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_q8_decode_step.restype = C.c_int
+    L.skv_q8_cache_bytes.argtypes = [QP, i64]
+    L.skv_q8_cache_bytes.restype = sz
     L.skv_status_string.argtypes = [C.c_int]
     L.skv_status_string.restype = C.c_char_p
     _lib = L
@@ -141,8 +155,43 @@ class Layer:
         return self._ws
 
 
+class QuantLayer:
+    """One layer's 8-bit quantised compressed cache (ranks multiples of 32).
+
+    k_scale, k_zero: float32 CUDA tensors [n_kv_heads, ceil(r_k / 64)] (static key ranges).
+    Codes are uint8 tensors; v_meta is int32 [batch, n_kv_heads, capacity, ceil(r_v / 64)]
+    holding a bf16 scale (low half) and a bf16 zero (high half) per value row and group.
+    """
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, k_scale, k_zero, capacity):
+        dev = p_k.device
+        self.batch, self.n_q_heads, self.n_kv_heads = int(batch), int(n_q_heads), int(n_kv_heads)
+        self.capacity = int(capacity)
+        self.r_k, self.r_v = int(p_k.shape[2]), int(p_v.shape[2])
+        self.p_k, self.p_v = p_k, p_v
+        self.k_scale = k_scale.to(device=dev, dtype=torch.float32).contiguous()
+        self.k_zero = k_zero.to(device=dev, dtype=torch.float32).contiguous()
+        ngv = (self.r_v + 63) // 64
+        self.k_cache = torch.empty((batch, n_kv_heads, capacity, self.r_k), dtype=torch.uint8, device=dev)
+        self.v_cache = torch.empty((batch, n_kv_heads, capacity, self.r_v), dtype=torch.uint8, device=dev)
+        self.v_meta = torch.empty((batch, n_kv_heads, capacity, ngv), dtype=torch.int32, device=dev)
+        base = skv_layer(
+            self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v, self.capacity,
+            self.k_cache.data_ptr(), self.v_cache.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
+            0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
+            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+        self.c = skv_q8_layer(base, self.k_scale.data_ptr(), self.k_zero.data_ptr(), self.v_meta.data_ptr())
+        self._ws = None
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            n = int(lib().skv_decode_workspace_bytes(C.byref(self.c.base)))
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.p_k.device)
+        return self._ws
+
+
 def _ref(layer):
-    return C.byref(layer.c if isinstance(layer, Layer) else layer)
+    return C.byref(layer.c if isinstance(layer, (Layer, QuantLayer)) else layer)
 
 
 # ---- the C ABI, same names -------------------------------------------------
@@ -240,3 +289,40 @@ def skv_layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, de
     if code not in (SKV_OK, SKV_ERR_BUDGET):
         raise SkvError(code, "skv_layer_ranks")
     return list(rk), list(rv), float(ach.value), code == SKV_OK
+
+
+# ---- 8-bit quantised cache ------------------------------------------------------
+
+
+def skv_q8_project_append(layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
+                          stream=None) -> None:
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
+    _check(lib().skv_q8_project_append(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                       int(k_new.shape[1]), int(cur_len), _stream_ptr(stream)),
+           "skv_q8_project_append")
+
+
+def skv_q8_decode_attention(layer: QuantLayer, q: torch.Tensor, out: torch.Tensor, n_ctx: int,
+                            scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_q8_decode_attention(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx), float(scale),
+                                         ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_q8_decode_attention")
+
+
+def skv_q8_decode_step(layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
+                       q: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
+                       workspace: torch.Tensor | None = None, stream=None) -> None:
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_q8_decode_step(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                    int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
+                                    float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                    _stream_ptr(stream)), "skv_q8_decode_step")
+
+
+def skv_q8_cache_bytes(layer: QuantLayer, n_tokens: int) -> int:
+    return int(lib().skv_q8_cache_bytes(_ref(layer), int(n_tokens)))

@@ -18,6 +18,7 @@ OUT = os.path.join(PKG, "libskv.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 KEY_RANKS = (16, 32, 48, 64, 80, 96, 112, 128)
+Q8_KEY_RANKS = (32, 64, 96, 128)          # the 8-bit quantised cache takes multiples of 32
 
 # Packed-FP32 instruction selection is switched off for all device code.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -40,6 +41,10 @@ def _jobs():
     for rk in KEY_RANKS:
         jobs.append((f"skv_decode_partial_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}"],
+                     DEVICE_FLAGS))
+    for rk in Q8_KEY_RANKS:
+        jobs.append((f"skv_decode_partial_q8_rk{rk}.o",
+                     ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_Q8=1"],
                      DEVICE_FLAGS))
     return jobs
 

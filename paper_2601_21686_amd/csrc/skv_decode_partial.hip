@@ -3,7 +3,12 @@
 //
 // This file is compiled once per key rank (-DSKV_RK=16,32,...,128); each
 // object holds the kernels for that r_K and every r_V in {16,...,128} and
-// 1, 2 or 4 query heads per workgroup.
+// 1, 2 or 4 query heads per workgroup.  With -DSKV_Q8=1 it is compiled for
+// the 8-bit quantised cache (Sec. 4.3; ranks 32, 64, 96, 128): rows hold one
+// byte per channel, key scales are already folded into q~ (the key zero point
+// adds the same constant to every score of a query and drops out of the
+// softmax), and every value row carries a (scale, zero) pair per 64-channel
+// group: a~ = sum_j (p_j scale_j) code_j + sum_j p_j zero_j.
 //
 // What is computed (App. A.1 Eq. 18 on the reconstructed cache of Sec. 3.2
 // Eq. 7, in the factored form q K~^T = (q P_K) K_down^T,
@@ -29,6 +34,9 @@
 #ifndef SKV_RK
 #error "compile with -DSKV_RK=<key rank>"
 #endif
+#ifndef SKV_Q8
+#define SKV_Q8 0
+#endif
 
 namespace skv {
 namespace {
@@ -38,22 +46,33 @@ constexpr float kRescaleSlack = 8.0f; // log2 units a score may exceed the softm
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// How the r channels of a row are dealt to the 8 lanes of an octet.
+// How the r channels of a row are dealt to the 8 lanes of an octet: lane j owns the j-th eighth
+// of the first 64 channels and the j-th eighth of the rest.
+#if SKV_Q8
+constexpr int kElemsPerDword = 4;                // one byte per channel
+#else
+constexpr int kElemsPerDword = 2;                // bf16
+#endif
 template <int R>
 struct RowMap {
-  static constexpr int NA = R < 64 ? R : 64;   // channels in the first segment (<= 128 bytes)
+  static constexpr int NA = R < 64 ? R : 64;   // channels in the first segment
   static constexpr int NB = R - NA;            // channels in the second segment
-  static constexpr int CA = NA / 8;            // channels per lane, first segment: 2,4,6,8
-  static constexpr int CB = NB / 8;            // second segment: 0,2,4,6,8
-  static constexpr int DA = CA / 2;            // dwords per lane
-  static constexpr int DB = CB / 2;
+  static constexpr int CA = NA / 8;            // channels per lane, first segment
+  static constexpr int CB = NB / 8;            // second segment
+  static constexpr int DA = CA / kElemsPerDword;   // dwords per lane
+  static constexpr int DB = CB / kElemsPerDword;
   static constexpr int CPL = CA + CB;          // channels per lane
   static constexpr int DPL = DA + DB;          // dwords per lane
-  static constexpr int ROW_DW = R / 2;         // dwords per row
+  static constexpr int ROW_DW = R / kElemsPerDword;    // dwords per row
+  static constexpr int SEG_B_DW = 64 / kElemsPerDword; // where the second segment starts
+  static constexpr int NG = (R + 63) / 64;     // 64-channel groups (quantisation groups)
+  static_assert(CA % kElemsPerDword == 0 && CB % kElemsPerDword == 0, "rank not supported by this format");
   // channel held in slot i of lane j
   __device__ static constexpr int chan(int j, int i) {
     return i < CA ? j * CA + i : NA + j * CB + (i - CA);
   }
+  // 64-channel group of slot i
+  __device__ static constexpr int group_of_slot(int i) { return i < CA ? 0 : 1; }
 };
 
 #ifndef SKV_NT
@@ -89,15 +108,22 @@ template <int R>
 __device__ __forceinline__ void load_row(const uint32_t* row, int j, uint32_t (&w)[RowMap<R>::DPL]) {
   using M = RowMap<R>;
   load_dwords<M::DA>(row + j * M::DA, &w[0]);
-  if constexpr (M::DB > 0) load_dwords<M::DB>(row + 32 + j * M::DB, &w[M::DA]);
+  if constexpr (M::DB > 0) load_dwords<M::DB>(row + M::SEG_B_DW + j * M::DB, &w[M::DA]);
 }
 
 template <int R>
 __device__ __forceinline__ void unpack_row(const uint32_t (&w)[RowMap<R>::DPL], float (&f)[RowMap<R>::CPL]) {
 #pragma unroll
   for (int i = 0; i < RowMap<R>::DPL; ++i) {
+#if SKV_Q8
+    f[4 * i] = (float)(w[i] & 0xffu);
+    f[4 * i + 1] = (float)((w[i] >> 8) & 0xffu);
+    f[4 * i + 2] = (float)((w[i] >> 16) & 0xffu);
+    f[4 * i + 3] = (float)(w[i] >> 24);
+#else
     f[2 * i] = bf16_lo(w[i]);
     f[2 * i + 1] = bf16_hi(w[i]);
+#endif
   }
 }
 
@@ -135,6 +161,9 @@ template <int RK, int RV, int U>
 struct TileRegs {
   uint32_t kw[U][RowMap<RK>::DPL];
   uint32_t vw[U][RowMap<RV>::DPL];
+#if SKV_Q8
+  uint32_t vm[U][RowMap<RV>::NG];              // per row and group: bf16 scale (low half), bf16 zero (high half)
+#endif
 };
 
 // Requests 8*U rows of a wave.  row0 is this lane's first row; the lane's rows
@@ -142,7 +171,8 @@ struct TileRegs {
 // that nothing outside [0, n_ctx) is ever read.
 template <int RK, int RV, int U, bool MASKED>
 __device__ __forceinline__ void issue_rows(const uint32_t* __restrict__ kbase,
-                                           const uint32_t* __restrict__ vbase, int row0, int t_end,
+                                           const uint32_t* __restrict__ vbase,
+                                           const uint32_t* __restrict__ mbase, int row0, int t_end,
                                            int j, TileRegs<RK, RV, U>& t) {
 #pragma unroll
   for (int u = 0; u < U; ++u) {
@@ -155,6 +185,10 @@ __device__ __forceinline__ void issue_rows(const uint32_t* __restrict__ kbase,
     int row = row0 + 8 * u;
     if constexpr (MASKED) row = row < t_end ? row : t_end - 1;
     load_row<RV>(vbase + (int64_t)row * RowMap<RV>::ROW_DW, j, t.vw[u]);
+#if SKV_Q8
+#pragma unroll
+    for (int g = 0; g < RowMap<RV>::NG; ++g) t.vm[u][g] = SKV_LOAD(mbase + (int64_t)row * RowMap<RV>::NG + g);
+#endif
   }
 }
 
@@ -185,7 +219,8 @@ template <int RK, int RV, int GT, int U, bool MASKED>
 __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int row0, int t_end, int qd,
                                              const float (&qreg)[GT][RowMap<RK>::CPL],
                                              float (&m)[HeadSplit<GT>::HL], float (&l)[HeadSplit<GT>::HL],
-                                             float (&acc)[GT][RowMap<RV>::CPL]) {
+                                             float (&acc)[GT][RowMap<RV>::CPL],
+                                             float (&zacc)[GT][RowMap<RV>::NG]) {
   using KM = RowMap<RK>;
   using VM = RowMap<RV>;
   using HS = HeadSplit<GT>;
@@ -248,7 +283,15 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
         const float cr = dpp_f32<0x141>(c[a]);   // the other quad's factor for its head
 #pragma unroll
         for (int i = 0; i < VM::CPL; ++i) acc[HL + a][i] *= cr;
+#if SKV_Q8
+#pragma unroll
+        for (int g = 0; g < VM::NG; ++g) zacc[HL + a][g] *= cr;
+#endif
       }
+#if SKV_Q8
+#pragma unroll
+      for (int g = 0; g < VM::NG; ++g) zacc[a][g] *= c[a];
+#endif
     }
   }
 
@@ -271,16 +314,38 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
   for (int u = 0; u < U; ++u) {
     float vf[VM::CPL];
     unpack_row<RV>(t.vw[u], vf);
+#if SKV_Q8
+    float sc[VM::NG], zr[VM::NG];
+#pragma unroll
+    for (int gq = 0; gq < VM::NG; ++gq) {
+      sc[gq] = bf16_lo(t.vm[u][gq]);
+      zr[gq] = bf16_hi(t.vm[u][gq]);
+    }
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      float ps[VM::NG];
+#pragma unroll
+      for (int gq = 0; gq < VM::NG; ++gq) {
+        ps[gq] = pw[u][g] * sc[gq];
+        zacc[g][gq] = fmaf(pw[u][g], zr[gq], zacc[g][gq]);
+      }
+#pragma unroll
+      for (int i = 0; i < VM::CPL; ++i) acc[g][i] = fmaf(ps[VM::group_of_slot(i)], vf[i], acc[g][i]);
+    }
+#else
 #pragma unroll
     for (int g = 0; g < GT; ++g) {
 #pragma unroll
       for (int i = 0; i < VM::CPL; ++i) acc[g][i] = fmaf(pw[u][g], vf[i], acc[g][i]);
     }
+#endif
   }
 }
 
-template <int RK, int RV, int GT>
+// FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes).
+template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
+  static_assert(FMT == SKV_Q8, "format tag must match the build");
   using KM = RowMap<RK>;
   using VM = RowMap<RV>;
   constexpr int U = Depth<RK, RV>::U;
@@ -321,6 +386,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 
   const uint32_t* kbase = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * KM::ROW_DW;
   const uint32_t* vbase = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * VM::ROW_DW;
+#if SKV_Q8
+  const uint32_t* mbase = p.v_meta + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * VM::NG;
+#else
+  const uint32_t* mbase = nullptr;
+#endif
   const int lane_row = wave * ROWS_PER_WAVE + oct;     // this lane's first row inside a tile
   const int n_full = (t1 - t0) / ROWS_PER_WG;         // tiles with every row valid
   using Tile = TileRegs<RK, RV, U>;
@@ -342,7 +412,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
       }
     }
   }
-  if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, t0 + lane_row, t1, j, ta);
+  if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
 
   // ---- stream the range ---------------------------------------------------------------
   using HS = HeadSplit<GT>;
@@ -354,10 +424,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     m[a] = kNegBig;
     l[a] = 0.f;
   }
+  float zacc[GT][VM::NG];                        // quantised cache: sum_j p_j zero_j per head and group
 #pragma unroll
-  for (int g = 0; g < GT; ++g)
+  for (int g = 0; g < GT; ++g) {
 #pragma unroll
     for (int i = 0; i < VM::CPL; ++i) acc[g][i] = 0.f;
+#pragma unroll
+    for (int gq = 0; gq < VM::NG; ++gq) zacc[g][gq] = 0.f;
+  }
 
   // A ring of NBUF register tiles: while one is being consumed the next NBUF-1 are already on
   // their way.  The steady-state loop issues unconditionally, so that the wait before each
@@ -369,15 +443,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     ring[0] = ta;                                   // tile 0 was requested before the projection
 #pragma unroll
     for (int k = 1; k < NBUF - 1; ++k)
-      if (k < n_full) issue_rows<RK, RV, U, false>(kbase, vbase, t0 + k * ROWS_PER_WG + lane_row, t1, j, ring[k]);
+      if (k < n_full) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + k * ROWS_PER_WG + lane_row, t1, j, ring[k]);
     int i = 0;
     if constexpr (NBUF > 1) {
       while (i + 2 * NBUF - 2 < n_full) {           // ring[k] holds tile i+k for k < NBUF-1
 #pragma unroll
         for (int k = 0; k < NBUF; ++k) {
-          issue_rows<RK, RV, U, false>(kbase, vbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
+          issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
                                        ring[(k + NBUF - 1) % NBUF]);
-          consume_rows<RK, RV, GT, U, false>(ring[k], 0, t1, qd, qreg, m, l, acc);
+          consume_rows<RK, RV, GT, U, false>(ring[k], 0, t1, qd, qreg, m, l, acc, zacc);
         }
         i += NBUF;
       }
@@ -387,17 +461,25 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     for (int k = 0; k < 2 * NBUF - 2 || k < 1; ++k) {
       if (i + k < n_full) {
         if (NBUF > 1 && i + k + NBUF - 1 < n_full)
-          issue_rows<RK, RV, U, false>(kbase, vbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
+          issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
                                        ring[(k + NBUF - 1) % NBUF]);
-        consume_rows<RK, RV, GT, U, false>(ring[k % NBUF], 0, t1, qd, qreg, m, l, acc);
+        consume_rows<RK, RV, GT, U, false>(ring[k % NBUF], 0, t1, qd, qreg, m, l, acc, zacc);
       }
     }
   }
   if (t0 + n_full * ROWS_PER_WG < t1) {               // ragged tail of the range
     const int row0 = t0 + n_full * ROWS_PER_WG + lane_row;
-    issue_rows<RK, RV, U, true>(kbase, vbase, row0, t1, j, ta);
-    consume_rows<RK, RV, GT, U, true>(ta, row0, t1, qd, qreg, m, l, acc);
+    issue_rows<RK, RV, U, true>(kbase, vbase, mbase, row0, t1, j, ta);
+    consume_rows<RK, RV, GT, U, true>(ta, row0, t1, qd, qreg, m, l, acc, zacc);
   }
+
+#if SKV_Q8
+  // every channel of a group receives that group's sum of weighted zero points
+#pragma unroll
+  for (int g = 0; g < GT; ++g)
+#pragma unroll
+    for (int i = 0; i < VM::CPL; ++i) acc[g][i] += zacc[g][VM::group_of_slot(i)];
+#endif
 
   // ---- merge the 8 octet streams of the wave (lanes 8, 16, 32 apart) ---------------------
 #pragma unroll
@@ -465,9 +547,9 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const dim3 grid((unsigned)p.n_splits, (unsigned)(p.batch * p.n_kv_heads * passes));
   const dim3 block(kDecodeThreads);
   switch (heads) {
-    case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1>), grid, block, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2>), grid, block, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 4>), grid, block, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, SKV_Q8>), grid, block, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, SKV_Q8>), grid, block, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 4, SKV_Q8>), grid, block, 0, stream, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -476,13 +558,15 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
 template <int RK>
 hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stream) {
   switch (r_v) {
+#if !SKV_Q8
     case 16: return launch_rv<RK, 16>(heads, p, stream);
-    case 32: return launch_rv<RK, 32>(heads, p, stream);
     case 48: return launch_rv<RK, 48>(heads, p, stream);
-    case 64: return launch_rv<RK, 64>(heads, p, stream);
     case 80: return launch_rv<RK, 80>(heads, p, stream);
-    case 96: return launch_rv<RK, 96>(heads, p, stream);
     case 112: return launch_rv<RK, 112>(heads, p, stream);
+#endif
+    case 32: return launch_rv<RK, 32>(heads, p, stream);
+    case 64: return launch_rv<RK, 64>(heads, p, stream);
+    case 96: return launch_rv<RK, 96>(heads, p, stream);
     case 128: return launch_rv<RK, 128>(heads, p, stream);
   }
   return hipErrorInvalidValue;
@@ -492,8 +576,12 @@ hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stre
 
 #define SKV_CAT2(a, b) a##b
 #define SKV_CAT(a, b) SKV_CAT2(a, b)
-hipError_t SKV_CAT(launch_decode_partial_rk, SKV_RK)(int r_v, int heads, const DecodeParams& p,
-                                                      hipStream_t stream) {
+#if SKV_Q8
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q8_rk, SKV_RK)
+#else
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_rk, SKV_RK)
+#endif
+hipError_t SKV_LAUNCHER_NAME(int r_v, int heads, const DecodeParams& p, hipStream_t stream) {
   return launch_rk<SKV_RK>(r_v, heads, p, stream);
 }
 

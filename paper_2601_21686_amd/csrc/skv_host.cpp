@@ -72,6 +72,8 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->n_ctx = 0;
   p->n_splits = n_splits;
   p->scale_log2e = 0.f;
+  p->k_scale = nullptr;
+  p->v_meta = nullptr;
   char* ws = static_cast<char*>(workspace);
   p->qt = reinterpret_cast<float*>(ws);
   p->part_acc = reinterpret_cast<float*>(ws + qt_bytes(L));
@@ -255,15 +257,31 @@ void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, 
   p->r_k = L->r_k;
   p->r_v = L->r_v;
   p->T = T;
+  p->k_scale = nullptr;
+  p->k_zero = nullptr;
+  p->v_meta = nullptr;
 }
 
 // ---- launches -----------------------------------------------------------------------------
 
-skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* workspace, void* stream) {
+decode_partial_launcher partial_q8_launcher_for(int r_k) {
+  switch (r_k) {
+    case 32: return launch_decode_partial_q8_rk32;
+    case 64: return launch_decode_partial_q8_rk64;
+    case 96: return launch_decode_partial_q8_rk96;
+    case 128: return launch_decode_partial_q8_rk128;
+  }
+  return nullptr;
+}
+
+// q8: the quantised layer the call is for, or null for the bf16 cache.
+skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* workspace, void* stream,
+                       const skv_q8_layer* q8 = nullptr) {
   DecodeParams p;
   fill_decode_params(L, &p, s, workspace);
   p.n_ctx = (int32_t)n_ctx;
-  decode_partial_launcher launch = partial_launcher_for(L->r_k);
+  if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
+  decode_partial_launcher launch = q8 ? partial_q8_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
@@ -366,6 +384,110 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
     if (launch_project(nullptr, &qp, hs) != hipSuccess) return SKV_ERR_HIP;
   }
   st = run_partial(L, n_ctx, s, workspace, stream);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// The quantised cache takes ranks that are multiples of 32 (one byte per channel, whole
+// dwords per lane).
+skv_status check_q8_layer(const skv_q8_layer* Q) {
+  if (!Q) return SKV_ERR_NULL;
+  const skv_status st = check_layer(&Q->base);
+  if (st != SKV_OK) return st;
+  if ((Q->base.r_k % 32) || (Q->base.r_v % 32)) return SKV_ERR_RANK;
+  if (!Q->k_scale || !Q->k_zero || !Q->v_meta) return SKV_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(Q->k_scale) | reinterpret_cast<uintptr_t>(Q->k_zero) |
+       reinterpret_cast<uintptr_t>(Q->v_meta)) & 3u)
+    return SKV_ERR_ALIGN;
+  return SKV_OK;
+}
+
+void fill_q8_query(const skv_q8_layer* Q, DecodeParams* p, const void* q, float scale, void* workspace) {
+  fill_query_params(&Q->base, p, q, scale, workspace);
+  p->k_scale = Q->k_scale;
+}
+
+void fill_q8_append(const skv_q8_layer* Q, AppendParams* p, const void* k_new, const void* v_new,
+                    int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len) {
+  fill_append_params(&Q->base, p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  p->k_scale = Q->k_scale;
+  p->k_zero = Q->k_zero;
+  p->v_meta = static_cast<uint32_t*>(Q->v_meta);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t skv_q8_cache_bytes(const skv_q8_layer* Q, int64_t n_tokens) {
+  if (!Q || n_tokens < 0) return 0;
+  const skv_layer* L = &Q->base;
+  const size_t groups_v = (size_t)(L->r_v + 63) / 64;
+  return (size_t)L->batch * L->n_kv_heads * (size_t)n_tokens * ((size_t)(L->r_k + L->r_v) + 4u * groups_v);
+}
+
+skv_status skv_q8_project_append(const skv_q8_layer* Q, const void* k_new, const void* v_new,
+                                 int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                                 int64_t cur_len, void* stream) {
+  skv_status st = check_q8_layer(Q);
+  if (st != SKV_OK) return st;
+  st = check_append(&Q->base, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK || T == 0) return st;
+  AppendParams p;
+  fill_q8_append(Q, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (launch_project(&p, nullptr, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_q8_decode_attention(const skv_q8_layer* Q, const void* q, void* out, int64_t n_ctx,
+                                   float scale, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+  skv_status st = check_q8_layer(Q);
+  if (st != SKV_OK) return st;
+  const skv_layer* L = &Q->base;
+  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams p;
+  fill_q8_query(Q, &p, q, scale, workspace);
+  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  st = run_partial(L, n_ctx, s, workspace, stream, Q);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                              int64_t cur_len, const void* q, void* out, float scale,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_q8_layer(Q);
+  if (st != SKV_OK) return st;
+  const skv_layer* L = &Q->base;
+  st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK) return st;
+  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int64_t n_ctx = cur_len + T;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams qp;
+  fill_q8_query(Q, &qp, q, scale, workspace);
+  AppendParams ap;
+  fill_q8_append(Q, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (launch_project(T > 0 ? &ap : nullptr, &qp, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  st = run_partial(L, n_ctx, s, workspace, stream, Q);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
 }

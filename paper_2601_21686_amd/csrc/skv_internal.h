@@ -18,6 +18,9 @@ struct DecodeParams {
   float* part_acc;           // [batch][n_q_heads][n_splits][r_v]
   float* part_ml;            // [batch][n_q_heads][n_splits][2]  (max in log2 units, normaliser)
   float* qt;                 // [batch][n_q_heads][r_k]: projected query times scale*log2(e)
+  // 8-bit quantised cache only (null otherwise)
+  const float* k_scale;      // [n_kv_heads][groups of r_k]: static key scales, folded into qt
+  const uint32_t* v_meta;    // [batch][n_kv_heads][capacity][groups of r_v]: bf16 scale | bf16 zero << 16
   float* out;                // [batch][n_q_heads][128]
   int64_t capacity;
   int64_t p_k_head_stride;
@@ -45,6 +48,10 @@ struct AppendParams {
   int32_t batch, n_kv_heads;
   int32_t r_k, r_v;
   int32_t T;
+  // 8-bit quantised cache only (null otherwise): the caches then hold one byte per channel
+  const float* k_scale;      // [n_kv_heads][groups of r_k]
+  const float* k_zero;
+  uint32_t* v_meta;          // [batch][n_kv_heads][capacity][groups of r_v]
 };
 
 // The context is cut into quanta of this many rows; a range is a run of whole quanta (the last
@@ -83,6 +90,10 @@ hipError_t launch_decode_partial_rk80(int, int, const DecodeParams&, hipStream_t
 hipError_t launch_decode_partial_rk96(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_rk112(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_rk128(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q8_rk32(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q8_rk64(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);

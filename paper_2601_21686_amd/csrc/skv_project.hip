@@ -1,6 +1,7 @@
 // Projections of a few rows onto a basis, on the vector ALUs:
 //   * new keys / values when only a few tokens are appended
-//     (Sec. 2.1 Eq. 1: k_down = k P_K, v_down = v P_V);
+//     (Sec. 2.1 Eq. 1: k_down = k P_K, v_down = v P_V), stored as bf16 or, for
+//     the quantised cache of Sec. 4.3, as 8-bit codes;
 //   * the decode query, q~ = (q P_K) * scale * log2(e), for all query heads
 //     (projecting the keys induces the same projection of the query inside
 //     q K~^T = (q P_K) K_down^T, Sec. 2.1 Eq. 2 and Sec. 2.2).
@@ -42,9 +43,41 @@ __global__ __launch_bounds__(kProjectThreads) void project_kernel(const AppendPa
     if (tid < D) x_s[tid] = bf16_to_f32((which ? ap.v_new : ap.k_new)[src + tid]);
     __syncthreads();
     project_rows_finish<1>(pp, r, x_s, part_s, y_s);
-    uint16_t* cache = which ? ap.v_cache : ap.k_cache;
     const int64_t row = ((int64_t)b * ap.n_kv_heads + h) * ap.capacity + ap.cur_len + t;
-    if (tid < r) cache[row * r + tid] = (uint16_t)f32_to_bf16_bits(y_s[tid]);
+    if (ap.v_meta == nullptr) {                    // bf16 cache
+      uint16_t* cache = which ? ap.v_cache : ap.k_cache;
+      if (tid < r) cache[row * r + tid] = (uint16_t)f32_to_bf16_bits(y_s[tid]);
+      return;
+    }
+    // 8-bit cache (Sec. 4.3): code = clamp(rne((y - zero) / scale), 0, 255) per 64-channel group.
+    // Thread c holds channel c; group g is wave g.
+    const int ng = (r + 63) >> 6;
+    const int g = tid >> 6;
+    const bool live = tid < r;
+    const float y = live ? y_s[tid] : 0.f;
+    float scale, zero;
+    if (which == 0) {                              // keys: static range of this KV head and group
+      scale = live ? ap.k_scale[h * ng + g] : 1.f;
+      zero = live ? ap.k_zero[h * ng + g] : 0.f;
+    } else {                                       // values: range of this token's group, kept as bf16
+      float lo = live ? y : 3.0e38f, hi = live ? y : -3.0e38f;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off));
+        hi = fmaxf(hi, __shfl_xor(hi, off));
+      }
+      uint32_t sb = f32_to_bf16_bits(__fdiv_rn(hi - lo, 255.0f));
+      if ((sb & 0x7fffu) == 0) sb = 0x3F80u;       // flat group: scale 1
+      const uint32_t zb = f32_to_bf16_bits(lo);
+      scale = __uint_as_float(sb << 16);
+      zero = __uint_as_float(zb << 16);
+      if (live && (tid & 63) == 0) ap.v_meta[row * ng + g] = sb | (zb << 16);
+    }
+    if (live) {
+      const float code = fminf(fmaxf(rintf(__fdiv_rn(y - zero, scale)), 0.f), 255.f);
+      uint8_t* cache = reinterpret_cast<uint8_t*>(which ? ap.v_cache : ap.k_cache);
+      cache[row * r + tid] = (uint8_t)code;
+    }
     return;
   }
 
@@ -62,7 +95,13 @@ __global__ __launch_bounds__(kProjectThreads) void project_kernel(const AppendPa
   __syncthreads();
   project_rows_finish<HEADS>(pp, dp.r_k, x_s, part_s, y_s);
   float* dst = dp.qt + ((int64_t)b * dp.n_q_heads + hq0) * dp.r_k;
-  for (int i = tid; i < HEADS * dp.r_k; i += kProjectThreads) dst[i] = y_s[i] * dp.scale_log2e;
+  const int ngk = (dp.r_k + 63) >> 6;
+  for (int i = tid; i < HEADS * dp.r_k; i += kProjectThreads) {
+    float v = y_s[i] * dp.scale_log2e;
+    // quantised keys: <q~, code * scale + zero> = <q~ * scale, code> + const; the constant drops out of the softmax
+    if (dp.k_scale != nullptr) v *= dp.k_scale[kv * ngk + ((i % dp.r_k) >> 6)];
+    dst[i] = v;
+  }
 }
 
 }  // namespace

@@ -205,3 +205,30 @@ def test_layer_ranks_argument_errors():
     assert f(2, 128, 0.8, ck, 2, ck, 2, delta, None, rv, None) == B.SKV_ERR_NULL
     assert f(2, 128, 0.3, ck, 2, ck, 2, delta, rk, rv, None) == B.SKV_ERR_BUDGET
     assert list(rk) == [64, 64] and list(rv) == [64, 64]
+
+
+def test_quantised_layer_argument_checks():
+    lib = B.lib()
+
+    def qlayer(base_kw=None, **kw):
+        d = dict(k_scale=FAKE, k_zero=FAKE, v_meta=FAKE)
+        d.update(kw)
+        return B.skv_q8_layer(_layer(**(base_kw or {})), d["k_scale"], d["k_zero"], d["v_meta"])
+
+    ok = qlayer()
+    ws = lib.skv_decode_workspace_bytes(C.byref(ok.base))
+    assert lib.skv_q8_cache_bytes(C.byref(ok), 1000) == 4 * 8 * 1000 * (128 + 4)
+    cases = [(qlayer(k_scale=None), B.SKV_ERR_NULL), (qlayer(v_meta=None), B.SKV_ERR_NULL),
+             (qlayer(k_zero=FAKE + 2), B.SKV_ERR_ALIGN),
+             (qlayer(dict(r_k=48, p_k_head_stride=128 * 48)), B.SKV_ERR_RANK),       # multiples of 32 only
+             (qlayer(dict(r_v=80, p_v_head_stride=128 * 80)), B.SKV_ERR_RANK),
+             (qlayer(dict(head_dim=64)), B.SKV_ERR_SHAPE)]
+    for Q, code in cases:
+        assert lib.skv_q8_project_append(C.byref(Q), FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == code
+        assert lib.skv_q8_decode_attention(C.byref(Q), FAKE, FAKE, 16, 0.0, FAKE, ws, None) == code
+        assert lib.skv_q8_decode_step(C.byref(Q), FAKE, FAKE, 8192, 1024, 128, 1, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == code
+    assert lib.skv_q8_project_append(None, FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_q8_project_append(C.byref(ok), FAKE, FAKE, 8192, 1024, 128, 2, 1023, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_q8_decode_attention(C.byref(ok), FAKE, FAKE, 0, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_q8_decode_attention(C.byref(ok), FAKE, FAKE, 16, 0.0, FAKE, 64, None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_q8_decode_step(C.byref(ok), FAKE, FAKE, 8192, 1024, 128, 1, 0, None, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL

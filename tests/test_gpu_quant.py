@@ -1,0 +1,135 @@
+"""GPU parity of the 8-bit quantised cache (Sec. 4.3) against the oracle: codes and
+per-row value ranges written by the append, decode attention over identical cache
+bytes, and the fused decode step."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import skv_oracle as O
+from paper_2601_21686_amd import binding as B
+from paper_2601_21686_amd import synth
+from _helpers import TOL, vec_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+class QPair:
+    """The same quantised layer on the GPU and in the oracle (same bases, same static key ranges)."""
+
+    def __init__(self, seed, batch, hq, hkv, r_k, r_v, capacity):
+        self.batch, self.hq, self.hkv, self.r_k, self.r_v, self.capacity = batch, hq, hkv, r_k, r_v, capacity
+        _, pk = synth.orthonormal_bases(synth.stable_seed(seed, "pk"), hkv, 128, r_k)
+        _, pv = synth.orthonormal_bases(synth.stable_seed(seed, "pv"), hkv, 128, r_v)
+        self.pk64 = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(pk))
+        self.pv64 = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(pv))
+        self.scales_k = synth.channel_scales(synth.stable_seed(seed, "sk"), hkv, 128)
+        self.scales_v = synth.channel_scales(synth.stable_seed(seed, "sv"), hkv, 128)
+        # static key ranges: calibrated by the oracle on a seeded sample of projected keys
+        cal = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(
+            synth.kv_activations(synth.stable_seed(seed, "cal"), 1, 512, hkv, 128, self.scales_k)))
+        ngk = len(O.group_slices(r_k))
+        ks, kz = np.empty((hkv, ngk), np.float32), np.empty((hkv, ngk), np.float32)
+        for h in range(hkv):
+            ks[h], kz[h] = O.calibrate_static_range(O.compress(cal[0, :, h], self.pk64[h]))
+        self.ora = O.new_quant_layer(batch, hq, hkv, 128, self.pk64, self.pv64, ks, kz, capacity)
+        self.gpu = B.QuantLayer(batch, hq, hkv, pk.cuda(), pv.cuda(), torch.from_numpy(ks), torch.from_numpy(kz), capacity)
+
+    def raw_kv(self, seed, T):
+        k = synth.kv_activations(synth.stable_seed(seed, "k"), self.batch, T, self.hkv, 128, self.scales_k, "cuda")
+        v = synth.kv_activations(synth.stable_seed(seed, "v"), self.batch, T, self.hkv, 128, self.scales_v, "cuda")
+        return k, v
+
+    def oracle_append(self, k, v, cur):
+        f = lambda t: O.bf16_bits_to_f64(synth.torch_bf16_to_bits(t))
+        O.quant_project_append(self.ora, f(k), f(v), cur)
+
+    def upload_oracle_cache(self, n):
+        self.gpu.k_cache[:, :, :n] = torch.from_numpy(self.ora.k_codes[:, :, :n]).cuda()
+        self.gpu.v_cache[:, :, :n] = torch.from_numpy(self.ora.v_codes[:, :, :n]).cuda()
+        meta = self.ora.v_scale_bits[:, :, :n].astype(np.uint32) | (self.ora.v_zero_bits[:, :, :n].astype(np.uint32) << 16)
+        self.gpu.v_meta[:, :, :n] = torch.from_numpy(meta.view(np.int32)).cuda()
+
+    def queries(self, seed):
+        return synth.queries(synth.stable_seed(seed, "q"), self.batch, self.hq, 128, "cuda")
+
+    def oracle_decode(self, q, n, scale=None):
+        return O.quant_decode_attention(self.ora, O.bf16_bits_to_f64(synth.torch_bf16_to_bits(q)), n, scale)
+
+
+@pytest.mark.parametrize("r_k,r_v", [(64, 64), (32, 96), (96, 32), (128, 128), (64, 128)])
+@pytest.mark.parametrize("batch,T,cur", [(2, 1, 5), (1, 40, 0)])
+def test_quantised_append_codes_and_ranges(r_k, r_v, batch, T, cur):
+    P = QPair(("qapp", r_k, r_v, T), batch, 8, 4, r_k, r_v, cur + T + 3)
+    P.gpu.k_cache.fill_(201)
+    P.gpu.v_cache.fill_(202)
+    P.gpu.v_meta.fill_(-7)
+    k, v = P.raw_kv(1, T)
+    B.skv_q8_project_append(P.gpu, k, v, cur)
+    torch.cuda.synchronize()
+    P.oracle_append(k, v, cur)
+    sl = slice(cur, cur + T)
+    gk = P.gpu.k_cache.cpu().numpy()
+    gv = P.gpu.v_cache.cpu().numpy()
+    gm = P.gpu.v_meta.cpu().numpy().view(np.uint32)
+    # keys: static ranges, so codes can differ only where float32 and float64 sums straddle a rounding boundary
+    dk = np.abs(gk[:, :, sl].astype(int) - P.ora.k_codes[:, :, sl].astype(int))
+    assert dk.max() <= 1 and (dk > 0).mean() < 0.01
+    # values: the stored (scale, zero) pairs are bf16 roundings of float32 results; nearly all rows match bit for bit
+    want_meta = P.ora.v_scale_bits[:, :, sl].astype(np.uint32) | (P.ora.v_zero_bits[:, :, sl].astype(np.uint32) << 16)
+    same = gm[:, :, sl] == want_meta
+    assert same.mean() > 0.98
+    dv = np.abs(gv[:, :, sl].astype(int) - P.ora.v_codes[:, :, sl].astype(int))
+    for gi, g in enumerate(O.group_slices(r_v)):
+        rows = same[..., gi]
+        assert dv[..., g][rows].max() <= 1 and (dv[..., g][rows] > 0).mean() < 0.01
+    # where a range differs, the dequantised rows still agree within one step
+    g_s = O.bf16_bits_to_f64((gm[:, :, sl] & 0xffff).astype(np.uint16))
+    g_z = O.bf16_bits_to_f64((gm[:, :, sl] >> 16).astype(np.uint16))
+    o_s = O.bf16_bits_to_f64(P.ora.v_scale_bits[:, :, sl])
+    o_z = O.bf16_bits_to_f64(P.ora.v_zero_bits[:, :, sl])
+    for b in range(batch):
+        for h in range(4):
+            a = O.dequantize(gv[b, h, sl], g_s[b, h], g_z[b, h])
+            c = O.dequantize(P.ora.v_codes[b, h, sl], o_s[b, h], o_z[b, h])
+            step = np.repeat(np.maximum(g_s[b, h], o_s[b, h]), [g.stop - g.start for g in O.group_slices(r_v)], axis=1)
+            assert np.all(np.abs(a - c) <= 1.51 * step)
+    # untouched rows keep their contents
+    rest = np.ones(P.capacity, bool)
+    rest[sl] = False
+    assert np.all(gk[:, :, rest] == 201) and np.all(gv[:, :, rest] == 202)
+    assert np.all(P.gpu.v_meta.cpu().numpy()[:, :, rest] == -7)
+
+
+@pytest.mark.parametrize("r_k,r_v", [(64, 64), (32, 32), (96, 128), (128, 96), (32, 128)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2)])
+def test_quantised_decode_matches_oracle_on_identical_cache_bytes(r_k, r_v, hq, hkv):
+    n = 1337
+    P = QPair(("qdec", r_k, r_v, hq), 2, hq, hkv, r_k, r_v, n)
+    k, v = P.raw_kv(2, n)
+    P.oracle_append(k, v, 0)
+    P.upload_oracle_cache(n)
+    q = P.queries(3)
+    out = torch.empty((2, hq, 128), dtype=torch.float32, device="cuda")
+    for n_ctx in (n, 65, 1):
+        B.skv_q8_decode_attention(P.gpu, q, out, n_ctx)
+        torch.cuda.synchronize()
+        assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
+
+
+def test_quantised_decode_steps_end_to_end():
+    # append through the library, then a few fused decode steps; both sides keep their own caches
+    n0, steps = 900, 3
+    P = QPair(("qe2e",), 2, 8, 2, 64, 64, n0 + steps)
+    k, v = P.raw_kv(4, n0)
+    B.skv_q8_project_append(P.gpu, k, v, 0)
+    P.oracle_append(k, v, 0)
+    out = torch.empty((2, 8, 128), dtype=torch.float32, device="cuda")
+    for s in range(steps):
+        k1, v1 = P.raw_kv(("s", s), 1)
+        q = P.queries(("s", s))
+        B.skv_q8_decode_step(P.gpu, k1, v1, n0 + s, q, out)
+        torch.cuda.synchronize()
+        P.oracle_append(k1, v1, n0 + s)
+        # a handful of codes may differ by one between the two caches: well inside the tolerance
+        assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n0 + s + 1)) <= TOL
+    assert B.skv_q8_cache_bytes(P.gpu, 1000) == 2 * 2 * 1000 * (128 + 4)
