@@ -221,6 +221,12 @@ skv_status skv_q8_decode_step(const skv_q8_layer* layer,
                               int32_t T, int64_t cur_len,
                               const void* q, void* out, float scale,
                               void* workspace, size_t workspace_bytes, void* stream);
+/* Stages of skv_q8_decode_attention (see skv_decode_project_query / skv_decode_partial); the
+ * third stage is skv_decode_combine(&layer->base, ...), which does not depend on the format. */
+skv_status skv_q8_decode_project_query(const skv_q8_layer* layer, const void* q, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_q8_decode_partial(const skv_q8_layer* layer, int64_t n_ctx, int32_t n_splits,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 /* Bytes the quantised cache of one layer holds for n tokens (codes + value metadata). */
 size_t skv_q8_cache_bytes(const skv_q8_layer* layer, int64_t n_tokens);
 

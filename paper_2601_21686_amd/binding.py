@@ -27,6 +27,7 @@ EXPORTS = (
     "skv_decode_partial", "skv_decode_combine",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
+    "skv_q8_decode_project_query", "skv_q8_decode_partial",
 )
 
 
@@ -96,6 +97,10 @@ def lib() -> C.CDLL:
     L.skv_q8_decode_attention.restype = C.c_int
     L.skv_q8_decode_step.argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_q8_decode_step.restype = C.c_int
+    L.skv_q8_decode_project_query.argtypes = [QP, vp, C.c_float, vp, sz, vp]
+    L.skv_q8_decode_project_query.restype = C.c_int
+    L.skv_q8_decode_partial.argtypes = [QP, i64, i32, vp, sz, vp]
+    L.skv_q8_decode_partial.restype = C.c_int
     L.skv_q8_cache_bytes.argtypes = [QP, i64]
     L.skv_q8_cache_bytes.restype = sz
     L.skv_status_string.argtypes = [C.c_int]
@@ -194,6 +199,11 @@ def _ref(layer):
     return C.byref(layer.c if isinstance(layer, (Layer, QuantLayer)) else layer)
 
 
+def _base_ref(layer):
+    """The plain skv_layer of a Layer or of a QuantLayer (for calls that do not depend on the format)."""
+    return C.byref(layer.c.base) if isinstance(layer, QuantLayer) else _ref(layer)
+
+
 # ---- the C ABI, same names -------------------------------------------------
 
 
@@ -208,11 +218,11 @@ def skv_project_append(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len:
 
 
 def skv_decode_workspace_bytes(layer) -> int:
-    return int(lib().skv_decode_workspace_bytes(_ref(layer)))
+    return int(lib().skv_decode_workspace_bytes(_base_ref(layer)))
 
 
 def skv_decode_default_splits(layer, n_ctx: int) -> int:
-    return int(lib().skv_decode_default_splits(_ref(layer), int(n_ctx)))
+    return int(lib().skv_decode_default_splits(_base_ref(layer), int(n_ctx)))
 
 
 def skv_decode_range(n_ctx: int, n_splits: int, rng: int):
@@ -264,7 +274,7 @@ def skv_decode_partial(layer, n_ctx: int, n_splits: int = 0, workspace: torch.Te
 def skv_decode_combine(layer, out: torch.Tensor, n_splits: int, workspace: torch.Tensor | None = None,
                        stream=None) -> None:
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_decode_combine(_ref(layer), out.data_ptr(), int(n_splits), ws.data_ptr(),
+    _check(lib().skv_decode_combine(_base_ref(layer), out.data_ptr(), int(n_splits), ws.data_ptr(),
                                     ws.numel() * ws.element_size(), _stream_ptr(stream)),
            "skv_decode_combine")
 
@@ -322,6 +332,22 @@ def skv_q8_decode_step(layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tens
                                     int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
                                     float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
                                     _stream_ptr(stream)), "skv_q8_decode_step")
+
+
+def skv_q8_decode_project_query(layer: QuantLayer, q: torch.Tensor, scale: float = 0.0,
+                                workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_q8_decode_project_query(_ref(layer), q.data_ptr(), float(scale), ws.data_ptr(),
+                                             ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_q8_decode_project_query")
+
+
+def skv_q8_decode_partial(layer: QuantLayer, n_ctx: int, n_splits: int = 0,
+                          workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_q8_decode_partial(_ref(layer), int(n_ctx), int(n_splits), ws.data_ptr(),
+                                       ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_q8_decode_partial")
 
 
 def skv_q8_cache_bytes(layer: QuantLayer, n_tokens: int) -> int:

@@ -464,6 +464,28 @@ skv_status skv_q8_decode_attention(const skv_q8_layer* Q, const void* q, void* o
   return run_combine(L, out, s, workspace, stream);
 }
 
+skv_status skv_q8_decode_project_query(const skv_q8_layer* Q, const void* q, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_q8_layer(Q);
+  if (st != SKV_OK) return st;
+  st = check_query_stage(&Q->base, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  DecodeParams p;
+  fill_q8_query(Q, &p, q, scale, workspace);
+  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_q8_decode_partial(const skv_q8_layer* Q, int64_t n_ctx, int32_t n_splits,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_q8_layer(Q);
+  if (st != SKV_OK) return st;
+  int32_t s = 0;
+  st = check_partial_stage(&Q->base, n_ctx, n_splits, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  return run_partial(&Q->base, n_ctx, s, workspace, stream, Q);
+}
+
 skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const void* v_new,
                               int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
                               int64_t cur_len, const void* q, void* out, float scale,

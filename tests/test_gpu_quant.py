@@ -114,6 +114,14 @@ def test_quantised_decode_matches_oracle_on_identical_cache_bytes(r_k, r_v, hq, 
         B.skv_q8_decode_attention(P.gpu, q, out, n_ctx)
         torch.cuda.synchronize()
         assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
+    # the three stages called one by one give the same bits as the fused call
+    ref = out.clone()
+    s_ = B.skv_decode_default_splits(P.gpu, 1)
+    B.skv_q8_decode_project_query(P.gpu, q, 0.0)
+    B.skv_q8_decode_partial(P.gpu, 1, s_)
+    B.skv_decode_combine(P.gpu, out, s_)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)
 
 
 def test_quantised_decode_steps_end_to_end():
