@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
+    ap.add_argument("--cache", choices=("bf16", "q8"), default="bf16",
+                    help="bf16: the benchmarked configuration; q8: the 8-bit quantised compressed cache "
+                         "(keys with static per-head group ranges, values with per-token group ranges)")
     ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
@@ -47,9 +50,10 @@ def parse_args():
     return ap.parse_args()
 
 
-def read_traffic(workload: str):
+def read_traffic(workload: str, cache: str = "bf16"):
     """HBM bytes per launch of the decode range kernel, from the committed counter summary."""
-    path = os.path.join(ROOT, "profiles", f"decode_partial_{workload}_traffic.txt")
+    tag = "" if cache == "bf16" else f"_{cache}"
+    path = os.path.join(ROOT, "profiles", f"decode_partial{tag}_{workload}_traffic.txt")
     if not os.path.exists(path):
         return None
     vals = {}
@@ -140,13 +144,38 @@ def main():
     cap = wl.n_ctx + K + 8
     assert n0 >= 1
 
-    layers, scales = [], []
+    q8 = args.cache == "q8"
+    append_fn = B.skv_q8_project_append if q8 else B.skv_project_append
+    step_fn = B.skv_q8_decode_step if q8 else B.skv_decode_step
+
+    def row_bytes(li):
+        """Bytes one cached token of one KV head occupies in layer li."""
+        if q8:
+            return ranks_k[li] + ranks_v[li] + 4 * ((ranks_v[li] + 63) // 64)
+        return 2 * (ranks_k[li] + ranks_v[li])
+
+    layers, scales, k_ranges = [], [], []
     for li in range(wl.n_layers):
         _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, li, "pk"), HKV, d, ranks_k[li])
         _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, li, "pv"), HKV, d, ranks_v[li])
-        layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
         scales.append((synth.channel_scales(synth.stable_seed(wl.name, li, "sk"), HKV, d),
                        synth.channel_scales(synth.stable_seed(wl.name, li, "sv"), HKV, d)))
+        if q8:
+            # The caller's calibration: static key ranges per KV head and 64-channel group, from the
+            # minimum and maximum of a seeded sample of projected keys (plain torch, not timed).
+            cal = synth.kv_activations(synth.stable_seed(wl.name, li, "cal"), 1, 2048, HKV, d, scales[li][0], dev)
+            proj = torch.einsum("thd,hdc->htc", cal[0].float(), pk.to(dev).float())          # [H, t, r_k]
+            groups = [(g0, min(g0 + 64, ranks_k[li])) for g0 in range(0, ranks_k[li], 64)]
+            lo = torch.stack([proj[:, :, a:b].amin(dim=(1, 2)) for a, b in groups], dim=1)
+            hi = torch.stack([proj[:, :, a:b].amax(dim=(1, 2)) for a, b in groups], dim=1)
+            # a margin of half the observed span on either side: rows outside it would clamp
+            span = hi - lo
+            lo, hi = lo - 0.5 * span, hi + 0.5 * span
+            ksc, kzr = ((hi - lo) / 255.0).contiguous(), lo.contiguous()
+            k_ranges.append((ksc, kzr))
+            layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap))
+        else:
+            layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
 
     # Prefill the caches through the library's own append (chunks on the matrix cores).
     CH = 4096
@@ -155,7 +184,7 @@ def main():
             t = min(CH, n0 - c0)
             k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
             v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
-            B.skv_project_append(L, k, v, c0)
+            append_fn(L, k, v, c0)
     torch.cuda.synchronize()
 
     # Per-step inputs: one new token per sequence and layer, one query per head.
@@ -172,7 +201,7 @@ def main():
     def step(s: int):
         cur = n0 + s
         for li, L in enumerate(layers):
-            B.skv_decode_step(L, new_k[li][:, s:s + 1], new_v[li][:, s:s + 1], cur, qs[s, li], outs[s, li], 0.0, ws)
+            step_fn(L, new_k[li][:, s:s + 1], new_v[li][:, s:s + 1], cur, qs[s, li], outs[s, li], 0.0, ws)
 
     for s in range(W):
         step(s)
@@ -207,7 +236,7 @@ def main():
     for s in range(W, W + K):
         n_ctx = n0 + s + 1
         for li in range(wl.n_layers):
-            bytes_steps += Bt * HKV * n_ctx * (ranks_k[li] + ranks_v[li]) * 2
+            bytes_steps += Bt * HKV * n_ctx * row_bytes(li)
     gbps = bytes_steps / elapsed / 1e9
     tokens_per_s = Bt * K / elapsed
 
@@ -217,22 +246,23 @@ def main():
     Lr = layers[li_big]
     n_roof = wl.n_ctx
     splits = args.splits if args.splits > 0 else B.skv_decode_default_splits(Lr, n_roof)
-    B.skv_decode_project_query(Lr, qs[0, li_big], 0.0, ws)
+    partial_fn = B.skv_q8_decode_partial if q8 else B.skv_decode_partial
+    (B.skv_q8_decode_project_query if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
     for _ in range(10):
-        B.skv_decode_partial(Lr, n_roof, splits, ws)
+        partial_fn(Lr, n_roof, splits, ws)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(args.kernel_iters):
-        B.skv_decode_partial(Lr, n_roof, splits, ws)
+        partial_fn(Lr, n_roof, splits, ws)
     e1.record()
     torch.cuda.synchronize()
     kern_ms = e0.elapsed_time(e1) / args.kernel_iters
     # algorithmic bytes of one launch: every cache row once per KV head, the projected
     # queries in, the per-range partial results out
     rk, rv = ranks_k[li_big], ranks_v[li_big]
-    kern_bytes = Bt * HKV * n_roof * (rk + rv) * 2 + Bt * HQ * rk * 4 + Bt * HQ * splits * (rv + 2) * 4
+    kern_bytes = Bt * HKV * n_roof * row_bytes(li_big) + Bt * HQ * rk * 4 + Bt * HQ * splits * (rv + 2) * 4
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
 
     result = {
@@ -253,11 +283,11 @@ def main():
                    "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
-                   "cache": "bf16", "step": "append 1 token/sequence + decode attention, every layer",
+                   "cache": "8-bit codes, group 64" if q8 else "bf16", "step": "append 1 token/sequence + decode attention, every layer",
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": read_traffic(wl.name), "bytes_per_launch": kern_bytes,
+                     "traffic": read_traffic(wl.name, args.cache), "bytes_per_launch": kern_bytes,
                      "us_per_launch": round(kern_ms * 1e3, 3), "n_ctx": n_roof, "r_k": rk, "r_v": rv,
                      "splits": splits},
     }
@@ -274,24 +304,30 @@ def main():
         li = 0
         s_chk = W + K - 1                                  # the last timed step
         n_chk = n0 + s_chk + 1
-        ora = O.new_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v), n_chk, store="bf16")
+        if q8:
+            ora = O.new_quant_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v),
+                                    k_ranges[li][0].cpu().numpy(), k_ranges[li][1].cpu().numpy(), n_chk)
+            ora_append, ora_decode = O.quant_project_append, O.quant_decode_attention
+        else:
+            ora = O.new_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v), n_chk, store="bf16")
+            ora_append, ora_decode = O.project_append, O.decode_attention
         for c0 in range(0, n0, CH):                        # same seeded raw inputs as the GPU prefill
             t = min(CH, n0 - c0)
             k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
             v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
-            O.project_append(ora, f64(k), f64(v), c0)
-        O.project_append(ora, f64(new_k[li][:, :s_chk + 1]), f64(new_v[li][:, :s_chk + 1]), n0)
+            ora_append(ora, f64(k), f64(v), c0)
+        ora_append(ora, f64(new_k[li][:, :s_chk + 1]), f64(new_v[li][:, :s_chk + 1]), n0)
         # bounded sample: the last timed steps, newest first, for about 12 s of host time
         budget_s, spent, errs, cpu_bytes, n_done = 12.0, 0.0, [], 0, 0
         for s_i in range(s_chk, W - 1, -1):
             n_i = n0 + s_i + 1
             qh = f64(qs[s_i, li])
             tb = time.perf_counter()
-            want = O.decode_attention(ora, qh, n_i)
+            want = ora_decode(ora, qh, n_i)
             spent += time.perf_counter() - tb
             got = outs[s_i, li].cpu().numpy().astype(np.float64)
             errs.append(float(np.max(np.max(np.abs(got - want), axis=-1) / np.max(np.abs(want), axis=-1))))
-            cpu_bytes += Bt * HKV * n_i * (ranks_k[li] + ranks_v[li]) * 2
+            cpu_bytes += Bt * HKV * n_i * row_bytes(li)
             n_done += 1
             if spent >= budget_s:
                 break
