@@ -15,6 +15,7 @@ Everything below is the paper's definition written out with numpy float64:
   * cache-size ratio       CR = (r_K + r_V) / (2 d_h)          (Sec. 2.1, Eq. 3)
   * sequential budgeted rank selection                         (Sec. 3.5, Eqs. 15-17; App. B, Alg. 2)
   * asymmetric integer quantisation of the compressed cache    (Sec. 4.3; 8 bits, group 64)
+  * the folded-weights variant: attention in the compressed space (Sec. 3.4 "Overheads")
 
 Readings taken where the paper is silent (all listed in the design notes):
 the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
@@ -256,6 +257,52 @@ def decode_attention_factored(layer: OracleLayer, q: np.ndarray, n_ctx: int,
             p = w / np.sum(w)
             a_low = p @ layer.v_cache[b, kv, :n_ctx, :]           # [r_V]
             out[b, h] = layer.basis_v(kv) @ a_low                 # [d_h]
+    return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.4 "Overheads": projections folded into the attention linear weights
+# --------------------------------------------------------------------------
+#
+# The paper notes that P_K and P_V can be folded into the attention linear
+# layers (W_K P_K, W_V P_V, W_Q P_K on the way in, P_V^T W_O on the way out).
+# The model then hands over rows that are already projected and takes the
+# attention output in rank-r_V coordinates; what is left of the path is
+# attention in the compressed space, with the scale of the ORIGINAL head dim:
+#     a_low = softmax(q_low K_down^T / sqrt(d_h)) V_down.
+
+
+def append_projected(layer: OracleLayer, k_low: np.ndarray, v_low: np.ndarray, cur_len: int) -> None:
+    """Store T already-projected tokens at rows [cur_len, cur_len + T).
+    k_low: [batch, T, n_kv_heads, r_k], v_low: [batch, T, n_kv_heads, r_v]; rounded
+    once to bf16 when the layer stores bf16."""
+    k_low, v_low = np.asarray(k_low, np.float64), np.asarray(v_low, np.float64)
+    B, T, H, _ = k_low.shape
+    if cur_len < 0 or cur_len + T > layer.capacity:
+        raise ValueError("append exceeds capacity")
+    kd = np.transpose(k_low, (0, 2, 1, 3))
+    vd = np.transpose(v_low, (0, 2, 1, 3))
+    if layer.store == "bf16":
+        kd, vd = round_to_bf16(kd), round_to_bf16(vd)
+    layer.k_cache[:, :, cur_len:cur_len + T, :] = kd
+    layer.v_cache[:, :, cur_len:cur_len + T, :] = vd
+
+
+def decode_attention_folded(layer: OracleLayer, q_low: np.ndarray, n_ctx: int,
+                            scale: float | None = None) -> np.ndarray:
+    """Attention in the compressed space.  q_low: [batch, n_q_heads, r_k] (the
+    query already multiplied by P_K); returns [batch, n_q_heads, r_v], to be
+    lifted by the caller's folded output projection.  Bases are not used."""
+    q_low = np.asarray(q_low, np.float64)
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.empty((layer.batch, layer.n_q_heads, layer.r_v), np.float64)
+    for b in range(layer.batch):
+        for h in range(layer.n_q_heads):
+            kv = h // G
+            out[b, h] = attention_single_query(q_low[b, h], layer.k_cache[b, kv, :n_ctx, :],
+                                               layer.v_cache[b, kv, :n_ctx, :], scale)
     return out
 
 

@@ -289,3 +289,48 @@ def test_cache_size_example_printed_in_the_introduction(golden_dir):
     assert half == full * O.compression_ratio(64, 64, 128)
     # one layer of the batch-4 / 32K workload at rank 64/64 is 256 MiB
     assert O.kv_cache_bytes(1, 8, 32768, 4, 64, 64) == 256 * 2 ** 20
+
+
+# ------------------------------------- Sec. 3.4: folded projections ----
+
+def test_folded_variant_equals_the_explicit_path():
+    rng = np.random.default_rng(20)
+    B, HQ, HKV, d, rk, rv, n = 2, 8, 2, 32, 12, 20, 150
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, rk, rv, n)
+    q = rng.standard_normal((B, HQ, d))
+    G = HQ // HKV
+    # what a model with folded weights would hand over
+    q_low = np.stack([[q[b, h] @ L.p_k[h // G] for h in range(HQ)] for b in range(B)])
+    k_low = np.einsum("bnhd,hdc->bnhc", K, L.p_k)
+    v_low = np.einsum("bnhd,hdc->bnhc", V, L.p_v)
+    F = O.new_layer(B, HQ, HKV, d, L.p_k, L.p_v, n, store="f64")
+    O.append_projected(F, k_low, v_low, 0)
+    assert np.allclose(F.k_cache, L.k_cache, rtol=1e-13, atol=1e-14)
+    a_low = O.decode_attention_folded(F, q_low, 131)
+    assert a_low.shape == (B, HQ, rv)
+    lifted = np.stack([[L.p_v[h // G] @ a_low[b, h] for h in range(HQ)] for b in range(B)])
+    assert np.allclose(lifted, O.decode_attention(L, q, 131), rtol=1e-12, atol=1e-13)
+
+
+def test_folded_variant_is_library_attention_in_rank_space_with_head_dim_scale():
+    rng = np.random.default_rng(21)
+    B, HQ, HKV, d, rk, rv, n = 1, 6, 3, 64, 16, 24, 40
+    L = O.new_layer(B, HQ, HKV, d, np.zeros((HKV, d, rk)), np.zeros((HKV, d, rv)), n, store="f64")
+    k_low = rng.standard_normal((B, n, HKV, rk))
+    v_low = rng.standard_normal((B, n, HKV, rv))
+    O.append_projected(L, k_low, v_low, 0)
+    q_low = rng.standard_normal((B, HQ, rk))
+    G = HQ // HKV
+    tq = torch.from_numpy(q_low)[:, :, None, :]
+    tk = torch.from_numpy(k_low).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    tv = torch.from_numpy(v_low).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    # the scale is 1/sqrt(head_dim) = 1/8, not 1/sqrt(r_k) = 1/4
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=1.0 / 8.0)[:, :, 0].numpy()
+    assert np.allclose(O.decode_attention_folded(L, q_low, n), want, rtol=1e-12, atol=1e-13)
+    wrong = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[:, :, 0].numpy()
+    assert not np.allclose(O.decode_attention_folded(L, q_low, n), wrong, rtol=1e-3)
+    # bf16 storage rounds the handed-over rows once
+    Lb = O.new_layer(B, HQ, HKV, d, np.zeros((HKV, d, rk)), np.zeros((HKV, d, rv)), n, store="bf16", fill=5.0)
+    O.append_projected(Lb, k_low[:, :7], v_low[:, :7], 3)
+    assert np.array_equal(Lb.k_cache[:, :, 3:10], O.round_to_bf16(np.transpose(k_low[:, :7], (0, 2, 1, 3))))
+    assert np.all(Lb.k_cache[:, :, :3] == 5.0) and np.all(Lb.v_cache[:, :, 10:] == 5.0)
