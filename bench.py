@@ -43,6 +43,10 @@ def parse_args():
     ap.add_argument("--cache", choices=("bf16", "q8"), default="bf16",
                     help="bf16: the benchmarked configuration; q8: the 8-bit quantised compressed cache "
                          "(keys with static per-head group ranges, values with per-token group ranges)")
+    ap.add_argument("--variant", choices=("explicit", "folded"), default="explicit",
+                    help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
+                         "folded: the bases are folded into the model's linear layers (Sec. 3.4), so rows and queries "
+                         "arrive projected and the output stays in rank-r_V coordinates")
     ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
@@ -145,6 +149,16 @@ def main():
     assert n0 >= 1
 
     q8 = args.cache == "q8"
+    folded = args.variant == "folded"
+    if folded and q8:
+        print("bench.py: --variant folded runs over the bf16 cache only", file=sys.stderr)
+        sys.exit(2)
+
+    def low(x, basis):
+        """Stand-in for a model whose linear layers carry the bases: [..., H, d] x [H, d, r] -> bf16 [..., H, r]
+        (plain torch, outside every timed region)."""
+        return torch.einsum("...hd,hdc->...hc", x.float(), basis.to(x.device).float()).to(torch.bfloat16).contiguous()
+
     append_fn = B.skv_q8_project_append if q8 else B.skv_project_append
     step_fn = B.skv_q8_decode_step if q8 else B.skv_decode_step
 
@@ -184,7 +198,10 @@ def main():
             t = min(CH, n0 - c0)
             k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
             v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
-            append_fn(L, k, v, c0)
+            if folded:
+                B.skv_append_projected(L, low(k, L.p_k), low(v, L.p_v), c0)
+            else:
+                append_fn(L, k, v, c0)
     torch.cuda.synchronize()
 
     # Per-step inputs: one new token per sequence and layer, one query per head.
@@ -198,10 +215,22 @@ def main():
     outs = torch.empty((n_steps_total, wl.n_layers, Bt, HQ, d), dtype=torch.float32, device=dev)
     ws = torch.empty(max(B.skv_decode_workspace_bytes(L) for L in layers), dtype=torch.uint8, device=dev)
 
+    if folded:
+        G = HQ // HKV
+        # per layer: [step][batch][1][H_KV][r] rows, [step][batch][H_Q][r_k] queries, [step][batch][H_Q][r_v] outputs
+        nk_low = [low(new_k[li], L.p_k).transpose(0, 1).unsqueeze(2).contiguous() for li, L in enumerate(layers)]
+        nv_low = [low(new_v[li], L.p_v).transpose(0, 1).unsqueeze(2).contiguous() for li, L in enumerate(layers)]
+        q_low = [low(qs[:, li], L.p_k.repeat_interleave(G, dim=0)) for li, L in enumerate(layers)]
+        outs_low = [torch.empty((n_steps_total, Bt, HQ, ranks_v[li]), dtype=torch.float32, device=dev)
+                    for li in range(wl.n_layers)]
+
     def step(s: int):
         cur = n0 + s
         for li, L in enumerate(layers):
-            step_fn(L, new_k[li][:, s:s + 1], new_v[li][:, s:s + 1], cur, qs[s, li], outs[s, li], 0.0, ws)
+            if folded:
+                B.skv_decode_step_folded(L, nk_low[li][s], nv_low[li][s], cur, q_low[li][s], outs_low[li][s], 0.0, ws)
+            else:
+                step_fn(L, new_k[li][:, s:s + 1], new_v[li][:, s:s + 1], cur, qs[s, li], outs[s, li], 0.0, ws)
 
     for s in range(W):
         step(s)
@@ -283,7 +312,9 @@ def main():
                    "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
-                   "cache": "8-bit codes, group 64" if q8 else "bf16", "step": "append 1 token/sequence + decode attention, every layer",
+                   "cache": "8-bit codes, group 64" if q8 else "bf16", "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
+                            else "append 1 token/sequence + decode attention, every layer"),
+                   "variant": args.variant,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
@@ -311,21 +342,27 @@ def main():
         else:
             ora = O.new_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v), n_chk, store="bf16")
             ora_append, ora_decode = O.project_append, O.decode_attention
+        if folded:
+            # the oracle is handed the same projected bf16 rows and queries as the library
+            ora_append = lambda lay, k_, v_, c_: O.append_projected(lay, f64(low(k_, layers[li].p_k)),
+                                                                    f64(low(v_, layers[li].p_v)), c_)
+            ora_decode = O.decode_attention_folded
         for c0 in range(0, n0, CH):                        # same seeded raw inputs as the GPU prefill
             t = min(CH, n0 - c0)
             k = synth.kv_activations(synth.stable_seed(wl.name, li, "k", c0), Bt, t, HKV, d, scales[li][0], dev)
             v = synth.kv_activations(synth.stable_seed(wl.name, li, "v", c0), Bt, t, HKV, d, scales[li][1], dev)
-            ora_append(ora, f64(k), f64(v), c0)
-        ora_append(ora, f64(new_k[li][:, :s_chk + 1]), f64(new_v[li][:, :s_chk + 1]), n0)
+            ora_append(ora, k if folded else f64(k), v if folded else f64(v), c0)
+        nk_, nv_ = new_k[li][:, :s_chk + 1], new_v[li][:, :s_chk + 1]
+        ora_append(ora, nk_ if folded else f64(nk_), nv_ if folded else f64(nv_), n0)
         # bounded sample: the last timed steps, newest first, for about 12 s of host time
         budget_s, spent, errs, cpu_bytes, n_done = 12.0, 0.0, [], 0, 0
         for s_i in range(s_chk, W - 1, -1):
             n_i = n0 + s_i + 1
-            qh = f64(qs[s_i, li])
+            qh = f64(q_low[li][s_i]) if folded else f64(qs[s_i, li])
             tb = time.perf_counter()
             want = ora_decode(ora, qh, n_i)
             spent += time.perf_counter() - tb
-            got = outs[s_i, li].cpu().numpy().astype(np.float64)
+            got = (outs_low[li][s_i] if folded else outs[s_i, li]).cpu().numpy().astype(np.float64)
             errs.append(float(np.max(np.max(np.abs(got - want), axis=-1) / np.max(np.abs(want), axis=-1))))
             cpu_bytes += Bt * HKV * n_i * row_bytes(li)
             n_done += 1

@@ -179,6 +179,36 @@ skv_status skv_decode_combine(const skv_layer* layer, void* out, int32_t n_split
                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ---- Folded-weights variant (Sec. 3.4 "Overheads") --------------------------
+ * The paper notes that P_K and P_V can be folded into the attention linear
+ * layers; the model then produces projected rows itself and consumes the
+ * attention output in rank-r_V coordinates (its output projection carries
+ * P_V^T).  What is left is attention in the compressed space, still with the
+ * scale of the ORIGINAL head dimension:
+ *     out_low[b][h][:] = softmax_j( scale * <q_low[b][h], K_down[b][kv][j]> ) . V_down[b][kv][0:n_ctx]
+ * layer->p_k and layer->p_v are not used and may be NULL.
+ *
+ * skv_append_projected: stores T already-projected tokens per sequence at rows
+ * [cur_len, cur_len + T) (a bit-exact copy).
+ *   k_low  device bf16 [batch][T][n_kv_heads][r_k], packed;  v_low likewise with r_v
+ * skv_decode_attention_folded:
+ *   q_low    device bf16 [batch][n_q_heads][r_k]
+ *   out_low  device float32 [batch][n_q_heads][r_v]
+ * skv_decode_step_folded: both for one decode step (rows placed by the same
+ *   small launch that scales the queries); attends cur_len + T tokens.
+ * Other arguments, workspace and errors as for skv_project_append /
+ * skv_decode_attention / skv_decode_step.
+ */
+skv_status skv_append_projected(const skv_layer* layer, const void* k_low, const void* v_low,
+                                int32_t T, int64_t cur_len, void* stream);
+skv_status skv_decode_attention_folded(const skv_layer* layer, const void* q_low, void* out_low,
+                                       int64_t n_ctx, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_decode_step_folded(const skv_layer* layer, const void* k_low, const void* v_low,
+                                  int32_t T, int64_t cur_len, const void* q_low, void* out_low,
+                                  float scale, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * ---- 8-bit quantised compressed cache (Sec. 4.3) --------------------------
  * Asymmetric integer quantisation of the compressed rows, group size 64
  * channels (the last group of a row may be shorter): code =

@@ -28,6 +28,7 @@ EXPORTS = (
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
+    "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
 )
 
 
@@ -103,6 +104,12 @@ def lib() -> C.CDLL:
     L.skv_q8_decode_partial.restype = C.c_int
     L.skv_q8_cache_bytes.argtypes = [QP, i64]
     L.skv_q8_cache_bytes.restype = sz
+    L.skv_append_projected.argtypes = [LP, vp, vp, i32, i64, vp]
+    L.skv_append_projected.restype = C.c_int
+    L.skv_decode_attention_folded.argtypes = [LP, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_decode_attention_folded.restype = C.c_int
+    L.skv_decode_step_folded.argtypes = [LP, vp, vp, i32, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_decode_step_folded.restype = C.c_int
     L.skv_status_string.argtypes = [C.c_int]
     L.skv_status_string.restype = C.c_char_p
     _lib = L
@@ -299,6 +306,37 @@ def skv_layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, de
     if code not in (SKV_OK, SKV_ERR_BUDGET):
         raise SkvError(code, "skv_layer_ranks")
     return list(rk), list(rv), float(ach.value), code == SKV_OK
+
+
+# ---- folded-weights variant ------------------------------------------------------
+
+
+def skv_append_projected(layer, k_low: torch.Tensor, v_low: torch.Tensor, cur_len: int, stream=None) -> None:
+    """k_low: bf16 [batch, T, n_kv_heads, r_k] contiguous; v_low likewise with r_v."""
+    assert k_low.dtype == torch.bfloat16 and v_low.dtype == torch.bfloat16
+    assert k_low.is_contiguous() and v_low.is_contiguous()
+    _check(lib().skv_append_projected(_base_ref(layer), k_low.data_ptr(), v_low.data_ptr(), int(k_low.shape[1]),
+                                      int(cur_len), _stream_ptr(stream)), "skv_append_projected")
+
+
+def skv_decode_attention_folded(layer, q_low: torch.Tensor, out_low: torch.Tensor, n_ctx: int,
+                                scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+    """q_low: bf16 [batch, n_q_heads, r_k]; out_low: float32 [batch, n_q_heads, r_v]."""
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_attention_folded(_base_ref(layer), q_low.data_ptr(), out_low.data_ptr(), int(n_ctx),
+                                             float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                             _stream_ptr(stream)), "skv_decode_attention_folded")
+
+
+def skv_decode_step_folded(layer, k_low: torch.Tensor, v_low: torch.Tensor, cur_len: int, q_low: torch.Tensor,
+                           out_low: torch.Tensor, scale: float = 0.0, workspace: torch.Tensor | None = None,
+                           stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    assert k_low.is_contiguous() and v_low.is_contiguous()
+    _check(lib().skv_decode_step_folded(_base_ref(layer), k_low.data_ptr(), v_low.data_ptr(), int(k_low.shape[1]),
+                                        int(cur_len), q_low.data_ptr(), out_low.data_ptr(), float(scale),
+                                        ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_step_folded")
 
 
 # ---- 8-bit quantised cache ------------------------------------------------------

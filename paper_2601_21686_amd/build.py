@@ -37,6 +37,7 @@ def _jobs():
     jobs = [("skv_host.o", [os.path.join(CSRC, "skv_host.cpp")], []),
             ("skv_decode_combine.o", ["-x", "hip", os.path.join(CSRC, "skv_decode_combine.hip")], DEVICE_FLAGS),
             ("skv_project.o", ["-x", "hip", os.path.join(CSRC, "skv_project.hip")], DEVICE_FLAGS),
+            ("skv_folded.o", ["-x", "hip", os.path.join(CSRC, "skv_folded.hip")], DEVICE_FLAGS),
             ("skv_append.o", ["-x", "hip", os.path.join(CSRC, "skv_append.hip")], DEVICE_FLAGS)]
     for rk in KEY_RANKS:
         jobs.append((f"skv_decode_partial_rk{rk}.o",

@@ -38,12 +38,13 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
   const float* pa = p.part_acc + (int64_t)bh * S * RV;
 
   // ---- every request first -----------------------------------------------------------------
+  const bool lift = p.lift != 0;                 // folded-weights callers take the rank-r_V result as it is
   const uint4* prow = reinterpret_cast<const uint4*>(p.p_v + (int64_t)kv * p.p_v_head_stride + (int64_t)tid * RV);
   const int nc8 = RV >> 3;
   uint4 pv[SKV_HEAD_DIM / 8];
 #pragma unroll
   for (int k = 0; k < SKV_HEAD_DIM / 8; ++k)
-    if (k < nc8) pv[k] = prow[k];
+    if (lift && k < nc8) pv[k] = prow[k];
   float2 mlr[kMlPerThread];
 #pragma unroll
   for (int k = 0; k < kMlPerThread; ++k) {
@@ -103,6 +104,10 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
     a_s[tid] = t / l;
   }
   __syncthreads();
+  if (!lift) {
+    if (tid < RV) p.out[(int64_t)bh * RV + tid] = a_s[tid];
+    return;
+  }
 
   // ---- out[d] = sum_c a[c] * P_V[kv][d][c] --------------------------------------------------
   float o = 0.f;

@@ -20,9 +20,11 @@ bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; 
 // 8 or 16 ranges per (sequence, KV head) are the fastest, 32 and 64 are slower.
 constexpr int kTargetWorkgroups = 512;
 
-skv_status check_layer(const skv_layer* L) {
+// need_bases = false: the folded-weights entry points, which never touch p_k / p_v.
+skv_status check_layer(const skv_layer* L, bool need_bases = true) {
   if (!L) return SKV_ERR_NULL;
-  if (!L->k_cache || !L->v_cache || !L->p_k || !L->p_v) return SKV_ERR_NULL;
+  if (!L->k_cache || !L->v_cache) return SKV_ERR_NULL;
+  if (need_bases && (!L->p_k || !L->p_v)) return SKV_ERR_NULL;
   if (L->head_dim != SKV_HEAD_DIM) return SKV_ERR_SHAPE;
   if (L->batch < 1 || L->n_kv_heads < 1 || L->n_q_heads < 1) return SKV_ERR_SHAPE;
   if (L->n_q_heads % L->n_kv_heads) return SKV_ERR_SHAPE;
@@ -33,11 +35,11 @@ skv_status check_layer(const skv_layer* L) {
   if (!rank_ok(L->r_k) || !rank_ok(L->r_v)) return SKV_ERR_RANK;
   if (L->capacity < 1 || L->capacity > std::numeric_limits<int32_t>::max()) return SKV_ERR_CAPACITY;
   const int64_t sk = L->p_k_head_stride, sv = L->p_v_head_stride;
-  if (sk != 0 && sk < (int64_t)SKV_HEAD_DIM * L->r_k) return SKV_ERR_SHAPE;
-  if (sv != 0 && sv < (int64_t)SKV_HEAD_DIM * L->r_v) return SKV_ERR_SHAPE;
-  if ((sk % 8) || (sv % 8)) return SKV_ERR_ALIGN;
-  if (!aligned16(L->k_cache) || !aligned16(L->v_cache) || !aligned16(L->p_k) || !aligned16(L->p_v))
-    return SKV_ERR_ALIGN;
+  if (need_bases && sk != 0 && sk < (int64_t)SKV_HEAD_DIM * L->r_k) return SKV_ERR_SHAPE;
+  if (need_bases && sv != 0 && sv < (int64_t)SKV_HEAD_DIM * L->r_v) return SKV_ERR_SHAPE;
+  if (need_bases && ((sk % 8) || (sv % 8))) return SKV_ERR_ALIGN;
+  if (!aligned16(L->k_cache) || !aligned16(L->v_cache)) return SKV_ERR_ALIGN;
+  if (need_bases && (!aligned16(L->p_k) || !aligned16(L->p_v))) return SKV_ERR_ALIGN;
   return SKV_OK;
 }
 
@@ -72,6 +74,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->n_ctx = 0;
   p->n_splits = n_splits;
   p->scale_log2e = 0.f;
+  p->lift = 1;
   p->k_scale = nullptr;
   p->v_meta = nullptr;
   char* ws = static_cast<char*>(workspace);
@@ -512,6 +515,96 @@ skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const vo
   st = run_partial(L, n_ctx, s, workspace, stream, Q);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// Folded-weights variant: the bases are not used.
+skv_status check_folded_append(const skv_layer* L, const void* k_low, const void* v_low, int32_t T, int64_t cur_len) {
+  const skv_status st = check_layer(L, false);
+  if (st != SKV_OK) return st;
+  if (T < 0) return SKV_ERR_SHAPE;
+  if (cur_len < 0 || cur_len + (int64_t)T > L->capacity) return SKV_ERR_CAPACITY;
+  if (T == 0) return SKV_OK;
+  if (!k_low || !v_low) return SKV_ERR_NULL;
+  if (!aligned16(k_low) || !aligned16(v_low)) return SKV_ERR_ALIGN;
+  if ((int64_t)L->batch * T > std::numeric_limits<int32_t>::max() / 64) return SKV_ERR_SHAPE;
+  return SKV_OK;
+}
+
+skv_status check_folded_decode(const skv_layer* L, const void* q_low, const void* out_low, int64_t n_ctx,
+                               float scale, const void* workspace, size_t workspace_bytes, int32_t* s_out) {
+  const skv_status st = check_layer(L, false);
+  if (st != SKV_OK) return st;
+  if (!q_low || !out_low || !workspace) return SKV_ERR_NULL;
+  if (!aligned16(q_low) || !aligned16(out_low) || !aligned16(workspace)) return SKV_ERR_ALIGN;
+  if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
+  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, s_out)) return SKV_ERR_SHAPE;
+  return check_decode_common(L, *s_out, workspace, workspace_bytes);
+}
+
+// Range kernel, then the merge of the ranges without the lift: out_low stays in rank-r_V coordinates.
+skv_status run_folded_attention(const skv_layer* L, void* out_low, int64_t n_ctx, int32_t s, void* workspace,
+                                void* stream) {
+  const skv_status st = run_partial(L, n_ctx, s, workspace, stream);
+  if (st != SKV_OK) return st;
+  DecodeParams cp;
+  fill_decode_params(L, &cp, s, workspace);
+  cp.out = static_cast<float*>(out_low);
+  cp.lift = 0;
+  if (launch_decode_combine(cp, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+skv_status skv_append_projected(const skv_layer* L, const void* k_low, const void* v_low, int32_t T,
+                                int64_t cur_len, void* stream) {
+  const skv_status st = check_folded_append(L, k_low, v_low, T, cur_len);
+  if (st != SKV_OK || T == 0) return st;
+  AppendParams p;
+  fill_append_params(L, &p, k_low, v_low, 0, 0, 0, T, cur_len);
+  if (launch_copy_projected(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_decode_attention_folded(const skv_layer* L, const void* q_low, void* out_low,
+                                       int64_t n_ctx, float scale, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  int32_t s = 0;
+  skv_status st = check_folded_decode(L, q_low, out_low, n_ctx, scale, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  DecodeParams qp;
+  fill_query_params(L, &qp, q_low, scale, workspace);
+  if (launch_scale_query(qp, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return run_folded_attention(L, out_low, n_ctx, s, workspace, stream);
+}
+
+skv_status skv_decode_step_folded(const skv_layer* L, const void* k_low, const void* v_low, int32_t T,
+                                  int64_t cur_len, const void* q_low, void* out_low, float scale,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_folded_append(L, k_low, v_low, T, cur_len);
+  if (st != SKV_OK) return st;
+  const int64_t n_ctx = cur_len + T;
+  int32_t s = 0;
+  st = check_folded_decode(L, q_low, out_low, n_ctx, scale, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  DecodeParams qp;
+  fill_query_params(L, &qp, q_low, scale, workspace);
+  if (T > 0) {
+    AppendParams ap;
+    fill_append_params(L, &ap, k_low, v_low, 0, 0, 0, T, cur_len);
+    if (launch_folded_prepare(ap, qp, hs) != hipSuccess) return SKV_ERR_HIP;
+  } else if (launch_scale_query(qp, hs) != hipSuccess) {
+    return SKV_ERR_HIP;
+  }
+  return run_folded_attention(L, out_low, n_ctx, s, workspace, stream);
 }
 
 skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho, const int32_t* cand_k,

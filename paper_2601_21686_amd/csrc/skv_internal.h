@@ -30,6 +30,7 @@ struct DecodeParams {
   int32_t n_ctx;
   int32_t n_splits;
   float scale_log2e;         // softmax scale times log2(e)
+  int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
 
 // Arguments of the append kernels.
@@ -97,6 +98,11 @@ hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStre
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);
+// Folded-weights variant: rows that arrive already projected.
+hipError_t launch_copy_projected(const AppendParams& p, hipStream_t stream);      // k_new / v_new are [b][t][h][r] packed
+hipError_t launch_scale_query(const DecodeParams& p, hipStream_t stream);        // q is [b][h_q][r_k]
+hipError_t launch_folded_prepare(const AppendParams& ap, const DecodeParams& dp, hipStream_t stream);  // both, one launch
+
 // Few-token appends (ap) and query projections (dp) in one launch; either may be null.
 hipError_t launch_project(const AppendParams* ap, const DecodeParams* dp, hipStream_t stream);
 

@@ -232,3 +232,29 @@ def test_quantised_layer_argument_checks():
     assert lib.skv_q8_decode_attention(C.byref(ok), FAKE, FAKE, 0, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
     assert lib.skv_q8_decode_attention(C.byref(ok), FAKE, FAKE, 16, 0.0, FAKE, 64, None) == B.SKV_ERR_WORKSPACE
     assert lib.skv_q8_decode_step(C.byref(ok), FAKE, FAKE, 8192, 1024, 128, 1, 0, None, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+
+
+def test_folded_variant_argument_checks():
+    lib = B.lib()
+    L = _layer(p_k=None, p_v=None)                       # bases are not needed here
+    ws = lib.skv_decode_workspace_bytes(C.byref(_layer()))
+    assert lib.skv_append_projected(C.byref(L), None, None, 0, 5, None) == B.SKV_OK          # T = 0: no-op
+    assert lib.skv_append_projected(C.byref(L), None, FAKE, 1, 5, None) == B.SKV_ERR_NULL
+    assert lib.skv_append_projected(C.byref(L), FAKE, FAKE, 2, 1023, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_append_projected(C.byref(L), FAKE + 4, FAKE, 1, 0, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_append_projected(C.byref(L), FAKE, FAKE, -1, 0, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_append_projected(C.byref(_layer(r_k=40)), FAKE, FAKE, 1, 0, None) == B.SKV_ERR_RANK
+    f = lib.skv_decode_attention_folded
+    assert f(C.byref(L), None, FAKE, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert f(C.byref(L), FAKE, FAKE, 0, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert f(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, 100, None) == B.SKV_ERR_WORKSPACE
+    assert f(C.byref(L), FAKE, FAKE, 16, float("nan"), FAKE, ws, None) == B.SKV_ERR_SHAPE
+    assert f(C.byref(_layer(k_cache=None)), FAKE, FAKE, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    # the explicit-projection entry points still insist on the bases
+    assert lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 16, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    g = lib.skv_decode_step_folded
+    assert g(C.byref(L), FAKE, FAKE, 1, 1024, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY
+    assert g(C.byref(L), None, FAKE, 1, 5, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert g(C.byref(L), FAKE, FAKE, 1, 5, None, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
+    assert g(C.byref(L), FAKE, FAKE, 0, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY   # nothing to attend
+    assert g(C.byref(L), FAKE, FAKE, 1, 5, FAKE, FAKE, 0.0, FAKE, 64, None) == B.SKV_ERR_WORKSPACE

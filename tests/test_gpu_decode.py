@@ -146,3 +146,37 @@ def test_decode_step_equals_append_then_decode(batch, T, hq, hkv, r_k, r_v):
     assert np.array_equal(out_a.cpu().numpy(), out_b)
     Pa.oracle_append(k1.cpu(), v1.cpu(), n0)
     assert vec_rel_err(out_b, Pa.oracle_decode(q, n0 + T)) <= TOL
+
+
+@pytest.mark.parametrize("r_k,r_v,hq,hkv", [(64, 64, 8, 2), (48, 80, 4, 4), (128, 32, 16, 2)])
+def test_folded_variant_matches_oracle(r_k, r_v, hq, hkv):
+    from oracle import skv_oracle as O
+    from paper_2601_21686_amd import synth
+    batch, n0, T = 2, 1000, 37
+    n = n0 + T
+    P = _filled_pair(("fold", r_k, r_v), batch, hq, hkv, r_k, r_v, n0, capacity=n)
+    # what a model with folded weights hands over: projected rows (bf16) and projected queries (bf16)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    k_low = torch.randn((batch, T, hkv, r_k), generator=g, device="cuda").to(torch.bfloat16)
+    v_low = torch.randn((batch, T, hkv, r_v), generator=g, device="cuda").to(torch.bfloat16)
+    q_low = torch.randn((batch, hq, r_k), generator=g, device="cuda").to(torch.bfloat16)
+    f64 = lambda t: O.bf16_bits_to_f64(synth.torch_bf16_to_bits(t))
+    B.skv_append_projected(P.gpu, k_low, v_low, n0)
+    O.append_projected(P.ora, f64(k_low), f64(v_low), n0)
+    torch.cuda.synchronize()
+    # placement and values are bit-exact copies
+    assert np.array_equal(f64(P.gpu.k_cache[:, :, :n]), P.ora.k_cache[:, :, :n])
+    assert np.array_equal(f64(P.gpu.v_cache[:, :, :n]), P.ora.v_cache[:, :, :n])
+    out_low = torch.empty((batch, hq, r_v), dtype=torch.float32, device="cuda")
+    for n_ctx in (n, 130):
+        B.skv_decode_attention_folded(P.gpu, q_low, out_low, n_ctx)
+        torch.cuda.synchronize()
+        want = O.decode_attention_folded(P.ora, f64(q_low), n_ctx)
+        assert vec_rel_err(out_low.cpu().numpy(), want) <= TOL
+    # one decode step: the same rows placed again one row earlier, then attention over n tokens
+    k1, v1 = k_low[:, -1:].contiguous(), v_low[:, -1:].contiguous()
+    out_step = torch.full_like(out_low, float("nan"))
+    B.skv_decode_step_folded(P.gpu, k1, v1, n - 1, q_low, out_step)
+    B.skv_decode_attention_folded(P.gpu, q_low, out_low, n)
+    torch.cuda.synchronize()
+    assert torch.equal(out_step, out_low)
