@@ -16,6 +16,7 @@ Everything below is the paper's definition written out with numpy float64:
   * sequential budgeted rank selection                         (Sec. 3.5, Eqs. 15-17; App. B, Alg. 2)
   * asymmetric integer quantisation of the compressed cache    (Sec. 4.3; 8 bits, group 64)
   * the folded-weights variant: attention in the compressed space (Sec. 3.4 "Overheads")
+  * a chunk of queries over the compressed cache (Eq. 18 with T > 1, causal mask)
 
 Readings taken where the paper is silent (all listed in the design notes):
 the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
@@ -36,7 +37,9 @@ tiny case; the library scaled-dot-product routine when P = I; the paper's
 printed 16 GB cache-size example; budget invariants and an exhaustive check
 of the greedy selector; for the quantiser: on-grid inputs are recovered exactly,
 the round-trip error bound, flat groups, library rounding, and the invariance
-of the output to the key zero point.  No function here is "parity unpinned".
+of the output to the key zero point; for the chunk form: the library's causal
+attention (with and without a cached prefix, off-by-one masks rejected), a
+pure-Python brute force and the first-token closed form.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -303,6 +306,76 @@ def decode_attention_folded(layer: OracleLayer, q_low: np.ndarray, n_ctx: int,
             kv = h // G
             out[b, h] = attention_single_query(q_low[b, h], layer.k_cache[b, kv, :n_ctx, :],
                                                layer.v_cache[b, kv, :n_ctx, :], scale)
+    return out
+
+
+# --------------------------------------------------------------------------
+# App. A.1 Eq. 18 with a whole chunk of queries (prefill over the compressed cache)
+# --------------------------------------------------------------------------
+#
+# Eq. 18 is written for Q in R^{T x d_h}.  With T > 1 new tokens whose
+# compressed keys and values are already in the cache, token t of the chunk
+# sits at position n_prev + t and, in the decoder-only models the paper
+# evaluates, attends positions 0 .. n_prev + t (causal mask; the paper's
+# formula leaves the mask implicit -- this is the reading taken here).
+
+
+def prefill_attention(layer: OracleLayer, q: np.ndarray, n_prev: int,
+                      scale: float | None = None, rows=None) -> np.ndarray:
+    """Definition form for a chunk.  q: float64 [batch, T, n_q_heads, head_dim];
+    rows [0, n_prev + T) of the cache are filled.  For every sequence b, chunk
+    token t and query head h: rebuild K~, V~ of KV head h // G (Sec. 3.2 Eq. 7)
+    for cache rows [0, n_prev + t] and apply softmax attention of that one query
+    (scale 1/sqrt(head_dim) unless given).  Returns [batch, T, n_q_heads,
+    head_dim]; `rows`, if given, is an iterable of (b, t, h) to compute (all
+    other rows are NaN)."""
+    q = np.asarray(q, np.float64)
+    B, T, HQ, d = q.shape
+    if (B, HQ, d) != (layer.batch, layer.n_q_heads, layer.head_dim):
+        raise ValueError("q must be [batch, T, n_q_heads, head_dim]")
+    if n_prev < 0 or T < 1 or n_prev + T > layer.capacity:
+        raise ValueError("chunk out of range")
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.full(q.shape, np.nan, np.float64)
+    wanted = None if rows is None else set((int(b), int(t), int(h)) for b, t, h in rows)
+    for b in range(B):
+        for kv in range(layer.n_kv_heads):
+            todo = [(t, h) for t in range(T) for h in range(kv * G, (kv + 1) * G)
+                    if wanted is None or (b, t, h) in wanted]
+            if not todo:
+                continue
+            n_max = n_prev + 1 + max(t for t, _ in todo)
+            K_tilde = reconstruct(layer.k_cache[b, kv, :n_max, :], layer.basis_k(kv))
+            V_tilde = reconstruct(layer.v_cache[b, kv, :n_max, :], layer.basis_v(kv))
+            for t, h in todo:
+                n_vis = n_prev + t + 1                      # positions this token may see
+                out[b, t, h] = attention_single_query(q[b, t, h], K_tilde[:n_vis], V_tilde[:n_vis], scale)
+    return out
+
+
+def prefill_attention_folded(layer: OracleLayer, q_low: np.ndarray, n_prev: int,
+                             scale: float | None = None, rows=None) -> np.ndarray:
+    """The same in the compressed space (Sec. 3.4 folded weights): q_low is
+    [batch, T, n_q_heads, r_k], the result [batch, T, n_q_heads, r_v]."""
+    q_low = np.asarray(q_low, np.float64)
+    B, T, HQ, _ = q_low.shape
+    if n_prev < 0 or T < 1 or n_prev + T > layer.capacity:
+        raise ValueError("chunk out of range")
+    if scale is None or scale <= 0:
+        scale = 1.0 / math.sqrt(layer.head_dim)
+    G = layer.n_q_heads // layer.n_kv_heads
+    out = np.full((B, T, HQ, layer.r_v), np.nan, np.float64)
+    wanted = None if rows is None else set((int(b), int(t), int(h)) for b, t, h in rows)
+    for b in range(B):
+        for t in range(T):
+            for h in range(HQ):
+                if wanted is not None and (b, t, h) not in wanted:
+                    continue
+                kv, n_vis = h // G, n_prev + t + 1
+                out[b, t, h] = attention_single_query(q_low[b, t, h], layer.k_cache[b, kv, :n_vis, :],
+                                                      layer.v_cache[b, kv, :n_vis, :], scale)
     return out
 
 

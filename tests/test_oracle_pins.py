@@ -334,3 +334,100 @@ def test_folded_variant_is_library_attention_in_rank_space_with_head_dim_scale()
     O.append_projected(Lb, k_low[:, :7], v_low[:, :7], 3)
     assert np.array_equal(Lb.k_cache[:, :, 3:10], O.round_to_bf16(np.transpose(k_low[:, :7], (0, 2, 1, 3))))
     assert np.all(Lb.k_cache[:, :, :3] == 5.0) and np.all(Lb.v_cache[:, :, 10:] == 5.0)
+
+
+# ------------------------------------------------------ chunk prefill ----
+
+def test_prefill_with_identity_basis_matches_library_causal_attention():
+    """P = I and an empty cache before the chunk: the chunk attention is the
+    library's causal scaled-dot-product attention (grouped heads)."""
+    rng = np.random.default_rng(30)
+    B, HQ, HKV, d, T = 2, 4, 2, 16, 23
+    eye = np.tile(np.eye(d)[None], (HKV, 1, 1))
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, d, d, T, eye, eye)
+    q = rng.standard_normal((B, T, HQ, d))
+    G = HQ // HKV
+    tq = torch.from_numpy(q).permute(0, 2, 1, 3)
+    tk = torch.from_numpy(K).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    tv = torch.from_numpy(V).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).permute(0, 2, 1, 3).numpy()
+    assert np.allclose(O.prefill_attention(L, q, 0), want, rtol=1e-12, atol=1e-13)
+
+
+def test_prefill_with_a_prefix_matches_library_attention_under_an_explicit_mask():
+    """n_prev cached tokens before the chunk: token t sees positions 0..n_prev+t.
+    The mask is written out here as a boolean matrix for the library routine."""
+    rng = np.random.default_rng(31)
+    B, HQ, HKV, d, n_prev, T = 1, 6, 3, 16, 9, 7
+    n = n_prev + T
+    eye = np.tile(np.eye(d)[None], (HKV, 1, 1))
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, d, d, n, eye, eye)
+    q = rng.standard_normal((B, T, HQ, d))
+    G = HQ // HKV
+    mask = torch.tensor([[j <= n_prev + t for j in range(n)] for t in range(T)])
+    tq = torch.from_numpy(q).permute(0, 2, 1, 3)
+    tk = torch.from_numpy(K).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    tv = torch.from_numpy(V).permute(0, 2, 1, 3).repeat_interleave(G, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask).permute(0, 2, 1, 3).numpy()
+    got = O.prefill_attention(L, q, n_prev)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-13)
+    # an off-by-one in the visible range (token t not seeing itself, or seeing t+1) is a different result
+    for bad in (-1, 1):
+        mask_bad = torch.tensor([[j <= n_prev + t + bad for j in range(n)] for t in range(T)])
+        other = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask_bad).permute(0, 2, 1, 3).numpy()
+        assert not np.allclose(got, other, rtol=1e-3)
+
+
+def test_prefill_rank_deficient_case_against_pure_python():
+    rng = np.random.default_rng(32)
+    B, HQ, HKV, d, rk, rv, n_prev, T = 1, 2, 1, 6, 3, 4, 2, 4
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, rk, rv, n_prev + T)
+    q = rng.standard_normal((B, T, HQ, d))
+    got = O.prefill_attention(L, q, n_prev)
+    Pk, Pv = L.p_k[0].tolist(), L.p_v[0].tolist()
+    Kt, Vt = [], []
+    for j in range(n_prev + T):          # K~ = (K P_K) P_K^T row by row, in plain loops
+        kd = [sum(K[0, j, 0, i] * Pk[i][c] for i in range(d)) for c in range(rk)]
+        vd = [sum(V[0, j, 0, i] * Pv[i][c] for i in range(d)) for c in range(rv)]
+        Kt.append([sum(kd[c] * Pk[i][c] for c in range(rk)) for i in range(d)])
+        Vt.append([sum(vd[c] * Pv[i][c] for c in range(rv)) for i in range(d)])
+    for t in range(T):
+        for h in range(HQ):
+            want = _brute_attention(q[0, t, h].tolist(), Kt[:n_prev + t + 1], Vt[:n_prev + t + 1], 1.0 / math.sqrt(d))
+            assert np.allclose(got[0, t, h], want, rtol=1e-12, atol=1e-13)
+
+
+def test_prefill_first_token_of_an_empty_cache_returns_its_own_value_row():
+    rng = np.random.default_rng(33)
+    B, HQ, HKV, d, rk, rv, T = 2, 4, 2, 16, 5, 7, 6
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, rk, rv, T)
+    q = rng.standard_normal((B, T, HQ, d))
+    got = O.prefill_attention(L, q, 0)
+    for b in range(B):
+        for h in range(HQ):
+            kv = h // (HQ // HKV)
+            assert np.allclose(got[b, 0, h], L.p_v[kv] @ (L.p_v[kv].T @ V[b, 0, kv]), rtol=1e-12, atol=1e-13)
+
+
+def test_prefill_rows_equal_decode_steps_and_row_selection():
+    """Token t of the chunk is the decode query at n_ctx = n_prev + t + 1; the
+    folded form lifted by P_V equals the explicit form."""
+    rng = np.random.default_rng(34)
+    B, HQ, HKV, d, rk, rv, n_prev, T = 2, 8, 2, 32, 12, 20, 40, 11
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, rk, rv, n_prev + T)
+    q = rng.standard_normal((B, T, HQ, d))
+    got = O.prefill_attention(L, q, n_prev)
+    for t in (0, 5, T - 1):
+        assert np.allclose(got[:, t], O.decode_attention(L, q[:, t], n_prev + t + 1), rtol=1e-12, atol=1e-13)
+    some = [(0, 3, 1), (1, 10, 7)]
+    part = O.prefill_attention(L, q, n_prev, rows=some)
+    for b, t, h in some:
+        assert np.array_equal(part[b, t, h], got[b, t, h])
+    assert np.isnan(part[0, 0, 0]).all()
+    G = HQ // HKV
+    q_low = np.einsum("bthd,hdc->bthc", q, np.repeat(L.p_k, G, axis=0))
+    a_low = O.prefill_attention_folded(L, q_low, n_prev)
+    lifted = np.einsum("bthc,hdc->bthd", a_low, np.repeat(L.p_v, G, axis=0))
+    assert np.allclose(lifted, got, rtol=1e-12, atol=1e-13)
+    part_low = O.prefill_attention_folded(L, q_low, n_prev, rows=some)
+    assert np.array_equal(part_low[1, 10, 7], a_low[1, 10, 7]) and np.isnan(part_low[0, 0, 0]).all()
