@@ -209,6 +209,56 @@ skv_status skv_decode_step_folded(const skv_layer* layer, const void* k_low, con
                                   float scale, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ---- A chunk of queries over the compressed cache (prefill) -----------------
+ * App. A.1 Eq. 18 is written for Q in R^{T x d_h}.  For T new tokens per
+ * sequence whose compressed keys and values are ALREADY in the cache at rows
+ * [n_prev, n_prev + T) (skv_project_append first), token t of the chunk sits at
+ * position n_prev + t and, as in the decoder-only models the paper evaluates,
+ * attends cache rows 0 .. n_prev + t (causal mask; its own row included):
+ *     out[b][t][h][:] = softmax_{j <= n_prev + t}( scale * <q[b][t][h], K~[b][kv][j]> ) . V~[b][kv]
+ * with K~, V~ the reconstructed cache of Sec. 3.2 Eq. 7 and kv = h / G.  With
+ * T = 1 this is skv_decode_attention at n_ctx = n_prev + 1.  Evaluated in the
+ * factored form on the matrix cores (bf16 operands, float32 accumulation,
+ * online softmax); needs no workspace.
+ *
+ *   q       device bf16, element (b,t,h,i) at b*q_stride_b + t*q_stride_t +
+ *           h*q_stride_h + i (strides in elements, multiples of 8)
+ *   out     device float32 [batch][T][n_q_heads][head_dim], packed
+ *   T       tokens in the chunk (0 is a no-op);  n_prev + T <= capacity
+ *   scale   <= 0 selects 1/sqrt(head_dim)
+ *   mode    SKV_PREFILL_EXACT: every float32 intermediate that feeds a bf16
+ *           product (projected queries, softmax weights, the normalised mix)
+ *           is split into two bf16 terms, so results keep float32-level
+ *           accuracy (same 2e-3 bound as the decode step).
+ *           SKV_PREFILL_FAST: one bf16 term each (half the matrix work); the
+ *           operand rounding of 2^-9 then shows in the output.
+ * skv_prefill_attention_folded is the same in the compressed space (Sec. 3.4
+ * "Overheads"): q_low bf16 [batch][T][n_q_heads][r_k] packed, out_low float32
+ * [batch][T][n_q_heads][r_v] packed; the bases are not used and may be NULL.
+ * skv_prefill_step = skv_project_append(k_new, v_new, T, cur_len) followed by
+ * skv_prefill_attention(n_prev = cur_len): one chunk of a chunked prefill.
+ * Errors: NULL, SHAPE (T < 0, bad strides or mode, grid too large), RANK,
+ * CAPACITY, ALIGN, HIP.
+ */
+#define SKV_PREFILL_EXACT 0
+#define SKV_PREFILL_FAST 1
+skv_status skv_prefill_attention(const skv_layer* layer, const void* q,
+                                 int64_t q_stride_b, int64_t q_stride_t, int64_t q_stride_h,
+                                 void* out, int32_t T, int64_t n_prev, float scale, int32_t mode,
+                                 void* stream);
+skv_status skv_prefill_attention_folded(const skv_layer* layer, const void* q_low, void* out_low,
+                                        int32_t T, int64_t n_prev, float scale, int32_t mode,
+                                        void* stream);
+skv_status skv_prefill_step(const skv_layer* layer, const void* k_new, const void* v_new,
+                            int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                            const void* q, int64_t q_stride_b, int64_t q_stride_t, int64_t q_stride_h,
+                            void* out, int32_t T, int64_t cur_len, float scale, int32_t mode,
+                            void* stream);
+/* Tokens of a chunk that one workgroup of the prefill kernel covers for this layer's head
+ * grouping (32, 64 or 128); 0 if the layer is invalid.  Host only. */
+int32_t skv_prefill_tile_tokens(const skv_layer* layer);
+
+/*
  * ---- 8-bit quantised compressed cache (Sec. 4.3) --------------------------
  * Asymmetric integer quantisation of the compressed rows, group size 64
  * channels (the last group of a row may be shorter): code =

@@ -20,6 +20,7 @@ SKV_ERR_NULL, SKV_ERR_SHAPE, SKV_ERR_RANK, SKV_ERR_CAPACITY = 1, 2, 3, 4
 SKV_ERR_ALIGN, SKV_ERR_WORKSPACE, SKV_ERR_BUDGET, SKV_ERR_HIP = 5, 6, 7, 8
 SKV_HEAD_DIM = 128
 SKV_MAX_SPLITS = 256
+SKV_PREFILL_EXACT, SKV_PREFILL_FAST = 0, 1
 
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
@@ -29,6 +30,7 @@ EXPORTS = (
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
+    "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
 )
 
 
@@ -110,6 +112,14 @@ def lib() -> C.CDLL:
     L.skv_decode_attention_folded.restype = C.c_int
     L.skv_decode_step_folded.argtypes = [LP, vp, vp, i32, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_decode_step_folded.restype = C.c_int
+    L.skv_prefill_attention.argtypes = [LP, vp, i64, i64, i64, vp, i32, i64, C.c_float, i32, vp]
+    L.skv_prefill_attention.restype = C.c_int
+    L.skv_prefill_attention_folded.argtypes = [LP, vp, vp, i32, i64, C.c_float, i32, vp]
+    L.skv_prefill_attention_folded.restype = C.c_int
+    L.skv_prefill_step.argtypes = [LP, vp, vp, i64, i64, i64, vp, i64, i64, i64, vp, i32, i64, C.c_float, i32, vp]
+    L.skv_prefill_step.restype = C.c_int
+    L.skv_prefill_tile_tokens.argtypes = [LP]
+    L.skv_prefill_tile_tokens.restype = i32
     L.skv_status_string.argtypes = [C.c_int]
     L.skv_status_string.restype = C.c_char_p
     _lib = L
@@ -337,6 +347,48 @@ def skv_decode_step_folded(layer, k_low: torch.Tensor, v_low: torch.Tensor, cur_
                                         int(cur_len), q_low.data_ptr(), out_low.data_ptr(), float(scale),
                                         ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
            "skv_decode_step_folded")
+
+
+# ---- a chunk of queries (prefill) ---------------------------------------------------
+
+
+def skv_prefill_attention(layer, q: torch.Tensor, out: torch.Tensor, n_prev: int, scale: float = 0.0,
+                          mode: int = SKV_PREFILL_EXACT, stream=None) -> None:
+    """q: bf16 [batch, T, n_q_heads, 128] (last axis contiguous); out: float32 of the same shape,
+    contiguous.  The chunk's rows [n_prev, n_prev + T) must already be in the cache."""
+    assert q.dtype == torch.bfloat16 and q.stride(3) == 1
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    sb, st, sh, _ = q.stride()
+    _check(lib().skv_prefill_attention(_base_ref(layer), q.data_ptr(), sb, st, sh, out.data_ptr(),
+                                       int(q.shape[1]), int(n_prev), float(scale), int(mode),
+                                       _stream_ptr(stream)), "skv_prefill_attention")
+
+
+def skv_prefill_attention_folded(layer, q_low: torch.Tensor, out_low: torch.Tensor, n_prev: int,
+                                 scale: float = 0.0, mode: int = SKV_PREFILL_EXACT, stream=None) -> None:
+    """q_low: bf16 [batch, T, n_q_heads, r_k] contiguous; out_low: float32 [batch, T, n_q_heads, r_v]."""
+    assert q_low.dtype == torch.bfloat16 and q_low.is_contiguous()
+    assert out_low.dtype == torch.float32 and out_low.is_contiguous()
+    _check(lib().skv_prefill_attention_folded(_base_ref(layer), q_low.data_ptr(), out_low.data_ptr(),
+                                              int(q_low.shape[1]), int(n_prev), float(scale), int(mode),
+                                              _stream_ptr(stream)), "skv_prefill_attention_folded")
+
+
+def skv_prefill_step(layer, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, out: torch.Tensor,
+                     cur_len: int, scale: float = 0.0, mode: int = SKV_PREFILL_EXACT, stream=None) -> None:
+    """Append the chunk k_new/v_new ([batch, T, n_kv_heads, 128]) at cur_len, then attend it causally."""
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16 and q.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1 and q.stride(3) == 1
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    sb, st, sh, _ = k_new.stride()
+    qb, qt, qh, _ = q.stride()
+    _check(lib().skv_prefill_step(_base_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                  q.data_ptr(), qb, qt, qh, out.data_ptr(), int(q.shape[1]), int(cur_len),
+                                  float(scale), int(mode), _stream_ptr(stream)), "skv_prefill_step")
+
+
+def skv_prefill_tile_tokens(layer) -> int:
+    return int(lib().skv_prefill_tile_tokens(_base_ref(layer)))
 
 
 # ---- 8-bit quantised cache ------------------------------------------------------

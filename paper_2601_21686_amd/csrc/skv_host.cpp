@@ -395,6 +395,124 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
 
 namespace {
 
+prefill_launcher prefill_launcher_for(int r_k) {
+  switch (r_k) {
+    case 16: return launch_prefill_rk16;
+    case 32: return launch_prefill_rk32;
+    case 48: return launch_prefill_rk48;
+    case 64: return launch_prefill_rk64;
+    case 80: return launch_prefill_rk80;
+    case 96: return launch_prefill_rk96;
+    case 112: return launch_prefill_rk112;
+    case 128: return launch_prefill_rk128;
+  }
+  return nullptr;
+}
+
+// Checks of the chunk attention that do not depend on where the queries come from.
+skv_status check_prefill(const skv_layer* L, bool folded, const void* q, const void* out, int32_t T,
+                         int64_t n_prev, float scale, int32_t mode) {
+  const skv_status st = check_layer(L, !folded);
+  if (st != SKV_OK) return st;
+  if (T < 0) return SKV_ERR_SHAPE;
+  if (mode != SKV_PREFILL_EXACT && mode != SKV_PREFILL_FAST) return SKV_ERR_SHAPE;
+  if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
+  if (n_prev < 0 || n_prev + (int64_t)T > L->capacity) return SKV_ERR_CAPACITY;
+  if (T == 0) return SKV_OK;
+  if (!q || !out) return SKV_ERR_NULL;
+  if (!aligned16(q) || !aligned16(out)) return SKV_ERR_ALIGN;
+  const int g = L->n_q_heads / L->n_kv_heads;
+  const int64_t tiles = ((int64_t)T + prefill_tile_tokens(g) - 1) / prefill_tile_tokens(g);
+  const int64_t rows_y = (int64_t)L->batch * L->n_kv_heads * (g / heads_per_pass(g));
+  if (tiles * rows_y > std::numeric_limits<int32_t>::max()) return SKV_ERR_SHAPE;
+  return SKV_OK;
+}
+
+skv_status run_prefill(const skv_layer* L, bool folded, const void* q, int64_t sb, int64_t st_, int64_t sh,
+                       void* out, int32_t T, int64_t n_prev, float scale, int32_t mode, void* stream) {
+  PrefillParams p;
+  p.k_cache = static_cast<const uint16_t*>(L->k_cache);
+  p.v_cache = static_cast<const uint16_t*>(L->v_cache);
+  p.p_k = static_cast<const uint16_t*>(L->p_k);
+  p.p_v = static_cast<const uint16_t*>(L->p_v);
+  p.q = static_cast<const uint16_t*>(q);
+  p.out = static_cast<float*>(out);
+  p.capacity = L->capacity;
+  p.p_k_head_stride = L->p_k_head_stride;
+  p.p_v_head_stride = L->p_v_head_stride;
+  p.q_stride_b = sb;
+  p.q_stride_t = st_;
+  p.q_stride_h = sh;
+  p.batch = L->batch;
+  p.n_q_heads = L->n_q_heads;
+  p.n_kv_heads = L->n_kv_heads;
+  p.group = L->n_q_heads / L->n_kv_heads;
+  p.T = T;
+  p.n_prev = (int32_t)n_prev;
+  p.n_tiles = (T + prefill_tile_tokens(p.group) - 1) / prefill_tile_tokens(p.group);
+  p.n_rows_y = L->batch * L->n_kv_heads * (p.group / heads_per_pass(p.group));
+  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
+  p.scale_log2e = (float)(sc * 1.4426950408889634);
+  p.folded = folded ? 1 : 0;
+  prefill_launcher launch = prefill_launcher_for(L->r_k);
+  if (!launch) return SKV_ERR_RANK;
+  if (launch(L->r_v, mode == SKV_PREFILL_FAST ? 1 : 0, p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status check_q_strides(int64_t sb, int64_t st, int64_t sh) {
+  if (sb < 0 || st < 0 || sh < 0) return SKV_ERR_SHAPE;
+  if ((sb % 8) || (st % 8) || (sh % 8)) return SKV_ERR_ALIGN;
+  return SKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t skv_prefill_tile_tokens(const skv_layer* L) {
+  if (check_layer(L, false) != SKV_OK) return 0;
+  return prefill_tile_tokens(L->n_q_heads / L->n_kv_heads);
+}
+
+skv_status skv_prefill_attention(const skv_layer* L, const void* q, int64_t q_stride_b,
+                                 int64_t q_stride_t, int64_t q_stride_h, void* out, int32_t T,
+                                 int64_t n_prev, float scale, int32_t mode, void* stream) {
+  skv_status st = check_prefill(L, false, q, out, T, n_prev, scale, mode);
+  if (st != SKV_OK || T == 0) return st;
+  st = check_q_strides(q_stride_b, q_stride_t, q_stride_h);
+  if (st != SKV_OK) return st;
+  return run_prefill(L, false, q, q_stride_b, q_stride_t, q_stride_h, out, T, n_prev, scale, mode, stream);
+}
+
+skv_status skv_prefill_attention_folded(const skv_layer* L, const void* q_low, void* out_low, int32_t T,
+                                        int64_t n_prev, float scale, int32_t mode, void* stream) {
+  const skv_status st = check_prefill(L, true, q_low, out_low, T, n_prev, scale, mode);
+  if (st != SKV_OK || T == 0) return st;
+  return run_prefill(L, true, q_low, 0, 0, 0, out_low, T, n_prev, scale, mode, stream);
+}
+
+skv_status skv_prefill_step(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
+                            int64_t stride_t, int64_t stride_h, const void* q, int64_t q_stride_b,
+                            int64_t q_stride_t, int64_t q_stride_h, void* out, int32_t T,
+                            int64_t cur_len, float scale, int32_t mode, void* stream) {
+  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK) return st;
+  st = check_prefill(L, false, q, out, T, cur_len, scale, mode);
+  if (st != SKV_OK || T == 0) return st;
+  st = check_q_strides(q_stride_b, q_stride_t, q_stride_h);
+  if (st != SKV_OK) return st;
+  AppendParams ap;
+  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return run_prefill(L, false, q, q_stride_b, q_stride_t, q_stride_h, out, T, cur_len, scale, mode, stream);
+}
+
+}  // extern "C"
+
+namespace {
+
 // The quantised cache takes ranks that are multiples of 32 (one byte per channel, whole
 // dwords per lane).
 skv_status check_q8_layer(const skv_q8_layer* Q) {

@@ -55,6 +55,37 @@ struct AppendParams {
   uint32_t* v_meta;          // [batch][n_kv_heads][capacity][groups of r_v]
 };
 
+// Heads of one KV group handled per workgroup pass (1, 2 or 4).
+inline int heads_per_pass(int group) { return group >= 4 ? 4 : group; }
+
+// Arguments of the chunk (prefill) attention kernel.
+struct PrefillParams {
+  const uint16_t* k_cache;
+  const uint16_t* v_cache;
+  const uint16_t* p_k;       // unused when folded
+  const uint16_t* p_v;
+  const uint16_t* q;         // bf16; element (b,t,h,i) at b*q_stride_b + t*q_stride_t + h*q_stride_h + i,
+                             // or packed [batch][T][n_q_heads][r_k] when folded
+  float* out;                // [batch][T][n_q_heads][128], or [..][r_v] when folded
+  int64_t capacity;
+  int64_t p_k_head_stride;
+  int64_t p_v_head_stride;
+  int64_t q_stride_b, q_stride_t, q_stride_h;
+  int32_t batch, n_q_heads, n_kv_heads, group;
+  int32_t T;                 // tokens of the chunk
+  int32_t n_prev;            // cache rows before the chunk; the chunk's own rows are already cached
+  int32_t n_tiles;           // token tiles per (sequence, KV head, pass)
+  int32_t n_rows_y;          // batch * n_kv_heads * passes
+  float scale_log2e;
+  int32_t folded;
+};
+
+constexpr int kPrefillKeyTile = 64;     // cache rows staged in LDS per step
+constexpr int kPrefillThreads = 256;
+// Tokens of the chunk handled by one workgroup: 4 waves of 32 query rows, split over
+// min(G, 4) heads of the group.
+inline int prefill_tile_tokens(int group) { return 32 * (4 / heads_per_pass(group)); }
+
 // The context is cut into quanta of this many rows; a range is a run of whole quanta (the last
 // one may be ragged), and the ranges of a call differ by at most one quantum.
 constexpr int kRangeQuantum = 64;
@@ -77,8 +108,6 @@ __host__ __device__ inline void range_of_split(int n_ctx, int n_splits, int spli
   *t1 = end < n_ctx ? end : n_ctx;
 }
 
-// Heads of one KV group handled per workgroup pass (1, 2 or 4).
-inline int heads_per_pass(int group) { return group >= 4 ? 4 : group; }
 
 // Launchers defined in the kernel translation units.  One per key rank.
 typedef hipError_t (*decode_partial_launcher)(int r_v, int heads, const DecodeParams& p,
@@ -95,6 +124,16 @@ hipError_t launch_decode_partial_q8_rk32(int, int, const DecodeParams&, hipStrea
 hipError_t launch_decode_partial_q8_rk64(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStream_t);
+
+typedef hipError_t (*prefill_launcher)(int r_v, int fast, const PrefillParams& p, hipStream_t stream);
+hipError_t launch_prefill_rk16(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk32(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk48(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk64(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk80(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk96(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk112(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk128(int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);

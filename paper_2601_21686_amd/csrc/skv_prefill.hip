@@ -1,0 +1,439 @@
+// Attention of a whole chunk of new tokens over the compressed cache
+// (App. A.1 Eq. 18 with Q in R^{T x d_h}, on K~ = K_down P_K^T, V~ = V_down P_V^T
+// of Sec. 3.2 Eq. 7; causal: token t of the chunk sits at position n_prev + t and
+// sees cache rows 0 .. n_prev + t).
+//
+// Unlike the single-query decode step this is a dense contraction, so it runs on
+// the matrix cores (v_mfma_f32_32x32x16_bf16, float32 accumulate), in the factored
+// form: Q~ = Q P_K, S = Q~ K_down^T, online softmax, A = P V_down, O = A P_V^T.
+//
+// Every product is computed transposed (keys or channels along the 32 result
+// rows, the 32 query rows of a wave along the result columns).  In the result
+// layout of the 32x32 MFMA a lane then holds 16 entries of ONE query row, so the
+// softmax statistics of a row live in one lane (plus its partner 32 lanes up),
+// the accumulator rescale is a per-lane scalar, and the probabilities are
+// already laid out as the next product's B operand.
+//
+//   operand layout (wave of 64, ln = lane % 32, lh = lane / 32):
+//     A[m = ln][k = 8 lh .. 8 lh + 7]      B[k = 8 lh .. 8 lh + 7][n = ln]
+//     C register 4 i + j  <->  C[m = 8 i + 4 lh + j][n = ln]
+//
+// The contraction index of a product may be enumerated in any order as long as
+// both operands agree; the orders are chosen so that every operand fetch is one
+// 16-byte piece:
+//   * P_K^T is staged in LDS with bits 2 and 3 of the channel index swapped, so
+//     registers 8u..8u+7 of a Q~^T result block are channels 16 kb + 8 lh + 0..7
+//     -- the B operand of score step kb, matching a plain 16-byte read of a key row.
+//   * V_down tiles are transposed on their way into LDS ([channel][key position]),
+//     with bits 2 and 3 of the key index swapped, so registers 8 kb..8 kb+7 of a
+//     score block (keys 16 kb + 8 (s/4) + 4 lh + s%4) meet 8 contiguous positions.
+//
+// Precision.  Q~ (a float32 sum over d_h), the probabilities and the normalised
+// mix are float32 numbers that the bf16 matrix cores cannot take directly.  In
+// the default mode each is split into a bf16 head and a bf16 remainder
+// (x ~ hi + lo, relative error 2^-17) and fed as two products; the fast mode
+// feeds the bf16 head only (relative operand error 2^-9).
+#include "skv_device_util.h"
+#include "skv_internal.h"
+
+#ifndef SKV_RK
+#error "compile with -DSKV_RK=<key rank>"
+#endif
+
+namespace skv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int D = SKV_HEAD_DIM;
+constexpr int KT = kPrefillKeyTile;     // keys per LDS tile
+constexpr int NT = kPrefillThreads;
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Eight float32 -> bf16 heads (and, if wanted, bf16 remainders).
+template <bool SPLIT>
+__device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
+  uint32_t h[4], l[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    h[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
+    if (SPLIT) l[e] = pack_bf16x2(x[2 * e] - bf16_lo(h[e]), x[2 * e + 1] - bf16_hi(h[e]));
+  }
+  hi = __builtin_bit_cast(bf16x8, uint4{h[0], h[1], h[2], h[3]});
+  lo = __builtin_bit_cast(bf16x8, uint4{l[0], l[1], l[2], l[3]});
+}
+
+__device__ __forceinline__ bf16x8 lds_frag(const uint16_t* p) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Swap bits 2 and 3 of an index.
+__device__ __forceinline__ int swap23(int c) { return (c & ~12) | ((c & 4) << 1) | ((c & 8) >> 1); }
+
+template <int RK, int RV, bool SPLIT>
+__global__ __launch_bounds__(NT) void prefill_kernel(const PrefillParams p) {
+  constexpr int KSTEPS = RK / 16;            // contraction steps of the score product
+  constexpr int RKB = (RK + 31) / 32;        // 32-channel result blocks of Q~^T
+  constexpr int RVB = (RV + 31) / 32;        // 32-channel result blocks of the mix
+  constexpr int VSTEPS = RV / 16;            // contraction steps of the lift
+  constexpr int KP = RK + 8;                 // LDS pitch of a key row (bf16 elements)
+  constexpr int VP = KT + 8;                 // LDS pitch of a value channel
+  constexpr int STAGE = KT * KP + RVB * 32 * VP;
+  constexpr int BP = D + 8;                  // LDS pitch of a transposed basis row
+  constexpr int BASIS = RKB * 32 * BP;
+  constexpr int SMEM = 2 * STAGE > BASIS ? 2 * STAGE : BASIS;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[SMEM];
+
+  constexpr int KC8 = RK / 8;                // 16-byte pieces per key row
+  constexpr int KPIECES = KT * KC8;
+  constexpr int KPT = (KPIECES + NT - 1) / NT;
+  constexpr int VCP = RV / 2;                // channel pairs per value row
+  constexpr int VUNITS = (KT / 8) * VCP;     // (8-key group, channel pair) units per tile
+  constexpr int VPT = (VUNITS + NT - 1) / NT;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int ln = lane & 31;
+  const int lh = lane >> 5;
+
+  // Workgroups are dealt to the 8 XCDs round-robin by their linear index; remap it so that
+  // the workgroups of one (sequence, KV head), which stream the same rows, share an L2.
+  const int total = gridDim.x;
+  const int full = total & ~7;
+  const int lid = blockIdx.x;
+  const int vid = lid < full ? (lid & 7) * (full >> 3) + (lid >> 3) : lid;
+  const int by = vid / p.n_tiles;
+  const int bx = vid % p.n_tiles;
+
+  const int hp = p.group >= 4 ? 4 : p.group;           // heads of a group per workgroup
+  const int passes = p.group / hp;
+  const int tile_tokens = 32 * (4 / hp);
+  const int pass = by % passes;
+  const int bkv = by / passes;
+  const int kv = bkv % p.n_kv_heads;
+  const int b = bkv / p.n_kv_heads;
+  const int head = kv * p.group + pass * hp + wave % hp;
+  const int t0 = (p.n_tiles - 1 - bx) * tile_tokens;   // longest contexts first
+  const int tw0 = t0 + 32 * (wave / hp);               // first token of this wave's rows
+  const bool wave_active = tw0 < p.T;
+  const int tok = tw0 + ln;
+  const int tok_c = tok < p.T ? tok : p.T - 1;
+  const int limit = p.n_prev + tok;                    // last cache row this lane's query sees
+  const int wave_last = tw0 + 31 < p.T ? tw0 + 31 : p.T - 1;
+
+  const int t_end = t0 + tile_tokens < p.T ? t0 + tile_tokens : p.T;
+  const int n_keys = p.n_prev + t_end;                 // rows any query of this workgroup sees
+  const int n_tiles_k = (n_keys + KT - 1) / KT;
+  const int last_row = n_keys - 1;
+
+  const uint16_t* kc = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RK;
+  const uint16_t* vc = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RV;
+
+  // ---- first key/value tile on its way -------------------------------------------------
+  uint4 kreg[KPT];
+  uint32_t vreg[VPT][8];
+  auto load_tile = [&](int j0) {
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int i = tid + u * NT;
+      if (KPIECES % NT == 0 || i < KPIECES) {
+        const int key = i / KC8, c8 = i % KC8;
+        int row = j0 + key;
+        row = row < last_row ? row : last_row;         // rows past the end re-read the last row; masked below
+        kreg[u] = *reinterpret_cast<const uint4*>(kc + (int64_t)row * RK + c8 * 8);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+      const int i = tid + u * NT;
+      if (VUNITS % NT == 0 || i < VUNITS) {
+        const int cp = i % VCP, kg = i / VCP;
+        const int kbase = 16 * (kg >> 1) + 4 * (kg & 1);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          int row = j0 + kbase + 8 * (e >> 2) + (e & 3);
+          row = row < last_row ? row : last_row;
+          vreg[u][e] = *reinterpret_cast<const uint32_t*>(vc + (int64_t)row * RV + 2 * cp);
+        }
+      }
+    }
+  };
+  auto store_tile = [&](uint16_t* stage) {
+    uint16_t* ks = stage;
+    uint16_t* vt = stage + KT * KP;
+#pragma unroll
+    for (int u = 0; u < KPT; ++u) {
+      const int i = tid + u * NT;
+      if (KPIECES % NT == 0 || i < KPIECES) {
+        const int key = i / KC8, c8 = i % KC8;
+        *reinterpret_cast<uint4*>(ks + key * KP + c8 * 8) = kreg[u];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+      const int i = tid + u * NT;
+      if (VUNITS % NT == 0 || i < VUNITS) {
+        const int cp = i % VCP, kg = i / VCP;
+        // keys 16x + 8y + 4z + w (x = kg/2, z = kg%2) go to positions 16x + 8z + 4y + w
+        const int pos = 16 * (kg >> 1) + 8 * (kg & 1);
+        uint4 even, odd;
+        uint32_t* ev = reinterpret_cast<uint32_t*>(&even);
+        uint32_t* od = reinterpret_cast<uint32_t*>(&odd);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t a = vreg[u][2 * e], c = vreg[u][2 * e + 1];
+          ev[e] = (a & 0xffffu) | (c << 16);
+          od[e] = (a >> 16) | (c & 0xffff0000u);
+        }
+        *reinterpret_cast<uint4*>(vt + (2 * cp) * VP + pos) = even;
+        *reinterpret_cast<uint4*>(vt + (2 * cp + 1) * VP + pos) = odd;
+      }
+    }
+  };
+
+  // ---- projected queries: Q~^T = P_K^T Q^T, scaled, split ------------------------------
+  bf16x8 qhi[KSTEPS], qlo[KSTEPS];
+  if (!p.folded) {
+    const uint16_t* basis = p.p_k + (int64_t)kv * p.p_k_head_stride;
+    for (int i = tid; i < D * KC8; i += NT) {
+      const int d = i / KC8, c8 = i % KC8;
+      const uint4 v = *reinterpret_cast<const uint4*>(basis + d * RK + c8 * 8);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        smem[swap23(c8 * 8 + 2 * e) * BP + d] = (uint16_t)(w[e] & 0xffffu);
+        smem[swap23(c8 * 8 + 2 * e + 1) * BP + d] = (uint16_t)(w[e] >> 16);
+      }
+    }
+    if (RK % 32) {                                      // rows of the last block that hold no channel
+      for (int i = tid; i < (RKB * 32 - RK) * D; i += NT) smem[(RK + i / D) * BP + i % D] = 0;
+    }
+    __syncthreads();
+    const uint16_t* qrow = p.q + (int64_t)b * p.q_stride_b + (int64_t)tok_c * p.q_stride_t +
+                           (int64_t)head * p.q_stride_h;
+    f32x16 qa[RKB];
+#pragma unroll
+    for (int cb = 0; cb < RKB; ++cb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) qa[cb][r] = 0.f;
+#pragma unroll
+    for (int kd = 0; kd < D / 16; ++kd) {
+      const bf16x8 bq = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qrow + 16 * kd + 8 * lh));
+#pragma unroll
+      for (int cb = 0; cb < RKB; ++cb)
+        qa[cb] = mfma32(lds_frag(&smem[(32 * cb + ln) * BP + 16 * kd + 8 * lh]), bq, qa[cb]);
+    }
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = qa[ks >> 1][8 * (ks & 1) + e] * p.scale_log2e;
+      split8<SPLIT>(x, qhi[ks], qlo[ks]);
+    }
+  } else {
+    const uint16_t* qrow = p.q + (((int64_t)b * p.T + tok_c) * p.n_q_heads + head) * RK;
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks) {
+      const uint4 v = *reinterpret_cast<const uint4*>(qrow + 16 * ks + 8 * lh);
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+      float x[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        x[2 * e] = bf16_lo(w[e]) * p.scale_log2e;
+        x[2 * e + 1] = bf16_hi(w[e]) * p.scale_log2e;
+      }
+      split8<SPLIT>(x, qhi[ks], qlo[ks]);
+    }
+  }
+  load_tile(0);
+  __syncthreads();                                      // the basis is no longer needed: stages may be written
+  if (RV % 32) {                                        // value channels that do not exist read as zero
+    for (int i = tid; i < 2 * (RVB * 32 - RV) * VP; i += NT) {
+      const int s = i / ((RVB * 32 - RV) * VP), o = i % ((RVB * 32 - RV) * VP);
+      smem[s * STAGE + KT * KP + RV * VP + o] = 0;
+    }
+  }
+
+  // ---- stream the cache ----------------------------------------------------------------
+  f32x16 oacc[RVB];
+#pragma unroll
+  for (int vb = 0; vb < RVB; ++vb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[vb][r] = 0.f;
+  float m_run = -1e30f;                                 // softmax reference (log2 units)
+  float l_run = 0.f;                                    // this lane's share of the normaliser
+
+  for (int it = 0; it < n_tiles_k; ++it) {
+    uint16_t* stage = smem + (it & 1) * STAGE;
+    store_tile(stage);
+    __syncthreads();
+    if (it + 1 < n_tiles_k) load_tile((it + 1) * KT);   // on its way while this tile computes
+    const int j0 = it * KT;
+    if (!wave_active || j0 > p.n_prev + wave_last) continue;   // nothing visible to this wave's rows
+
+    const uint16_t* ks_s = stage;
+    const uint16_t* vt_s = stage + KT * KP;
+    f32x16 s[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        const bf16x8 ka = lds_frag(&ks_s[(32 * a + ln) * KP + 16 * ks + 8 * lh]);
+        s[a] = mfma32(ka, qhi[ks], s[a]);
+        if (SPLIT) s[a] = mfma32(ka, qlo[ks], s[a]);
+      }
+    }
+    if (j0 + KT - 1 > p.n_prev + tw0) {                 // the tile crosses the diagonal for some row
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = j0 + 32 * a + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (key > limit) s[a][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[a][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // The reference follows the maximum only when a score exceeds it by more than 8 (log2
+    // units): weights stay <= 2^8 and the accumulator rescale leaves the steady state.
+    const float m_new = mx > m_run + 8.f ? mx : m_run;
+    if (__any(m_new != m_run)) {
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int vb = 0; vb < RVB; ++vb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[vb][r] *= alpha;
+      m_run = m_new;
+    }
+    bf16x8 phi[4], plo[4];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_exp2f(s[a][8 * kb + e] - m_run);
+        split8<SPLIT>(x, phi[2 * a + kb], plo[2 * a + kb]);
+        if (SPLIT) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) l_run += x[e];
+        } else {                                        // normalise by the weights actually used
+#pragma unroll
+          for (int e = 0; e < 8; ++e) l_run += (float)phi[2 * a + kb][e];
+        }
+      }
+#pragma unroll
+    for (int vb = 0; vb < RVB; ++vb)
+#pragma unroll
+      for (int st = 0; st < 4; ++st) {
+        const bf16x8 va = lds_frag(&vt_s[(32 * vb + ln) * VP + 16 * st + 8 * lh]);
+        oacc[vb] = mfma32(va, phi[st], oacc[vb]);
+        if (SPLIT) oacc[vb] = mfma32(va, plo[st], oacc[vb]);
+      }
+  }
+
+  if (!wave_active) return;
+  const float l_all = l_run + __shfl_xor(l_run, 32);
+  const float inv = 1.f / l_all;
+  const bool row_ok = tok < p.T;
+
+  if (p.folded) {
+    // rank-r_V coordinates: lane holds channels 32 vb + 8 i + 4 lh + (0..3) of its row
+    float* orow = p.out + (((int64_t)b * p.T + tok_c) * p.n_q_heads + head) * RV;
+#pragma unroll
+    for (int vb = 0; vb < RVB; ++vb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int c = 32 * vb + 8 * i + 4 * lh;
+        if (row_ok && c < RV)
+          *reinterpret_cast<float4*>(orow + c) = float4{oacc[vb][4 * i] * inv, oacc[vb][4 * i + 1] * inv,
+                                                         oacc[vb][4 * i + 2] * inv, oacc[vb][4 * i + 3] * inv};
+      }
+    return;
+  }
+
+  // ---- lift: O^T = P_V A^T --------------------------------------------------------------
+  // Contraction step st of the lift covers channels 16 st + 8 (s/4) + 4 lh + s%4 (the order
+  // the mix accumulators have them): two 8-byte pieces of a basis row per lane.
+  bf16x8 ahi[VSTEPS], alo[VSTEPS];
+#pragma unroll
+  for (int st = 0; st < VSTEPS; ++st) {
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = oacc[st >> 1][8 * (st & 1) + e] * inv;
+    split8<SPLIT>(x, ahi[st], alo[st]);
+  }
+  const uint16_t* pv = p.p_v + (int64_t)kv * p.p_v_head_stride;
+  float* orow = p.out + (((int64_t)b * p.T + tok_c) * p.n_q_heads + head) * D;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db) {
+    f32x16 o;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[r] = 0.f;
+    const uint16_t* prow = pv + (32 * db + ln) * RV;
+#pragma unroll
+    for (int st = 0; st < VSTEPS; ++st) {
+      const uint2 w0 = *reinterpret_cast<const uint2*>(prow + 16 * st + 4 * lh);
+      const uint2 w1 = *reinterpret_cast<const uint2*>(prow + 16 * st + 8 + 4 * lh);
+      const bf16x8 pa = __builtin_bit_cast(bf16x8, uint4{w0.x, w0.y, w1.x, w1.y});
+      o = mfma32(pa, ahi[st], o);
+      if (SPLIT) o = mfma32(pa, alo[st], o);
+    }
+    if (row_ok) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<float4*>(orow + 32 * db + 8 * i + 4 * lh) =
+            float4{o[4 * i], o[4 * i + 1], o[4 * i + 2], o[4 * i + 3]};
+    }
+  }
+}
+
+template <int RV>
+hipError_t launch_rv(int fast, const PrefillParams& p, hipStream_t stream) {
+  const dim3 grid((unsigned)((int64_t)p.n_tiles * p.n_rows_y));
+  if (fast)
+    hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, false>), grid, dim3(NT), 0, stream, p);
+  else
+    hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, true>), grid, dim3(NT), 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+#define SKV_CAT2(a, b) a##b
+#define SKV_CAT(a, b) SKV_CAT2(a, b)
+
+hipError_t SKV_CAT(launch_prefill_rk, SKV_RK)(int r_v, int fast, const PrefillParams& p, hipStream_t stream) {
+  switch (r_v) {
+    case 16: return launch_rv<16>(fast, p, stream);
+    case 32: return launch_rv<32>(fast, p, stream);
+    case 48: return launch_rv<48>(fast, p, stream);
+    case 64: return launch_rv<64>(fast, p, stream);
+    case 80: return launch_rv<80>(fast, p, stream);
+    case 96: return launch_rv<96>(fast, p, stream);
+    case 112: return launch_rv<112>(fast, p, stream);
+    case 128: return launch_rv<128>(fast, p, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace skv

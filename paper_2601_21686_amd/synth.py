@@ -136,6 +136,14 @@ def queries(seed: int, batch: int, n_q_heads: int, head_dim: int, device="cpu") 
                        dtype=torch.float32).to(torch.bfloat16)
 
 
+def chunk_queries(seed: int, batch: int, n_tokens: int, n_q_heads: int, width: int, device="cpu") -> torch.Tensor:
+    """bf16 [batch, n_tokens, n_q_heads, width]: the queries of a chunk of new tokens."""
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    return torch.randn((batch, n_tokens, n_q_heads, width), generator=g, device=device,
+                       dtype=torch.float32).to(torch.bfloat16)
+
+
 def layer_rank_draw(seed: int, n_layers: int):
     """Per-layer (r_K, r_V) drawn independently from RANK_CHOICES."""
     rng = np.random.default_rng(seed)
