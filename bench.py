@@ -47,10 +47,18 @@ def parse_args():
                     help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
                          "folded: the bases are folded into the model's linear layers (Sec. 3.4), so rows and queries "
                          "arrive projected and the output stays in rank-r_V coordinates")
-    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append"), default="bench",
+    ap.add_argument("--prefill-precision", choices=("exact", "fast"), default="exact",
+                    help="--mode prefill: exact = split-bf16 operands (float32-level accuracy), fast = single bf16 operands")
+    ap.add_argument("--prefill-sched", choices=("default", "together", "ahead"), default="default",
+                    help="--mode prefill: force one of the kernel's two schedules")
+    ap.add_argument("--prefill-chunk", type=int, default=0, help="--mode prefill: tokens in the chunk (0 = the workload's append chunk)")
+    ap.add_argument("--prefill-prev", type=int, default=-1, help="--mode prefill: cached tokens before the chunk (-1 = n_ctx - chunk)")
+    ap.add_argument("--ranks", default="", help="--mode prefill/append: override the workload's ranks, as r_k,r_v")
+    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append", "prefill"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
-                         "append: the chunk append of the workload (projection on the matrix cores) alone")
+                         "append: the chunk append of the workload (projection on the matrix cores) alone; "
+                         "prefill: causal attention of the workload's chunk over the compressed cache (matrix cores) alone")
     return ap.parse_args()
 
 
@@ -133,6 +141,79 @@ def main():
                           "achieved_GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                           "achieved_TFLOPs": round(flops / us / 1e6, 1), "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / 2500.0, 4),
                           "launches": iters + 3}))
+        return
+    if args.mode == "prefill":
+        # attention of a chunk of T new tokens over n_prev cached ones (rows of the chunk already appended)
+        T = args.prefill_chunk or max(wl.append_chunk, 256)
+        n_prev = args.prefill_prev if args.prefill_prev >= 0 else wl.n_ctx - T
+        rk, rv = (wl.r_k or 64), (wl.r_v or 64)
+        if args.ranks:
+            rk, rv = (int(x) for x in args.ranks.split(","))
+        Bt, HQ, HKV, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+        _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pk"), HKV, d, rk)
+        _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pv"), HKV, d, rv)
+        L = B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), n_prev + T)
+        sck = synth.channel_scales(synth.stable_seed(wl.name, 0, "sk"), HKV, d)
+        scv = synth.channel_scales(synth.stable_seed(wl.name, 0, "sv"), HKV, d)
+        for c0 in range(0, n_prev + T, 4096):
+            t = min(4096, n_prev + T - c0)
+            k = synth.kv_activations(synth.stable_seed(wl.name, 0, "k", c0), Bt, t, HKV, d, sck, dev)
+            v = synth.kv_activations(synth.stable_seed(wl.name, 0, "v", c0), Bt, t, HKV, d, scv, dev)
+            B.skv_project_append(L, k, v, c0)
+        q = synth.chunk_queries(synth.stable_seed(wl.name, "cq"), Bt, T, HQ, d, dev)
+        out = torch.empty((Bt, T, HQ, d), dtype=torch.float32, device=dev)
+        pmode = B.SKV_PREFILL_FAST if args.prefill_precision == "fast" else B.SKV_PREFILL_EXACT
+        pmode |= {"default": 0, "together": B.SKV_PREFILL_SCHED_TOGETHER, "ahead": B.SKV_PREFILL_SCHED_AHEAD}[args.prefill_sched]
+        iters = max(1, args.kernel_iters // 20)
+        for _ in range(2):
+            B.skv_prefill_attention(L, q, out, n_prev, 0.0, pmode)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            B.skv_prefill_attention(L, q, out, n_prev, 0.0, pmode)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / iters
+        # algorithmic flops: per (sequence, query head, token t): 2 (r_K + r_V) per visible row, plus the
+        # query projection and the lift (2 * 128 * r each)
+        visible = sum(n_prev + t + 1 for t in range(T))
+        flops = Bt * HQ * (2 * (rk + rv) * visible + T * 2 * d * (rk + rv))
+        nbytes = Bt * HKV * (n_prev + T) * (rk + rv) * 2 + Bt * T * HQ * d * (2 + 4)
+        res = {"mode": "prefill", "workload": wl.name, "batch": Bt, "T": T, "n_prev": n_prev, "r_k": rk, "r_v": rv,
+               "precision": args.prefill_precision, "sched": args.prefill_sched, "ms_per_launch": round(ms, 4),
+               "chunk_tokens_per_s": round(Bt * T / (ms * 1e-3), 1),
+               "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / (ms * 1e-3) / 1e12, 1),
+                            "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4),
+                            "flops_per_launch": flops, "compulsory_hbm_bytes": nbytes},
+               "launches": iters + 2}
+        if not args.no_cpu_baseline:
+            # sampled rows against the oracle (its own float64 append of the same seeded inputs)
+            from oracle import skv_oracle as O
+            f64 = lambda t_: O.bf16_bits_to_f64(synth.torch_bf16_to_bits(t_))
+            rng = np.random.default_rng(5)
+            b_s, kv_s = int(rng.integers(Bt)), int(rng.integers(HKV))
+            ora = O.new_layer(1, HQ // HKV, 1, d, f64(pk[kv_s:kv_s + 1]), f64(pv[kv_s:kv_s + 1]), n_prev + T, store="bf16")
+            for c0 in range(0, n_prev + T, 4096):
+                t = min(4096, n_prev + T - c0)
+                k = synth.kv_activations(synth.stable_seed(wl.name, 0, "k", c0), Bt, t, HKV, d, sck, dev)
+                v = synth.kv_activations(synth.stable_seed(wl.name, 0, "v", c0), Bt, t, HKV, d, scv, dev)
+                O.project_append(ora, f64(k[b_s:b_s + 1, :, kv_s:kv_s + 1]), f64(v[b_s:b_s + 1, :, kv_s:kv_s + 1]), c0)
+            G = HQ // HKV
+            toks = sorted(set([0, T - 1] + [int(x) for x in rng.integers(0, T, size=6)]))
+            rows = [(0, t, g) for t in toks for g in range(G)]
+            qs_ = f64(q[b_s:b_s + 1, :, kv_s * G:(kv_s + 1) * G])
+            tb = time.perf_counter()
+            want = O.prefill_attention(ora, qs_, n_prev, rows=rows)
+            spent = time.perf_counter() - tb
+            got = out[b_s, :, kv_s * G:(kv_s + 1) * G].cpu().numpy().astype(np.float64)
+            err = max(float(np.max(np.abs(got[t, g] - want[0, t, g])) / np.max(np.abs(want[0, t, g]))) for _, t, g in rows)
+            res["parity"] = {"max_rel_err_vs_oracle": err, "rows_checked": len(rows),
+                             "tolerance": 1.5e-2 if (pmode & B.SKV_PREFILL_FAST) else 2e-3}
+            row_flops = sum(2 * (rk + rv) * (n_prev + t + 1) for _, t, _ in rows)
+            res["cpu_baseline"] = {"value": round(row_flops / spent / 1e12, 6), "unit": "TFLOP/s (algorithmic)",
+                                   "kind": "oracle", "sample": f"{len(rows)} query rows of one (sequence, KV head), {spent:.2f} s"}
+        print(json.dumps(res))
         return
     K, W = args.steps, args.warmup
     if args.mode == "kernel":

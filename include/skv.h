@@ -237,11 +237,18 @@ skv_status skv_decode_step_folded(const skv_layer* layer, const void* k_low, con
  * [batch][T][n_q_heads][r_v] packed; the bases are not used and may be NULL.
  * skv_prefill_step = skv_project_append(k_new, v_new, T, cur_len) followed by
  * skv_prefill_attention(n_prev = cur_len): one chunk of a chunked prefill.
- * Errors: NULL, SHAPE (T < 0, bad strides or mode, grid too large), RANK,
+ * Errors: NULL, SHAPE (T < 0, bad strides or mode bits, grid too large), RANK,
  * CAPACITY, ALIGN, HIP.
  */
 #define SKV_PREFILL_EXACT 0
 #define SKV_PREFILL_FAST 1
+/* Optional, OR-ed into mode: force one of the kernel's two schedules instead of the default for
+ * the shape (results are identical up to summation order; for tuning and benchmarks).
+ * TOGETHER stages a tile's keys and values in one step (fewer live registers, more waves per
+ * SIMD); AHEAD keeps keys one tile ahead so that the score products of the next tile overlap
+ * the softmax of the current one. */
+#define SKV_PREFILL_SCHED_TOGETHER 0x10
+#define SKV_PREFILL_SCHED_AHEAD 0x20
 skv_status skv_prefill_attention(const skv_layer* layer, const void* q,
                                  int64_t q_stride_b, int64_t q_stride_t, int64_t q_stride_h,
                                  void* out, int32_t T, int64_t n_prev, float scale, int32_t mode,

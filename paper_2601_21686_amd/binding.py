@@ -21,6 +21,7 @@ SKV_ERR_ALIGN, SKV_ERR_WORKSPACE, SKV_ERR_BUDGET, SKV_ERR_HIP = 5, 6, 7, 8
 SKV_HEAD_DIM = 128
 SKV_MAX_SPLITS = 256
 SKV_PREFILL_EXACT, SKV_PREFILL_FAST = 0, 1
+SKV_PREFILL_SCHED_TOGETHER, SKV_PREFILL_SCHED_AHEAD = 0x10, 0x20
 
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",

@@ -22,6 +22,9 @@ Q8_KEY_RANKS = (32, 64, 96, 128)          # the 8-bit quantised cache takes mult
 
 # Packed-FP32 instruction selection is switched off for all device code.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# The chunk attention keeps its matrix-core accumulators in ordinary vector registers (they are
+# read by the softmax right after each product), which saves the copies out of the accumulation file.
+PREFILL_FLAGS = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
 
@@ -46,7 +49,7 @@ def _jobs():
     for rk in KEY_RANKS:
         jobs.append((f"skv_prefill_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_prefill.hip"), f"-DSKV_RK={rk}"],
-                     DEVICE_FLAGS))
+                     DEVICE_FLAGS + PREFILL_FLAGS))
     for rk in Q8_KEY_RANKS:
         jobs.append((f"skv_decode_partial_q8_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_Q8=1"],

@@ -125,15 +125,16 @@ hipError_t launch_decode_partial_q8_rk64(int, int, const DecodeParams&, hipStrea
 hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStream_t);
 
-typedef hipError_t (*prefill_launcher)(int r_v, int fast, const PrefillParams& p, hipStream_t stream);
-hipError_t launch_prefill_rk16(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk32(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk48(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk64(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk80(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk96(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk112(int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk128(int, int, const PrefillParams&, hipStream_t);
+// sched: 0 = the default schedule for the shape, 1 = keys and values staged together, 2 = keys a tile ahead
+typedef hipError_t (*prefill_launcher)(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream);
+hipError_t launch_prefill_rk16(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk32(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk48(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk64(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk80(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk96(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk112(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk128(int, int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);
