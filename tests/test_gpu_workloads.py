@@ -187,3 +187,41 @@ def test_b8_ctx128k_mha_r64_96():
         q, out = S.step(("step", s))
     assert S.cur == 131072
     print("b8_ctx128k_mha_r64_96 worst rel err", S.check(q, out), flush=True)
+
+
+def test_b8_chunk4k_r48_80_chunk_prefill_attention():
+    """The same chunk as one step of a chunked prefill: append 4096 tokens behind 28672 cached ones and
+    attend them causally (skv_prefill_step, default precision and schedule); sampled query rows of sampled
+    streams against the oracle's definition form."""
+    wl = synth.WORKLOADS["b8_chunk4k_r48_80"]
+    T = wl.append_chunk
+    S = Stack(wl, [0], [(1, 2), (6, 5)])
+    S.fill_to(wl.n_ctx - T)
+    L = S.layers[0]
+    k = synth.kv_activations(synth.stable_seed(wl.name, 0, "k", "chunk"), wl.batch, T, wl.n_kv_heads, 128,
+                             S.scales[0][0], "cuda")
+    v = synth.kv_activations(synth.stable_seed(wl.name, 0, "v", "chunk"), wl.batch, T, wl.n_kv_heads, 128,
+                             S.scales[0][1], "cuda")
+    q = synth.chunk_queries(synth.stable_seed(wl.name, "cq"), wl.batch, T, wl.n_q_heads, 128, "cuda")
+    out = torch.full((wl.batch, T, wl.n_q_heads, 128), float("nan"), dtype=torch.float32, device="cuda")
+    B.skv_prefill_step(L, k, v, q, out, S.cur)
+    torch.cuda.synchronize()
+    assert torch.all(torch.isfinite(out))
+    n_prev, G = S.cur, wl.n_q_heads // wl.n_kv_heads
+    toks = [0, 1, 31, 32, 63, 64, 2047, 4064, 4095]
+    worst = 0.0
+    for b, kv in S.sample_streams:
+        kb = np.concatenate(S.raw[(0, b, kv)][0] + [synth.torch_bf16_to_bits(k[b, :, kv])])[None, :, None, :]
+        vb = np.concatenate(S.raw[(0, b, kv)][1] + [synth.torch_bf16_to_bits(v[b, :, kv])])[None, :, None, :]
+        ora = O.new_layer(1, G, 1, 128, O.bf16_bits_to_f64(S.pk_bits[0][kv:kv + 1]),
+                          O.bf16_bits_to_f64(S.pv_bits[0][kv:kv + 1]), n_prev + T, store="bf16")
+        O.project_append(ora, O.bf16_bits_to_f64(kb), O.bf16_bits_to_f64(vb), 0)
+        qh = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(q[b:b + 1, :, kv * G:(kv + 1) * G]))
+        rows = [(0, t, g) for t in toks for g in range(G)]
+        want = O.prefill_attention(ora, qh, n_prev, rows=rows)
+        got = out[b, :, kv * G:(kv + 1) * G].cpu().numpy()
+        for _, t, g in rows:
+            err = float(np.max(np.abs(got[t, g] - want[0, t, g])) / np.max(np.abs(want[0, t, g])))
+            worst = max(worst, err)
+            assert err <= TOL, (b, kv, t, g, err)
+    print("b8_chunk4k_r48_80 chunk prefill worst rel err", worst, flush=True)
