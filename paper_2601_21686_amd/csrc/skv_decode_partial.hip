@@ -342,6 +342,96 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
   }
 }
 
+#if !SKV_Q8
+// The rows a decode step appends (Sec. 2.1 Eq. 1: k_down = k P_K, v_down = v P_V, rounded to bf16 and
+// cached, Sec. 3.2) and their share of the attention, for one (sequence, KV head, pass): projects the
+// T_new new keys and values exactly as the few-token append does (same sums, same rounding), stores
+// them at rows [cur_len, cur_len + T_new), and attends them with the group's projected queries.  The
+// result is one more partial (m, l, a~) for the combine kernel, so the streaming workgroups never
+// have to wait for these rows to land in the cache.
+template <int RK, int RV, int GT>
+__device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, int kv, int pass, int hq0,
+                                                 float* x_s, float* part_s, float* y_s) {
+  constexpr int D = SKV_HEAD_DIM;
+  __shared__ float qt_s[GT * RK];
+  __shared__ float kd_s[RK];
+  __shared__ float vd_s[RV];
+  __shared__ float w_s[GT][2];                   // per head: factor of the sums so far, weight of the new row
+  const int tid = threadIdx.x;
+  const uint16_t* pk = p.p_k + (int64_t)kv * p.p_k_head_stride;
+  const uint16_t* pv = p.p_v + (int64_t)kv * p.p_v_head_stride;
+  {
+    ProjectPieces pp;
+    project_rows_issue(pk, RK, pp);
+    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
+    for (int i = tid; i < GT * D; i += kDecodeThreads) x_s[i] = bf16_to_f32(qptr[i]);
+    __syncthreads();
+    project_rows_finish<GT>(pp, RK, x_s, part_s, y_s);
+    for (int i = tid; i < GT * RK; i += kDecodeThreads) qt_s[i] = y_s[i] * p.scale_log2e;
+  }
+  float m = kNegBig, l = 0.f;                    // thread g < GT: softmax state of head g
+  float acc[GT];                                 // thread c < RV: channel c of every head's mix
+#pragma unroll
+  for (int g = 0; g < GT; ++g) acc[g] = 0.f;
+  for (int t = 0; t < p.T_new; ++t) {
+    const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
+    const int64_t row = ((int64_t)b * p.n_kv_heads + kv) * p.capacity + p.cur_len + t;
+    {
+      ProjectPieces pp;
+      project_rows_issue(pk, RK, pp);
+      if (tid < D) x_s[tid] = bf16_to_f32(p.k_new[src + tid]);
+      __syncthreads();
+      project_rows_finish<1>(pp, RK, x_s, part_s, y_s);
+      if (tid < RK) {
+        const uint32_t bits = f32_to_bf16_bits(y_s[tid]);
+        if (pass == 0) p.k_cache_w[row * RK + tid] = (uint16_t)bits;
+        kd_s[tid] = bf16_to_f32((uint16_t)bits);
+      }
+    }
+    {
+      ProjectPieces pp;
+      project_rows_issue(pv, RV, pp);
+      if (tid < D) x_s[tid] = bf16_to_f32(p.v_new[src + tid]);
+      __syncthreads();
+      project_rows_finish<1>(pp, RV, x_s, part_s, y_s);
+      if (tid < RV) {
+        const uint32_t bits = f32_to_bf16_bits(y_s[tid]);
+        if (pass == 0) p.v_cache_w[row * RV + tid] = (uint16_t)bits;
+        vd_s[tid] = bf16_to_f32((uint16_t)bits);
+      }
+    }
+    __syncthreads();
+    if (tid < GT) {
+      float sc = 0.f;
+      for (int c = 0; c < RK; ++c) sc = fmaf(qt_s[tid * RK + c], kd_s[c], sc);
+      const float mn = fmaxf(m, sc);
+      const float alpha = fast_exp2(m - mn);
+      const float pw = fast_exp2(sc - mn);
+      l = l * alpha + pw;
+      m = mn;
+      w_s[tid][0] = alpha;
+      w_s[tid][1] = pw;
+    }
+    __syncthreads();
+    if (tid < RV) {
+#pragma unroll
+      for (int g = 0; g < GT; ++g) acc[g] = acc[g] * w_s[g][0] + w_s[g][1] * vd_s[tid];
+    }
+    __syncthreads();
+  }
+  float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + p.n_stream) * RV;
+  float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + p.n_stream) * 2;
+  if (tid < RV) {
+#pragma unroll
+    for (int g = 0; g < GT; ++g) out_acc[(int64_t)g * p.n_splits * RV + tid] = acc[g];
+  }
+  if (tid < GT) {
+    out_ml[(int64_t)tid * p.n_splits * 2] = m;
+    out_ml[(int64_t)tid * p.n_splits * 2 + 1] = l;
+  }
+}
+#endif
+
 // FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes).
 template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
@@ -353,6 +443,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   constexpr int ROWS_PER_WG = 4 * ROWS_PER_WAVE;
 
   __shared__ float red[4 * GT * (RV + 2)];       // cross-wave merge at the end of the range
+#if !SKV_Q8
+  // scratch of the in-kernel projections (queries; new rows of a fused decode step)
+  __shared__ float px_s[GT * SKV_HEAD_DIM];
+  __shared__ float ppart_s[kProjectThreads * GT * 8];
+  __shared__ float py_s[GT * SKV_HEAD_DIM];
+#endif
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -360,17 +456,33 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   const int oct = lane >> 3;
   const int j = lane & 7;
 
-  const int split = blockIdx.x;
+  int split = blockIdx.x;
   const int passes = p.group / GT;
-  const int col = blockIdx.y;                    // ((b * H_KV + kv) * passes + pass)
+  int col = blockIdx.y;                          // ((b * H_KV + kv) * passes + pass)
+  const int n_cols = p.batch * p.n_kv_heads * passes;
+  // Grid rows past the last column hold the fresh-rows workgroups of a fused decode step, one per
+  // column: they are dispatched after every streaming workgroup, so the streaming ones spread over
+  // the compute units exactly as in a launch without them.
+  const bool fresh = col >= n_cols;
+  if (fresh) {
+    col = (col - n_cols) * (int)gridDim.x + split;
+    if (col >= n_cols) return;
+    split = p.n_stream;
+  }
   const int pass = col % passes;
   const int bkv = col / passes;
   const int kv = bkv % p.n_kv_heads;
   const int b = bkv / p.n_kv_heads;
   const int hq0 = kv * p.group + pass * GT;      // first query head of this pass
 
+#if !SKV_Q8
+  if (fresh) {                                   // the extra workgroup of a fused decode step
+    fresh_rows_block<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s);
+    return;
+  }
+#endif
   int t0, t1;
-  range_of_split(p.n_ctx, p.n_splits, split, &t0, &t1);
+  range_of_split(p.n_ctx, p.n_stream, split, &t0, &t1);
 
   float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
   float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;
@@ -396,9 +508,39 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   using Tile = TileRegs<RK, RV, U>;
   Tile ta;
 
-  // ---- this lane's slice of the projected queries (prepared by the projection kernel), in
-  //      slot order; requested first, the first tile of the range right behind it ---------------
+  // ---- this lane's slice of the projected queries, in slot order.  They come from the workspace
+  //      (prepared by the projection kernel) or, when the raw queries are handed over, are projected
+  //      here: q~ = (q P_K) * scale * log2(e), the same sums as the projection kernel.  Either way the
+  //      first tile of the range is requested before the queries are waited for. -----------------
   float qreg[GT][KM::CPL];
+  Tile tb;                                       // second tile of the range, when requested early
+  bool pre2 = false;
+#if !SKV_Q8
+  if (p.q != nullptr) {
+    ProjectPieces pp;
+    project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
+    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
+    uint16_t qraw[(GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads];
+#pragma unroll
+    for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
+      if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) qraw[k] = qptr[tid + k * kDecodeThreads];
+    if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
+    // the projection below takes about as long as a round trip to HBM: keep a second tile on its way
+    pre2 = SKV_PIPELINE == 1 && n_full >= 3;
+    if (pre2) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + ROWS_PER_WG + lane_row, t1, j, tb);
+#pragma unroll
+    for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
+      if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) px_s[tid + k * kDecodeThreads] = bf16_to_f32(qraw[k]);
+    __syncthreads();
+    project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
+#pragma unroll
+    for (int g = 0; g < GT; ++g) {
+      const float* qh = py_s + HeadSplit<GT>::head_of_slot(g, j >> 2) * RK;
+#pragma unroll
+      for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = qh[KM::chan(j, i)] * p.scale_log2e;
+    }
+  } else
+#endif
   {
     const float* qt = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;
 #pragma unroll
@@ -411,8 +553,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
         qreg[g][i + 1] = v.y;
       }
     }
+    if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
   }
-  if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
 
   // ---- stream the range ---------------------------------------------------------------
   using HS = HeadSplit<GT>;
@@ -445,6 +587,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     for (int k = 1; k < NBUF - 1; ++k)
       if (k < n_full) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + k * ROWS_PER_WG + lane_row, t1, j, ring[k]);
     int i = 0;
+    if constexpr (NBUF == 2) {
+      if (pre2) {                                   // tiles 0 and 1 are both on their way (n_full >= 3)
+        ring[1] = tb;
+        consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
+        issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + 2 * ROWS_PER_WG + lane_row, t1, j, ring[0]);
+        consume_rows<RK, RV, GT, U, false>(ring[1], 0, t1, qd, qreg, m, l, acc, zacc);
+        i = 2;                                      // ring[0] holds tile 2: the loop's invariant
+      }
+    }
     if constexpr (NBUF > 1) {
       while (i + 2 * NBUF - 2 < n_full) {           // ring[k] holds tile i+k for k < NBUF-1
 #pragma unroll
@@ -544,7 +695,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 template <int RK, int RV>
 hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const int passes = p.group / heads;
-  const dim3 grid((unsigned)p.n_splits, (unsigned)(p.batch * p.n_kv_heads * passes));
+  const int cols = p.batch * p.n_kv_heads * passes;
+  const int fresh_rows = p.T_new > 0 ? (cols + p.n_stream - 1) / p.n_stream : 0;
+  const dim3 grid((unsigned)p.n_stream, (unsigned)(cols + fresh_rows));
   const dim3 block(kDecodeThreads);
   switch (heads) {
     case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, SKV_Q8>), grid, block, 0, stream, p); break;

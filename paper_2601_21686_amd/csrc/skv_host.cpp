@@ -12,6 +12,12 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Softmax scale times log2(e); scale <= 0 selects 1/sqrt(head_dim), the ORIGINAL head dimension.
+float scale_log2e_of(float scale) {
+  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
+  return (float)(sc * 1.4426950408889634);
+}
+
 bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; }
 
 // Workgroups the streaming launch aims for: two per compute unit of the 256-CU part.  Each
@@ -73,6 +79,14 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->r_v = L->r_v;
   p->n_ctx = 0;
   p->n_splits = n_splits;
+  p->n_stream = n_splits;
+  p->k_new = nullptr;
+  p->v_new = nullptr;
+  p->k_cache_w = static_cast<uint16_t*>(L->k_cache);
+  p->v_cache_w = static_cast<uint16_t*>(L->v_cache);
+  p->stride_b = p->stride_t = p->stride_h = 0;
+  p->cur_len = 0;
+  p->T_new = 0;
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
@@ -235,8 +249,7 @@ skv_status check_append(const skv_layer* L, const void* k_new, const void* v_new
 void fill_query_params(const skv_layer* L, DecodeParams* p, const void* q, float scale, void* workspace) {
   fill_decode_params(L, p, 1, workspace);
   p->q = static_cast<const uint16_t*>(q);
-  const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
-  p->scale_log2e = (float)(sc * 1.4426950408889634);
+  p->scale_log2e = scale_log2e_of(scale);
 }
 
 void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, const void* v_new,
@@ -285,6 +298,33 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
   p.n_ctx = (int32_t)n_ctx;
   if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
   decode_partial_launcher launch = q8 ? partial_q8_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
+  if (!launch) return SKV_ERR_RANK;
+  if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+// The range kernel with the query projection folded in (bf16 cache): s_stream context ranges over
+// rows [0, n_ctx) and, when T_new > 0, one more partial from the workgroups that project, store
+// and attend the new rows [n_ctx, n_ctx + T_new).
+skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int64_t n_ctx, int32_t s_stream,
+                             const void* k_new, const void* v_new, int64_t stride_b, int64_t stride_t,
+                             int64_t stride_h, int32_t T_new, void* workspace, void* stream) {
+  DecodeParams p;
+  const int32_t total = s_stream + (T_new > 0 ? 1 : 0);
+  fill_decode_params(L, &p, total, workspace);
+  p.n_stream = s_stream;
+  p.n_ctx = (int32_t)n_ctx;
+  p.q = static_cast<const uint16_t*>(q);
+  p.scale_log2e = scale_log2e_of(scale);
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.stride_b = stride_b;
+  p.stride_t = stride_t;
+  p.stride_h = stride_h;
+  p.cur_len = n_ctx;
+  p.T_new = T_new;
+  decode_partial_launcher launch = partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
@@ -340,10 +380,8 @@ skv_status skv_decode_attention(const skv_layer* L, const void* q, void* out, in
   if (st != SKV_OK) return st;
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
-  DecodeParams p;
-  fill_query_params(L, &p, q, scale, workspace);
-  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  st = run_partial(L, n_ctx, s, workspace, stream);
+  // two launches: the range kernel projects the queries itself
+  st = run_partial_fused(L, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
 }
@@ -375,18 +413,26 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
   if (st != SKV_OK) return st;
 
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  DecodeParams qp;
-  fill_query_params(L, &qp, q, scale, workspace);
-  AppendParams ap;
-  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
-  if (T > 0 && (int64_t)L->batch * T <= kVectorAppendMaxRows) {
-    // the usual decode step: new keys, new values and queries projected by one small launch
-    if (launch_project(&ap, &qp, hs) != hipSuccess) return SKV_ERR_HIP;
-  } else {
-    if (T > 0 && launch_append(ap, hs) != hipSuccess) return SKV_ERR_HIP;
-    if (launch_project(nullptr, &qp, hs) != hipSuccess) return SKV_ERR_HIP;
+  const int gq = L->n_q_heads / L->n_kv_heads;
+  // (the fused launch adds up to one grid row per column: stay inside the grid's y limit)
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
+  if (T > 0 && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
+    // The usual decode step, two launches: context ranges over the rows already cached, plus one
+    // workgroup per (sequence, KV head) that projects, stores and attends the new rows; then the merge.
+    int32_t s_old = 0;
+    if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    st = run_partial_fused(L, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
+                           stream);
+    if (st != SKV_OK) return st;
+    return run_combine(L, out, s_old + 1, workspace, stream);
   }
-  st = run_partial(L, n_ctx, s, workspace, stream);
+  if (T > 0) {
+    AppendParams ap;
+    fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+    if (launch_append(ap, hs) != hipSuccess) return SKV_ERR_HIP;
+  }
+  st = run_partial_fused(L, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
 }

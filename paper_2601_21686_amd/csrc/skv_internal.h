@@ -27,8 +27,18 @@ struct DecodeParams {
   int64_t p_v_head_stride;
   int32_t batch, n_q_heads, n_kv_heads, group;
   int32_t r_k, r_v;
-  int32_t n_ctx;
-  int32_t n_splits;
+  int32_t n_ctx;             // cache rows the context ranges cover
+  int32_t n_splits;          // partial results per (sequence, head): what the combine kernel merges
+  int32_t n_stream;          // context ranges over [0, n_ctx); n_splits - 1 when a fresh-rows block is added
+  // Fused decode step (bf16 cache): the range kernel projects the queries itself (q != null) and one extra
+  // workgroup per (sequence, KV head, pass) projects, stores and attends the T_new new rows [cur_len, cur_len + T_new).
+  const uint16_t* k_new;
+  const uint16_t* v_new;
+  uint16_t* k_cache_w;
+  uint16_t* v_cache_w;
+  int64_t stride_b, stride_t, stride_h;
+  int64_t cur_len;
+  int32_t T_new;
   float scale_log2e;         // softmax scale times log2(e)
   int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
@@ -145,6 +155,9 @@ hipError_t launch_folded_prepare(const AppendParams& ap, const DecodeParams& dp,
 
 // Few-token appends (ap) and query projections (dp) in one launch; either may be null.
 hipError_t launch_project(const AppendParams* ap, const DecodeParams* dp, hipStream_t stream);
+
+// New tokens per sequence up to which a decode step folds its append into the range kernel.
+constexpr int kFusedStepMaxTokens = 4;
 
 // Token rows (batch * T) up to which an append runs as vector projections.
 constexpr int kVectorAppendMaxRows = 64;
