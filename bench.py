@@ -356,8 +356,13 @@ def main():
     Lr = layers[li_big]
     n_roof = wl.n_ctx
     splits = args.splits if args.splits > 0 else B.skv_decode_default_splits(Lr, n_roof)
-    partial_fn = B.skv_q8_decode_partial if q8 else B.skv_decode_partial
-    (B.skv_q8_decode_project_query if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
+    if q8 or folded:
+        # these variants keep the projected queries in the workspace (prepared by a small launch)
+        (B.skv_q8_decode_project_query if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
+        partial_fn = B.skv_q8_decode_partial if q8 else B.skv_decode_partial
+    else:
+        # the launch the decode step makes: every workgroup projects its head group's queries itself
+        partial_fn = lambda L_, n_, s_, ws_: B.skv_decode_partial_q(L_, qs[0, li_big], n_, s_, 0.0, ws_)
     for _ in range(10):
         partial_fn(Lr, n_roof, splits, ws)
     torch.cuda.synchronize()
@@ -372,7 +377,8 @@ def main():
     # algorithmic bytes of one launch: every cache row once per KV head, the projected
     # queries in, the per-range partial results out
     rk, rv = ranks_k[li_big], ranks_v[li_big]
-    kern_bytes = Bt * HKV * n_roof * row_bytes(li_big) + Bt * HQ * rk * 4 + Bt * HQ * splits * (rv + 2) * 4
+    q_in = Bt * HQ * rk * 4 if (q8 or folded) else Bt * HQ * d * 2 + HKV * d * rk * 2   # projected queries, or queries + key bases
+    kern_bytes = Bt * HKV * n_roof * row_bytes(li_big) + q_in + Bt * HQ * splits * (rv + 2) * 4
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
 
     result = {
@@ -394,7 +400,7 @@ def main():
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
                    "cache": "8-bit codes, group 64" if q8 else "bf16", "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
-                            else "append 1 token/sequence + decode attention, every layer"),
+                            else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
         "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(achieved, 1),

@@ -139,8 +139,12 @@ skv_status skv_decode_range(int64_t n_ctx, int32_t n_splits, int32_t range,
  * skv_decode_attention(q, out, n_ctx = cur_len + T), i.e. the query attends
  * the freshly appended rows too (Sec. 3.2: attention always sees the
  * reconstructed, compressed forms).  Doing both in one call lets the library
- * project new keys, new values and queries in a single small launch ahead of
- * the streaming kernel.  Arguments and errors as for the two calls.
+ * fold the append into the streaming launch: for T <= 4 the context ranges
+ * cover the rows already cached while one more workgroup per (sequence, KV
+ * head) projects, stores and attends the new rows as a range of their own, so a
+ * step is two launches (ranges, merge).  The cache ends up bit-identical to
+ * the two separate calls; outputs agree up to the order in which ranges are
+ * merged.  Arguments and errors as for the two calls.
  */
 skv_status skv_decode_step(const skv_layer* layer,
                            const void* k_new, const void* v_new,
@@ -152,7 +156,8 @@ skv_status skv_decode_step(const skv_layer* layer,
 /*
  * The three stages of skv_decode_attention, exposed so that a caller can time
  * or schedule them separately; calling them back to back on one stream with
- * the same workspace and n_splits is exactly skv_decode_attention.
+ * the same workspace and n_splits gives bit for bit the result of
+ * skv_decode_attention (which folds the first stage into the second).
  *
  * skv_decode_project_query: q~ = (q P_K) * scale for every query head, with the
  * key basis of the head's KV group (projecting the keys induces the same
@@ -177,6 +182,12 @@ skv_status skv_decode_partial(const skv_layer* layer, int64_t n_ctx, int32_t n_s
                               void* workspace, size_t workspace_bytes, void* stream);
 skv_status skv_decode_combine(const skv_layer* layer, void* out, int32_t n_splits,
                               void* workspace, size_t workspace_bytes, void* stream);
+/* skv_decode_partial with the first stage folded in: every workgroup projects the queries of its
+ * head group itself (the same sums as skv_decode_project_query, so results are bit-identical) --
+ * the launch skv_decode_attention and skv_decode_step actually make.  q as for
+ * skv_decode_attention. */
+skv_status skv_decode_partial_q(const skv_layer* layer, const void* q, float scale, int64_t n_ctx,
+                                int32_t n_splits, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * ---- Folded-weights variant (Sec. 3.4 "Overheads") --------------------------

@@ -26,7 +26,7 @@ SKV_PREFILL_SCHED_TOGETHER, SKV_PREFILL_SCHED_AHEAD = 0x10, 0x20
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
     "skv_decode_default_splits", "skv_decode_range", "skv_decode_step", "skv_decode_project_query",
-    "skv_decode_partial", "skv_decode_combine",
+    "skv_decode_partial", "skv_decode_combine", "skv_decode_partial_q",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
     L.skv_decode_project_query.restype = C.c_int
     L.skv_decode_partial.argtypes = [LP, i64, i32, vp, sz, vp]
     L.skv_decode_partial.restype = C.c_int
+    L.skv_decode_partial_q.argtypes = [LP, vp, C.c_float, i64, i32, vp, sz, vp]
+    L.skv_decode_partial_q.restype = C.c_int
     L.skv_decode_combine.argtypes = [LP, vp, i32, vp, sz, vp]
     L.skv_decode_combine.restype = C.c_int
     L.skv_layer_ranks.argtypes = [i32, i32, C.c_double, C.POINTER(i32), i32, C.POINTER(i32), i32,
@@ -287,6 +289,15 @@ def skv_decode_partial(layer, n_ctx: int, n_splits: int = 0, workspace: torch.Te
     _check(lib().skv_decode_partial(_ref(layer), int(n_ctx), int(n_splits), ws.data_ptr(),
                                     ws.numel() * ws.element_size(), _stream_ptr(stream)),
            "skv_decode_partial")
+
+
+def skv_decode_partial_q(layer, q: torch.Tensor, n_ctx: int, n_splits: int = 0, scale: float = 0.0,
+                         workspace: torch.Tensor | None = None, stream=None) -> None:
+    """The range kernel with the query projection folded in (what skv_decode_attention launches)."""
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_partial_q(_ref(layer), q.data_ptr(), float(scale), int(n_ctx), int(n_splits),
+                                      ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_partial_q")
 
 
 def skv_decode_combine(layer, out: torch.Tensor, n_splits: int, workspace: torch.Tensor | None = None,

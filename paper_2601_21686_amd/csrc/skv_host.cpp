@@ -361,6 +361,16 @@ skv_status skv_decode_partial(const skv_layer* L, int64_t n_ctx, int32_t n_split
   return run_partial(L, n_ctx, s, workspace, stream);
 }
 
+skv_status skv_decode_partial_q(const skv_layer* L, const void* q, float scale, int64_t n_ctx, int32_t n_splits,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_ctx, n_splits, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  return run_partial_fused(L, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream);
+}
+
 skv_status skv_decode_combine(const skv_layer* L, void* out, int32_t n_splits, void* workspace,
                               size_t workspace_bytes, void* stream) {
   const skv_status st = check_combine_stage(L, out, n_splits, workspace, workspace_bytes);

@@ -100,6 +100,11 @@ def test_decode_is_deterministic_and_stage_calls_equal_the_fused_call():
     B.skv_decode_combine(P.gpu, out, s)
     torch.cuda.synchronize()
     assert np.array_equal(out.cpu().numpy(), a)
+    # the range kernel that projects the queries itself gives the same bits
+    B.skv_decode_partial_q(P.gpu, q, n, s)
+    B.skv_decode_combine(P.gpu, out, s)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), a)
     # a different split of the context gives the same result up to float32 rounding
     for s2 in (1, 7):
         B.skv_decode_partial(P.gpu, n, s2)
