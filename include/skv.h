@@ -357,6 +357,23 @@ skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho,
                            const double* delta,
                            int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio);
 
+/*
+ * Ranks that are not multiples of 16.  The paper trains its bases at ranks
+ * spread between 50 % and 90 % of head_dim (App. C: about 64, 77, 90, 102, 115
+ * for head_dim 128); the kernels take multiples of 16.  A rank-r basis is
+ * served exactly by zero columns up to skv_padded_rank(r): zero columns give
+ * zero coefficients, so the cached rows, scores and outputs are those of the
+ * rank-r basis (Sec. 2.1 Eqs. 1-2), at the cache-byte cost of the padding.
+ *
+ * skv_padded_rank: the next multiple of 16 (16..128) for 1 <= r <= 128, else 0.
+ * skv_pad_basis:   dst[b][d][c] = src[b][d][c] for c < r, 0 for r <= c < skv_padded_rank(r).
+ *   src  device bf16 [n_bases][head_dim][r], packed (any 2-byte alignment)
+ *   dst  device bf16 [n_bases][head_dim][skv_padded_rank(r)], packed; must not overlap src
+ * Errors: NULL, SHAPE (n_bases < 1), RANK (r outside [1, 128]), HIP.
+ */
+int32_t skv_padded_rank(int32_t r);
+skv_status skv_pad_basis(const void* src, int32_t n_bases, int32_t r, void* dst, void* stream);
+
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
 size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);

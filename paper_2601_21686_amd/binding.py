@@ -31,6 +31,7 @@ EXPORTS = (
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
+    "skv_padded_rank", "skv_pad_basis",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
 )
 
@@ -123,6 +124,10 @@ def lib() -> C.CDLL:
     L.skv_prefill_step.restype = C.c_int
     L.skv_prefill_tile_tokens.argtypes = [LP]
     L.skv_prefill_tile_tokens.restype = i32
+    L.skv_padded_rank.argtypes = [i32]
+    L.skv_padded_rank.restype = i32
+    L.skv_pad_basis.argtypes = [vp, i32, i32, vp, vp]
+    L.skv_pad_basis.restype = C.c_int
     L.skv_status_string.argtypes = [C.c_int]
     L.skv_status_string.restype = C.c_char_p
     _lib = L
@@ -359,6 +364,27 @@ def skv_decode_step_folded(layer, k_low: torch.Tensor, v_low: torch.Tensor, cur_
                                         int(cur_len), q_low.data_ptr(), out_low.data_ptr(), float(scale),
                                         ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
            "skv_decode_step_folded")
+
+
+# ---- ranks that are not multiples of 16 --------------------------------------------------------
+
+
+def skv_padded_rank(r: int) -> int:
+    return int(lib().skv_padded_rank(int(r)))
+
+
+def skv_pad_basis(basis: torch.Tensor, stream=None) -> torch.Tensor:
+    """basis: bf16 CUDA [n_bases, 128, r] contiguous -> new tensor [n_bases, 128, skv_padded_rank(r)] whose
+    extra columns are zero (the allocation is the binding's; the fill is the library's)."""
+    assert basis.dtype == torch.bfloat16 and basis.is_contiguous() and basis.shape[1] == SKV_HEAD_DIM
+    r = int(basis.shape[2])
+    r_pad = skv_padded_rank(r)
+    if r_pad == 0:
+        raise SkvError(SKV_ERR_RANK, "skv_pad_basis")
+    out = torch.empty((basis.shape[0], SKV_HEAD_DIM, r_pad), dtype=torch.bfloat16, device=basis.device)
+    _check(lib().skv_pad_basis(basis.data_ptr(), int(basis.shape[0]), r, out.data_ptr(), _stream_ptr(stream)),
+           "skv_pad_basis")
+    return out
 
 
 # ---- a chunk of queries (prefill) ---------------------------------------------------

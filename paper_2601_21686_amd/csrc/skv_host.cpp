@@ -783,6 +783,23 @@ skv_status skv_decode_step_folded(const skv_layer* L, const void* k_low, const v
   return run_folded_attention(L, out_low, n_ctx, s, workspace, stream);
 }
 
+int32_t skv_padded_rank(int32_t r) {
+  if (r < 1 || r > SKV_HEAD_DIM) return 0;
+  return (r + 15) / 16 * 16;
+}
+
+skv_status skv_pad_basis(const void* src, int32_t n_bases, int32_t r, void* dst, void* stream) {
+  if (!src || !dst) return SKV_ERR_NULL;
+  if (n_bases < 1) return SKV_ERR_SHAPE;
+  const int32_t r_pad = skv_padded_rank(r);
+  if (r_pad == 0) return SKV_ERR_RANK;
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 1u) return SKV_ERR_ALIGN;
+  if (launch_pad_basis(src, dst, r, r_pad, (int64_t)n_bases * SKV_HEAD_DIM, static_cast<hipStream_t>(stream)) !=
+      hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
 skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho, const int32_t* cand_k,
                            int32_t n_k, const int32_t* cand_v, int32_t n_v, const double* delta,
                            int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio) {

@@ -258,3 +258,15 @@ def test_folded_variant_argument_checks():
     assert g(C.byref(L), FAKE, FAKE, 1, 5, None, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_NULL
     assert g(C.byref(L), FAKE, FAKE, 0, 0, FAKE, FAKE, 0.0, FAKE, ws, None) == B.SKV_ERR_CAPACITY   # nothing to attend
     assert g(C.byref(L), FAKE, FAKE, 1, 5, FAKE, FAKE, 0.0, FAKE, 64, None) == B.SKV_ERR_WORKSPACE
+
+
+def test_padded_rank_and_pad_basis_argument_checks():
+    lib = B.lib()
+    assert [lib.skv_padded_rank(r) for r in (1, 16, 17, 64, 77, 90, 102, 115, 128)] == [16, 16, 32, 64, 80, 96, 112, 128, 128]
+    assert lib.skv_padded_rank(0) == 0 and lib.skv_padded_rank(129) == 0 and lib.skv_padded_rank(-3) == 0
+    buf = (C.c_uint16 * 8)()
+    p = C.cast(buf, C.c_void_p)
+    assert lib.skv_pad_basis(None, 1, 77, p, None) == B.SKV_ERR_NULL
+    assert lib.skv_pad_basis(p, 0, 77, p, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_pad_basis(p, 1, 0, p, None) == B.SKV_ERR_RANK
+    assert lib.skv_pad_basis(p, 1, 200, p, None) == B.SKV_ERR_RANK

@@ -431,3 +431,29 @@ def test_prefill_rows_equal_decode_steps_and_row_selection():
     assert np.allclose(lifted, got, rtol=1e-12, atol=1e-13)
     part_low = O.prefill_attention_folded(L, q_low, n_prev, rows=some)
     assert np.array_equal(part_low[1, 10, 7], a_low[1, 10, 7]) and np.isnan(part_low[0, 0, 0]).all()
+
+
+# ------------------------------------------------- zero-padded bases ----
+
+
+def test_zero_padded_basis_serves_any_rank_exactly():
+    """Sec. 2.1 Eqs. 1-2: a zero column of a basis yields a zero coefficient, so a rank-77 basis padded
+    with zero columns to 80 must give the rank-77 cache in its first 77 channels, zeros in the rest, and
+    the very same attention output.  The reference side is a brute force on the UNPADDED rank-77
+    reconstruction, so nothing here compares the oracle with itself."""
+    rng = np.random.default_rng(77)
+    B, HQ, HKV, d, n = 1, 4, 2, 16, 9
+    rk, rv, rk_pad, rv_pad = 5, 7, 8, 16
+    P_k = np.stack([_rand_orthogonal(rng, d)[:, :rk] for _ in range(HKV)])
+    P_v = np.stack([_rand_orthogonal(rng, d)[:, :rv] for _ in range(HKV)])
+    pad = lambda P, r: np.concatenate([P, np.zeros(P.shape[:2] + (r - P.shape[2],))], axis=2)
+    L, K, V = _layer_f64(rng, B, HQ, HKV, d, rk_pad, rv_pad, n, P_k=pad(P_k, rk_pad), P_v=pad(P_v, rv_pad))
+    assert np.all(L.k_cache[..., rk:] == 0.0) and np.all(L.v_cache[..., rv:] == 0.0)
+    q = rng.standard_normal((B, HQ, d))
+    got = O.decode_attention(L, q, n)
+    for h in range(HQ):
+        kv = h // 2
+        Kt = (K[0, :, kv] @ P_k[kv]) @ P_k[kv].T            # rank-5 reconstruction, unpadded
+        Vt = (V[0, :, kv] @ P_v[kv]) @ P_v[kv].T
+        want = _brute_attention(list(q[0, h]), Kt.tolist(), Vt.tolist(), 1.0 / math.sqrt(d))
+        assert np.max(np.abs(got[0, h] - np.array(want))) < 1e-12
