@@ -358,6 +358,37 @@ skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho,
                            int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio);
 
 /*
+ * ---- Per-sequence lengths -----------------------------------------------------
+ * A serving batch mixes sequences of different lengths; Eq. 18 applies to each
+ * with its own context.  The lengths live on the device (no host round trip in
+ * a serving loop), so the host cannot validate them: each is clamped into
+ * [0, max] where max is the host-side bound the call is checked against.
+ *
+ *   seq_lens / cur_lens  device int32 [batch]
+ *   max_len / max_cur_len  host: an upper bound of the lengths; max_len <= capacity,
+ *                        max_cur_len + T <= capacity
+ * skv_decode_attention_varlen: sequence b attends rows [0, seq_lens[b]); a
+ *   sequence of length 0 has nothing to attend and its outputs are zeros.
+ * skv_project_append_varlen:   the T new rows of sequence b go to rows
+ *   [cur_lens[b], cur_lens[b] + T).
+ * skv_decode_step_varlen:      both for a decode step (T >= 1): rows appended at
+ *   cur_lens[b], then cur_lens[b] + T rows attended.  The caller advances the
+ *   lengths afterwards.
+ * Other arguments, workspace and errors as for the calls without _varlen.
+ */
+skv_status skv_decode_attention_varlen(const skv_layer* layer, const void* q, void* out,
+                                       const int32_t* seq_lens, int64_t max_len, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_project_append_varlen(const skv_layer* layer, const void* k_new, const void* v_new,
+                                     int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                                     const int32_t* cur_lens, int64_t max_cur_len, void* stream);
+skv_status skv_decode_step_varlen(const skv_layer* layer, const void* k_new, const void* v_new,
+                                  int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                                  const int32_t* cur_lens, int64_t max_cur_len,
+                                  const void* q, void* out, float scale,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Ranks that are not multiples of 16.  The paper trains its bases at ranks
  * spread between 50 % and 90 % of head_dim (App. C: about 64, 77, 90, 102, 115
  * for head_dim 128); the kernels take multiples of 16.  A rank-r basis is

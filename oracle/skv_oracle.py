@@ -17,6 +17,7 @@ Everything below is the paper's definition written out with numpy float64:
   * asymmetric integer quantisation of the compressed cache    (Sec. 4.3; 8 bits, group 64)
   * the folded-weights variant: attention in the compressed space (Sec. 3.4 "Overheads")
   * a chunk of queries over the compressed cache (Eq. 18 with T > 1, causal mask)
+  * per-sequence context lengths (Eq. 18 per sequence of a mixed batch)
 
 Readings taken where the paper is silent (all listed in the design notes):
 the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
@@ -39,7 +40,8 @@ of the greedy selector; for the quantiser: on-grid inputs are recovered exactly,
 the round-trip error bound, flat groups, library rounding, and the invariance
 of the output to the key zero point; for the chunk form: the library's causal
 attention (with and without a cached prefix, off-by-one masks rejected), a
-pure-Python brute force and the first-token closed form.  No function here is "parity unpinned".
+pure-Python brute force and the first-token closed form; for per-sequence
+lengths: the library's attention under a key-padding mask.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -260,6 +262,39 @@ def decode_attention_factored(layer: OracleLayer, q: np.ndarray, n_ctx: int,
             p = w / np.sum(w)
             a_low = p @ layer.v_cache[b, kv, :n_ctx, :]           # [r_V]
             out[b, h] = layer.basis_v(kv) @ a_low                 # [d_h]
+    return out
+
+
+# --------------------------------------------------------------------------
+# Per-sequence lengths: Eq. 18 applies to every sequence with its own context
+# --------------------------------------------------------------------------
+
+
+def _one_sequence(layer: OracleLayer, b: int) -> OracleLayer:
+    """A batch-1 layer holding sequence b's cache (views, not copies)."""
+    return OracleLayer(1, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.r_k, layer.r_v,
+                       layer.capacity, layer.p_k, layer.p_v, layer.k_cache[b:b + 1], layer.v_cache[b:b + 1],
+                       layer.store)
+
+
+def project_append_varlen(layer: OracleLayer, k_new: np.ndarray, v_new: np.ndarray, cur_lens) -> None:
+    """project_append with a first row per sequence: the T new rows of sequence b go to
+    [cur_lens[b], cur_lens[b] + T)."""
+    for b in range(layer.batch):
+        project_append(_one_sequence(layer, b), np.asarray(k_new)[b:b + 1], np.asarray(v_new)[b:b + 1],
+                       int(cur_lens[b]))
+
+
+def decode_attention_varlen(layer: OracleLayer, q: np.ndarray, seq_lens, scale: float | None = None) -> np.ndarray:
+    """decode_attention with a context length per sequence: sequence b attends rows [0, seq_lens[b]).
+    A sequence of length 0 has nothing to attend; its outputs are zeros (a convention: the softmax over
+    an empty set is undefined)."""
+    q = np.asarray(q, np.float64)
+    out = np.zeros(q.shape, np.float64)
+    for b in range(layer.batch):
+        n_b = int(seq_lens[b])
+        if n_b > 0:
+            out[b] = decode_attention(_one_sequence(layer, b), q[b:b + 1], n_b, scale)[0]
     return out
 
 

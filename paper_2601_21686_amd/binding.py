@@ -32,6 +32,7 @@ EXPORTS = (
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
     "skv_padded_rank", "skv_pad_basis",
+    "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
 )
 
@@ -124,6 +125,12 @@ def lib() -> C.CDLL:
     L.skv_prefill_step.restype = C.c_int
     L.skv_prefill_tile_tokens.argtypes = [LP]
     L.skv_prefill_tile_tokens.restype = i32
+    L.skv_decode_attention_varlen.argtypes = [LP, vp, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_decode_attention_varlen.restype = C.c_int
+    L.skv_project_append_varlen.argtypes = [LP, vp, vp, i64, i64, i64, i32, vp, i64, vp]
+    L.skv_project_append_varlen.restype = C.c_int
+    L.skv_decode_step_varlen.argtypes = [LP, vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_decode_step_varlen.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
     L.skv_padded_rank.restype = i32
     L.skv_pad_basis.argtypes = [vp, i32, i32, vp, vp]
@@ -364,6 +371,49 @@ def skv_decode_step_folded(layer, k_low: torch.Tensor, v_low: torch.Tensor, cur_
                                         int(cur_len), q_low.data_ptr(), out_low.data_ptr(), float(scale),
                                         ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
            "skv_decode_step_folded")
+
+
+# ---- per-sequence lengths -------------------------------------------------------------------------
+
+
+def _lens_ok(t: torch.Tensor, batch: int) -> None:
+    assert t.dtype == torch.int32 and t.is_cuda and t.is_contiguous() and t.numel() == batch
+
+
+def skv_decode_attention_varlen(layer, q: torch.Tensor, out: torch.Tensor, seq_lens: torch.Tensor, max_len: int,
+                                scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+    """seq_lens: int32 CUDA [batch]; max_len: host upper bound of the lengths."""
+    _lens_ok(seq_lens, layer.batch)
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_attention_varlen(_base_ref(layer), q.data_ptr(), out.data_ptr(), seq_lens.data_ptr(),
+                                             int(max_len), float(scale), ws.data_ptr(),
+                                             ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_decode_attention_varlen")
+
+
+def skv_project_append_varlen(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_lens: torch.Tensor,
+                              max_cur_len: int, stream=None) -> None:
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    _lens_ok(cur_lens, layer.batch)
+    sb, st, sh, _ = k_new.stride()
+    _check(lib().skv_project_append_varlen(_base_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                           int(k_new.shape[1]), cur_lens.data_ptr(), int(max_cur_len),
+                                           _stream_ptr(stream)), "skv_project_append_varlen")
+
+
+def skv_decode_step_varlen(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_lens: torch.Tensor, max_cur_len: int,
+                           q: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
+                           workspace: torch.Tensor | None = None, stream=None) -> None:
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    _lens_ok(cur_lens, layer.batch)
+    sb, st, sh, _ = k_new.stride()
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_step_varlen(_base_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                        int(k_new.shape[1]), cur_lens.data_ptr(), int(max_cur_len), q.data_ptr(),
+                                        out.data_ptr(), float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                        _stream_ptr(stream)), "skv_decode_step_varlen")
 
 
 # ---- ranks that are not multiples of 16 --------------------------------------------------------

@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
   if (tid < RV) {
     float t = part_s[tid];
     for (int g = 1; g < ng; ++g) t += part_s[g * RV + tid];
-    a_s[tid] = t / l;
+    a_s[tid] = l > 0.f ? t / l : 0.f;            // a sequence with no rows (per-sequence lengths) gives zeros
   }
   __syncthreads();
   if (!lift) {

@@ -375,7 +375,7 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
   for (int g = 0; g < GT; ++g) acc[g] = 0.f;
   for (int t = 0; t < p.T_new; ++t) {
     const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
-    const int64_t row = ((int64_t)b * p.n_kv_heads + kv) * p.capacity + p.cur_len + t;
+    const int64_t row = ((int64_t)b * p.n_kv_heads + kv) * p.capacity + clamped_len(p.seq_lens, b, p.cur_len) + t;
     {
       ProjectPieces pp;
       project_rows_issue(pk, RK, pp);
@@ -482,7 +482,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   }
 #endif
   int t0, t1;
-  range_of_split(p.n_ctx, p.n_stream, split, &t0, &t1);
+  range_of_split((int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add, p.n_stream, split, &t0, &t1);
 
   float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
   float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void folded_kernel(const AppendParams p, const
     const int64_t bt = row / p.n_kv_heads;
     const int t = (int)(bt % p.T);
     const int64_t b = bt / p.T;
-    const int64_t drow = (b * p.n_kv_heads + h) * p.capacity + p.cur_len + t;
+    const int64_t drow = (b * p.n_kv_heads + h) * p.capacity + clamped_len(p.cur_lens, (int)b, p.cur_len) + t;
     dst[drow * pieces + piece] = src[i];
   }
 }

@@ -87,6 +87,8 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->stride_b = p->stride_t = p->stride_h = 0;
   p->cur_len = 0;
   p->T_new = 0;
+  p->seq_lens = nullptr;
+  p->len_add = 0;
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
@@ -268,6 +270,7 @@ void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, 
   p->stride_t = stride_t;
   p->stride_h = stride_h;
   p->cur_len = cur_len;
+  p->cur_lens = nullptr;
   p->batch = L->batch;
   p->n_kv_heads = L->n_kv_heads;
   p->r_k = L->r_k;
@@ -309,7 +312,8 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
 // and attend the new rows [n_ctx, n_ctx + T_new).
 skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int64_t n_ctx, int32_t s_stream,
                              const void* k_new, const void* v_new, int64_t stride_b, int64_t stride_t,
-                             int64_t stride_h, int32_t T_new, void* workspace, void* stream) {
+                             int64_t stride_h, int32_t T_new, void* workspace, void* stream,
+                             const int32_t* seq_lens = nullptr, int32_t len_add = 0) {
   DecodeParams p;
   const int32_t total = s_stream + (T_new > 0 ? 1 : 0);
   fill_decode_params(L, &p, total, workspace);
@@ -324,6 +328,8 @@ skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int
   p.stride_h = stride_h;
   p.cur_len = n_ctx;
   p.T_new = T_new;
+  p.seq_lens = seq_lens;
+  p.len_add = len_add;
   decode_partial_launcher launch = partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
@@ -781,6 +787,75 @@ skv_status skv_decode_step_folded(const skv_layer* L, const void* k_low, const v
     return SKV_ERR_HIP;
   }
   return run_folded_attention(L, out_low, n_ctx, s, workspace, stream);
+}
+
+skv_status skv_project_append_varlen(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
+                                     int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
+                                     int64_t max_cur_len, void* stream) {
+  const skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (!cur_lens) return SKV_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  if (T == 0) return SKV_OK;
+  AppendParams p;
+  fill_append_params(L, &p, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  p.cur_lens = cur_lens;
+  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_decode_attention_varlen(const skv_layer* L, const void* q, void* out, const int32_t* seq_lens,
+                                       int64_t max_len, float scale, void* workspace, size_t workspace_bytes,
+                                       void* stream) {
+  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  if (!seq_lens) return SKV_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return SKV_ERR_ALIGN;
+  int32_t s = 0;
+  st = check_partial_stage(L, max_len, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  st = run_partial_fused(L, q, scale, max_len, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, seq_lens, 0);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status skv_decode_step_varlen(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
+                                  int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
+                                  int64_t max_cur_len, const void* q, void* out, float scale, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (T < 1) return SKV_ERR_SHAPE;                       // a step appends at least one row per sequence
+  if (!cur_lens) return SKV_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int64_t n_max = max_cur_len + T;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_max, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int gq = L->n_q_heads / L->n_kv_heads;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
+  if (T <= kFusedStepMaxTokens && max_cur_len > 0 && grid_ok) {
+    int32_t s_old = 0;
+    if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    st = run_partial_fused(L, q, scale, max_cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
+                           stream, cur_lens, 0);
+    if (st != SKV_OK) return st;
+    return run_combine(L, out, s_old + 1, workspace, stream);
+  }
+  AppendParams ap;
+  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  ap.cur_lens = cur_lens;
+  if (launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  st = run_partial_fused(L, q, scale, n_max, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, cur_lens, T);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
 }
 
 int32_t skv_padded_rank(int32_t r) {

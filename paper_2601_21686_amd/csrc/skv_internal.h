@@ -39,6 +39,11 @@ struct DecodeParams {
   int64_t stride_b, stride_t, stride_h;
   int64_t cur_len;
   int32_t T_new;
+  // Per-sequence lengths (device int32 [batch]) or null: sequence b then attends rows [0, len_b) with
+  // len_b = seq_lens[b] clamped into [0, n_ctx]; in a fused step len_b is also where its new rows go.
+  const int32_t* seq_lens;
+  int32_t len_add;           // rows added to every per-sequence length (an append that ran just before): len_b =
+                             // clamp(seq_lens[b], 0, n_ctx - len_add) + len_add
   float scale_log2e;         // softmax scale times log2(e)
   int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
@@ -56,6 +61,7 @@ struct AppendParams {
   int64_t p_v_head_stride;
   int64_t stride_b, stride_t, stride_h;
   int64_t cur_len;
+  const int32_t* cur_lens;   // device int32 [batch] or null: per-sequence first row, clamped into [0, cur_len]
   int32_t batch, n_kv_heads;
   int32_t r_k, r_v;
   int32_t T;
@@ -64,6 +70,13 @@ struct AppendParams {
   const float* k_zero;
   uint32_t* v_meta;          // [batch][n_kv_heads][capacity][groups of r_v]
 };
+
+// Length of sequence b: the uniform value, or the per-sequence one clamped into [0, uniform].
+__host__ __device__ inline int64_t clamped_len(const int32_t* lens, int b, int64_t uniform) {
+  if (!lens) return uniform;
+  const int64_t v = lens[b];
+  return v < 0 ? 0 : (v > uniform ? uniform : v);
+}
 
 // Heads of one KV group handled per workgroup pass (1, 2 or 4).
 inline int heads_per_pass(int group) { return group >= 4 ? 4 : group; }

@@ -270,3 +270,29 @@ def test_padded_rank_and_pad_basis_argument_checks():
     assert lib.skv_pad_basis(p, 0, 77, p, None) == B.SKV_ERR_SHAPE
     assert lib.skv_pad_basis(p, 1, 0, p, None) == B.SKV_ERR_RANK
     assert lib.skv_pad_basis(p, 1, 200, p, None) == B.SKV_ERR_RANK
+
+
+def test_varlen_and_prefill_argument_checks():
+    lib = B.lib()
+    L = _layer()
+    big = 1 << 30
+    # per-sequence lengths: the device array is required and 4-byte aligned; the host bound is checked like n_ctx
+    assert lib.skv_decode_attention_varlen(C.byref(L), FAKE, FAKE, None, 16, 0.0, FAKE, big, None) == B.SKV_ERR_NULL
+    assert lib.skv_decode_attention_varlen(C.byref(L), FAKE, FAKE, FAKE + 2, 16, 0.0, FAKE, big, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_decode_attention_varlen(C.byref(L), FAKE, FAKE, FAKE, 1025, 0.0, FAKE, big, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_project_append_varlen(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 4, None, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_project_append_varlen(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 4, FAKE, 1021, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_decode_step_varlen(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 0, FAKE, 10, FAKE, FAKE, 0.0, FAKE, big,
+                                      None) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_step_varlen(C.byref(L), FAKE, FAKE, 8192, 1024, 128, 1, FAKE, 1024, FAKE, FAKE, 0.0, FAKE,
+                                      big, None) == B.SKV_ERR_CAPACITY
+    # chunk attention
+    assert lib.skv_prefill_attention(C.byref(L), FAKE, 8192, 4096, 128, FAKE, 16, 1010, 0.0, 0, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_prefill_attention(C.byref(L), FAKE, 8192, 4096, 128, FAKE, -1, 0, 0.0, 0, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_prefill_attention(C.byref(L), FAKE, 8192, 4096, 128, FAKE, 16, 0, 0.0, 0x30, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_prefill_attention(C.byref(L), FAKE, 8192, 4100, 128, FAKE, 16, 0, 0.0, 0, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_prefill_attention(C.byref(L), None, 8192, 4096, 128, FAKE, 16, 0, 0.0, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_prefill_attention(C.byref(L), FAKE, 8192, 4096, 128, FAKE, 0, 0, 0.0, 0, None) == B.SKV_OK   # T = 0: no-op
+    Lf = _layer(p_k=None, p_v=None)
+    assert lib.skv_prefill_attention_folded(C.byref(Lf), FAKE, FAKE, 16, 2000, 0.0, 0, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_prefill_tile_tokens(C.byref(L)) == 32 and lib.skv_prefill_tile_tokens(C.byref(_layer(n_q_heads=8))) == 128

@@ -457,3 +457,43 @@ def test_zero_padded_basis_serves_any_rank_exactly():
         Vt = (V[0, :, kv] @ P_v[kv]) @ P_v[kv].T
         want = _brute_attention(list(q[0, h]), Kt.tolist(), Vt.tolist(), 1.0 / math.sqrt(d))
         assert np.max(np.abs(got[0, h] - np.array(want))) < 1e-12
+
+
+# ------------------------------------------------- per-sequence lengths ----
+
+
+def test_per_sequence_lengths_match_library_attention_under_a_padding_mask():
+    """With P = I the varlen routine must equal the library's scaled-dot-product attention where each
+    sequence masks the keys at and beyond its own length; rows placed by the varlen append at
+    per-sequence offsets must be the ones the mask exposes."""
+    rng = np.random.default_rng(123)
+    B, HQ, HKV, d, cap = 3, 4, 2, 8, 12
+    eye = np.stack([np.eye(d)] * HKV)
+    L = O.new_layer(B, HQ, HKV, d, eye, eye, cap, store="f64", fill=7.5)      # sentinel in unwritten rows
+    lens0 = [0, 4, 9]
+    K = rng.standard_normal((B, cap, HKV, d))
+    V = rng.standard_normal((B, cap, HKV, d))
+    for b in range(B):                                                        # fill each sequence to its own length
+        if lens0[b]:
+            O.project_append(O._one_sequence(L, b), K[b:b + 1, :lens0[b]], V[b:b + 1, :lens0[b]], 0)
+    # varlen append of 2 rows per sequence at its own offset
+    k2 = np.stack([K[b, lens0[b]:lens0[b] + 2] for b in range(B)])
+    v2 = np.stack([V[b, lens0[b]:lens0[b] + 2] for b in range(B)])
+    O.project_append_varlen(L, k2, v2, lens0)
+    lens = [n + 2 for n in lens0]
+    for b in range(B):
+        assert np.array_equal(L.k_cache[b, :, :lens[b]], np.transpose(K[b, :lens[b]], (1, 0, 2)))
+        assert np.all(L.k_cache[b, :, lens[b]:] == 7.5)                        # nothing beyond the new rows
+    q = rng.standard_normal((B, HQ, d))
+    got = O.decode_attention_varlen(L, q, lens)
+    G = HQ // HKV
+    kt = torch.from_numpy(np.repeat(np.transpose(K, (0, 2, 1, 3)), G, axis=1))     # [B, HQ, cap, d]
+    vt = torch.from_numpy(np.repeat(np.transpose(V, (0, 2, 1, 3)), G, axis=1))
+    mask = torch.zeros((B, 1, 1, cap), dtype=torch.bool)
+    for b in range(B):
+        mask[b, ..., :lens[b]] = True
+    want = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(q)[:, :, None, :], kt, vt,
+                                                            attn_mask=mask)[:, :, 0].numpy()
+    assert np.max(np.abs(got - want)) < 1e-12
+    # a sequence with no rows yields zeros
+    assert np.all(O.decode_attention_varlen(L, q, [0, 3, 5])[0] == 0.0)
