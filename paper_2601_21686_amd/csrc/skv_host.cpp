@@ -438,6 +438,7 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
     int32_t s_old = 0;
     if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused(L, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
                            stream);
     if (st != SKV_OK) return st;
@@ -844,6 +845,7 @@ skv_status skv_decode_step_varlen(const skv_layer* L, const void* k_new, const v
     int32_t s_old = 0;
     if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused(L, q, scale, max_cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
                            stream, cur_lens, 0);
     if (st != SKV_OK) return st;
