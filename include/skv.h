@@ -405,6 +405,24 @@ skv_status skv_decode_step_varlen(const skv_layer* layer, const void* k_new, con
 int32_t skv_padded_rank(int32_t r);
 skv_status skv_pad_basis(const void* src, int32_t n_bases, int32_t r, void* dst, void* stream);
 
+/*
+ * Basis construction (Sec. 3.3 "Orthonormalization via QR": the predicted
+ * matrix A = Q R is replaced by its orthonormal factor, P-bar = Q; Sec. 3.2
+ * Eq. 6: the rank-r projection matrix is the leading r columns of P-bar).
+ * For every matrix: p_out[:, 0:r] = bf16 of the leading r columns of the Q
+ * factor with positive diagonal of R (unique when those columns of A are
+ * independent; a column that depends on earlier ones becomes a zero column),
+ * computed in float32 by Gram-Schmidt with a second pass per column, rounded
+ * to bf16 once; columns r .. r_out-1 are zero, r_out = skv_padded_rank(r) if
+ * pad != 0, else r.  The result can be used as p_k / p_v of a layer as it is.
+ *   a      device float32 [n_bases][head_dim][head_dim] row-major
+ *   p_out  device bf16 [n_bases][head_dim][r_out], packed
+ * Errors: NULL, SHAPE (n_bases < 1), RANK (r outside [1, 128]), ALIGN (a not
+ * 4-byte, p_out not 2-byte aligned), HIP.
+ */
+skv_status skv_orthonormalize(const void* a, int32_t n_bases, int32_t r, int32_t pad,
+                              void* p_out, void* stream);
+
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
 size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);

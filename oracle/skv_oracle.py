@@ -18,6 +18,8 @@ Everything below is the paper's definition written out with numpy float64:
   * the folded-weights variant: attention in the compressed space (Sec. 3.4 "Overheads")
   * a chunk of queries over the compressed cache (Eq. 18 with T > 1, causal mask)
   * per-sequence context lengths (Eq. 18 per sequence of a mixed batch)
+  * bases from predicted matrices: orthonormal factor of a QR, leading r columns
+                                                               (Sec. 3.3 Eqs. 13-14; Sec. 3.2 Eq. 6)
 
 Readings taken where the paper is silent (all listed in the design notes):
 the softmax scale uses the ORIGINAL head dimension d_h, never the rank; no
@@ -41,7 +43,10 @@ the round-trip error bound, flat groups, library rounding, and the invariance
 of the output to the key zero point; for the chunk form: the library's causal
 attention (with and without a cached prefix, off-by-one masks rejected), a
 pure-Python brute force and the first-token closed form; for per-sequence
-lengths: the library's attention under a key-padding mask.  No function here is "parity unpinned".
+lengths: the library's attention under a key-padding mask; for the basis
+construction: the three properties that make the factor unique (orthonormal
+columns, Q R = A, R upper triangular with positive diagonal), a hand-computed
+2 x 2 case and the projector onto the span of A's leading columns.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -412,6 +417,26 @@ def prefill_attention_folded(layer: OracleLayer, q_low: np.ndarray, n_prev: int,
                 out[b, t, h] = attention_single_query(q_low[b, t, h], layer.k_cache[b, kv, :n_vis, :],
                                                       layer.v_cache[b, kv, :n_vis, :], scale)
     return out
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.3 "Orthonormalization via QR" and Sec. 3.2 Eq. 6: bases from predicted matrices
+# --------------------------------------------------------------------------
+
+
+def orthonormal_basis(A: np.ndarray, r: int) -> np.ndarray:
+    """The rank-r projection matrix built from a predicted square matrix A: factor A = Q R
+    (Sec. 3.3 Eqs. 13-14), keep the orthonormal factor, P-bar = Q, and take its leading r
+    columns (Sec. 3.2 Eq. 6).  QR is unique only up to the signs of the columns of Q; the
+    convention here is a positive diagonal of R, which makes Q unique when the leading r
+    columns of A are independent.  float64 throughout; A is [..., d, d], the result [..., d, r]."""
+    A = np.asarray(A, np.float64)
+    if A.shape[-1] != A.shape[-2] or not 1 <= r <= A.shape[-1]:
+        raise ValueError("A must be square and 1 <= r <= d")
+    Q, R = np.linalg.qr(A)
+    sign = np.sign(np.diagonal(R, axis1=-2, axis2=-1))
+    sign = np.where(sign == 0, 1.0, sign)
+    return (Q * sign[..., None, :])[..., :, :r]
 
 
 # --------------------------------------------------------------------------

@@ -31,7 +31,7 @@ EXPORTS = (
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
-    "skv_padded_rank", "skv_pad_basis",
+    "skv_padded_rank", "skv_pad_basis", "skv_orthonormalize",
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
 )
@@ -131,6 +131,8 @@ def lib() -> C.CDLL:
     L.skv_project_append_varlen.restype = C.c_int
     L.skv_decode_step_varlen.argtypes = [LP, vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_decode_step_varlen.restype = C.c_int
+    L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
+    L.skv_orthonormalize.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
     L.skv_padded_rank.restype = i32
     L.skv_pad_basis.argtypes = [vp, i32, i32, vp, vp]
@@ -434,6 +436,19 @@ def skv_pad_basis(basis: torch.Tensor, stream=None) -> torch.Tensor:
     out = torch.empty((basis.shape[0], SKV_HEAD_DIM, r_pad), dtype=torch.bfloat16, device=basis.device)
     _check(lib().skv_pad_basis(basis.data_ptr(), int(basis.shape[0]), r, out.data_ptr(), _stream_ptr(stream)),
            "skv_pad_basis")
+    return out
+
+
+def skv_orthonormalize(a: torch.Tensor, r: int, pad: bool = True, stream=None) -> torch.Tensor:
+    """a: float32 CUDA [n_bases, 128, 128] -> bf16 [n_bases, 128, r_out]: the leading r columns of each
+    matrix's orthonormal factor (positive diagonal of R), zero-padded to a multiple of 16 if pad."""
+    assert a.dtype == torch.float32 and a.is_contiguous() and a.shape[1:] == (SKV_HEAD_DIM, SKV_HEAD_DIM)
+    r_out = skv_padded_rank(r) if pad else int(r)
+    if not 1 <= int(r) <= SKV_HEAD_DIM:
+        raise SkvError(SKV_ERR_RANK, "skv_orthonormalize")
+    out = torch.empty((a.shape[0], SKV_HEAD_DIM, r_out), dtype=torch.bfloat16, device=a.device)
+    _check(lib().skv_orthonormalize(a.data_ptr(), int(a.shape[0]), int(r), 1 if pad else 0, out.data_ptr(),
+                                    _stream_ptr(stream)), "skv_orthonormalize")
     return out
 
 

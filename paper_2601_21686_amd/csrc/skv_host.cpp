@@ -877,6 +877,17 @@ skv_status skv_pad_basis(const void* src, int32_t n_bases, int32_t r, void* dst,
   return SKV_OK;
 }
 
+skv_status skv_orthonormalize(const void* a, int32_t n_bases, int32_t r, int32_t pad, void* p_out, void* stream) {
+  if (!a || !p_out) return SKV_ERR_NULL;
+  if (n_bases < 1) return SKV_ERR_SHAPE;
+  if (r < 1 || r > SKV_HEAD_DIM) return SKV_ERR_RANK;
+  if ((reinterpret_cast<uintptr_t>(a) & 3u) || (reinterpret_cast<uintptr_t>(p_out) & 1u)) return SKV_ERR_ALIGN;
+  const int32_t r_out = pad ? skv_padded_rank(r) : r;
+  if (launch_orthonormalize(a, p_out, n_bases, r, r_out, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
 skv_status skv_layer_ranks(int32_t n_layers, int32_t head_dim, double rho, const int32_t* cand_k,
                            int32_t n_k, const int32_t* cand_v, int32_t n_v, const double* delta,
                            int32_t* r_k_out, int32_t* r_v_out, double* achieved_ratio) {

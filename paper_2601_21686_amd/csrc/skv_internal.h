@@ -162,6 +162,8 @@ hipError_t launch_prefill_rk128(int, int, int, const PrefillParams&, hipStream_t
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)
 hipError_t launch_pad_basis(const void* src, void* dst, int r, int r_pad, int64_t rows, hipStream_t stream);
+// out bf16 [n][128][r_out]: leading r columns of the orthonormal factor of a float32 [n][128][128], zero columns behind
+hipError_t launch_orthonormalize(const void* a, void* out, int n, int r, int r_out, hipStream_t stream);
 hipError_t launch_append(const AppendParams& p, hipStream_t stream);
 // Folded-weights variant: rows that arrive already projected.
 hipError_t launch_copy_projected(const AppendParams& p, hipStream_t stream);      // k_new / v_new are [b][t][h][r] packed

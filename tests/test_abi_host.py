@@ -296,3 +296,12 @@ def test_varlen_and_prefill_argument_checks():
     Lf = _layer(p_k=None, p_v=None)
     assert lib.skv_prefill_attention_folded(C.byref(Lf), FAKE, FAKE, 16, 2000, 0.0, 0, None) == B.SKV_ERR_CAPACITY
     assert lib.skv_prefill_tile_tokens(C.byref(L)) == 32 and lib.skv_prefill_tile_tokens(C.byref(_layer(n_q_heads=8))) == 128
+
+
+def test_orthonormalize_argument_checks():
+    lib = B.lib()
+    assert lib.skv_orthonormalize(None, 1, 64, 1, FAKE, None) == B.SKV_ERR_NULL
+    assert lib.skv_orthonormalize(FAKE, 0, 64, 1, FAKE, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_orthonormalize(FAKE, 1, 0, 1, FAKE, None) == B.SKV_ERR_RANK
+    assert lib.skv_orthonormalize(FAKE, 1, 129, 0, FAKE, None) == B.SKV_ERR_RANK
+    assert lib.skv_orthonormalize(FAKE + 2, 1, 64, 1, FAKE, None) == B.SKV_ERR_ALIGN

@@ -497,3 +497,41 @@ def test_per_sequence_lengths_match_library_attention_under_a_padding_mask():
     assert np.max(np.abs(got - want)) < 1e-12
     # a sequence with no rows yields zeros
     assert np.all(O.decode_attention_varlen(L, q, [0, 3, 5])[0] == 0.0)
+
+
+# ------------------------------------------------- basis construction ----
+
+
+def test_orthonormal_basis_hand_computed_two_by_two():
+    # A = [[3, 1], [4, 2]]: q1 = a1 / 5 = (0.6, 0.8); a2 - <q1, a2> q1 = (1, 2) - 2.2 (0.6, 0.8) = (-0.32, 0.24),
+    # of norm 0.4, so q2 = (-0.8, 0.6)  (Gram-Schmidt by hand; Sec. 3.3 Eqs. 13-14)
+    Q = O.orthonormal_basis(np.array([[3.0, 1.0], [4.0, 2.0]]), 2)
+    assert np.allclose(Q, [[0.6, -0.8], [0.8, 0.6]], atol=1e-15)
+    assert np.allclose(O.orthonormal_basis(np.array([[3.0, 1.0], [4.0, 2.0]]), 1), [[0.6], [0.8]], atol=1e-15)
+    # negating a column of A must not flip the basis column's sign convention: R_11 stays positive
+    Qn = O.orthonormal_basis(np.array([[-3.0, 1.0], [-4.0, 2.0]]), 2)
+    assert np.allclose(Qn[:, 0], [-0.6, -0.8], atol=1e-15)
+
+
+def test_orthonormal_basis_is_the_unique_positive_diagonal_factor():
+    """Orthonormal columns, R = Q^T A upper triangular with positive diagonal, Q R = A: together these
+    determine Q for a full-rank A, so verifying them pins the routine without calling it twice."""
+    rng = np.random.default_rng(5)
+    d = 128
+    A = rng.standard_normal((3, d, d))
+    for r in (1, 16, 77, 128):
+        Q = O.orthonormal_basis(A, r)
+        assert Q.shape == (3, d, r)
+        for i in range(3):
+            assert np.max(np.abs(Q[i].T @ Q[i] - np.eye(r))) < 1e-13
+            R = Q[i].T @ A[i][:, :r]
+            assert np.max(np.abs(np.tril(R, -1))) < 1e-12
+            assert np.all(np.diag(R) > 0)
+            assert np.max(np.abs(Q[i] @ R - A[i][:, :r])) < 1e-12
+            # the projector depends on the span of A's leading columns only (Sec. 3.3)
+            Ar = A[i][:, :r]
+            proj = Ar @ np.linalg.solve(Ar.T @ Ar, Ar.T)
+            assert np.max(np.abs(Q[i] @ Q[i].T - proj)) < 1e-10
+    # a matrix that already has orthonormal columns scaled by positive numbers comes back unscaled
+    Q0 = _rand_orthogonal(rng, d)
+    assert np.max(np.abs(O.orthonormal_basis(Q0 * rng.uniform(0.5, 2.0, d)[None, :], 40) - Q0[:, :40])) < 1e-13
