@@ -54,11 +54,14 @@ def parse_args():
     ap.add_argument("--prefill-chunk", type=int, default=0, help="--mode prefill: tokens in the chunk (0 = the workload's append chunk)")
     ap.add_argument("--prefill-prev", type=int, default=-1, help="--mode prefill: cached tokens before the chunk (-1 = n_ctx - chunk)")
     ap.add_argument("--ranks", default="", help="--mode prefill/append: override the workload's ranks, as r_k,r_v")
-    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append", "prefill"), default="bench",
+    ap.add_argument("--lengths", default="1.0,0.5,0.25,0.03125",
+                    help="--mode varlen: per-sequence context lengths as fractions of the workload's context, cycled over the batch")
+    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append", "prefill", "varlen"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
                          "append: the chunk append of the workload (projection on the matrix cores) alone; "
-                         "prefill: causal attention of the workload's chunk over the compressed cache (matrix cores) alone")
+                         "prefill: causal attention of the workload's chunk over the compressed cache (matrix cores) alone; "
+                         "varlen: decode steps over a batch whose sequences have different context lengths")
     return ap.parse_args()
 
 
@@ -141,6 +144,45 @@ def main():
                           "achieved_GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                           "achieved_TFLOPs": round(flops / us / 1e6, 1), "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / 2500.0, 4),
                           "launches": iters + 3}))
+        return
+    if args.mode == "varlen":
+        # decode steps (append one token per sequence at its own position, attend its own context) over a batch
+        # of mixed lengths; bytes counted are the rows each sequence really attends
+        Bt, HQ, HKV, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
+        rk, rv = (wl.r_k or 64), (wl.r_v or 64)
+        fr = [float(x) for x in args.lengths.split(",")]
+        lens0 = [max(1, int(wl.n_ctx * fr[b % len(fr)])) - 1 for b in range(Bt)]
+        K = args.steps
+        cap = wl.n_ctx + K + 8
+        _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pk"), HKV, d, rk)
+        _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pv"), HKV, d, rv)
+        L = B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap)
+        sck = synth.channel_scales(synth.stable_seed(wl.name, 0, "sk"), HKV, d)
+        for c0 in range(0, max(lens0), 4096):                       # every sequence filled up to the longest one
+            t = min(4096, max(lens0) - c0)
+            k = synth.kv_activations(synth.stable_seed(wl.name, 0, "k", c0), Bt, t, HKV, d, sck, dev)
+            B.skv_project_append(L, k, k, c0)
+        nk = synth.kv_activations(1, Bt, K + 4, HKV, d, sck, dev)
+        q = synth.queries(2, Bt, HQ, d, dev)
+        out = torch.empty((Bt, HQ, d), dtype=torch.float32, device=dev)
+        lens = torch.tensor(lens0, dtype=torch.int32, device=dev)
+        lens_steps = torch.stack([lens + s for s in range(K + 4)]).contiguous()   # the caller advances the lengths
+        for s in range(4):
+            B.skv_decode_step_varlen(L, nk[:, s:s + 1], nk[:, s:s + 1], lens_steps[s], max(lens0) + s, q, out)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for s in range(4, K + 4):
+            B.skv_decode_step_varlen(L, nk[:, s:s + 1], nk[:, s:s + 1], lens_steps[s], max(lens0) + s, q, out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / K
+        nbytes = sum(HKV * (n + K // 2 + 5) * (rk + rv) * 2 for n in lens0)
+        print(json.dumps({"mode": "varlen", "workload": wl.name, "batch": Bt, "context_lengths": [n + 1 for n in lens0],
+                          "r_k": rk, "r_v": rv, "steps": K, "us_per_step": round(us, 2),
+                          "cache_bytes_per_step": nbytes, "achieved_GBps": round(nbytes / us / 1e3, 1),
+                          "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
+                          "tokens_per_s": round(Bt / (us * 1e-6), 1), "launch": "per-call launches"}))
         return
     if args.mode == "prefill":
         # attention of a chunk of T new tokens over n_prev cached ones (rows of the chunk already appended)

@@ -217,3 +217,39 @@ def test_alternating_calls_on_one_workspace_are_bit_stable():
         name = "a" if i % 2 == 0 else "b"
         assert np.array_equal(got[i], got[i % 2]), i                     # same bits as the first call of its kind
         assert vec_rel_err(got[i], ref[name]) < 1e-5                      # and the two-launch path's values
+
+
+def test_decode_steps_captured_in_a_hip_graph_replay_identically():
+    # The benchmark replays a captured graph of decode steps.  Capture three steps, replay the graph
+    # several times with eager work and synchronisations in between, and compare every replay with the
+    # eager result: the launches record no memset nodes and keep no state between calls.
+    n0, steps = 900, 3
+    P = Pair(("graph",), 2, 8, 2, 64, 64, n0 + steps)
+    k0, v0 = P.raw_kv(1, n0)
+    B.skv_project_append(P.gpu, k0, v0, 0)
+    kn, vn = P.raw_kv(2, steps)
+    qs = [P.queries(10 + s) for s in range(steps)]
+    ws = P.gpu.workspace()
+    eager = torch.empty((steps, 2, 8, 128), dtype=torch.float32, device="cuda")
+    for s in range(steps):
+        B.skv_decode_step(P.gpu, kn[:, s:s + 1], vn[:, s:s + 1], n0 + s, qs[s], eager[s], 0.0, ws)
+    torch.cuda.synchronize()
+    cache_after = P.gpu.k_cache.clone()
+    outs = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for s in range(steps):
+                B.skv_decode_step(P.gpu, kn[:, s:s + 1], vn[:, s:s + 1], n0 + s, qs[s], outs[s], 0.0, ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        outs.fill_(float("nan"))
+        P.gpu.k_cache[:, :, n0:] = 0                      # eager work between replays: wipe the appended rows
+        ws.random_(0, 255)                                # and scribble over the workspace
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, eager), rep
+        assert torch.equal(P.gpu.k_cache.view(torch.int16), cache_after.view(torch.int16)), rep
