@@ -40,8 +40,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
-    ap.add_argument("--cache", choices=("bf16", "q8"), default="bf16",
-                    help="bf16: the benchmarked configuration; q8: the 8-bit quantised compressed cache "
+    ap.add_argument("--cache", choices=("bf16", "q8", "q4"), default="bf16",
+                    help="bf16: the benchmarked configuration; q8 / q4: the 8- or 4-bit quantised compressed cache "
                          "(keys with static per-head group ranges, values with per-token group ranges)")
     ap.add_argument("--variant", choices=("explicit", "folded"), default="explicit",
                     help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
@@ -271,7 +271,10 @@ def main():
     cap = wl.n_ctx + K + 8
     assert n0 >= 1
 
-    q8 = args.cache == "q8"
+    qbits = {"bf16": 0, "q8": 8, "q4": 4}[args.cache]
+    q8 = qbits != 0                                  # any quantised cache
+    QF = {8: (B.skv_q8_project_append, B.skv_q8_decode_step, B.skv_q8_decode_project_query, B.skv_q8_decode_partial),
+          4: (B.skv_q4_project_append, B.skv_q4_decode_step, B.skv_q4_decode_project_query, B.skv_q4_decode_partial)}
     folded = args.variant == "folded"
     if folded and q8:
         print("bench.py: --variant folded runs over the bf16 cache only", file=sys.stderr)
@@ -282,13 +285,13 @@ def main():
         (plain torch, outside every timed region)."""
         return torch.einsum("...hd,hdc->...hc", x.float(), basis.to(x.device).float()).to(torch.bfloat16).contiguous()
 
-    append_fn = B.skv_q8_project_append if q8 else B.skv_project_append
-    step_fn = B.skv_q8_decode_step if q8 else B.skv_decode_step
+    append_fn = QF[qbits][0] if q8 else B.skv_project_append
+    step_fn = QF[qbits][1] if q8 else B.skv_decode_step
 
     def row_bytes(li):
         """Bytes one cached token of one KV head occupies in layer li."""
         if q8:
-            return ranks_k[li] + ranks_v[li] + 4 * ((ranks_v[li] + 63) // 64)
+            return (ranks_k[li] + ranks_v[li]) * qbits // 8 + 4 * ((ranks_v[li] + 63) // 64)
         return 2 * (ranks_k[li] + ranks_v[li])
 
     layers, scales, k_ranges = [], [], []
@@ -308,9 +311,9 @@ def main():
             # a margin of half the observed span on either side: rows outside it would clamp
             span = hi - lo
             lo, hi = lo - 0.5 * span, hi + 0.5 * span
-            ksc, kzr = ((hi - lo) / 255.0).contiguous(), lo.contiguous()
+            ksc, kzr = ((hi - lo) / float(2 ** qbits - 1)).contiguous(), lo.contiguous()
             k_ranges.append((ksc, kzr))
-            layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap))
+            layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap, qbits))
         else:
             layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
 
@@ -400,8 +403,8 @@ def main():
     splits = args.splits if args.splits > 0 else B.skv_decode_default_splits(Lr, n_roof)
     if q8 or folded:
         # these variants keep the projected queries in the workspace (prepared by a small launch)
-        (B.skv_q8_decode_project_query if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
-        partial_fn = B.skv_q8_decode_partial if q8 else B.skv_decode_partial
+        (QF[qbits][2] if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
+        partial_fn = QF[qbits][3] if q8 else B.skv_decode_partial
     else:
         # the launch the decode step makes: every workgroup projects its head group's queries itself
         partial_fn = lambda L_, n_, s_, ws_: B.skv_decode_partial_q(L_, qs[0, li_big], n_, s_, 0.0, ws_)
@@ -441,7 +444,7 @@ def main():
                    "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
-                   "cache": "8-bit codes, group 64" if q8 else "bf16", "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
+                   "cache": f"{qbits}-bit codes, group 64" if q8 else "bf16", "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
@@ -466,7 +469,7 @@ def main():
         n_chk = n0 + s_chk + 1
         if q8:
             ora = O.new_quant_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v),
-                                    k_ranges[li][0].cpu().numpy(), k_ranges[li][1].cpu().numpy(), n_chk)
+                                    k_ranges[li][0].cpu().numpy(), k_ranges[li][1].cpu().numpy(), n_chk, qbits)
             ora_append, ora_decode = O.quant_project_append, O.quant_decode_attention
         else:
             ora = O.new_layer(Bt, HQ, HKV, d, f64(layers[li].p_k), f64(layers[li].p_v), n_chk, store="bf16")

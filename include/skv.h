@@ -329,6 +329,33 @@ skv_status skv_q8_decode_partial(const skv_q8_layer* layer, int64_t n_ctx, int32
 size_t skv_q8_cache_bytes(const skv_q8_layer* layer, int64_t n_tokens);
 
 /*
+ * The same with 4-bit codes (the paper lowers the bit width further, Sec. 4.3):
+ * code = clamp(round_half_even((x - zero) / scale), 0, 15); two channels per
+ * byte, channel 2c in the low half of byte c and channel 2c + 1 in the high
+ * half; value ranges scale = bf16((max - min)/15).  Ranks must be multiples
+ * of 64.  The struct is shared: only the meaning of the code arrays differs.
+ *   base.k_cache  device uint8 [batch][n_kv_heads][capacity][r_k / 2]
+ *   base.v_cache  device uint8 [batch][n_kv_heads][capacity][r_v / 2]
+ * Everything else as for the skv_q8_ functions of the same name.
+ */
+typedef skv_q8_layer skv_q4_layer;
+skv_status skv_q4_project_append(const skv_q4_layer* layer, const void* k_new, const void* v_new,
+                                 int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                                 int32_t T, int64_t cur_len, void* stream);
+skv_status skv_q4_decode_attention(const skv_q4_layer* layer, const void* q, void* out,
+                                   int64_t n_ctx, float scale,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_q4_decode_step(const skv_q4_layer* layer, const void* k_new, const void* v_new,
+                              int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                              int32_t T, int64_t cur_len, const void* q, void* out, float scale,
+                              void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_q4_decode_project_query(const skv_q4_layer* layer, const void* q, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_q4_decode_partial(const skv_q4_layer* layer, int64_t n_ctx, int32_t n_splits,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+size_t skv_q4_cache_bytes(const skv_q4_layer* layer, int64_t n_tokens);
+
+/*
  * Sequential budgeted rank selection (Sec. 3.5 Eqs. 15-17; App. B Alg. 2).
  * Host only; touches no GPU.  delta is host float64 [n_layers][n_k][n_v]
  * row-major: the layer-output error of layer l at ranks (cand_k[i], cand_v[j]).

@@ -30,6 +30,8 @@ EXPORTS = (
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial",
+    "skv_q4_project_append", "skv_q4_decode_attention", "skv_q4_decode_step", "skv_q4_cache_bytes",
+    "skv_q4_decode_project_query", "skv_q4_decode_partial",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
     "skv_padded_rank", "skv_pad_basis", "skv_orthonormalize",
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
@@ -111,6 +113,16 @@ def lib() -> C.CDLL:
     L.skv_q8_decode_partial.restype = C.c_int
     L.skv_q8_cache_bytes.argtypes = [QP, i64]
     L.skv_q8_cache_bytes.restype = sz
+    for w in ("q4",):
+        getattr(L, f"skv_{w}_project_append").argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp]
+        getattr(L, f"skv_{w}_decode_attention").argtypes = [QP, vp, vp, i64, C.c_float, vp, sz, vp]
+        getattr(L, f"skv_{w}_decode_step").argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
+        getattr(L, f"skv_{w}_decode_project_query").argtypes = [QP, vp, C.c_float, vp, sz, vp]
+        getattr(L, f"skv_{w}_decode_partial").argtypes = [QP, i64, i32, vp, sz, vp]
+        getattr(L, f"skv_{w}_cache_bytes").argtypes = [QP, i64]
+        for f in ("project_append", "decode_attention", "decode_step", "decode_project_query", "decode_partial"):
+            getattr(L, f"skv_{w}_{f}").restype = C.c_int
+        getattr(L, f"skv_{w}_cache_bytes").restype = sz
     L.skv_append_projected.argtypes = [LP, vp, vp, i32, i64, vp]
     L.skv_append_projected.restype = C.c_int
     L.skv_decode_attention_folded.argtypes = [LP, vp, vp, i64, C.c_float, vp, sz, vp]
@@ -195,15 +207,18 @@ class Layer:
 
 
 class QuantLayer:
-    """One layer's 8-bit quantised compressed cache (ranks multiples of 32).
+    """One layer's quantised compressed cache: 8-bit codes (ranks multiples of 32, one byte per channel)
+    or 4-bit codes (bits=4: ranks multiples of 64, two channels per byte).
 
     k_scale, k_zero: float32 CUDA tensors [n_kv_heads, ceil(r_k / 64)] (static key ranges).
     Codes are uint8 tensors; v_meta is int32 [batch, n_kv_heads, capacity, ceil(r_v / 64)]
     holding a bf16 scale (low half) and a bf16 zero (high half) per value row and group.
     """
 
-    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, k_scale, k_zero, capacity):
+    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, k_scale, k_zero, capacity, bits=8):
         dev = p_k.device
+        assert bits in (8, 4)
+        self.bits = int(bits)
         self.batch, self.n_q_heads, self.n_kv_heads = int(batch), int(n_q_heads), int(n_kv_heads)
         self.capacity = int(capacity)
         self.r_k, self.r_v = int(p_k.shape[2]), int(p_v.shape[2])
@@ -211,8 +226,8 @@ class QuantLayer:
         self.k_scale = k_scale.to(device=dev, dtype=torch.float32).contiguous()
         self.k_zero = k_zero.to(device=dev, dtype=torch.float32).contiguous()
         ngv = (self.r_v + 63) // 64
-        self.k_cache = torch.empty((batch, n_kv_heads, capacity, self.r_k), dtype=torch.uint8, device=dev)
-        self.v_cache = torch.empty((batch, n_kv_heads, capacity, self.r_v), dtype=torch.uint8, device=dev)
+        self.k_cache = torch.empty((batch, n_kv_heads, capacity, self.r_k * self.bits // 8), dtype=torch.uint8, device=dev)
+        self.v_cache = torch.empty((batch, n_kv_heads, capacity, self.r_v * self.bits // 8), dtype=torch.uint8, device=dev)
         self.v_meta = torch.empty((batch, n_kv_heads, capacity, ngv), dtype=torch.int32, device=dev)
         base = skv_layer(
             self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v, self.capacity,
@@ -494,54 +509,76 @@ def skv_prefill_tile_tokens(layer) -> int:
     return int(lib().skv_prefill_tile_tokens(_base_ref(layer)))
 
 
-# ---- 8-bit quantised cache ------------------------------------------------------
+# ---- quantised cache (8- or 4-bit codes; a QuantLayer knows its width) ------------------------
 
 
-def skv_q8_project_append(layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
-                          stream=None) -> None:
+def _qfn(layer: "QuantLayer", name: str, bits: int):
+    """The C function of that name for the given code width; it must be the layer's."""
+    assert layer.bits == bits, f"a {layer.bits}-bit layer was passed to a q{bits} call"
+    return getattr(lib(), f"skv_q{bits}_{name}")
+
+
+def _q_project_append(bits, layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
+                      stream=None) -> None:
     assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
     assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
     sb, st, sh, _ = k_new.stride()
-    _check(lib().skv_q8_project_append(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
-                                       int(k_new.shape[1]), int(cur_len), _stream_ptr(stream)),
-           "skv_q8_project_append")
+    _check(_qfn(layer, "project_append", bits)(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                               int(k_new.shape[1]), int(cur_len), _stream_ptr(stream)),
+           f"skv_q{bits}_project_append")
 
 
-def skv_q8_decode_attention(layer: QuantLayer, q: torch.Tensor, out: torch.Tensor, n_ctx: int,
-                            scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+def _q_decode_attention(bits, layer: QuantLayer, q: torch.Tensor, out: torch.Tensor, n_ctx: int,
+                        scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_q8_decode_attention(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx), float(scale),
-                                         ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
-           "skv_q8_decode_attention")
+    _check(_qfn(layer, "decode_attention", bits)(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx), float(scale),
+                                                 ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           f"skv_q{bits}_decode_attention")
 
 
-def skv_q8_decode_step(layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
-                       q: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
-                       workspace: torch.Tensor | None = None, stream=None) -> None:
+def _q_decode_step(bits, layer: QuantLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int,
+                   q: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
+                   workspace: torch.Tensor | None = None, stream=None) -> None:
     assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
     sb, st, sh, _ = k_new.stride()
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_q8_decode_step(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
-                                    int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
-                                    float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
-                                    _stream_ptr(stream)), "skv_q8_decode_step")
+    _check(_qfn(layer, "decode_step", bits)(_ref(layer), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                            int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
+                                            float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                            _stream_ptr(stream)), f"skv_q{bits}_decode_step")
 
 
-def skv_q8_decode_project_query(layer: QuantLayer, q: torch.Tensor, scale: float = 0.0,
-                                workspace: torch.Tensor | None = None, stream=None) -> None:
+def _q_decode_project_query(bits, layer: QuantLayer, q: torch.Tensor, scale: float = 0.0,
+                            workspace: torch.Tensor | None = None, stream=None) -> None:
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_q8_decode_project_query(_ref(layer), q.data_ptr(), float(scale), ws.data_ptr(),
-                                             ws.numel() * ws.element_size(), _stream_ptr(stream)),
-           "skv_q8_decode_project_query")
+    _check(_qfn(layer, "decode_project_query", bits)(_ref(layer), q.data_ptr(), float(scale), ws.data_ptr(),
+                                                     ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           f"skv_q{bits}_decode_project_query")
 
 
-def skv_q8_decode_partial(layer: QuantLayer, n_ctx: int, n_splits: int = 0,
-                          workspace: torch.Tensor | None = None, stream=None) -> None:
+def _q_decode_partial(bits, layer: QuantLayer, n_ctx: int, n_splits: int = 0,
+                      workspace: torch.Tensor | None = None, stream=None) -> None:
     ws = layer.workspace() if workspace is None else workspace
-    _check(lib().skv_q8_decode_partial(_ref(layer), int(n_ctx), int(n_splits), ws.data_ptr(),
-                                       ws.numel() * ws.element_size(), _stream_ptr(stream)),
-           "skv_q8_decode_partial")
+    _check(_qfn(layer, "decode_partial", bits)(_ref(layer), int(n_ctx), int(n_splits), ws.data_ptr(),
+                                               ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           f"skv_q{bits}_decode_partial")
 
 
-def skv_q8_cache_bytes(layer: QuantLayer, n_tokens: int) -> int:
-    return int(lib().skv_q8_cache_bytes(_ref(layer), int(n_tokens)))
+def _q_cache_bytes(bits, layer: QuantLayer, n_tokens: int) -> int:
+    return int(_qfn(layer, "cache_bytes", bits)(_ref(layer), int(n_tokens)))
+
+
+def _bind(fn, bits):
+    def bound(*a, **kw):
+        return fn(bits, *a, **kw)
+    bound.__doc__ = fn.__doc__
+    return bound
+
+
+skv_q8_project_append, skv_q4_project_append = _bind(_q_project_append, 8), _bind(_q_project_append, 4)
+skv_q8_decode_attention, skv_q4_decode_attention = _bind(_q_decode_attention, 8), _bind(_q_decode_attention, 4)
+skv_q8_decode_step, skv_q4_decode_step = _bind(_q_decode_step, 8), _bind(_q_decode_step, 4)
+skv_q8_decode_project_query, skv_q4_decode_project_query = (_bind(_q_decode_project_query, 8),
+                                                            _bind(_q_decode_project_query, 4))
+skv_q8_decode_partial, skv_q4_decode_partial = _bind(_q_decode_partial, 8), _bind(_q_decode_partial, 4)
+skv_q8_cache_bytes, skv_q4_cache_bytes = _bind(_q_cache_bytes, 8), _bind(_q_cache_bytes, 4)

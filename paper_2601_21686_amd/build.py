@@ -19,6 +19,7 @@ BUILD_DIR = os.path.join(ROOT, "_build")
 
 KEY_RANKS = (16, 32, 48, 64, 80, 96, 112, 128)
 Q8_KEY_RANKS = (32, 64, 96, 128)          # the 8-bit quantised cache takes multiples of 32
+Q4_KEY_RANKS = (64, 128)                  # the 4-bit one multiples of 64 (a lane owns whole 32-bit words of a row)
 
 # Packed-FP32 instruction selection is switched off for all device code.
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -53,7 +54,11 @@ def _jobs():
                      DEVICE_FLAGS + PREFILL_FLAGS))
     for rk in Q8_KEY_RANKS:
         jobs.append((f"skv_decode_partial_q8_rk{rk}.o",
-                     ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_Q8=1"],
+                     ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=8"],
+                     DEVICE_FLAGS))
+    for rk in Q4_KEY_RANKS:
+        jobs.append((f"skv_decode_partial_q4_rk{rk}.o",
+                     ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=4"],
                      DEVICE_FLAGS))
     return jobs
 

@@ -3,9 +3,9 @@
 //
 // This file is compiled once per key rank (-DSKV_RK=16,32,...,128); each
 // object holds the kernels for that r_K and every r_V in {16,...,128} and
-// 1, 2 or 4 query heads per workgroup.  With -DSKV_Q8=1 it is compiled for
-// the 8-bit quantised cache (Sec. 4.3; ranks 32, 64, 96, 128): rows hold one
-// byte per channel, key scales are already folded into q~ (the key zero point
+// 1, 2 or 4 query heads per workgroup.  With -DSKV_QBITS=8 (or 4) it is compiled
+// for the quantised cache (Sec. 4.3; 8 bits: ranks 32, 64, 96, 128, one byte per
+// channel; 4 bits: ranks 64, 128, two channels per byte): key scales are already folded into q~ (the key zero point
 // adds the same constant to every score of a query and drops out of the
 // softmax), and every value row carries a (scale, zero) pair per 64-channel
 // group: a~ = sum_j (p_j scale_j) code_j + sum_j p_j zero_j.
@@ -34,8 +34,12 @@
 #ifndef SKV_RK
 #error "compile with -DSKV_RK=<key rank>"
 #endif
-#ifndef SKV_Q8
-#define SKV_Q8 0
+#ifndef SKV_QBITS
+#define SKV_QBITS 0                 // 0: bf16 rows; 8 or 4: integer codes of that width (Sec. 4.3)
+#endif
+#define SKV_Q8 (SKV_QBITS != 0)     // any quantised build: codes plus per-row value ranges
+#if SKV_QBITS != 0 && SKV_QBITS != 8 && SKV_QBITS != 4
+#error "SKV_QBITS must be 0, 8 or 4"
 #endif
 
 namespace skv {
@@ -48,10 +52,15 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // How the r channels of a row are dealt to the 8 lanes of an octet: lane j owns the j-th eighth
 // of the first 64 channels and the j-th eighth of the rest.
-#if SKV_Q8
+#if SKV_QBITS == 8
 constexpr int kElemsPerDword = 4;                // one byte per channel
+constexpr int kFmt = 1;
+#elif SKV_QBITS == 4
+constexpr int kElemsPerDword = 8;                // two channels per byte, the even one in the low half
+constexpr int kFmt = 2;
 #else
 constexpr int kElemsPerDword = 2;                // bf16
+constexpr int kFmt = 0;
 #endif
 template <int R>
 struct RowMap {
@@ -115,11 +124,23 @@ template <int R>
 __device__ __forceinline__ void unpack_row(const uint32_t (&w)[RowMap<R>::DPL], float (&f)[RowMap<R>::CPL]) {
 #pragma unroll
   for (int i = 0; i < RowMap<R>::DPL; ++i) {
-#if SKV_Q8
+#if SKV_QBITS == 8
     f[4 * i] = (float)(w[i] & 0xffu);
     f[4 * i + 1] = (float)((w[i] >> 8) & 0xffu);
     f[4 * i + 2] = (float)((w[i] >> 16) & 0xffu);
     f[4 * i + 3] = (float)(w[i] >> 24);
+#elif SKV_QBITS == 4
+    // even channels sit in the low halves of the bytes, odd ones in the high halves: two masks,
+    // then one byte-to-float conversion per channel
+    const uint32_t ev = w[i] & 0x0f0f0f0fu, od = (w[i] >> 4) & 0x0f0f0f0fu;
+    f[8 * i] = (float)(ev & 0xffu);
+    f[8 * i + 1] = (float)(od & 0xffu);
+    f[8 * i + 2] = (float)((ev >> 8) & 0xffu);
+    f[8 * i + 3] = (float)((od >> 8) & 0xffu);
+    f[8 * i + 4] = (float)((ev >> 16) & 0xffu);
+    f[8 * i + 5] = (float)((od >> 16) & 0xffu);
+    f[8 * i + 6] = (float)(ev >> 24);
+    f[8 * i + 7] = (float)(od >> 24);
 #else
     f[2 * i] = bf16_lo(w[i]);
     f[2 * i + 1] = bf16_hi(w[i]);
@@ -432,10 +453,10 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
 }
 #endif
 
-// FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes).
+// FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes, 2: 4-bit codes).
 template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
-  static_assert(FMT == SKV_Q8, "format tag must match the build");
+  static_assert(FMT == kFmt, "format tag must match the build");
   using KM = RowMap<RK>;
   using VM = RowMap<RV>;
   constexpr int U = Depth<RK, RV>::U;
@@ -700,9 +721,9 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const dim3 grid((unsigned)p.n_stream, (unsigned)(cols + fresh_rows));
   const dim3 block(kDecodeThreads);
   switch (heads) {
-    case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, SKV_Q8>), grid, block, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, SKV_Q8>), grid, block, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 4, SKV_Q8>), grid, block, 0, stream, p); break;
+    case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
+    case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
+    case 4: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 4, kFmt>), grid, block, 0, stream, p); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -711,15 +732,17 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
 template <int RK>
 hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stream) {
   switch (r_v) {
-#if !SKV_Q8
+#if SKV_QBITS == 0
     case 16: return launch_rv<RK, 16>(heads, p, stream);
     case 48: return launch_rv<RK, 48>(heads, p, stream);
     case 80: return launch_rv<RK, 80>(heads, p, stream);
     case 112: return launch_rv<RK, 112>(heads, p, stream);
 #endif
+#if SKV_QBITS != 4
     case 32: return launch_rv<RK, 32>(heads, p, stream);
-    case 64: return launch_rv<RK, 64>(heads, p, stream);
     case 96: return launch_rv<RK, 96>(heads, p, stream);
+#endif
+    case 64: return launch_rv<RK, 64>(heads, p, stream);
     case 128: return launch_rv<RK, 128>(heads, p, stream);
   }
   return hipErrorInvalidValue;
@@ -729,8 +752,10 @@ hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stre
 
 #define SKV_CAT2(a, b) a##b
 #define SKV_CAT(a, b) SKV_CAT2(a, b)
-#if SKV_Q8
+#if SKV_QBITS == 8
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q8_rk, SKV_RK)
+#elif SKV_QBITS == 4
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q4_rk, SKV_RK)
 #else
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_rk, SKV_RK)
 #endif

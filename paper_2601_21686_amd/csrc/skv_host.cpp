@@ -279,11 +279,19 @@ void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, 
   p->k_scale = nullptr;
   p->k_zero = nullptr;
   p->v_meta = nullptr;
+  p->qbits = 0;
 }
 
 // ---- launches -----------------------------------------------------------------------------
 
-decode_partial_launcher partial_q8_launcher_for(int r_k) {
+decode_partial_launcher partial_q_launcher_for(int bits, int r_k) {
+  if (bits == 4) {
+    switch (r_k) {
+      case 64: return launch_decode_partial_q4_rk64;
+      case 128: return launch_decode_partial_q4_rk128;
+    }
+    return nullptr;
+  }
   switch (r_k) {
     case 32: return launch_decode_partial_q8_rk32;
     case 64: return launch_decode_partial_q8_rk64;
@@ -295,12 +303,12 @@ decode_partial_launcher partial_q8_launcher_for(int r_k) {
 
 // q8: the quantised layer the call is for, or null for the bf16 cache.
 skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* workspace, void* stream,
-                       const skv_q8_layer* q8 = nullptr) {
+                       const skv_q8_layer* q8 = nullptr, int bits = 8) {
   DecodeParams p;
   fill_decode_params(L, &p, s, workspace);
   p.n_ctx = (int32_t)n_ctx;
   if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
-  decode_partial_launcher launch = q8 ? partial_q8_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
+  decode_partial_launcher launch = q8 ? partial_q_launcher_for(bits, L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
@@ -578,13 +586,14 @@ skv_status skv_prefill_step(const skv_layer* L, const void* k_new, const void* v
 
 namespace {
 
-// The quantised cache takes ranks that are multiples of 32 (one byte per channel, whole
-// dwords per lane).
-skv_status check_q8_layer(const skv_q8_layer* Q) {
+// The quantised cache stores whole 32-bit words of a row per lane: ranks are multiples of 32 with
+// 8-bit codes (one byte per channel) and of 64 with 4-bit codes (two channels per byte).
+skv_status check_q_layer(const skv_q8_layer* Q, int bits) {
   if (!Q) return SKV_ERR_NULL;
   const skv_status st = check_layer(&Q->base);
   if (st != SKV_OK) return st;
-  if ((Q->base.r_k % 32) || (Q->base.r_v % 32)) return SKV_ERR_RANK;
+  const int step = bits == 8 ? 32 : 64;
+  if ((Q->base.r_k % step) || (Q->base.r_v % step)) return SKV_ERR_RANK;
   if (!Q->k_scale || !Q->k_zero || !Q->v_meta) return SKV_ERR_NULL;
   if ((reinterpret_cast<uintptr_t>(Q->k_scale) | reinterpret_cast<uintptr_t>(Q->k_zero) |
        reinterpret_cast<uintptr_t>(Q->v_meta)) & 3u)
@@ -592,95 +601,73 @@ skv_status check_q8_layer(const skv_q8_layer* Q) {
   return SKV_OK;
 }
 
-void fill_q8_query(const skv_q8_layer* Q, DecodeParams* p, const void* q, float scale, void* workspace) {
+void fill_q_query(const skv_q8_layer* Q, DecodeParams* p, const void* q, float scale, void* workspace) {
   fill_query_params(&Q->base, p, q, scale, workspace);
   p->k_scale = Q->k_scale;
 }
 
-void fill_q8_append(const skv_q8_layer* Q, AppendParams* p, const void* k_new, const void* v_new,
-                    int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len) {
+void fill_q_append(const skv_q8_layer* Q, int bits, AppendParams* p, const void* k_new, const void* v_new,
+                   int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len) {
   fill_append_params(&Q->base, p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   p->k_scale = Q->k_scale;
   p->k_zero = Q->k_zero;
   p->v_meta = static_cast<uint32_t*>(Q->v_meta);
+  p->qbits = bits;
 }
 
-}  // namespace
-
-extern "C" {
-
-size_t skv_q8_cache_bytes(const skv_q8_layer* Q, int64_t n_tokens) {
+size_t q_cache_bytes(const skv_q8_layer* Q, int bits, int64_t n_tokens) {
   if (!Q || n_tokens < 0) return 0;
   const skv_layer* L = &Q->base;
   const size_t groups_v = (size_t)(L->r_v + 63) / 64;
-  return (size_t)L->batch * L->n_kv_heads * (size_t)n_tokens * ((size_t)(L->r_k + L->r_v) + 4u * groups_v);
+  return (size_t)L->batch * L->n_kv_heads * (size_t)n_tokens *
+         ((size_t)(L->r_k + L->r_v) * (size_t)bits / 8u + 4u * groups_v);
 }
 
-skv_status skv_q8_project_append(const skv_q8_layer* Q, const void* k_new, const void* v_new,
-                                 int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
-                                 int64_t cur_len, void* stream) {
-  skv_status st = check_q8_layer(Q);
+skv_status q_project_append(const skv_q8_layer* Q, int bits, const void* k_new, const void* v_new, int64_t stride_b,
+                            int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, void* stream) {
+  skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   st = check_append(&Q->base, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   if (st != SKV_OK || T == 0) return st;
   AppendParams p;
-  fill_q8_append(Q, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  fill_q_append(Q, bits, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   if (launch_project(&p, nullptr, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
   return SKV_OK;
 }
 
-skv_status skv_q8_decode_attention(const skv_q8_layer* Q, const void* q, void* out, int64_t n_ctx,
-                                   float scale, void* workspace, size_t workspace_bytes,
-                                   void* stream) {
-  skv_status st = check_q8_layer(Q);
-  if (st != SKV_OK) return st;
-  const skv_layer* L = &Q->base;
-  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  int32_t s = 0;
-  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
-  if (st != SKV_OK) return st;
-  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  DecodeParams p;
-  fill_q8_query(Q, &p, q, scale, workspace);
-  if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  st = run_partial(L, n_ctx, s, workspace, stream, Q);
-  if (st != SKV_OK) return st;
-  return run_combine(L, out, s, workspace, stream);
-}
-
-skv_status skv_q8_decode_project_query(const skv_q8_layer* Q, const void* q, float scale,
-                                       void* workspace, size_t workspace_bytes, void* stream) {
-  skv_status st = check_q8_layer(Q);
+skv_status q_decode_project_query(const skv_q8_layer* Q, int bits, const void* q, float scale, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   st = check_query_stage(&Q->base, q, scale, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   DecodeParams p;
-  fill_q8_query(Q, &p, q, scale, workspace);
+  fill_q_query(Q, &p, q, scale, workspace);
   if (launch_project(nullptr, &p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
   return SKV_OK;
 }
 
-skv_status skv_q8_decode_partial(const skv_q8_layer* Q, int64_t n_ctx, int32_t n_splits,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
-  skv_status st = check_q8_layer(Q);
+skv_status q_decode_partial(const skv_q8_layer* Q, int bits, int64_t n_ctx, int32_t n_splits, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+  skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   int32_t s = 0;
   st = check_partial_stage(&Q->base, n_ctx, n_splits, workspace, workspace_bytes, &s);
   if (st != SKV_OK) return st;
-  return run_partial(&Q->base, n_ctx, s, workspace, stream, Q);
+  return run_partial(&Q->base, n_ctx, s, workspace, stream, Q, bits);
 }
 
-skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const void* v_new,
-                              int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
-                              int64_t cur_len, const void* q, void* out, float scale,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-  skv_status st = check_q8_layer(Q);
+// T = 0: attention only
+skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, const void* v_new, int64_t stride_b,
+                         int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q, void* out,
+                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   const skv_layer* L = &Q->base;
-  st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
-  if (st != SKV_OK) return st;
+  if (T > 0 || k_new || v_new) {
+    st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+    if (st != SKV_OK) return st;
+  }
   st = check_query_stage(L, q, scale, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   const int64_t n_ctx = cur_len + T;
@@ -690,14 +677,72 @@ skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const vo
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   DecodeParams qp;
-  fill_q8_query(Q, &qp, q, scale, workspace);
+  fill_q_query(Q, &qp, q, scale, workspace);
   AppendParams ap;
-  fill_q8_append(Q, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (T > 0) fill_q_append(Q, bits, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   if (launch_project(T > 0 ? &ap : nullptr, &qp, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
-  st = run_partial(L, n_ctx, s, workspace, stream, Q);
+  st = run_partial(L, n_ctx, s, workspace, stream, Q, bits);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t skv_q8_cache_bytes(const skv_q8_layer* Q, int64_t n_tokens) { return q_cache_bytes(Q, 8, n_tokens); }
+size_t skv_q4_cache_bytes(const skv_q4_layer* Q, int64_t n_tokens) { return q_cache_bytes(Q, 4, n_tokens); }
+
+skv_status skv_q8_project_append(const skv_q8_layer* Q, const void* k_new, const void* v_new, int64_t stride_b,
+                                 int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, void* stream) {
+  return q_project_append(Q, 8, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len, stream);
+}
+skv_status skv_q4_project_append(const skv_q4_layer* Q, const void* k_new, const void* v_new, int64_t stride_b,
+                                 int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, void* stream) {
+  return q_project_append(Q, 4, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len, stream);
+}
+
+skv_status skv_q8_decode_attention(const skv_q8_layer* Q, const void* q, void* out, int64_t n_ctx, float scale,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  return q_decode_step(Q, 8, nullptr, nullptr, 0, 0, 0, 0, n_ctx, q, out, scale, workspace, workspace_bytes, stream);
+}
+skv_status skv_q4_decode_attention(const skv_q4_layer* Q, const void* q, void* out, int64_t n_ctx, float scale,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  return q_decode_step(Q, 4, nullptr, nullptr, 0, 0, 0, 0, n_ctx, q, out, scale, workspace, workspace_bytes, stream);
+}
+
+skv_status skv_q8_decode_project_query(const skv_q8_layer* Q, const void* q, float scale, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  return q_decode_project_query(Q, 8, q, scale, workspace, workspace_bytes, stream);
+}
+skv_status skv_q4_decode_project_query(const skv_q4_layer* Q, const void* q, float scale, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  return q_decode_project_query(Q, 4, q, scale, workspace, workspace_bytes, stream);
+}
+
+skv_status skv_q8_decode_partial(const skv_q8_layer* Q, int64_t n_ctx, int32_t n_splits, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return q_decode_partial(Q, 8, n_ctx, n_splits, workspace, workspace_bytes, stream);
+}
+skv_status skv_q4_decode_partial(const skv_q4_layer* Q, int64_t n_ctx, int32_t n_splits, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  return q_decode_partial(Q, 4, n_ctx, n_splits, workspace, workspace_bytes, stream);
+}
+
+skv_status skv_q8_decode_step(const skv_q8_layer* Q, const void* k_new, const void* v_new, int64_t stride_b,
+                              int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q, void* out,
+                              float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0) return SKV_ERR_SHAPE;
+  return q_decode_step(Q, 8, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len, q, out, scale, workspace,
+                       workspace_bytes, stream);
+}
+skv_status skv_q4_decode_step(const skv_q4_layer* Q, const void* k_new, const void* v_new, int64_t stride_b,
+                              int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q, void* out,
+                              float scale, void* workspace, size_t workspace_bytes, void* stream) {
+  if (T < 0) return SKV_ERR_SHAPE;
+  return q_decode_step(Q, 4, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len, q, out, scale, workspace,
+                       workspace_bytes, stream);
 }
 
 }  // extern "C"

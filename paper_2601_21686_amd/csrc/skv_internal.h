@@ -65,10 +65,12 @@ struct AppendParams {
   int32_t batch, n_kv_heads;
   int32_t r_k, r_v;
   int32_t T;
-  // 8-bit quantised cache only (null otherwise): the caches then hold one byte per channel
+  // quantised cache only (null otherwise): the caches then hold qbits-wide codes (8: one byte per channel;
+  // 4: two channels per byte, the even one in the low half)
   const float* k_scale;      // [n_kv_heads][groups of r_k]
   const float* k_zero;
   uint32_t* v_meta;          // [batch][n_kv_heads][capacity][groups of r_v]
+  int32_t qbits;
 };
 
 // Length of sequence b: the uniform value, or the per-sequence one clamped into [0, uniform].
@@ -147,6 +149,8 @@ hipError_t launch_decode_partial_q8_rk32(int, int, const DecodeParams&, hipStrea
 hipError_t launch_decode_partial_q8_rk64(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q4_rk64(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_q4_rk128(int, int, const DecodeParams&, hipStream_t);
 
 // sched: 0 = the default schedule for the shape, 1 = keys and values staged together, 2 = keys a tile ahead
 typedef hipError_t (*prefill_launcher)(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream);

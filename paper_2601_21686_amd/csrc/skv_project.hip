@@ -1,7 +1,7 @@
 // Projections of a few rows onto a basis, on the vector ALUs:
 //   * new keys / values when only a few tokens are appended
 //     (Sec. 2.1 Eq. 1: k_down = k P_K, v_down = v P_V), stored as bf16 or, for
-//     the quantised cache of Sec. 4.3, as 8-bit codes;
+//     the quantised cache of Sec. 4.3, as 8- or 4-bit codes;
 //   * the decode query, q~ = (q P_K) * scale * log2(e), for all query heads
 //     (projecting the keys induces the same projection of the query inside
 //     q K~^T = (q P_K) K_down^T, Sec. 2.1 Eq. 2 and Sec. 2.2).
@@ -49,8 +49,9 @@ __global__ __launch_bounds__(kProjectThreads) void project_kernel(const AppendPa
       if (tid < r) cache[row * r + tid] = (uint16_t)f32_to_bf16_bits(y_s[tid]);
       return;
     }
-    // 8-bit cache (Sec. 4.3): code = clamp(rne((y - zero) / scale), 0, 255) per 64-channel group.
-    // Thread c holds channel c; group g is wave g.
+    // Quantised cache (Sec. 4.3): code = clamp(rne((y - zero) / scale), 0, 2^bits - 1) per 64-channel
+    // group.  Thread c holds channel c; group g is wave g.
+    const float top = (float)((1 << ap.qbits) - 1);
     const int ng = (r + 63) >> 6;
     const int g = tid >> 6;
     const bool live = tid < r;
@@ -66,17 +67,20 @@ __global__ __launch_bounds__(kProjectThreads) void project_kernel(const AppendPa
         lo = fminf(lo, __shfl_xor(lo, off));
         hi = fmaxf(hi, __shfl_xor(hi, off));
       }
-      uint32_t sb = f32_to_bf16_bits(__fdiv_rn(hi - lo, 255.0f));
+      uint32_t sb = f32_to_bf16_bits(__fdiv_rn(hi - lo, top));
       if ((sb & 0x7fffu) == 0) sb = 0x3F80u;       // flat group: scale 1
       const uint32_t zb = f32_to_bf16_bits(lo);
       scale = __uint_as_float(sb << 16);
       zero = __uint_as_float(zb << 16);
       if (live && (tid & 63) == 0) ap.v_meta[row * ng + g] = sb | (zb << 16);
     }
-    if (live) {
-      const float code = fminf(fmaxf(rintf(__fdiv_rn(y - zero, scale)), 0.f), 255.f);
-      uint8_t* cache = reinterpret_cast<uint8_t*>(which ? ap.v_cache : ap.k_cache);
-      cache[row * r + tid] = (uint8_t)code;
+    const uint32_t code = live ? (uint32_t)fminf(fmaxf(rintf(__fdiv_rn(y - zero, scale)), 0.f), top) : 0u;
+    uint8_t* cache = reinterpret_cast<uint8_t*>(which ? ap.v_cache : ap.k_cache);
+    if (ap.qbits == 8) {
+      if (live) cache[row * r + tid] = (uint8_t)code;
+    } else {                                       // 4 bits: channel 2c in the low half of byte c, 2c + 1 in the high half
+      const uint32_t next = __shfl_down(code, 1);
+      if (live && (tid & 1) == 0) cache[(row * r + tid) >> 1] = (uint8_t)(code | (next << 4));
     }
     return;
   }

@@ -305,3 +305,16 @@ def test_orthonormalize_argument_checks():
     assert lib.skv_orthonormalize(FAKE, 1, 0, 1, FAKE, None) == B.SKV_ERR_RANK
     assert lib.skv_orthonormalize(FAKE, 1, 129, 0, FAKE, None) == B.SKV_ERR_RANK
     assert lib.skv_orthonormalize(FAKE + 2, 1, 64, 1, FAKE, None) == B.SKV_ERR_ALIGN
+
+
+def test_four_bit_layer_argument_checks():
+    lib = B.lib()
+    big = 1 << 30
+    Q = B.skv_q8_layer(_layer(), FAKE, FAKE, FAKE)
+    assert lib.skv_q4_decode_attention(C.byref(Q), FAKE, FAKE, 2000, 0.0, FAKE, big, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_q4_cache_bytes(C.byref(Q), 10) == 4 * 8 * 10 * (64 + 4)
+    Q32 = B.skv_q8_layer(_layer(r_k=32, p_k_head_stride=128 * 32), FAKE, FAKE, FAKE)
+    assert lib.skv_q8_decode_attention(C.byref(Q32), FAKE, FAKE, 2000, 0.0, FAKE, big, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_q4_decode_attention(C.byref(Q32), FAKE, FAKE, 16, 0.0, FAKE, big, None) == B.SKV_ERR_RANK
+    assert lib.skv_q4_project_append(C.byref(Q32), FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_RANK
+    assert lib.skv_q4_decode_step(C.byref(Q), FAKE, FAKE, 8192, 1024, 128, -1, 0, FAKE, FAKE, 0.0, FAKE, big, None) == B.SKV_ERR_SHAPE

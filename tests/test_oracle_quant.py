@@ -154,3 +154,28 @@ def test_quant_append_places_rows_and_leaves_the_rest():
         for h in range(HKV):
             want = np.clip(np.rint((K[b, :, h] @ P64[h]).astype(np.float32)), 0, 255)
             assert np.array_equal(L.k_codes[b, h, cur:cur + T], want.astype(np.uint8))
+
+
+def test_four_bit_codes_by_hand_and_round_trip():
+    # 16 levels: scale 0.5, zero -1 -> codes 0..15, half-way cases to the even code, clamping at 15
+    y = np.array([[-1.0, -0.75, -0.5, 0.25, 6.5, 6.4, 7.0, -2.0]])
+    want = np.array([[0, 0, 1, 2, 15, 15, 15, 0]], np.uint8)
+    #            (x+1)/.5 =  0, 0.5->0, 1, 2.5->2, 15, 14.8->15, 16->clamp, clamp
+    got = O.quantize_static(y, np.array([0.5], np.float32), np.array([-1.0], np.float32), bits=4)
+    assert np.array_equal(got, want)
+    rng = np.random.default_rng(3)
+    # on-grid inputs come back exactly; the calibrated range spans codes 0..15; error at most half a step
+    codes = rng.integers(0, 16, size=(30, 128)).astype(np.uint8)
+    scale, zero = np.array([0.25, 2.0 ** -4], np.float32), np.array([-2.0, 0.5], np.float32)
+    assert np.array_equal(O.quantize_static(O.dequantize(codes, scale, zero), scale, zero, bits=4), codes)
+    x = rng.uniform(-1.0, 2.0, size=(100, 64))
+    sc, zr = O.calibrate_static_range(x, bits=4)
+    c = O.quantize_static(x, sc, zr, bits=4)
+    assert c.min() == 0 and c.max() == 15
+    assert np.all(np.abs(O.dequantize(c, sc, zr) - x) <= sc[0] / 2 * (1 + 1e-4) + 1e-6)
+    # per-row ranges: scale = bf16((max - min) / 15)
+    row = np.concatenate([np.arange(64) % 16 * 0.125, np.full(64, 3.0)])[None]
+    cd, sb, zb = O.quantize_dynamic(row, bits=4)
+    assert O.bf16_bits_to_f64(sb)[0, 0] == 0.125 and O.bf16_bits_to_f64(zb)[0, 0] == 0.0
+    assert np.array_equal(cd[0, :64], np.arange(64) % 16)
+    assert O.bf16_bits_to_f64(sb)[0, 1] == 1.0 and np.all(cd[0, 64:] == 0)          # flat group
