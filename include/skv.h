@@ -295,9 +295,10 @@ int32_t skv_prefill_tile_tokens(const skv_layer* layer);
  *   v_meta        device uint32 [batch][n_kv_heads][capacity][ceil(r_v/64)]:
  *                 bf16 scale in the low half, bf16 zero in the high half
  * Everything else (bases, strides, workspace, streams, errors) as for the bf16
- * cache; workspace size is skv_decode_workspace_bytes(&q->base).  Appends of any
- * T run as per-token projections (a matrix-core chunk path is not part of this
- * variant).
+ * cache; workspace size is skv_decode_workspace_bytes(&q->base).  Chunks are
+ * projected on the matrix cores and quantised from the float32 accumulators;
+ * a few rows run as vector projections (the two may round a projection
+ * differently in its last float32 bit, which can move a code by one).
  */
 typedef struct {
   skv_layer base;

@@ -4,7 +4,7 @@
 //
 // A chunk of tokens is a dense [tokens x 128] . [128 x r] contraction per KV
 // head and runs on the matrix cores (MFMA 16x16x32 bf16, float32 accumulate);
-// this file holds that kernel.  A handful of tokens (a decode step appends one
+// this file holds that kernel, for the bf16 cache and for the quantised one.  A handful of tokens (a decode step appends one
 // per sequence) is a matrix-vector product and runs on the vector ALUs (see
 // skv_project.hip).  Both round the float32 sum to bf16 once, to nearest even.
 #include "skv_device_util.h"
@@ -64,6 +64,9 @@ __device__ __forceinline__ void load_token_frags(const AppendParams& p, const ui
   }
 }
 
+// QBITS: 0 = bf16 rows; 8 / 4 = the quantised cache of Sec. 4.3 (codes of that width, static key ranges,
+// per-token value ranges), quantised straight from the float32 accumulators.
+template <int QBITS>
 __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t pt_s[SKV_HEAD_DIM * kLdsPitch];   // [channel][d]
 
@@ -116,25 +119,98 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
       dst_row[nt] = ((int64_t)b * p.n_kv_heads + h) * p.capacity + clamped_len(p.cur_lens, b, p.cur_len) + t;
     }
 
-    for (int mt = 0; mt < (r >> 4); ++mt) {
-      f32x4 acc[kTilesPerWave];
+    if constexpr (QBITS == 0) {
+      for (int mt = 0; mt < (r >> 4); ++mt) {
+        f32x4 acc[kTilesPerWave];
 #pragma unroll
-      for (int nt = 0; nt < kTilesPerWave; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int nt = 0; nt < kTilesPerWave; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        const bf16x8 a = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4*>(&pt_s[(mt * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
+        for (int ks = 0; ks < 4; ++ks) {
+          const bf16x8 a = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const uint4*>(&pt_s[(mt * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
 #pragma unroll
-        for (int nt = 0; nt < kTilesPerWave; ++nt)
-          acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cur.b[nt][ks], acc[nt], 0, 0, 0);
+          for (int nt = 0; nt < kTilesPerWave; ++nt)
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cur.b[nt][ks], acc[nt], 0, 0, 0);
+        }
+#pragma unroll
+        for (int nt = 0; nt < kTilesPerWave; ++nt) {
+          if (!valid[nt]) continue;
+          uint2 o;
+          o.x = pack_bf16x2(acc[nt][0], acc[nt][1]);
+          o.y = pack_bf16x2(acc[nt][2], acc[nt][3]);
+          *reinterpret_cast<uint2*>(cache + dst_row[nt] * r + mt * 16 + lk * 4) = o;
+        }
       }
+    } else {
+      // One 64-channel quantisation group (4 channel tiles, fewer in a short last group) at a time:
+      // code = clamp(rne((y - zero) / scale), 0, 2^bits - 1), the same float32 operations as the
+      // few-token path.  A lane holds 4 consecutive channels of a token per tile; the 4 lanes that
+      // share a token sit 16 apart.
+      constexpr float top = (float)((1 << QBITS) - 1);
+      const int ng = (r + 63) >> 6;
+      uint8_t* codes = reinterpret_cast<uint8_t*>(cache);
+      for (int g = 0; g < ng; ++g) {
+        const int mt0 = g * 4;
+        const int mtn = (r >> 4) - mt0 < 4 ? (r >> 4) - mt0 : 4;
+        f32x4 acc[4][kTilesPerWave];
 #pragma unroll
-      for (int nt = 0; nt < kTilesPerWave; ++nt) {
-        if (!valid[nt]) continue;
-        uint2 o;
-        o.x = pack_bf16x2(acc[nt][0], acc[nt][1]);
-        o.y = pack_bf16x2(acc[nt][2], acc[nt][3]);
-        *reinterpret_cast<uint2*>(cache + dst_row[nt] * r + mt * 16 + lk * 4) = o;
+        for (int m = 0; m < 4; ++m) {
+#pragma unroll
+          for (int nt = 0; nt < kTilesPerWave; ++nt) acc[m][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (m < mtn) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+              const bf16x8 a = __builtin_bit_cast(
+                  bf16x8, *reinterpret_cast<const uint4*>(&pt_s[((mt0 + m) * 16 + lrow) * kLdsPitch + ks * 32 + lk * 8]));
+#pragma unroll
+              for (int nt = 0; nt < kTilesPerWave; ++nt)
+                acc[m][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, cur.b[nt][ks], acc[m][nt], 0, 0, 0);
+            }
+          }
+        }
+#pragma unroll
+        for (int nt = 0; nt < kTilesPerWave; ++nt) {
+          float scale, zero;
+          if (which == 0) {                            // keys: static range of this KV head and group
+            scale = p.k_scale[h * ng + g];
+            zero = p.k_zero[h * ng + g];
+          } else {                                     // values: this token's range over the group, kept as bf16
+            float lo = 3.0e38f, hi = -3.0e38f;
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+              if (m < mtn) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  lo = fminf(lo, acc[m][nt][e]);
+                  hi = fmaxf(hi, acc[m][nt][e]);
+                }
+              }
+            lo = fminf(lo, __shfl_xor(lo, 16));
+            hi = fmaxf(hi, __shfl_xor(hi, 16));
+            lo = fminf(lo, __shfl_xor(lo, 32));
+            hi = fmaxf(hi, __shfl_xor(hi, 32));
+            uint32_t sb = f32_to_bf16_bits(__fdiv_rn(hi - lo, top));
+            if ((sb & 0x7fffu) == 0) sb = 0x3F80u;     // flat group: scale 1
+            const uint32_t zb = f32_to_bf16_bits(lo);
+            scale = __uint_as_float(sb << 16);
+            zero = __uint_as_float(zb << 16);
+            if (valid[nt] && lk == 0) p.v_meta[dst_row[nt] * ng + g] = sb | (zb << 16);
+          }
+          if (!valid[nt]) continue;
+#pragma unroll
+          for (int m = 0; m < 4; ++m)
+            if (m < mtn) {
+              uint32_t c[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                c[e] = (uint32_t)fminf(fmaxf(rintf(__fdiv_rn(acc[m][nt][e] - zero, scale)), 0.f), top);
+              const int64_t ch = dst_row[nt] * r + (mt0 + m) * 16 + lk * 4;      // first of this lane's 4 channels
+              if constexpr (QBITS == 8)
+                *reinterpret_cast<uint32_t*>(codes + ch) = c[0] | (c[1] << 8) | (c[2] << 16) | (c[3] << 24);
+              else
+                *reinterpret_cast<uint16_t*>(codes + (ch >> 1)) = (uint16_t)(c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12));
+            }
+        }
       }
     }
     cur = nxt;
@@ -149,7 +225,9 @@ hipError_t launch_append(const AppendParams& p, hipStream_t stream) {
   int64_t blocks = (rows + kTokensPerWg - 1) / kTokensPerWg;
   if (blocks > kMaxBlocksPerHead) blocks = kMaxBlocksPerHead;
   const dim3 grid((unsigned)blocks, (unsigned)p.n_kv_heads, 2u);
-  hipLaunchKernelGGL(append_mfma_kernel, grid, dim3(256), 0, stream, p);
+  if (p.qbits == 8) hipLaunchKernelGGL(append_mfma_kernel<8>, grid, dim3(256), 0, stream, p);
+  else if (p.qbits == 4) hipLaunchKernelGGL(append_mfma_kernel<4>, grid, dim3(256), 0, stream, p);
+  else hipLaunchKernelGGL(append_mfma_kernel<0>, grid, dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 

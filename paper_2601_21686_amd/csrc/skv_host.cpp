@@ -631,7 +631,7 @@ skv_status q_project_append(const skv_q8_layer* Q, int bits, const void* k_new, 
   if (st != SKV_OK || T == 0) return st;
   AppendParams p;
   fill_q_append(Q, bits, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
-  if (launch_project(&p, nullptr, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;   // few rows: vector path; a chunk: matrix cores
   return SKV_OK;
 }
 
@@ -680,7 +680,9 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   fill_q_query(Q, &qp, q, scale, workspace);
   AppendParams ap;
   if (T > 0) fill_q_append(Q, bits, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
-  if (launch_project(T > 0 ? &ap : nullptr, &qp, static_cast<hipStream_t>(stream)) != hipSuccess)
+  const bool few = T > 0 && (int64_t)L->batch * T <= kVectorAppendMaxRows;
+  if (T > 0 && !few && launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  if (launch_project(few ? &ap : nullptr, &qp, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   st = run_partial(L, n_ctx, s, workspace, stream, Q, bits);
   if (st != SKV_OK) return st;
