@@ -40,9 +40,11 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
-    ap.add_argument("--cache", choices=("bf16", "q8", "q4"), default="bf16",
+    ap.add_argument("--cache", choices=("bf16", "q8", "q4", "paged"), default="bf16",
                     help="bf16: the benchmarked configuration; q8 / q4: the 8- or 4-bit quantised compressed cache "
-                         "(keys with static per-head group ranges, values with per-token group ranges)")
+                         "(keys with static per-head group ranges, values with per-token group ranges); "
+                         "paged: bf16 rows in a pool of pages behind a shuffled block table")
+    ap.add_argument("--page-tokens", type=int, default=64, help="--cache paged: rows per page (a power of two >= 64)")
     ap.add_argument("--variant", choices=("explicit", "folded"), default="explicit",
                     help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
                          "folded: the bases are folded into the model's linear layers (Sec. 3.4), so rows and queries "
@@ -283,13 +285,14 @@ def main():
     cap = wl.n_ctx + K + 8
     assert n0 >= 1
 
-    qbits = {"bf16": 0, "q8": 8, "q4": 4}[args.cache]
+    qbits = {"bf16": 0, "q8": 8, "q4": 4, "paged": 0}[args.cache]
+    paged = args.cache == "paged"
     q8 = qbits != 0                                  # any quantised cache
     QF = {8: (B.skv_q8_project_append, B.skv_q8_decode_step, B.skv_q8_decode_project_query, B.skv_q8_decode_partial),
           4: (B.skv_q4_project_append, B.skv_q4_decode_step, B.skv_q4_decode_project_query, B.skv_q4_decode_partial)}
     folded = args.variant == "folded"
-    if folded and q8:
-        print("bench.py: --variant folded runs over the bf16 cache only", file=sys.stderr)
+    if folded and (q8 or paged):
+        print("bench.py: --variant folded runs over the contiguous bf16 cache only", file=sys.stderr)
         sys.exit(2)
 
     def low(x, basis):
@@ -299,6 +302,9 @@ def main():
 
     append_fn = QF[qbits][0] if q8 else B.skv_project_append
     step_fn = QF[qbits][1] if q8 else B.skv_decode_step
+    if paged:                                        # every sequence at the same length: no length array
+        append_fn = lambda L_, k_, v_, c_: B.skv_paged_project_append(L_, k_, v_, None, c_)
+        step_fn = lambda L_, k_, v_, c_, q_, o_, sc_, ws_: B.skv_paged_decode_step(L_, k_, v_, None, c_, q_, o_, sc_, ws_)
 
     def row_bytes(li):
         """Bytes one cached token of one KV head occupies in layer li."""
@@ -326,6 +332,15 @@ def main():
             ksc, kzr = ((hi - lo) / float(2 ** qbits - 1)).contiguous(), lo.contiguous()
             k_ranges.append((ksc, kzr))
             layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap, qbits))
+        elif paged:
+            # a pool with a few spare pages; the table is a seeded shuffle, so consecutive logical pages of a
+            # sequence are scattered over the pool
+            pt = args.page_tokens
+            per_seq = (cap + pt - 1) // pt
+            n_pages = Bt * per_seq + 16
+            order = np.random.default_rng(synth.stable_seed(wl.name, li, "pages")).permutation(n_pages)
+            table = torch.from_numpy(order[:Bt * per_seq].reshape(Bt, per_seq).astype(np.int32)).to(dev)
+            layers.append(B.PagedLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), pt, n_pages, table))
         else:
             layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
 
@@ -417,6 +432,8 @@ def main():
         # these variants keep the projected queries in the workspace (prepared by a small launch)
         (QF[qbits][2] if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
         partial_fn = QF[qbits][3] if q8 else B.skv_decode_partial
+    elif paged:
+        partial_fn = lambda L_, n_, s_, ws_: B.skv_paged_decode_partial_q(L_, qs[0, li_big], None, n_, s_, 0.0, ws_)
     else:
         # the launch the decode step makes: every workgroup projects its head group's queries itself
         partial_fn = lambda L_, n_, s_, ws_: B.skv_decode_partial_q(L_, qs[0, li_big], n_, s_, 0.0, ws_)
@@ -456,7 +473,7 @@ def main():
                    "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
-                   "cache": f"{qbits}-bit codes, group 64" if q8 else "bf16", "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
+                   "cache": f"{qbits}-bit codes, group 64" if q8 else (f"bf16, pages of {args.page_tokens} rows, shuffled block table" if paged else "bf16"), "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},

@@ -451,6 +451,72 @@ skv_status skv_pad_basis(const void* src, int32_t n_bases, int32_t r, void* dst,
 skv_status skv_orthonormalize(const void* a, int32_t n_bases, int32_t r, int32_t pad,
                               void* p_out, void* stream);
 
+/*
+ * ---- Paged cache ---------------------------------------------------------------
+ * For serving: the compressed rows of Sec. 2.1 Eq. 1 live in a pool of fixed-size
+ * pages instead of one contiguous run per sequence, and a block table maps each
+ * sequence's logical pages to pool pages, so that sequences grow, finish and are
+ * replaced without moving cache rows.  What is computed is unchanged (Eq. 18 per
+ * sequence over its own rows); only where row t of sequence b is found differs:
+ * page = block_table[b][t / page_tokens], row t % page_tokens of that page.
+ *
+ *   layer        shapes, ranks and bases as for skv_layer, with
+ *                  k_cache  device bf16 [n_pages][n_kv_heads][page_tokens][r_k]  (the key pool)
+ *                  v_cache  device bf16 [n_pages][n_kv_heads][page_tokens][r_v]
+ *                  batch    sequences served by the call (rows of block_table)
+ *                  capacity page_tokens * max_pages_per_seq exactly (rows a sequence can address)
+ *   block_table  device int32 [batch][max_pages_per_seq]; only entries of pages a call touches
+ *                are read.  The table lives on the device and cannot be validated by the host:
+ *                an entry outside [0, n_pages) is clamped into that range, so nothing outside
+ *                the pool is accessed (the result is then meaningless).  Two sequences may
+ *                name the same page for rows both only read (a shared prefix); pages written
+ *                by an append must belong to one sequence.
+ *   page_tokens  rows per page: a power of two, at least 64
+ *   n_pages      pages in the pool
+ * Lengths: seq_lens / cur_lens are device int32 [batch] as for the _varlen calls (clamped the
+ * same way against max_len / max_cur_len), or NULL when every sequence has exactly the
+ * host-side length.  Workspace: skv_decode_workspace_bytes(&paged->layer).
+ *
+ * skv_paged_project_append   rows [cur_lens[b], cur_lens[b] + T) of sequence b, as skv_project_append_varlen
+ * skv_paged_decode_attention as skv_decode_attention_varlen
+ * skv_paged_decode_partial_q the first of skv_paged_decode_attention's two launches alone (as
+ *                            skv_decode_partial_q: n_splits ranges, 0 = default); the second is
+ *                            skv_decode_combine(&paged->layer, ...) with the same count
+ * skv_paged_decode_step      as skv_decode_step_varlen
+ * skv_paged_prefill_attention as skv_prefill_attention (one n_prev for the whole batch)
+ * skv_paged_pool_bytes       bytes of both pools: n_pages * n_kv_heads * page_tokens * (r_k + r_v) * 2
+ *                            (0 for an invalid description)
+ * Errors: those of the calls named, plus SHAPE (page_tokens not a power of two >= 64, n_pages or
+ * max_pages_per_seq < 1), CAPACITY (capacity != page_tokens * max_pages_per_seq), NULL / ALIGN
+ * (block_table missing or not 4-byte aligned).
+ */
+typedef struct {
+  skv_layer layer;
+  const int32_t* block_table;
+  int32_t page_tokens;
+  int32_t n_pages;
+  int32_t max_pages_per_seq;
+} skv_paged_layer;
+
+size_t skv_paged_pool_bytes(const skv_paged_layer* paged);
+skv_status skv_paged_project_append(const skv_paged_layer* paged, const void* k_new, const void* v_new,
+                                    int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                                    const int32_t* cur_lens, int64_t max_cur_len, void* stream);
+skv_status skv_paged_decode_attention(const skv_paged_layer* paged, const void* q, void* out,
+                                      const int32_t* seq_lens, int64_t max_len, float scale,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_paged_decode_partial_q(const skv_paged_layer* paged, const void* q, const int32_t* seq_lens,
+                                      float scale, int64_t max_len, int32_t n_splits,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_paged_decode_step(const skv_paged_layer* paged, const void* k_new, const void* v_new,
+                                 int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
+                                 const int32_t* cur_lens, int64_t max_cur_len,
+                                 const void* q, void* out, float scale,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_paged_prefill_attention(const skv_paged_layer* paged, const void* q, int64_t q_stride_b,
+                                       int64_t q_stride_t, int64_t q_stride_h, void* out, int32_t T,
+                                       int64_t n_prev, float scale, int32_t mode, void* stream);
+
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
 size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);

@@ -18,6 +18,7 @@ Everything below is the paper's definition written out with numpy float64:
   * the folded-weights variant: attention in the compressed space (Sec. 3.4 "Overheads")
   * a chunk of queries over the compressed cache (Eq. 18 with T > 1, causal mask)
   * per-sequence context lengths (Eq. 18 per sequence of a mixed batch)
+  * a paged cache: the same rows found through a block table (addressing only)
   * bases from predicted matrices: orthonormal factor of a QR, leading r columns
                                                                (Sec. 3.3 Eqs. 13-14; Sec. 3.2 Eq. 6)
 
@@ -43,7 +44,9 @@ the round-trip error bound, flat groups, library rounding, and the invariance
 of the output to the key zero point; for the chunk form: the library's causal
 attention (with and without a cached prefix, off-by-one masks rejected), a
 pure-Python brute force and the first-token closed form; for per-sequence
-lengths: the library's attention under a key-padding mask; for the basis
+lengths: the library's attention under a key-padding mask; for the paged
+cache: a hand-labelled pool and table, the identity table, and invariance of
+every result under a relabelling of the pool's pages; for the basis
 construction: the three properties that make the factor unique (orthonormal
 columns, Q R = A, R upper triangular with positive diagonal), a hand-computed
 2 x 2 case and the projector onto the span of A's leading columns.  No function here is "parity unpinned".
@@ -301,6 +304,78 @@ def decode_attention_varlen(layer: OracleLayer, q: np.ndarray, seq_lens, scale: 
         if n_b > 0:
             out[b] = decode_attention(_one_sequence(layer, b), q[b:b + 1], n_b, scale)[0]
     return out
+
+
+# --------------------------------------------------------------------------
+# Paged cache: where a row lives, nothing else
+# --------------------------------------------------------------------------
+#
+# A serving system keeps the compressed rows of Eq. 1 in a pool of pages of
+# page_tokens rows and a table per sequence: row t of sequence b is row
+# t % page_tokens of pool page table[b][t // page_tokens].  The attention of
+# Eq. 18 is unchanged; the functions below move rows between a pool and the
+# contiguous layout the functions above work on, one row at a time.
+
+
+@dataclass
+class OraclePagedCache:
+    """k_pool, v_pool: float64 [n_pages, n_kv_heads, page_tokens, r]; block_table: int [batch, max_pages]."""
+    k_pool: np.ndarray
+    v_pool: np.ndarray
+    block_table: np.ndarray
+    page_tokens: int
+
+
+def paged_rows(pool: np.ndarray, table_row, page_tokens: int, n_rows: int) -> np.ndarray:
+    """Rows [0, n_rows) of one sequence, gathered from the pool: [n_kv_heads, n_rows, r]."""
+    out = np.empty((pool.shape[1], n_rows, pool.shape[3]), pool.dtype)
+    for t in range(n_rows):
+        out[:, t, :] = pool[int(table_row[t // page_tokens]), :, t % page_tokens, :]
+    return out
+
+
+def paged_store_rows(pool: np.ndarray, table_row, page_tokens: int, first_row: int, rows: np.ndarray) -> None:
+    """Writes rows [first_row, first_row + T) of one sequence ([n_kv_heads, T, r]) into the pool."""
+    for i in range(rows.shape[1]):
+        t = first_row + i
+        pool[int(table_row[t // page_tokens]), :, t % page_tokens, :] = rows[:, i, :]
+
+
+def paged_as_contiguous(layer: OracleLayer, cache: OraclePagedCache, n_rows) -> OracleLayer:
+    """A contiguous layer holding rows [0, n_rows[b]) of every sequence of the paged cache (a copy)."""
+    out = new_layer(layer.batch, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.p_k, layer.p_v,
+                    max(1, int(max(n_rows))), layer.store)
+    for b in range(layer.batch):
+        n_b = int(n_rows[b])
+        out.k_cache[b, :, :n_b] = paged_rows(cache.k_pool, cache.block_table[b], cache.page_tokens, n_b)
+        out.v_cache[b, :, :n_b] = paged_rows(cache.v_pool, cache.block_table[b], cache.page_tokens, n_b)
+    return out
+
+
+def paged_project_append(layer: OracleLayer, cache: OraclePagedCache, k_new: np.ndarray, v_new: np.ndarray,
+                         cur_lens) -> None:
+    """project_append into the paged cache: the T new rows of sequence b become its rows
+    [cur_lens[b], cur_lens[b] + T).  `layer` supplies shapes, bases and the storage precision."""
+    T = np.asarray(k_new).shape[1]
+    tmp = new_layer(layer.batch, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.p_k, layer.p_v,
+                    max(1, T), layer.store)
+    project_append(tmp, k_new, v_new, 0)
+    for b in range(layer.batch):
+        paged_store_rows(cache.k_pool, cache.block_table[b], cache.page_tokens, int(cur_lens[b]), tmp.k_cache[b, :, :T])
+        paged_store_rows(cache.v_pool, cache.block_table[b], cache.page_tokens, int(cur_lens[b]), tmp.v_cache[b, :, :T])
+
+
+def paged_decode_attention(layer: OracleLayer, cache: OraclePagedCache, q: np.ndarray, seq_lens,
+                           scale: float | None = None) -> np.ndarray:
+    """decode_attention_varlen over the rows the block table names."""
+    return decode_attention_varlen(paged_as_contiguous(layer, cache, seq_lens), q, seq_lens, scale)
+
+
+def paged_prefill_attention(layer: OracleLayer, cache: OraclePagedCache, q: np.ndarray, n_prev: int,
+                            scale: float | None = None, rows=None) -> np.ndarray:
+    """prefill_attention over the rows the block table names (the chunk's rows already stored)."""
+    T = np.asarray(q).shape[1]
+    return prefill_attention(paged_as_contiguous(layer, cache, [n_prev + T] * layer.batch), q, n_prev, scale, rows)
 
 
 # --------------------------------------------------------------------------

@@ -36,6 +36,8 @@ EXPORTS = (
     "skv_padded_rank", "skv_pad_basis", "skv_orthonormalize",
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
+    "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q",
 )
 
 
@@ -58,6 +60,11 @@ class skv_layer(C.Structure):
 
 class skv_q8_layer(C.Structure):
     _fields_ = [("base", skv_layer), ("k_scale", C.c_void_p), ("k_zero", C.c_void_p), ("v_meta", C.c_void_p)]
+
+
+class skv_paged_layer(C.Structure):
+    _fields_ = [("layer", skv_layer), ("block_table", C.c_void_p), ("page_tokens", C.c_int32),
+                ("n_pages", C.c_int32), ("max_pages_per_seq", C.c_int32)]
 
 
 _lib = None
@@ -143,6 +150,19 @@ def lib() -> C.CDLL:
     L.skv_project_append_varlen.restype = C.c_int
     L.skv_decode_step_varlen.argtypes = [LP, vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_decode_step_varlen.restype = C.c_int
+    PP = C.POINTER(skv_paged_layer)
+    L.skv_paged_pool_bytes.argtypes = [PP]
+    L.skv_paged_pool_bytes.restype = sz
+    L.skv_paged_project_append.argtypes = [PP, vp, vp, i64, i64, i64, i32, vp, i64, vp]
+    L.skv_paged_project_append.restype = C.c_int
+    L.skv_paged_decode_attention.argtypes = [PP, vp, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_paged_decode_attention.restype = C.c_int
+    L.skv_paged_decode_partial_q.argtypes = [PP, vp, vp, C.c_float, i64, i32, vp, sz, vp]
+    L.skv_paged_decode_partial_q.restype = C.c_int
+    L.skv_paged_decode_step.argtypes = [PP, vp, vp, i64, i64, i64, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_paged_decode_step.restype = C.c_int
+    L.skv_paged_prefill_attention.argtypes = [PP, vp, i64, i64, i64, vp, i32, i64, C.c_float, i32, vp]
+    L.skv_paged_prefill_attention.restype = C.c_int
     L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
     L.skv_orthonormalize.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
@@ -249,8 +269,13 @@ def _ref(layer):
 
 
 def _base_ref(layer):
-    """The plain skv_layer of a Layer or of a QuantLayer (for calls that do not depend on the format)."""
-    return C.byref(layer.c.base) if isinstance(layer, QuantLayer) else _ref(layer)
+    """The plain skv_layer of a Layer, a QuantLayer or a PagedLayer (for calls that do not depend on the
+    format or on where the rows live)."""
+    if isinstance(layer, QuantLayer):
+        return C.byref(layer.c.base)
+    if isinstance(layer, PagedLayer):
+        return C.byref(layer.c.layer)
+    return _ref(layer)
 
 
 # ---- the C ABI, same names -------------------------------------------------
@@ -431,6 +456,111 @@ def skv_decode_step_varlen(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_
                                         int(k_new.shape[1]), cur_lens.data_ptr(), int(max_cur_len), q.data_ptr(),
                                         out.data_ptr(), float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
                                         _stream_ptr(stream)), "skv_decode_step_varlen")
+
+
+# ---- paged cache -------------------------------------------------------------------------------
+
+
+class PagedLayer:
+    """A layer whose compressed rows live in page pools [n_pages, n_kv_heads, page_tokens, r] addressed
+    through block_table (int32 CUDA [batch, max_pages_per_seq]).  The pools are allocated here
+    (uninitialised) unless passed in."""
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, page_tokens, n_pages, block_table,
+                 k_pool=None, v_pool=None):
+        dev = p_k.device
+        assert p_k.dtype == torch.bfloat16 and p_v.dtype == torch.bfloat16
+        assert p_k.is_contiguous() and p_v.is_contiguous()
+        assert block_table.dtype == torch.int32 and block_table.is_cuda and block_table.is_contiguous()
+        assert block_table.dim() == 2 and block_table.shape[0] == batch
+        self.batch, self.n_q_heads, self.n_kv_heads = int(batch), int(n_q_heads), int(n_kv_heads)
+        self.page_tokens, self.n_pages = int(page_tokens), int(n_pages)
+        self.max_pages_per_seq = int(block_table.shape[1])
+        self.capacity = self.page_tokens * self.max_pages_per_seq
+        self.r_k, self.r_v = int(p_k.shape[2]), int(p_v.shape[2])
+        self.p_k, self.p_v, self.block_table = p_k, p_v, block_table
+        if k_pool is None:
+            k_pool = torch.empty((n_pages, n_kv_heads, page_tokens, self.r_k), dtype=torch.bfloat16, device=dev)
+        if v_pool is None:
+            v_pool = torch.empty((n_pages, n_kv_heads, page_tokens, self.r_v), dtype=torch.bfloat16, device=dev)
+        assert k_pool.is_contiguous() and v_pool.is_contiguous()
+        self.k_pool, self.v_pool = k_pool, v_pool
+        base = skv_layer(self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v,
+                         self.capacity, k_pool.data_ptr(), v_pool.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
+                         0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
+                         0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+        self.c = skv_paged_layer(base, block_table.data_ptr(), self.page_tokens, self.n_pages,
+                                 self.max_pages_per_seq)
+        self._ws = None
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            n = int(lib().skv_decode_workspace_bytes(C.byref(self.c.layer)))
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.p_k.device)
+        return self._ws
+
+
+def _lens_ptr(t, batch: int):
+    if t is None:
+        return None
+    _lens_ok(t, batch)
+    return t.data_ptr()
+
+
+def skv_paged_pool_bytes(layer: PagedLayer) -> int:
+    return int(lib().skv_paged_pool_bytes(C.byref(layer.c)))
+
+
+def skv_paged_project_append(layer: PagedLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_lens, max_cur_len: int,
+                             stream=None) -> None:
+    """cur_lens: int32 CUDA [batch], or None when every sequence stands at max_cur_len."""
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
+    _check(lib().skv_paged_project_append(C.byref(layer.c), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                          int(k_new.shape[1]), _lens_ptr(cur_lens, layer.batch), int(max_cur_len),
+                                          _stream_ptr(stream)), "skv_paged_project_append")
+
+
+def skv_paged_decode_attention(layer: PagedLayer, q: torch.Tensor, out: torch.Tensor, seq_lens, max_len: int,
+                               scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_paged_decode_attention(C.byref(layer.c), q.data_ptr(), out.data_ptr(),
+                                            _lens_ptr(seq_lens, layer.batch), int(max_len), float(scale),
+                                            ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_paged_decode_attention")
+
+
+def skv_paged_decode_partial_q(layer: PagedLayer, q: torch.Tensor, seq_lens, max_len: int, n_splits: int = 0,
+                               scale: float = 0.0, workspace: torch.Tensor | None = None, stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_paged_decode_partial_q(C.byref(layer.c), q.data_ptr(), _lens_ptr(seq_lens, layer.batch),
+                                            float(scale), int(max_len), int(n_splits), ws.data_ptr(),
+                                            ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_paged_decode_partial_q")
+
+
+def skv_paged_decode_step(layer: PagedLayer, k_new: torch.Tensor, v_new: torch.Tensor, cur_lens, max_cur_len: int,
+                          q: torch.Tensor, out: torch.Tensor, scale: float = 0.0,
+                          workspace: torch.Tensor | None = None, stream=None) -> None:
+    assert k_new.dtype == torch.bfloat16 and v_new.dtype == torch.bfloat16
+    assert k_new.stride() == v_new.stride() and k_new.stride(3) == 1
+    sb, st, sh, _ = k_new.stride()
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_paged_decode_step(C.byref(layer.c), k_new.data_ptr(), v_new.data_ptr(), sb, st, sh,
+                                       int(k_new.shape[1]), _lens_ptr(cur_lens, layer.batch), int(max_cur_len),
+                                       q.data_ptr(), out.data_ptr(), float(scale), ws.data_ptr(),
+                                       ws.numel() * ws.element_size(), _stream_ptr(stream)), "skv_paged_decode_step")
+
+
+def skv_paged_prefill_attention(layer: PagedLayer, q: torch.Tensor, out: torch.Tensor, n_prev: int,
+                                scale: float = 0.0, mode: int = SKV_PREFILL_EXACT, stream=None) -> None:
+    assert q.dtype == torch.bfloat16 and q.stride(3) == 1
+    assert out.dtype == torch.float32 and out.is_contiguous() and out.shape == q.shape
+    sb, st, sh, _ = q.stride()
+    _check(lib().skv_paged_prefill_attention(C.byref(layer.c), q.data_ptr(), sb, st, sh, out.data_ptr(),
+                                             int(q.shape[1]), int(n_prev), float(scale), int(mode),
+                                             _stream_ptr(stream)), "skv_paged_prefill_attention")
 
 
 # ---- ranks that are not multiples of 16 --------------------------------------------------------

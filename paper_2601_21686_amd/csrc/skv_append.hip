@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
       valid[nt] = tok < M;
       const int tc = valid[nt] ? tok : M - 1;
       const int b = tc / p.T, t = tc % p.T;
-      dst_row[nt] = ((int64_t)b * p.n_kv_heads + h) * p.capacity + clamped_len(p.cur_lens, b, p.cur_len) + t;
+      dst_row[nt] = cache_row(p.pages, p.capacity, p.n_kv_heads, b, h, clamped_len(p.cur_lens, b, p.cur_len) + t);
     }
 
     if constexpr (QBITS == 0) {

@@ -38,6 +38,12 @@
 #define SKV_QBITS 0                 // 0: bf16 rows; 8 or 4: integer codes of that width (Sec. 4.3)
 #endif
 #define SKV_Q8 (SKV_QBITS != 0)     // any quantised build: codes plus per-row value ranges
+#ifndef SKV_PAGED
+#define SKV_PAGED 0                 // 1: the caches are page pools addressed through a block table (bf16 rows only)
+#endif
+#if SKV_PAGED && SKV_QBITS != 0
+#error "the paged build streams bf16 rows"
+#endif
 #if SKV_QBITS != 0 && SKV_QBITS != 8 && SKV_QBITS != 4
 #error "SKV_QBITS must be 0, 8 or 4"
 #endif
@@ -60,7 +66,7 @@ constexpr int kElemsPerDword = 8;                // two channels per byte, the e
 constexpr int kFmt = 2;
 #else
 constexpr int kElemsPerDword = 2;                // bf16
-constexpr int kFmt = 0;
+constexpr int kFmt = SKV_PAGED ? 3 : 0;
 #endif
 template <int R>
 struct RowMap {
@@ -396,7 +402,7 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
   for (int g = 0; g < GT; ++g) acc[g] = 0.f;
   for (int t = 0; t < p.T_new; ++t) {
     const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
-    const int64_t row = ((int64_t)b * p.n_kv_heads + kv) * p.capacity + clamped_len(p.seq_lens, b, p.cur_len) + t;
+    const int64_t row = cache_row(p.pages, p.capacity, p.n_kv_heads, b, kv, clamped_len(p.seq_lens, b, p.cur_len) + t);
     {
       ProjectPieces pp;
       project_rows_issue(pk, RK, pp);
@@ -453,7 +459,8 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
 }
 #endif
 
-// FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes, 2: 4-bit codes).
+// FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes, 2: 4-bit codes,
+// 3: bf16 rows in pages).
 template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
@@ -517,6 +524,47 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     return;
   }
 
+  const int lane_row = wave * ROWS_PER_WAVE + oct;     // this lane's first row inside a tile
+  const int n_full = (t1 - t0) / ROWS_PER_WG;         // tiles with every row valid
+  using Tile = TileRegs<RK, RV, U>;
+  Tile ta;
+#if SKV_PAGED
+  // Ranges start at multiples of 64 rows and a page holds a multiple of 64 rows, so the 8*U <= 64 rows a
+  // wave requests in a full tile lie in ONE page: the page is looked up once per wave and tile.  Lane i
+  // keeps the table entry of the range's page (first + i); a full tile takes its entry with a lane read,
+  // so no load sits between a tile and the addresses of its rows.  Ranges longer than 64 pages refill.
+  static_assert(ROWS_PER_WAVE <= kRangeQuantum && kRangeQuantum % ROWS_PER_WAVE == 0, "a wave's rows must share a page");
+  const int page_rows_mask = (1 << p.pages.page_shift) - 1;
+  const int page_first = t0 >> p.pages.page_shift;
+  const int pages_in_range = ((t1 - 1) >> p.pages.page_shift) - page_first + 1;
+  int held_first = 0;                            // which page of the range lane 0 holds
+  int held = lane < pages_in_range ? clamped_page(p.pages, b, page_first + lane) : 0;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // requests the full tile whose first row is `tile_row` (a multiple of ROWS_PER_WG past t0)
+  auto issue_full = [&](int tile_row, Tile& t) {
+    const int r = tile_row + wave_u * ROWS_PER_WAVE;           // this wave's first row: wave-uniform
+    const int rel = (r >> p.pages.page_shift) - page_first;
+    while (rel - held_first >= 64) {
+      held_first += 64;
+      held = held_first + lane < pages_in_range ? clamped_page(p.pages, b, page_first + held_first + lane) : 0;
+    }
+    const int page = __builtin_amdgcn_readlane(held, rel - held_first);
+    const int64_t blk = ((int64_t)page * p.n_kv_heads + kv) << p.pages.page_shift;
+    issue_rows<RK, RV, U, false>(p.k_cache + blk * KM::ROW_DW, p.v_cache + blk * VM::ROW_DW, nullptr,
+                                 (r & page_rows_mask) + oct, 0, j, t);
+  };
+  // the ragged tail: rows clamped to the last valid one, each looked up by itself
+  auto issue_tail = [&](int row0, Tile& t) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int row = row0 + 8 * u;
+      row = row < t1 ? row : t1 - 1;
+      const int64_t at = cache_row(p.pages, 0, p.n_kv_heads, b, kv, row);
+      load_row<RK>(p.k_cache + at * KM::ROW_DW, j, t.kw[u]);
+      load_row<RV>(p.v_cache + at * VM::ROW_DW, j, t.vw[u]);
+    }
+  };
+#else
   const uint32_t* kbase = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * KM::ROW_DW;
   const uint32_t* vbase = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * VM::ROW_DW;
 #if SKV_Q8
@@ -524,10 +572,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 #else
   const uint32_t* mbase = nullptr;
 #endif
-  const int lane_row = wave * ROWS_PER_WAVE + oct;     // this lane's first row inside a tile
-  const int n_full = (t1 - t0) / ROWS_PER_WG;         // tiles with every row valid
-  using Tile = TileRegs<RK, RV, U>;
-  Tile ta;
+  auto issue_full = [&](int tile_row, Tile& t) {
+    issue_rows<RK, RV, U, false>(kbase, vbase, mbase, tile_row + lane_row, t1, j, t);
+  };
+  auto issue_tail = [&](int row0, Tile& t) { issue_rows<RK, RV, U, true>(kbase, vbase, mbase, row0, t1, j, t); };
+#endif
 
   // ---- this lane's slice of the projected queries, in slot order.  They come from the workspace
   //      (prepared by the projection kernel) or, when the raw queries are handed over, are projected
@@ -545,10 +594,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 #pragma unroll
     for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
       if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) qraw[k] = qptr[tid + k * kDecodeThreads];
-    if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
+    if (n_full > 0) issue_full(t0, ta);
     // the projection below takes about as long as a round trip to HBM: keep a second tile on its way
     pre2 = SKV_PIPELINE == 1 && n_full >= 3;
-    if (pre2) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + ROWS_PER_WG + lane_row, t1, j, tb);
+    if (pre2) issue_full(t0 + ROWS_PER_WG, tb);
 #pragma unroll
     for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
       if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) px_s[tid + k * kDecodeThreads] = bf16_to_f32(qraw[k]);
@@ -574,7 +623,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
         qreg[g][i + 1] = v.y;
       }
     }
-    if (n_full > 0) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + lane_row, t1, j, ta);
+    if (n_full > 0) issue_full(t0, ta);
   }
 
   // ---- stream the range ---------------------------------------------------------------
@@ -606,13 +655,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     ring[0] = ta;                                   // tile 0 was requested before the projection
 #pragma unroll
     for (int k = 1; k < NBUF - 1; ++k)
-      if (k < n_full) issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + k * ROWS_PER_WG + lane_row, t1, j, ring[k]);
+      if (k < n_full) issue_full(t0 + k * ROWS_PER_WG, ring[k]);
     int i = 0;
     if constexpr (NBUF == 2) {
       if (pre2) {                                   // tiles 0 and 1 are both on their way (n_full >= 3)
         ring[1] = tb;
         consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
-        issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + 2 * ROWS_PER_WG + lane_row, t1, j, ring[0]);
+        issue_full(t0 + 2 * ROWS_PER_WG, ring[0]);
         consume_rows<RK, RV, GT, U, false>(ring[1], 0, t1, qd, qreg, m, l, acc, zacc);
         i = 2;                                      // ring[0] holds tile 2: the loop's invariant
       }
@@ -621,8 +670,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
       while (i + 2 * NBUF - 2 < n_full) {           // ring[k] holds tile i+k for k < NBUF-1
 #pragma unroll
         for (int k = 0; k < NBUF; ++k) {
-          issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
-                                       ring[(k + NBUF - 1) % NBUF]);
+          issue_full(t0 + (i + k + NBUF - 1) * ROWS_PER_WG, ring[(k + NBUF - 1) % NBUF]);
           consume_rows<RK, RV, GT, U, false>(ring[k], 0, t1, qd, qreg, m, l, acc, zacc);
         }
         i += NBUF;
@@ -633,15 +681,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     for (int k = 0; k < 2 * NBUF - 2 || k < 1; ++k) {
       if (i + k < n_full) {
         if (NBUF > 1 && i + k + NBUF - 1 < n_full)
-          issue_rows<RK, RV, U, false>(kbase, vbase, mbase, t0 + (i + k + NBUF - 1) * ROWS_PER_WG + lane_row, t1, j,
-                                       ring[(k + NBUF - 1) % NBUF]);
+          issue_full(t0 + (i + k + NBUF - 1) * ROWS_PER_WG, ring[(k + NBUF - 1) % NBUF]);
         consume_rows<RK, RV, GT, U, false>(ring[k % NBUF], 0, t1, qd, qreg, m, l, acc, zacc);
       }
     }
   }
   if (t0 + n_full * ROWS_PER_WG < t1) {               // ragged tail of the range
     const int row0 = t0 + n_full * ROWS_PER_WG + lane_row;
-    issue_rows<RK, RV, U, true>(kbase, vbase, mbase, row0, t1, j, ta);
+    issue_tail(row0, ta);
     consume_rows<RK, RV, GT, U, true>(ta, row0, t1, qd, qreg, m, l, acc, zacc);
   }
 
@@ -756,6 +803,8 @@ hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stre
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q8_rk, SKV_RK)
 #elif SKV_QBITS == 4
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q4_rk, SKV_RK)
+#elif SKV_PAGED
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_paged_rk, SKV_RK)
 #else
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_rk, SKV_RK)
 #endif

@@ -89,6 +89,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->T_new = 0;
   p->seq_lens = nullptr;
   p->len_add = 0;
+  p->pages = PageMap{nullptr, 0, 0, 0};
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
@@ -109,6 +110,20 @@ decode_partial_launcher partial_launcher_for(int r_k) {
     case 96: return launch_decode_partial_rk96;
     case 112: return launch_decode_partial_rk112;
     case 128: return launch_decode_partial_rk128;
+  }
+  return nullptr;
+}
+
+decode_partial_launcher paged_partial_launcher_for(int r_k) {
+  switch (r_k) {
+    case 16: return launch_decode_partial_paged_rk16;
+    case 32: return launch_decode_partial_paged_rk32;
+    case 48: return launch_decode_partial_paged_rk48;
+    case 64: return launch_decode_partial_paged_rk64;
+    case 80: return launch_decode_partial_paged_rk80;
+    case 96: return launch_decode_partial_paged_rk96;
+    case 112: return launch_decode_partial_paged_rk112;
+    case 128: return launch_decode_partial_paged_rk128;
   }
   return nullptr;
 }
@@ -280,6 +295,7 @@ void fill_append_params(const skv_layer* L, AppendParams* p, const void* k_new, 
   p->k_zero = nullptr;
   p->v_meta = nullptr;
   p->qbits = 0;
+  p->pages = PageMap{nullptr, 0, 0, 0};
 }
 
 // ---- launches -----------------------------------------------------------------------------
@@ -321,7 +337,7 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
 skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int64_t n_ctx, int32_t s_stream,
                              const void* k_new, const void* v_new, int64_t stride_b, int64_t stride_t,
                              int64_t stride_h, int32_t T_new, void* workspace, void* stream,
-                             const int32_t* seq_lens = nullptr, int32_t len_add = 0) {
+                             const int32_t* seq_lens = nullptr, int32_t len_add = 0, const PageMap* pages = nullptr) {
   DecodeParams p;
   const int32_t total = s_stream + (T_new > 0 ? 1 : 0);
   fill_decode_params(L, &p, total, workspace);
@@ -338,7 +354,8 @@ skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int
   p.T_new = T_new;
   p.seq_lens = seq_lens;
   p.len_add = len_add;
-  decode_partial_launcher launch = partial_launcher_for(L->r_k);
+  if (pages) p.pages = *pages;
+  decode_partial_launcher launch = pages ? paged_partial_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
@@ -501,8 +518,10 @@ skv_status check_prefill(const skv_layer* L, bool folded, const void* q, const v
 }
 
 skv_status run_prefill(const skv_layer* L, bool folded, const void* q, int64_t sb, int64_t st_, int64_t sh,
-                       void* out, int32_t T, int64_t n_prev, float scale, int32_t mode, void* stream) {
+                       void* out, int32_t T, int64_t n_prev, float scale, int32_t mode, void* stream,
+                       const PageMap* pages = nullptr) {
   PrefillParams p;
+  p.pages = pages ? *pages : PageMap{nullptr, 0, 0, 0};
   p.k_cache = static_cast<const uint16_t*>(L->k_cache);
   p.v_cache = static_cast<const uint16_t*>(L->v_cache);
   p.p_k = static_cast<const uint16_t*>(L->p_k);
@@ -791,6 +810,97 @@ skv_status run_folded_attention(const skv_layer* L, void* out_low, int64_t n_ctx
 
 }  // namespace
 
+namespace {
+
+// The paged layer's checks; fills the device-side description of its page table.
+skv_status check_paged(const skv_paged_layer* P, PageMap* pm) {
+  if (!P) return SKV_ERR_NULL;
+  const skv_status st = check_layer(&P->layer);
+  if (st != SKV_OK) return st;
+  if (!P->block_table) return SKV_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(P->block_table) & 3u) return SKV_ERR_ALIGN;
+  const int32_t pt = P->page_tokens;
+  if (pt < kRangeQuantum || pt > (1 << 20) || (pt & (pt - 1))) return SKV_ERR_SHAPE;   // a power of two, >= 64
+  if (P->n_pages < 1 || P->max_pages_per_seq < 1) return SKV_ERR_SHAPE;
+  if (P->layer.capacity != (int64_t)pt * P->max_pages_per_seq) return SKV_ERR_CAPACITY;
+  int shift = 0;
+  while ((1 << shift) < pt) ++shift;
+  *pm = PageMap{P->block_table, P->max_pages_per_seq, shift, P->n_pages};
+  return SKV_OK;
+}
+
+// The calls with per-sequence lengths; lens may be null (every sequence at the host-side bound) and pages
+// null (contiguous cache).
+skv_status append_lens(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b, int64_t stride_t,
+                       int64_t stride_h, int32_t T, const int32_t* cur_lens, int64_t max_cur_len, void* stream,
+                       const PageMap* pages) {
+  const skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  if (T == 0) return SKV_OK;
+  AppendParams p;
+  fill_append_params(L, &p, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  p.cur_lens = cur_lens;
+  if (pages) p.pages = *pages;
+  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status attention_lens(const skv_layer* L, const void* q, void* out, const int32_t* seq_lens, int64_t max_len,
+                          float scale, void* workspace, size_t workspace_bytes, void* stream, const PageMap* pages) {
+  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return SKV_ERR_ALIGN;
+  int32_t s = 0;
+  st = check_partial_stage(L, max_len, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  st = run_partial_fused(L, q, scale, max_len, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, seq_lens, 0, pages);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status step_lens(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b, int64_t stride_t,
+                     int64_t stride_h, int32_t T, const int32_t* cur_lens, int64_t max_cur_len, const void* q,
+                     void* out, float scale, void* workspace, size_t workspace_bytes, void* stream,
+                     const PageMap* pages) {
+  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (T < 1) return SKV_ERR_SHAPE;                       // a step appends at least one row per sequence
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int64_t n_max = max_cur_len + T;
+  int32_t s = 0;
+  st = check_partial_stage(L, n_max, 0, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  const int gq = L->n_q_heads / L->n_kv_heads;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
+  if (T <= kFusedStepMaxTokens && max_cur_len > 0 && grid_ok) {
+    int32_t s_old = 0;
+    if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
+    st = run_partial_fused(L, q, scale, max_cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
+                           stream, cur_lens, 0, pages);
+    if (st != SKV_OK) return st;
+    return run_combine(L, out, s_old + 1, workspace, stream);
+  }
+  AppendParams ap;
+  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
+  ap.cur_lens = cur_lens;
+  if (pages) ap.pages = *pages;
+  if (launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  st = run_partial_fused(L, q, scale, n_max, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, cur_lens, T, pages);
+  if (st != SKV_OK) return st;
+  return run_combine(L, out, s, workspace, stream);
+}
+
+}  // namespace
+
 extern "C" {
 
 skv_status skv_append_projected(const skv_layer* L, const void* k_low, const void* v_low, int32_t T,
@@ -840,71 +950,90 @@ skv_status skv_decode_step_folded(const skv_layer* L, const void* k_low, const v
 skv_status skv_project_append_varlen(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
                                      int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
                                      int64_t max_cur_len, void* stream) {
-  const skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
-  if (st != SKV_OK) return st;
   if (!cur_lens) return SKV_ERR_NULL;
-  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
-  if (T == 0) return SKV_OK;
-  AppendParams p;
-  fill_append_params(L, &p, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
-  p.cur_lens = cur_lens;
-  if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  return SKV_OK;
+  return append_lens(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, stream, nullptr);
 }
 
 skv_status skv_decode_attention_varlen(const skv_layer* L, const void* q, void* out, const int32_t* seq_lens,
                                        int64_t max_len, float scale, void* workspace, size_t workspace_bytes,
                                        void* stream) {
-  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
   if (!seq_lens) return SKV_ERR_NULL;
-  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return SKV_ERR_ALIGN;
-  int32_t s = 0;
-  st = check_partial_stage(L, max_len, 0, workspace, workspace_bytes, &s);
-  if (st != SKV_OK) return st;
-  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  st = run_partial_fused(L, q, scale, max_len, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, seq_lens, 0);
-  if (st != SKV_OK) return st;
-  return run_combine(L, out, s, workspace, stream);
+  return attention_lens(L, q, out, seq_lens, max_len, scale, workspace, workspace_bytes, stream, nullptr);
 }
 
 skv_status skv_decode_step_varlen(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
                                   int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
                                   int64_t max_cur_len, const void* q, void* out, float scale, void* workspace,
                                   size_t workspace_bytes, void* stream) {
-  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
-  if (st != SKV_OK) return st;
-  if (T < 1) return SKV_ERR_SHAPE;                       // a step appends at least one row per sequence
   if (!cur_lens) return SKV_ERR_NULL;
-  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  return step_lens(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, q, out, scale, workspace,
+                   workspace_bytes, stream, nullptr);
+}
+
+// ---- paged cache ------------------------------------------------------------------------------
+
+size_t skv_paged_pool_bytes(const skv_paged_layer* P) {
+  PageMap pm;
+  if (check_paged(P, &pm) != SKV_OK) return 0;
+  return (size_t)P->n_pages * P->layer.n_kv_heads * (size_t)P->page_tokens * (size_t)(P->layer.r_k + P->layer.r_v) * 2u;
+}
+
+skv_status skv_paged_project_append(const skv_paged_layer* P, const void* k_new, const void* v_new, int64_t stride_b,
+                                    int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
+                                    int64_t max_cur_len, void* stream) {
+  PageMap pm;
+  const skv_status st = check_paged(P, &pm);
+  if (st != SKV_OK) return st;
+  return append_lens(&P->layer, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, stream, &pm);
+}
+
+skv_status skv_paged_decode_attention(const skv_paged_layer* P, const void* q, void* out, const int32_t* seq_lens,
+                                      int64_t max_len, float scale, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  PageMap pm;
+  const skv_status st = check_paged(P, &pm);
+  if (st != SKV_OK) return st;
+  return attention_lens(&P->layer, q, out, seq_lens, max_len, scale, workspace, workspace_bytes, stream, &pm);
+}
+
+skv_status skv_paged_decode_partial_q(const skv_paged_layer* P, const void* q, const int32_t* seq_lens, float scale,
+                                      int64_t max_len, int32_t n_splits, void* workspace, size_t workspace_bytes,
+                                      void* stream) {
+  PageMap pm;
+  skv_status st = check_paged(P, &pm);
+  if (st != SKV_OK) return st;
+  const skv_layer* L = &P->layer;
   st = check_query_stage(L, q, scale, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
-  const int64_t n_max = max_cur_len + T;
+  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return SKV_ERR_ALIGN;
   int32_t s = 0;
-  st = check_partial_stage(L, n_max, 0, workspace, workspace_bytes, &s);
+  st = check_partial_stage(L, max_len, n_splits, workspace, workspace_bytes, &s);
   if (st != SKV_OK) return st;
-  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  return run_partial_fused(L, q, scale, max_len, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, seq_lens, 0, &pm);
+}
+
+skv_status skv_paged_decode_step(const skv_paged_layer* P, const void* k_new, const void* v_new, int64_t stride_b,
+                                 int64_t stride_t, int64_t stride_h, int32_t T, const int32_t* cur_lens,
+                                 int64_t max_cur_len, const void* q, void* out, float scale, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+  PageMap pm;
+  const skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
-  const int gq = L->n_q_heads / L->n_kv_heads;
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
-  if (T <= kFusedStepMaxTokens && max_cur_len > 0 && grid_ok) {
-    int32_t s_old = 0;
-    if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
-    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
-    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
-    st = run_partial_fused(L, q, scale, max_cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
-                           stream, cur_lens, 0);
-    if (st != SKV_OK) return st;
-    return run_combine(L, out, s_old + 1, workspace, stream);
-  }
-  AppendParams ap;
-  fill_append_params(L, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len);
-  ap.cur_lens = cur_lens;
-  if (launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  st = run_partial_fused(L, q, scale, n_max, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, cur_lens, T);
+  return step_lens(&P->layer, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, q, out, scale,
+                   workspace, workspace_bytes, stream, &pm);
+}
+
+skv_status skv_paged_prefill_attention(const skv_paged_layer* P, const void* q, int64_t q_stride_b, int64_t q_stride_t,
+                                       int64_t q_stride_h, void* out, int32_t T, int64_t n_prev, float scale,
+                                       int32_t mode, void* stream) {
+  PageMap pm;
+  skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
-  return run_combine(L, out, s, workspace, stream);
+  st = check_prefill(&P->layer, false, q, out, T, n_prev, scale, mode);
+  if (st != SKV_OK || T == 0) return st;
+  st = check_q_strides(q_stride_b, q_stride_t, q_stride_h);
+  if (st != SKV_OK) return st;
+  return run_prefill(&P->layer, false, q, q_stride_b, q_stride_t, q_stride_h, out, T, n_prev, scale, mode, stream, &pm);
 }
 
 int32_t skv_padded_rank(int32_t r) {

@@ -8,6 +8,30 @@
 
 namespace skv {
 
+// Where the rows of a sequence live.  table == null: one contiguous run of `capacity` rows per
+// (sequence, KV head).  Otherwise the cache is a pool of pages [n_pages][n_kv_heads][page rows][r] and
+// table[b * table_stride + i] names the page that holds rows [i << page_shift, (i + 1) << page_shift) of
+// sequence b; entries are clamped into [0, n_pages) so that no access leaves the pool.
+struct PageMap {
+  const int32_t* table;
+  int32_t table_stride;
+  int32_t page_shift;
+  int32_t n_pages;
+};
+
+__device__ __forceinline__ int clamped_page(const PageMap& pm, int b, int logical_page) {
+  const int v = pm.table[(int64_t)b * pm.table_stride + logical_page];
+  return v < 0 ? 0 : (v >= pm.n_pages ? pm.n_pages - 1 : v);
+}
+
+// Index, in rows, of row t of (sequence b, KV head kv); multiply by the row width.
+__device__ __forceinline__ int64_t cache_row(const PageMap& pm, int64_t capacity, int n_kv_heads, int b, int kv,
+                                             int64_t t) {
+  if (pm.table == nullptr) return ((int64_t)b * n_kv_heads + kv) * capacity + t;
+  const int page = clamped_page(pm, b, (int)(t >> pm.page_shift));
+  return ((((int64_t)page * n_kv_heads + kv)) << pm.page_shift) + (t & ((1 << pm.page_shift) - 1));
+}
+
 // Arguments of the decode kernels (passed by value).
 struct DecodeParams {
   const uint32_t* k_cache;   // bf16 pairs
@@ -44,6 +68,7 @@ struct DecodeParams {
   const int32_t* seq_lens;
   int32_t len_add;           // rows added to every per-sequence length (an append that ran just before): len_b =
                              // clamp(seq_lens[b], 0, n_ctx - len_add) + len_add
+  PageMap pages;             // paged cache: k_cache / v_cache are the pools
   float scale_log2e;         // softmax scale times log2(e)
   int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
@@ -71,6 +96,7 @@ struct AppendParams {
   const float* k_zero;
   uint32_t* v_meta;          // [batch][n_kv_heads][capacity][groups of r_v]
   int32_t qbits;
+  PageMap pages;             // paged cache (bf16 only): k_cache / v_cache are the pools
 };
 
 // Length of sequence b: the uniform value, or the per-sequence one clamped into [0, uniform].
@@ -103,6 +129,7 @@ struct PrefillParams {
   int32_t n_rows_y;          // batch * n_kv_heads * passes
   float scale_log2e;
   int32_t folded;
+  PageMap pages;             // paged cache: k_cache / v_cache are the pools; a key tile never straddles a page
 };
 
 constexpr int kPrefillKeyTile = 64;     // cache rows staged in LDS per step
@@ -145,6 +172,14 @@ hipError_t launch_decode_partial_rk80(int, int, const DecodeParams&, hipStream_t
 hipError_t launch_decode_partial_rk96(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_rk112(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_rk128(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk16(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk32(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk48(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk64(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk80(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk96(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk112(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_rk128(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk32(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk64(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStream_t);

@@ -150,8 +150,11 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
   const int n_tiles_k = (n_keys + KT - 1) / KT;
   const int last_row = n_keys - 1;
 
-  const uint16_t* kc = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RK;
-  const uint16_t* vc = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RV;
+  // First cache row of key tile `tile`, in rows.  A tile is 64 rows from a multiple of 64 and a page
+  // holds a multiple of 64 rows, so a tile never straddles a page: one table entry per tile.
+  auto tile_row = [&](int tile) -> int64_t {
+    return cache_row(p.pages, p.capacity, p.n_kv_heads, b, kv, (int64_t)tile * KT);
+  };
 
   // ---- key/value tiles: global -> registers -> LDS --------------------------------------
   // Tiles that lie wholly inside every query's visible range are fetched with addresses that
@@ -174,7 +177,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
   // INNER: the tile needs no clamping
   auto load_k = [&](auto inner_tag, int tile) {
     const int j0 = tile * KT;
-    const uint16_t* kt = kc + (int64_t)j0 * RK;
+    const uint16_t* kt = p.k_cache + tile_row(tile) * RK;
 #pragma unroll
     for (int u = 0; u < KPT; ++u) {
       const int i = tid + u * NT;
@@ -182,16 +185,16 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         if (decltype(inner_tag)::value) {
           kreg[u] = *reinterpret_cast<const uint4*>(kt + koff[u]);
         } else {
-          int row = j0 + i / KC8;
-          row = row < last_row ? row : last_row;       // rows past the end re-read the last row; masked later
-          kreg[u] = *reinterpret_cast<const uint4*>(kc + (int64_t)row * RK + (i % KC8) * 8);
+          int row = i / KC8;                           // inside the tile
+          row = row < last_row - j0 ? row : last_row - j0;   // rows past the end re-read the last row; masked later
+          kreg[u] = *reinterpret_cast<const uint4*>(kt + row * RK + (i % KC8) * 8);
         }
       }
     }
   };
   auto load_v = [&](auto inner_tag, int tile) {
     const int j0 = tile * KT;
-    const uint16_t* vt = vc + (int64_t)j0 * RV;
+    const uint16_t* vt = p.v_cache + tile_row(tile) * RV;
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
       const int i = tid + u * NT;
@@ -204,9 +207,9 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
           if (decltype(inner_tag)::value) {
             vreg[u][e] = *reinterpret_cast<const uint32_t*>(vt + voff[u] + dk * RV);
           } else {
-            int row = j0 + kbase + dk;
-            row = row < last_row ? row : last_row;
-            vreg[u][e] = *reinterpret_cast<const uint32_t*>(vc + (int64_t)row * RV + 2 * cp);
+            int row = kbase + dk;
+            row = row < last_row - j0 ? row : last_row - j0;
+            vreg[u][e] = *reinterpret_cast<const uint32_t*>(vt + row * RV + 2 * cp);
           }
         }
       }

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(kProjectThreads) void project_kernel(const AppendPa
     if (tid < D) x_s[tid] = bf16_to_f32((which ? ap.v_new : ap.k_new)[src + tid]);
     __syncthreads();
     project_rows_finish<1>(pp, r, x_s, part_s, y_s);
-    const int64_t row = ((int64_t)b * ap.n_kv_heads + h) * ap.capacity + clamped_len(ap.cur_lens, b, ap.cur_len) + t;
+    const int64_t row = cache_row(ap.pages, ap.capacity, ap.n_kv_heads, b, h, clamped_len(ap.cur_lens, b, ap.cur_len) + t);
     if (ap.v_meta == nullptr) {                    // bf16 cache
       uint16_t* cache = which ? ap.v_cache : ap.k_cache;
       if (tid < r) cache[row * r + tid] = (uint16_t)f32_to_bf16_bits(y_s[tid]);

@@ -318,3 +318,36 @@ def test_four_bit_layer_argument_checks():
     assert lib.skv_q4_decode_attention(C.byref(Q32), FAKE, FAKE, 16, 0.0, FAKE, big, None) == B.SKV_ERR_RANK
     assert lib.skv_q4_project_append(C.byref(Q32), FAKE, FAKE, 8192, 1024, 128, 1, 0, None) == B.SKV_ERR_RANK
     assert lib.skv_q4_decode_step(C.byref(Q), FAKE, FAKE, 8192, 1024, 128, -1, 0, FAKE, FAKE, 0.0, FAKE, big, None) == B.SKV_ERR_SHAPE
+
+
+def test_paged_layer_argument_checks():
+    lib = B.lib()
+    big = 1 << 30
+
+    def paged(page_tokens=64, n_pages=100, max_pages=16, table=FAKE, **kw):
+        return B.skv_paged_layer(_layer(capacity=kw.pop("capacity", page_tokens * max_pages), **kw), table, page_tokens,
+                                 n_pages, max_pages)
+
+    P = paged()
+    assert lib.skv_paged_pool_bytes(C.byref(P)) == 100 * 8 * 64 * (64 + 64) * 2
+    att = lambda p, n: lib.skv_paged_decode_attention(C.byref(p), FAKE, FAKE, None, n, 0.0, FAKE, big, None)
+    assert att(P, 1025) == B.SKV_ERR_CAPACITY                     # beyond what the table can address
+    assert att(paged(page_tokens=48), 10) == B.SKV_ERR_SHAPE      # not a power of two
+    assert att(paged(page_tokens=32), 10) == B.SKV_ERR_SHAPE      # smaller than a range quantum
+    assert att(paged(n_pages=0), 10) == B.SKV_ERR_SHAPE
+    assert att(paged(max_pages=0, capacity=64), 10) == B.SKV_ERR_SHAPE
+    assert att(paged(capacity=1000), 10) == B.SKV_ERR_CAPACITY    # capacity must be page_tokens * max_pages_per_seq
+    assert att(paged(table=None), 10) == B.SKV_ERR_NULL
+    assert att(paged(table=FAKE + 2), 10) == B.SKV_ERR_ALIGN
+    assert att(paged(r_k=72), 10) == B.SKV_ERR_RANK
+    assert lib.skv_paged_pool_bytes(C.byref(paged(page_tokens=48))) == 0
+    # lengths are optional here, but must be aligned when given
+    assert lib.skv_paged_decode_attention(C.byref(P), FAKE, FAKE, FAKE + 2, 16, 0.0, FAKE, big, None) == B.SKV_ERR_ALIGN
+    assert lib.skv_paged_project_append(C.byref(P), FAKE, FAKE, 8192, 1024, 128, 4, None, 1021, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_paged_project_append(C.byref(P), FAKE, FAKE, 8192, 1024, 128, 0, None, 10, None) == B.SKV_OK
+    assert lib.skv_paged_decode_step(C.byref(P), FAKE, FAKE, 8192, 1024, 128, 0, None, 10, FAKE, FAKE, 0.0, FAKE, big,
+                                     None) == B.SKV_ERR_SHAPE
+    assert lib.skv_paged_decode_step(C.byref(P), FAKE, FAKE, 8192, 1024, 128, 1, None, 10, FAKE, FAKE, 0.0, FAKE, 64,
+                                     None) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_paged_prefill_attention(C.byref(P), FAKE, 8192, 4096, 128, FAKE, 16, 1010, 0.0, 0, None) == B.SKV_ERR_CAPACITY
+    assert lib.skv_paged_prefill_attention(C.byref(P), FAKE, 8192, 4096, 128, FAKE, 0, 0, 0.0, 0, None) == B.SKV_OK
