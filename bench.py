@@ -208,26 +208,37 @@ def main():
         Bt, HQ, HKV, d = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim
         _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pk"), HKV, d, rk)
         _, pv = synth.orthonormal_bases(synth.stable_seed(wl.name, 0, "pv"), HKV, d, rv)
-        L = B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), n_prev + T)
+        if args.cache == "paged":
+            pt = args.page_tokens
+            per_seq = (n_prev + T + pt - 1) // pt
+            order = np.random.default_rng(synth.stable_seed(wl.name, "pages")).permutation(Bt * per_seq + 16)
+            table = torch.from_numpy(order[:Bt * per_seq].reshape(Bt, per_seq).astype(np.int32)).to(dev)
+            L = B.PagedLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), pt, Bt * per_seq + 16, table)
+            append = lambda k_, v_, c_: B.skv_paged_project_append(L, k_, v_, None, c_)
+            attend = lambda: B.skv_paged_prefill_attention(L, q, out, n_prev, 0.0, pmode)
+        else:
+            L = B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), n_prev + T)
+            append = lambda k_, v_, c_: B.skv_project_append(L, k_, v_, c_)
+            attend = lambda: B.skv_prefill_attention(L, q, out, n_prev, 0.0, pmode)
         sck = synth.channel_scales(synth.stable_seed(wl.name, 0, "sk"), HKV, d)
         scv = synth.channel_scales(synth.stable_seed(wl.name, 0, "sv"), HKV, d)
         for c0 in range(0, n_prev + T, 4096):
             t = min(4096, n_prev + T - c0)
             k = synth.kv_activations(synth.stable_seed(wl.name, 0, "k", c0), Bt, t, HKV, d, sck, dev)
             v = synth.kv_activations(synth.stable_seed(wl.name, 0, "v", c0), Bt, t, HKV, d, scv, dev)
-            B.skv_project_append(L, k, v, c0)
+            append(k, v, c0)
         q = synth.chunk_queries(synth.stable_seed(wl.name, "cq"), Bt, T, HQ, d, dev)
         out = torch.empty((Bt, T, HQ, d), dtype=torch.float32, device=dev)
         pmode = B.SKV_PREFILL_FAST if args.prefill_precision == "fast" else B.SKV_PREFILL_EXACT
         pmode |= {"default": 0, "together": B.SKV_PREFILL_SCHED_TOGETHER, "ahead": B.SKV_PREFILL_SCHED_AHEAD}[args.prefill_sched]
         iters = max(1, args.kernel_iters // 20)
         for _ in range(2):
-            B.skv_prefill_attention(L, q, out, n_prev, 0.0, pmode)
+            attend()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(iters):
-            B.skv_prefill_attention(L, q, out, n_prev, 0.0, pmode)
+            attend()
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / iters
@@ -237,7 +248,7 @@ def main():
         flops = Bt * HQ * (2 * (rk + rv) * visible + T * 2 * d * (rk + rv))
         nbytes = Bt * HKV * (n_prev + T) * (rk + rv) * 2 + Bt * T * HQ * d * (2 + 4)
         res = {"mode": "prefill", "workload": wl.name, "batch": Bt, "T": T, "n_prev": n_prev, "r_k": rk, "r_v": rv,
-               "precision": args.prefill_precision, "sched": args.prefill_sched, "ms_per_launch": round(ms, 4),
+               "precision": args.prefill_precision, "sched": args.prefill_sched, "cache": args.cache, "ms_per_launch": round(ms, 4),
                "chunk_tokens_per_s": round(Bt * T / (ms * 1e-3), 1),
                "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / (ms * 1e-3) / 1e12, 1),
                             "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4),

@@ -483,7 +483,8 @@ skv_status skv_orthonormalize(const void* a, int32_t n_bases, int32_t r, int32_t
  *                            skv_decode_partial_q: n_splits ranges, 0 = default); the second is
  *                            skv_decode_combine(&paged->layer, ...) with the same count
  * skv_paged_decode_step      as skv_decode_step_varlen
- * skv_paged_prefill_attention as skv_prefill_attention (one n_prev for the whole batch)
+ * skv_paged_prefill_attention as skv_prefill_attention (one n_prev for the whole batch);
+ *                            n_prev + T at most 1048576 rows (CAPACITY beyond)
  * skv_paged_pool_bytes       bytes of both pools: n_pages * n_kv_heads * page_tokens * (r_k + r_v) * 2
  *                            (0 for an invalid description)
  * Errors: those of the calls named, plus SHAPE (page_tokens not a power of two >= 64, n_pages or

@@ -52,6 +52,10 @@ def _jobs():
         jobs.append((f"skv_prefill_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_prefill.hip"), f"-DSKV_RK={rk}"],
                      DEVICE_FLAGS + PREFILL_FLAGS))
+    for rk in KEY_RANKS:                  # the chunk kernel over a paged cache
+        jobs.append((f"skv_prefill_paged_rk{rk}.o",
+                     ["-x", "hip", os.path.join(CSRC, "skv_prefill.hip"), f"-DSKV_RK={rk}", "-DSKV_PAGED=1"],
+                     DEVICE_FLAGS + PREFILL_FLAGS))
     for rk in KEY_RANKS:                  # the same range kernel addressing its rows through a page table
         jobs.append((f"skv_decode_partial_paged_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_PAGED=1"],

@@ -497,6 +497,20 @@ prefill_launcher prefill_launcher_for(int r_k) {
   return nullptr;
 }
 
+prefill_launcher paged_prefill_launcher_for(int r_k) {
+  switch (r_k) {
+    case 16: return launch_prefill_paged_rk16;
+    case 32: return launch_prefill_paged_rk32;
+    case 48: return launch_prefill_paged_rk48;
+    case 64: return launch_prefill_paged_rk64;
+    case 80: return launch_prefill_paged_rk80;
+    case 96: return launch_prefill_paged_rk96;
+    case 112: return launch_prefill_paged_rk112;
+    case 128: return launch_prefill_paged_rk128;
+  }
+  return nullptr;
+}
+
 // Checks of the chunk attention that do not depend on where the queries come from.
 skv_status check_prefill(const skv_layer* L, bool folded, const void* q, const void* out, int32_t T,
                          int64_t n_prev, float scale, int32_t mode) {
@@ -545,7 +559,7 @@ skv_status run_prefill(const skv_layer* L, bool folded, const void* q, int64_t s
   const double sc = scale > 0.f ? (double)scale : 1.0 / std::sqrt((double)SKV_HEAD_DIM);
   p.scale_log2e = (float)(sc * 1.4426950408889634);
   p.folded = folded ? 1 : 0;
-  prefill_launcher launch = prefill_launcher_for(L->r_k);
+  prefill_launcher launch = pages ? paged_prefill_launcher_for(L->r_k) : prefill_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   const int sched = (mode & SKV_PREFILL_SCHED_TOGETHER) ? 1 : (mode & SKV_PREFILL_SCHED_AHEAD) ? 2 : 0;
   if (launch(L->r_v, (mode & SKV_PREFILL_FAST) ? 1 : 0, sched, p, static_cast<hipStream_t>(stream)) != hipSuccess)
@@ -1031,6 +1045,7 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* P, const void* q, 
   if (st != SKV_OK) return st;
   st = check_prefill(&P->layer, false, q, out, T, n_prev, scale, mode);
   if (st != SKV_OK || T == 0) return st;
+  if (n_prev + (int64_t)T > kPagedPrefillMaxRows) return SKV_ERR_CAPACITY;   // the kernel's table of tile starts
   st = check_q_strides(q_stride_b, q_stride_t, q_stride_h);
   if (st != SKV_OK) return st;
   return run_prefill(&P->layer, false, q, q_stride_b, q_stride_t, q_stride_h, out, T, n_prev, scale, mode, stream, &pm);

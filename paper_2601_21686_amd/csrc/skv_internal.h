@@ -134,6 +134,8 @@ struct PrefillParams {
 
 constexpr int kPrefillKeyTile = 64;     // cache rows staged in LDS per step
 constexpr int kPrefillThreads = 256;
+// Paged chunk attention keeps one table entry per key tile in LDS: contexts up to this many rows.
+constexpr int64_t kPagedPrefillMaxRows = (int64_t)kPrefillKeyTile * 16384;
 // Tokens of the chunk handled by one workgroup: 4 waves of 32 query rows, split over
 // min(G, 4) heads of the group.
 inline int prefill_tile_tokens(int group) { return 32 * (4 / heads_per_pass(group)); }
@@ -197,6 +199,14 @@ hipError_t launch_prefill_rk80(int, int, int, const PrefillParams&, hipStream_t)
 hipError_t launch_prefill_rk96(int, int, int, const PrefillParams&, hipStream_t);
 hipError_t launch_prefill_rk112(int, int, int, const PrefillParams&, hipStream_t);
 hipError_t launch_prefill_rk128(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk16(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk32(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk48(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk64(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk80(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk96(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk112(int, int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)

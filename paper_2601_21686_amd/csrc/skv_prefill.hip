@@ -41,6 +41,9 @@
 #ifndef SKV_MINB3_SUM
 #define SKV_MINB3_SUM 128
 #endif
+#ifndef SKV_PAGED
+#define SKV_PAGED 0                 // 1: the caches are page pools addressed through a block table
+#endif
 #ifndef SKV_RK
 #error "compile with -DSKV_RK=<key rank>"
 #endif
@@ -90,7 +93,8 @@ __device__ __forceinline__ int swap23(int c) { return (c & ~12) | ((c & 4) << 1)
 // one instruction every 8-10 cycles, so both the vector and the matrix pipe stay busy only with
 // several waves resident; 3 where the live state fits in 168 registers without spilling.
 constexpr int prefill_min_blocks(int rk, int rv, bool split, bool pipe) {
-  return (!pipe && rk + rv <= SKV_MINB3_SUM) ? 3 : 1;
+  // (the paged build needs a few registers more: held to two waves per SIMD rather than left to drop to one)
+  return (!pipe && rk + rv <= SKV_MINB3_SUM) ? 3 : (SKV_PAGED ? 2 : 1);
 }
 
 template <int RK, int RV, bool SPLIT, bool PIPE>
@@ -150,12 +154,28 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
   const int n_tiles_k = (n_keys + KT - 1) / KT;
   const int last_row = n_keys - 1;
 
-  // First cache row of key tile `tile`, in rows.  A tile is 64 rows from a multiple of 64 and a page
-  // holds a multiple of 64 rows, so a tile never straddles a page: one table entry per tile.
-  auto tile_row = [&](int tile) -> int64_t {
-    return cache_row(p.pages, p.capacity, p.n_kv_heads, b, kv, (int64_t)tile * KT);
+  // The caches as one run of rows per (sequence, KV head).  With a paged cache that run exists only
+  // tile by tile: a key tile is 64 rows from a multiple of 64 and a page holds a multiple of 64 rows, so
+  // a tile never straddles a page, and row j of tile `tile` is found at base(tile) + j * r with the base
+  // moved back by the tile's first row (one table entry per tile, uniform over the workgroup).
+  const uint16_t* kc_flat = p.k_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RK;
+  const uint16_t* vc_flat = p.v_cache + ((int64_t)b * p.n_kv_heads + kv) * p.capacity * RV;
+  constexpr bool paged = SKV_PAGED != 0;              // a build of its own: the kernel has no scalar registers to spare
+#if SKV_PAGED
+  // Where each key tile of this (sequence, KV head) starts in the pools, in blocks of 64 rows: looked up
+  // once, kept in LDS (4 bytes per tile, sized by the launcher), so that the loop below carries no table
+  // pointer, stride or bounds in scalar registers.
+  static_assert(KT == 64, "a key tile is one 64-row block of a page");
+  extern __shared__ int32_t tile_block_s[];
+  for (int i = tid; i < n_tiles_k; i += NT)
+    tile_block_s[i] = (int32_t)(cache_row(p.pages, 0, p.n_kv_heads, b, kv, (int64_t)i * KT) >> 6);
+  __syncthreads();
+  auto page_shift_rows = [&](int tile) -> int64_t {        // physical minus logical first row of the tile
+    return ((int64_t)__builtin_amdgcn_readfirstlane(tile_block_s[tile]) - tile) * KT;
   };
-
+#else
+  auto page_shift_rows = [&](int) -> int64_t { return 0; };
+#endif
   // ---- key/value tiles: global -> registers -> LDS --------------------------------------
   // Tiles that lie wholly inside every query's visible range are fetched with addresses that
   // are a per-thread constant plus a uniform tile base; the last few tiles (the causal
@@ -177,7 +197,8 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
   // INNER: the tile needs no clamping
   auto load_k = [&](auto inner_tag, int tile) {
     const int j0 = tile * KT;
-    const uint16_t* kt = p.k_cache + tile_row(tile) * RK;
+    const uint16_t* kc = paged ? p.k_cache + page_shift_rows(tile) * RK : kc_flat;
+    const uint16_t* kt = kc + (int64_t)j0 * RK;
 #pragma unroll
     for (int u = 0; u < KPT; ++u) {
       const int i = tid + u * NT;
@@ -185,16 +206,17 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         if (decltype(inner_tag)::value) {
           kreg[u] = *reinterpret_cast<const uint4*>(kt + koff[u]);
         } else {
-          int row = i / KC8;                           // inside the tile
-          row = row < last_row - j0 ? row : last_row - j0;   // rows past the end re-read the last row; masked later
-          kreg[u] = *reinterpret_cast<const uint4*>(kt + row * RK + (i % KC8) * 8);
+          int row = j0 + i / KC8;
+          row = row < last_row ? row : last_row;       // rows past the end re-read the last row; masked later
+          kreg[u] = *reinterpret_cast<const uint4*>(kc + (int64_t)row * RK + (i % KC8) * 8);
         }
       }
     }
   };
   auto load_v = [&](auto inner_tag, int tile) {
     const int j0 = tile * KT;
-    const uint16_t* vt = p.v_cache + tile_row(tile) * RV;
+    const uint16_t* vc = paged ? p.v_cache + page_shift_rows(tile) * RV : vc_flat;
+    const uint16_t* vt = vc + (int64_t)j0 * RV;
 #pragma unroll
     for (int u = 0; u < VPT; ++u) {
       const int i = tid + u * NT;
@@ -207,9 +229,9 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
           if (decltype(inner_tag)::value) {
             vreg[u][e] = *reinterpret_cast<const uint32_t*>(vt + voff[u] + dk * RV);
           } else {
-            int row = kbase + dk;
-            row = row < last_row - j0 ? row : last_row - j0;
-            vreg[u][e] = *reinterpret_cast<const uint32_t*>(vt + row * RV + 2 * cp);
+            int row = j0 + kbase + dk;
+            row = row < last_row ? row : last_row;
+            vreg[u][e] = *reinterpret_cast<const uint32_t*>(vc + (int64_t)row * RV + 2 * cp);
           }
         }
       }
@@ -590,18 +612,29 @@ constexpr bool pipe_default(int rk, int rv, bool split) {
   return false;
 }
 
+template <int RV, bool SPLIT, bool PIPE>
+hipError_t launch_variant(const PrefillParams& p, hipStream_t stream) {
+  const dim3 grid((unsigned)((int64_t)p.n_tiles * p.n_rows_y));
+  auto* kernel = prefill_kernel<SKV_RK, RV, SPLIT, PIPE>;
+  size_t dyn = 0;
+#if SKV_PAGED
+  // one table entry per key tile of the longest context of the launch
+  dyn = (((size_t)p.n_prev + p.T + KT - 1) / KT * sizeof(int32_t) + 15) & ~(size_t)15;
+  if (dyn > 8192) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+    if (e != hipSuccess) return e;
+  }
+#endif
+  hipLaunchKernelGGL(kernel, grid, dim3(NT), dyn, stream, p);
+  return hipGetLastError();
+}
+
 template <int RV>
 hipError_t launch_rv(int fast, int sched, const PrefillParams& p, hipStream_t stream) {
-  const dim3 grid((unsigned)((int64_t)p.n_tiles * p.n_rows_y));
   const bool pipe = sched == 1 ? false : sched == 2 ? true : pipe_default(SKV_RK, RV, !fast);
-  if (fast) {
-    if (pipe) hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, false, true>), grid, dim3(NT), 0, stream, p);
-    else hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, false, false>), grid, dim3(NT), 0, stream, p);
-  } else {
-    if (pipe) hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, true, true>), grid, dim3(NT), 0, stream, p);
-    else hipLaunchKernelGGL((prefill_kernel<SKV_RK, RV, true, false>), grid, dim3(NT), 0, stream, p);
-  }
-  return hipGetLastError();
+  if (fast) return pipe ? launch_variant<RV, false, true>(p, stream) : launch_variant<RV, false, false>(p, stream);
+  return pipe ? launch_variant<RV, true, true>(p, stream) : launch_variant<RV, true, false>(p, stream);
 }
 
 }  // namespace
@@ -609,7 +642,12 @@ hipError_t launch_rv(int fast, int sched, const PrefillParams& p, hipStream_t st
 #define SKV_CAT2(a, b) a##b
 #define SKV_CAT(a, b) SKV_CAT2(a, b)
 
-hipError_t SKV_CAT(launch_prefill_rk, SKV_RK)(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream) {
+#if SKV_PAGED
+#define SKV_PREFILL_LAUNCHER SKV_CAT(launch_prefill_paged_rk, SKV_RK)
+#else
+#define SKV_PREFILL_LAUNCHER SKV_CAT(launch_prefill_rk, SKV_RK)
+#endif
+hipError_t SKV_PREFILL_LAUNCHER(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream) {
   switch (r_v) {
     case 16: return launch_rv<16>(fast, sched, p, stream);
     case 32: return launch_rv<32>(fast, sched, p, stream);

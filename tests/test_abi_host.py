@@ -351,3 +351,7 @@ def test_paged_layer_argument_checks():
                                      None) == B.SKV_ERR_WORKSPACE
     assert lib.skv_paged_prefill_attention(C.byref(P), FAKE, 8192, 4096, 128, FAKE, 16, 1010, 0.0, 0, None) == B.SKV_ERR_CAPACITY
     assert lib.skv_paged_prefill_attention(C.byref(P), FAKE, 8192, 4096, 128, FAKE, 0, 0, 0.0, 0, None) == B.SKV_OK
+    # the chunk kernel keeps one table entry per key tile in LDS: contexts up to 2^20 rows
+    Pbig = paged(page_tokens=65536, max_pages=32, n_pages=64)
+    assert lib.skv_paged_prefill_attention(C.byref(Pbig), FAKE, 8192, 4096, 128, FAKE, 16, (1 << 20) - 15, 0.0, 0,
+                                           None) == B.SKV_ERR_CAPACITY

@@ -241,11 +241,13 @@ def test_paged_prefill_matches_oracle_and_contiguous_cache(r_k, r_v, group, page
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
     assert vec_rel_err(got, O.paged_prefill_attention(P.ora, P.cache, _f64(q), n_prev)) <= TOL
+    # the contiguous cache with the same rows: the same algorithm from a build of its own (the compiler may
+    # fuse multiply-adds differently), so agreement is to float32 rounding, not to the bit
     L = P.contiguous_gpu([n, n])
     ref = torch.empty_like(out)
     B.skv_prefill_attention(L, q, ref, n_prev)
     torch.cuda.synchronize()
-    assert torch.equal(out, ref)
+    assert vec_rel_err(got, ref.cpu().numpy()) <= 1e-5
 
 
 def test_table_entries_outside_the_pool_are_clamped():
