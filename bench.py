@@ -184,19 +184,32 @@ def main():
         for s in range(4):
             B.skv_decode_step_varlen(L, nk[:, s:s + 1], nk[:, s:s + 1], lens_steps[s], max(lens0) + s, q, out)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for s in range(4, K + 4):
-            B.skv_decode_step_varlen(L, nk[:, s:s + 1], nk[:, s:s + 1], lens_steps[s], max(lens0) + s, q, out)
-        e1.record()
+        def steps():
+            for s in range(4, K + 4):
+                B.skv_decode_step_varlen(L, nk[:, s:s + 1], nk[:, s:s + 1], lens_steps[s], max(lens0) + s, q, out)
+        use_graph = not args.no_graph
+        if use_graph:                                               # as the main benchmark: the K steps as one graph
+            side = torch.cuda.Stream()
+            g = torch.cuda.CUDAGraph()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                with torch.cuda.graph(g, stream=side):
+                    steps()
+            torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if use_graph:
+            g.replay()
+        else:
+            steps()
         torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / K
+        us = (time.perf_counter() - t0) * 1e6 / K
         nbytes = sum(HKV * (n + K // 2 + 5) * (rk + rv) * 2 for n in lens0)
         print(json.dumps({"mode": "varlen", "workload": wl.name, "batch": Bt, "context_lengths": [n + 1 for n in lens0],
                           "r_k": rk, "r_v": rv, "steps": K, "us_per_step": round(us, 2),
                           "cache_bytes_per_step": nbytes, "achieved_GBps": round(nbytes / us / 1e3, 1),
                           "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
-                          "tokens_per_s": round(Bt / (us * 1e-6), 1), "launch": "per-call launches"}))
+                          "tokens_per_s": round(Bt / (us * 1e-6), 1),
+                          "launch": "hip graph replay" if use_graph else "per-call launches"}))
         return
     if args.mode == "prefill":
         # attention of a chunk of T new tokens over n_prev cached ones (rows of the chunk already appended)

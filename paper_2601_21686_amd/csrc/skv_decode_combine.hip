@@ -92,8 +92,21 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
     const int s = sg + k * ng;
     if (active && s < S) a = fmaf(av[k], w_s[s], a);
   }
-  if (active)
-    for (int s = sg + kPreload * ng; s < S; s += ng) a = fmaf(pa[(int64_t)s * RV + c], w_s[s], a);
+  // more ranges than were requested up front (a schedule for unequal lengths can have up to 255): the rest
+  // in batches of kPreload loads in flight, same order of summation
+  for (int s0 = sg + kPreload * ng; s0 < S; s0 += kPreload * ng) {
+    float more[kPreload];
+#pragma unroll
+    for (int k = 0; k < kPreload; ++k) {
+      const int s = s0 + k * ng;
+      more[k] = (active && s < S) ? pa[(int64_t)s * RV + c] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < kPreload; ++k) {
+      const int s = s0 + k * ng;
+      if (active && s < S) a = fmaf(more[k], w_s[s], a);
+    }
+  }
   if (active) part_s[sg * RV + c] = a;
   float l = 0.f;
   for (int s = 0; s < S; ++s) l += lw_s[s];
