@@ -58,7 +58,9 @@ def parse_args():
     ap.add_argument("--ranks", default="", help="--mode prefill/append: override the workload's ranks, as r_k,r_v")
     ap.add_argument("--lengths", default="1.0,0.5,0.25,0.03125",
                     help="--mode varlen: per-sequence context lengths as fractions of the workload's context, cycled over the batch")
-    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "append", "prefill", "varlen"), default="bench",
+    ap.add_argument("--engine", choices=("vector", "matrix"), default="vector",
+                    help="range kernel over bf16 rows: vector arithmetic (default) or matrix cores")
+    ap.add_argument("--mode", choices=("bench", "kernel", "copy", "read", "append", "prefill", "varlen"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
                          "append: the chunk append of the workload (projection on the matrix cores) alone; "
@@ -107,6 +109,33 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    B.skv_set_decode_engine(1 if args.engine == "matrix" else 0)
+    if args.mode == "read":
+        # what a kernel that only reads gets from this memory system, by working-set size: the yardstick beside
+        # the published peak (sizes up to the 256 MiB last-level cache are partly served from it when re-read)
+        sink = torch.zeros(65536, dtype=torch.float32, device=dev)
+        rows = []
+        for mib in (64, 128, 256, 512, 1024, 2048):
+            src = torch.empty(mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+            best = None
+            for wgs in (512, 2048):
+                for _ in range(3):
+                    n = B.skv_probe_stream_read(src, wgs, sink)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(20):
+                    B.skv_probe_stream_read(src, wgs, sink)
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / 20
+                if best is None or us < best[0]:
+                    best = (us, wgs, n)
+            rows.append({"MiB": mib, "us_per_launch": round(best[0], 2), "workgroups": best[1],
+                         "GBps": round(best[2] / best[0] / 1e3, 1), "frac_of_hbm_peak": round(best[2] / best[0] / 1e3 / HBM_PEAK_GBPS, 4)})
+            del src
+        print(json.dumps({"mode": "read", "kernel": "stream_read_kernel", "launches_per_size": 46, "sizes": rows}))
+        return
     if args.mode == "copy":
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -479,6 +508,22 @@ def main():
     kern_bytes = Bt * HKV * n_roof * row_bytes(li_big) + q_in + Bt * HQ * splits * (rv + 2) * 4
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
 
+    # the yardstick: a kernel that only reads a buffer of the same size (same launch stream, same events)
+    probe_bytes = min(max(int(kern_bytes), 1 << 24), 2 << 30)
+    probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
+    probe_sink = torch.zeros(4096, dtype=torch.float32, device=dev)
+    for _ in range(5):
+        probe_n = B.skv_probe_stream_read(probe_src, 2048, probe_sink)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(20):
+        B.skv_probe_stream_read(probe_src, 2048, probe_sink)
+    e1.record()
+    torch.cuda.synchronize()
+    probe_us = e0.elapsed_time(e1) * 1e3 / 20
+    probe_gbps = probe_n / probe_us / 1e3
+    del probe_src
+
     result = {
         "metric": METRIC,
         "value": round(gbps, 1),
@@ -499,13 +544,16 @@ def main():
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
                    "cache": f"{qbits}-bit codes, group 64" if q8 else (f"bf16, pages of {args.page_tokens} rows, shuffled block table" if paged else "bf16"), "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
-                   "variant": args.variant,
+                   "variant": args.variant, "engine": args.engine,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_kernel", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" and not q8) else "decode_partial_kernel",
+                     "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(wl.name, args.cache), "bytes_per_launch": kern_bytes,
                      "us_per_launch": round(kern_ms * 1e3, 3), "n_ctx": n_roof, "r_k": rk, "r_v": rv,
-                     "splits": splits},
+                     "splits": splits,
+                     "plain_read": {"kernel": "stream_read_kernel", "bytes": probe_n, "us_per_launch": round(probe_us, 3),
+                                    "GBps": round(probe_gbps, 1), "range_kernel_vs_plain_read": round(achieved / probe_gbps, 4)}},
     }
 
     # ---- CPU baseline: the float64 oracle, one decode step of the same workload ----------

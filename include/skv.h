@@ -518,6 +518,28 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* paged, const void*
                                        int64_t q_stride_t, int64_t q_stride_h, void* out, int32_t T,
                                        int64_t n_prev, float scale, int32_t mode, void* stream);
 
+/*
+ * Which kernel streams the bf16 cache in the decode calls (contiguous and paged; the quantised
+ * formats have their own): 0 = vector arithmetic, 1 = matrix cores (the query heads of a group as
+ * columns of 16x16x16 bf16 products, float32 operands split into two bf16 terms).  Both compute
+ * App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in speed only.
+ * Process-wide and not synchronised: set it before issuing work.  Returns the previous value;
+ * any other argument changes nothing (a way to read the current value).
+ */
+int32_t skv_set_decode_engine(int32_t engine);
+
+/*
+ * A measuring stick for the benchmark, no part of the method: one launch that only READS.  The first
+ * *bytes_read <= bytes bytes of src (whole multiples of workgroups * 16 KiB) are streamed, each
+ * workgroup a contiguous slice, and nothing is written.  Timing it tells what a plain streaming read of
+ * that size reaches on the machine at hand, which the range kernels are compared with.
+ *   src   device, 16-byte aligned, at least `bytes` long
+ *   sink  device float32 [workgroups]: never written in practice, must be valid
+ * Errors: NULL, ALIGN, SHAPE (workgroups outside [1, 65535], or bytes below workgroups * 16 KiB), HIP.
+ */
+skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgroups, void* sink,
+                                 size_t* bytes_read, void* stream);
+
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
 size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);

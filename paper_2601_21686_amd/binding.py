@@ -37,7 +37,7 @@ EXPORTS = (
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
-    "skv_paged_prefill_attention", "skv_paged_decode_partial_q",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read",
 )
 
 
@@ -163,6 +163,10 @@ def lib() -> C.CDLL:
     L.skv_paged_decode_step.restype = C.c_int
     L.skv_paged_prefill_attention.argtypes = [PP, vp, i64, i64, i64, vp, i32, i64, C.c_float, i32, vp]
     L.skv_paged_prefill_attention.restype = C.c_int
+    L.skv_probe_stream_read.argtypes = [vp, sz, i32, vp, C.POINTER(C.c_size_t), vp]
+    L.skv_probe_stream_read.restype = C.c_int
+    L.skv_set_decode_engine.argtypes = [i32]
+    L.skv_set_decode_engine.restype = i32
     L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
     L.skv_orthonormalize.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
@@ -456,6 +460,20 @@ def skv_decode_step_varlen(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_
                                         int(k_new.shape[1]), cur_lens.data_ptr(), int(max_cur_len), q.data_ptr(),
                                         out.data_ptr(), float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
                                         _stream_ptr(stream)), "skv_decode_step_varlen")
+
+
+def skv_probe_stream_read(src: torch.Tensor, workgroups: int, sink: torch.Tensor, stream=None) -> int:
+    """One read-only launch over src (a contiguous CUDA tensor); returns the bytes it read."""
+    assert src.is_cuda and src.is_contiguous() and sink.dtype == torch.float32 and sink.numel() >= workgroups
+    n = C.c_size_t(0)
+    _check(lib().skv_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), int(workgroups),
+                                       sink.data_ptr(), C.byref(n), _stream_ptr(stream)), "skv_probe_stream_read")
+    return int(n.value)
+
+
+def skv_set_decode_engine(engine: int) -> int:
+    """0 = vector arithmetic, 1 = matrix cores; returns the previous choice (any other value: no change)."""
+    return int(lib().skv_set_decode_engine(int(engine)))
 
 
 # ---- paged cache -------------------------------------------------------------------------------

@@ -760,6 +760,337 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   }
 }
 
+#if !SKV_Q8
+// ---------------------------------------------------------------------------------------------------
+// The same range on the matrix cores.
+//
+// With G query heads per KV head the scores and the mix are products of a [G x r] block with the streamed
+// rows: 2 G (r_K + r_V) multiply-adds per cache row, which at G = 4 keeps the vector pipe almost as busy as
+// the memory system.  Here both products run as 16x16x16 bf16 matrix instructions with the query heads in
+// 4 of the 16 columns (the matrix pipe has two orders of magnitude to spare at this arithmetic intensity),
+// and the vector pipe is left with the softmax and the operand conversions.
+//
+//   S^T [keys x queries]   = K_down [keys x r_K] . Q~^T          A = cache rows as they are loaded
+//   O^T [r_V x queries]   += V_down^T [r_V x keys] . P^T         B = 2^(S^T - m): the accumulator layout of the
+//                                                                 first product is the B layout of the second
+// A wave works on tiles of 32 consecutive rows by itself (wave w of the workgroup takes tiles w, w + 4, ...
+// of the range): no workgroup barrier in the loop.  Lane (m = lane % 16, g = lane / 16) loads the g-th
+// quarter of key row m of each 16-row block (contiguous, r_K / 2 bytes), which is the A operand if the
+// contraction index is enumerated as channel = g r_K / 4 + 4 step + i; Q~ is laid out to match.  Value
+// rows go through a per-wave LDS region, transposed on the way ([channel][key], 8-key runs per 16-byte
+// store), and come back as A operands of the second product.  float32 operands (Q~, the weights) are
+// split into two bf16 terms (x ~ hi + lo, relative error 2^-17), two products each, so the 2e-3 bound of
+// the vector kernel holds.
+// ---------------------------------------------------------------------------------------------------
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f32x4 mfma16(uint2 a, uint2 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// four float32 -> bf16 heads and bf16 remainders, packed as matrix operands
+__device__ __forceinline__ void split4(const float (&x)[4], uint2& hi, uint2& lo) {
+  hi.x = pack_bf16_pair(x[0], x[1]);
+  hi.y = pack_bf16_pair(x[2], x[3]);
+  lo.x = pack_bf16_pair(x[0] - bf16_lo(hi.x), x[1] - bf16_hi(hi.x));
+  lo.y = pack_bf16_pair(x[2] - bf16_lo(hi.y), x[3] - bf16_hi(hi.y));
+}
+
+#ifndef SKV_MMA_DEPTH
+#define SKV_MMA_DEPTH 1          // tiles a wave has requested ahead of the one it computes on (1 or 2)
+#endif
+constexpr int kMmaTileRows = 32;                 // rows a wave takes at a time
+constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel (bf16 elements; 80 bytes)
+
+template <int RK, int RV, int GT, int FMT>
+__global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(const DecodeParams p) {
+  static_assert(FMT == kFmt, "format tag must match the build");
+  constexpr int KSTEPS = RK / 16;                // contraction steps of the score product
+  constexpr int VBLOCKS = RV / 16;               // 16-channel blocks of the mix
+  constexpr int VUNITS = 4 * (RV / 2);           // (8-row group, channel pair) units of a value tile
+  constexpr int VPL = (VUNITS + 63) / 64;        // units per lane
+  constexpr int VP = kMmaVPitch;
+
+  // The projection scratch is needed before the first tile only, the value tiles after it: one region.
+  constexpr int kProjBytes = kProjectThreads * GT * 8 * (int)sizeof(float);
+  constexpr int kTileBytes = 4 * RV * VP * (int)sizeof(uint16_t);           // per wave: value tile, [channel][row]
+  __shared__ __attribute__((aligned(16))) unsigned char scratch_s[kProjBytes > kTileBytes ? kProjBytes : kTileBytes];
+  __shared__ float red[4 * GT * (RV + 2)];
+  __shared__ float px_s[GT * SKV_HEAD_DIM];
+  __shared__ float py_s[GT * SKV_HEAD_DIM];
+  float* ppart_s = reinterpret_cast<float*>(scratch_s);
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lane = tid & 63;
+  const int lm = lane & 15;                      // row of a 16-row block (first product), channel (second), query column
+  const int g = lane >> 4;
+
+  int split = blockIdx.x;
+  const int passes = p.group / GT;
+  int col = blockIdx.y;
+  const int n_cols = p.batch * p.n_kv_heads * passes;
+  const bool fresh = col >= n_cols;              // the fresh-rows workgroups of a fused decode step
+  if (fresh) {
+    col = (col - n_cols) * (int)gridDim.x + split;
+    if (col >= n_cols) return;
+    split = p.n_stream;
+  }
+  const int pass = col % passes;
+  const int bkv = col / passes;
+  const int kv = bkv % p.n_kv_heads;
+  const int b = bkv / p.n_kv_heads;
+  const int hq0 = kv * p.group + pass * GT;
+  if (fresh) {
+    fresh_rows_block<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s);
+    return;
+  }
+  int t0, t1;
+  range_of_split((int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add, p.n_stream, split, &t0, &t1);
+
+  float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
+  float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;
+  const int64_t head_step_acc = (int64_t)p.n_splits * RV;
+  const int64_t head_step_ml = (int64_t)p.n_splits * 2;
+  if (t0 >= t1) {
+    for (int i = tid; i < GT * RV; i += kDecodeThreads) out_acc[(i / RV) * head_step_acc + (i % RV)] = 0.f;
+    if (tid < GT) { out_ml[tid * head_step_ml] = kNegBig; out_ml[tid * head_step_ml + 1] = 0.f; }
+    return;
+  }
+
+  // ---- where the rows of a tile are ---------------------------------------------------------------
+  // rows [row, row + 32) lie in one page (ranges start at multiples of 64, pages hold multiples of 64)
+#if SKV_PAGED
+  const int page_rows_mask = (1 << p.pages.page_shift) - 1;
+  auto tile_base = [&](int row) -> int64_t {                     // index of the tile's first row, in rows
+    const int page = clamped_page(p.pages, b, row >> p.pages.page_shift);   // wave-uniform: a scalar load
+    return ((((int64_t)page * p.n_kv_heads + kv)) << p.pages.page_shift) + (row & page_rows_mask);
+  };
+#else
+  const int64_t flat0 = ((int64_t)b * p.n_kv_heads + kv) * p.capacity;
+  auto tile_base = [&](int row) -> int64_t { return flat0 + row; };
+#endif
+  const uint16_t* kc = reinterpret_cast<const uint16_t*>(p.k_cache);
+  const uint16_t* vc = reinterpret_cast<const uint16_t*>(p.v_cache);
+
+  // ---- tile loads: keys straight into operand layout, values as (8 rows x channel pair) units ------------
+  const int n_tiles = (t1 - t0 + kMmaTileRows - 1) / kMmaTileRows;
+  struct TileRegsM {
+    uint2 k[2][KSTEPS];
+    uint32_t v[VPL][8];
+  };
+  auto issue_tile = [&](int tile, TileRegsM& tr) {
+    const int row0 = t0 + tile * kMmaTileRows;
+    const int last = t1 - 1 - row0;                              // rows past it re-read it; their weights are zero
+    const int64_t base = tile_base(row0);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      int r = 16 * kb + lm;
+      r = r < last ? r : last;
+      const uint16_t* src = kc + (base + r) * RK + g * (RK / 4);
+      if constexpr (RK % 32 == 0) {
+#pragma unroll
+        for (int k2 = 0; k2 < KSTEPS / 2; ++k2) {
+          const uint4 w = *reinterpret_cast<const uint4*>(src + 8 * k2);
+          tr.k[kb][2 * k2] = make_uint2(w.x, w.y);
+          tr.k[kb][2 * k2 + 1] = make_uint2(w.z, w.w);
+        }
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) tr.k[kb][ks] = *reinterpret_cast<const uint2*>(src + 4 * ks);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) {
+      const int i = lane + 64 * u;
+      if (VUNITS % 64 == 0 || i < VUNITS) {
+        const int cp = i % (RV / 2), kg = i / (RV / 2);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          int r = 8 * kg + e;
+          r = r < last ? r : last;
+          tr.v[u][e] = *reinterpret_cast<const uint32_t*>(vc + (base + r) * RV + 2 * cp);
+        }
+      }
+    }
+  };
+  // the value tile into this wave's LDS region, transposed: channel c, rows 8 kg .. 8 kg + 7 as one 16-byte run
+  uint16_t* vt = reinterpret_cast<uint16_t*>(scratch_s) + wave * (RV * VP);
+  auto store_values = [&](const TileRegsM& tr) {
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) {
+      const int i = lane + 64 * u;
+      if (VUNITS % 64 == 0 || i < VUNITS) {
+        const int cp = i % (RV / 2), kg = i / (RV / 2);
+        uint4 even, odd;
+        even.x = __builtin_amdgcn_perm(tr.v[u][1], tr.v[u][0], 0x05040100u);
+        even.y = __builtin_amdgcn_perm(tr.v[u][3], tr.v[u][2], 0x05040100u);
+        even.z = __builtin_amdgcn_perm(tr.v[u][5], tr.v[u][4], 0x05040100u);
+        even.w = __builtin_amdgcn_perm(tr.v[u][7], tr.v[u][6], 0x05040100u);
+        odd.x = __builtin_amdgcn_perm(tr.v[u][1], tr.v[u][0], 0x07060302u);
+        odd.y = __builtin_amdgcn_perm(tr.v[u][3], tr.v[u][2], 0x07060302u);
+        odd.z = __builtin_amdgcn_perm(tr.v[u][5], tr.v[u][4], 0x07060302u);
+        odd.w = __builtin_amdgcn_perm(tr.v[u][7], tr.v[u][6], 0x07060302u);
+        *reinterpret_cast<uint4*>(vt + (2 * cp) * VP + 8 * kg) = even;
+        *reinterpret_cast<uint4*>(vt + (2 * cp + 1) * VP + 8 * kg) = odd;
+      }
+    }
+  };
+
+  // ---- projected queries as B operands: column lm is query head lm of the pass (zero beyond GT) ---------
+  // SKV_MMA_DEPTH tiles per wave on their way while the queries are prepared, and from then on (one register
+  // set each).  Measured: a second set is slower at every shape tried (45.1 against 43.5 us at b4/32K, 64/64).
+  TileRegsM ta;
+  if (wave < n_tiles) issue_tile(wave, ta);
+#if SKV_MMA_DEPTH == 2
+  TileRegsM tb;
+  if (wave + 4 < n_tiles) issue_tile(wave + 4, tb);
+#endif
+  const float* qsrc;
+  float qscale;
+  if (p.q != nullptr) {
+    ProjectPieces pp;
+    project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
+    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
+    for (int i = tid; i < GT * SKV_HEAD_DIM; i += kDecodeThreads) px_s[i] = bf16_to_f32(qptr[i]);
+    __syncthreads();
+    project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
+    qsrc = py_s;
+    qscale = p.scale_log2e;
+  } else {
+    qsrc = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;          // already scaled
+    qscale = 1.f;
+  }
+  uint2 qhi[KSTEPS], qlo[KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    float x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = lm < GT ? qsrc[lm * RK + g * (RK / 4) + 4 * ks + i] * qscale : 0.f;
+    split4(x, qhi[ks], qlo[ks]);
+  }
+
+  // ---- stream this wave's tiles -------------------------------------------------------------------
+  // Per lane: query column lm, rows 4 g + i of each 16-row block.  m_ref is the softmax reference of the
+  // column (log2 units; the same in the four lanes of a column), l this lane's share of the normaliser.
+  float m_ref = 0.f, l = 0.f;
+  bool first = true;
+  f32x4 oacc[VBLOCKS];
+#pragma unroll
+  for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // one tile from register set tr; the tile after next is requested into the same set once it is free
+  auto process = [&](int tile, TileRegsM& tr) {
+    const int row0 = t0 + tile * kMmaTileRows;
+    // scores minus the reference: the reference rides in as the initial accumulator
+    f32x4 sc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      sc[kb] = f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        sc[kb] = mfma16(tr.k[kb][ks], qhi[ks], sc[kb]);
+        sc[kb] = mfma16(tr.k[kb][ks], qlo[ks], sc[kb]);
+      }
+    }
+    store_values(tr);
+    __builtin_amdgcn_wave_barrier();
+    if (tile + 4 * SKV_MMA_DEPTH < n_tiles) issue_tile(tile + 4 * SKV_MMA_DEPTH, tr);
+    // rows past the end of the range do not count
+    if (row0 + kMmaTileRows > t1) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (row0 + 16 * kb + 4 * g + i >= t1) sc[kb][i] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
+                     fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (first || mx > kRescaleSlack) {                           // the reference moves (lanes of a column agree)
+      const float f = first ? 0.f : fast_exp2(-mx);
+      m_ref = first ? mx : m_ref + mx;
+      l *= f;
+#pragma unroll
+      for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] *= f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) sc[kb] -= mx;
+    }
+    first = false;
+    uint2 phi[2], plo[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float x[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[i] = fast_exp2(sc[kb][i]);
+        l += x[i];
+      }
+      split4(x, phi[kb], plo[kb]);
+    }
+#pragma unroll
+    for (int cb = 0; cb < VBLOCKS; ++cb)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const uint2 a = *reinterpret_cast<const uint2*>(vt + (16 * cb + lm) * VP + 16 * kb + 4 * g);
+        oacc[cb] = mfma16(a, phi[kb], oacc[cb]);
+        oacc[cb] = mfma16(a, plo[kb], oacc[cb]);
+      }
+    __builtin_amdgcn_wave_barrier();
+  };
+#if SKV_MMA_DEPTH == 2
+  for (int tile = wave; tile < n_tiles; tile += 8) {
+    process(tile, ta);
+    if (tile + 4 < n_tiles) process(tile + 4, tb);
+  }
+#else
+  for (int tile = wave; tile < n_tiles; tile += 4) process(tile, ta);
+#endif
+
+  // ---- the four lanes of a column hold shares of l; then merge the 4 waves through LDS, in wave order ----
+  l += __shfl_xor(l, 16);
+  l += __shfl_xor(l, 32);
+  if (lm < GT) {
+    float* r = red + (wave * GT + lm) * (RV + 2);
+#pragma unroll
+    for (int cb = 0; cb < VBLOCKS; ++cb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r[16 * cb + 4 * g + i] = oacc[cb][i];
+    if (g == 0) {
+      r[RV] = first ? kNegBig : m_ref;                           // a wave without tiles: the neutral element
+      r[RV + 1] = l;
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < GT * (RV + 2); i += kDecodeThreads) {
+    const int hg = i / (RV + 2), c = i % (RV + 2);
+    float mt = red[(0 * GT + hg) * (RV + 2) + RV];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) mt = fmaxf(mt, red[(w * GT + hg) * (RV + 2) + RV]);
+    if (c == RV) {
+      out_ml[hg * head_step_ml] = mt;
+    } else {
+      const int src = c == RV + 1 ? RV + 1 : c;
+      float a = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float* r = red + (w * GT + hg) * (RV + 2);
+        a += r[src] * fast_exp2(r[RV] - mt);
+      }
+      if (c == RV + 1) out_ml[hg * head_step_ml + 1] = a;
+      else out_acc[hg * head_step_acc + c] = a;
+    }
+  }
+}
+#endif  // !SKV_Q8
+
 template <int RK, int RV>
 hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const int passes = p.group / heads;
@@ -767,6 +1098,17 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const int fresh_rows = p.T_new > 0 ? (cols + p.n_stream - 1) / p.n_stream : 0;
   const dim3 grid((unsigned)p.n_stream, (unsigned)(cols + fresh_rows));
   const dim3 block(kDecodeThreads);
+#if !SKV_Q8
+  if (p.engine == 1) {
+    switch (heads) {
+      case 1: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
+      case 2: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
+      case 4: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 4, kFmt>), grid, block, 0, stream, p); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+#endif
   switch (heads) {
     case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;

@@ -26,6 +26,9 @@ bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; 
 // 8 or 16 ranges per (sequence, KV head) are the fastest, 32 and 64 are slower.
 constexpr int kTargetWorkgroups = 512;
 
+// Which range kernel streams bf16 rows: 0 = vector arithmetic, 1 = matrix cores (process-wide, see skv.h).
+int g_decode_engine = 0;
+
 // need_bases = false: the folded-weights entry points, which never touch p_k / p_v.
 skv_status check_layer(const skv_layer* L, bool need_bases = true) {
   if (!L) return SKV_ERR_NULL;
@@ -90,6 +93,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->seq_lens = nullptr;
   p->len_add = 0;
   p->pages = PageMap{nullptr, 0, 0, 0};
+  p->engine = g_decode_engine;
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
@@ -176,6 +180,26 @@ const char* skv_status_string(skv_status s) {
     case SKV_ERR_HIP: return "SKV_ERR_HIP";
   }
   return "SKV_ERR_UNKNOWN";
+}
+
+skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgroups, void* sink, size_t* bytes_read,
+                                 void* stream) {
+  if (!src || !sink || !bytes_read) return SKV_ERR_NULL;
+  if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKV_ERR_ALIGN;
+  if (workgroups < 1 || workgroups > 65535) return SKV_ERR_SHAPE;
+  const size_t stride = 1024;                                        // 256 lanes x 4 pieces in flight
+  const size_t per_wg = bytes / 16 / (size_t)workgroups / stride * stride;
+  if (per_wg == 0) return SKV_ERR_SHAPE;
+  *bytes_read = per_wg * (size_t)workgroups * 16;
+  if (launch_stream_read(src, per_wg, workgroups, sink, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+int32_t skv_set_decode_engine(int32_t engine) {
+  const int32_t before = g_decode_engine;
+  if (engine == 0 || engine == 1) g_decode_engine = engine;
+  return before;
 }
 
 size_t skv_cache_bytes(const skv_layer* L, int64_t n_tokens) {

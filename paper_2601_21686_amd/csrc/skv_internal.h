@@ -69,6 +69,7 @@ struct DecodeParams {
   int32_t len_add;           // rows added to every per-sequence length (an append that ran just before): len_b =
                              // clamp(seq_lens[b], 0, n_ctx - len_add) + len_add
   PageMap pages;             // paged cache: k_cache / v_cache are the pools
+  int32_t engine;            // range kernel over bf16 rows: 0 = vector arithmetic, 1 = matrix cores
   float scale_log2e;         // softmax scale times log2(e)
   int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
@@ -209,6 +210,8 @@ hipError_t launch_prefill_paged_rk112(int, int, int, const PrefillParams&, hipSt
 hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
+// reads workgroups * pieces_per_wg 16-byte pieces (pieces_per_wg a multiple of 1024), writes nothing
+hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)
 hipError_t launch_pad_basis(const void* src, void* dst, int r, int r_pad, int64_t rows, hipStream_t stream);
 // out bf16 [n][128][r_out]: leading r columns of the orthonormal factor of a float32 [n][128][128], zero columns behind

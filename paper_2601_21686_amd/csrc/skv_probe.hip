@@ -1,0 +1,35 @@
+// A measuring stick, not part of the attention path: a kernel that only reads.  Every workgroup streams a
+// contiguous slice with four 16-byte loads in flight per lane and writes nothing (one guarded store that never
+// fires keeps the loads alive).  What it reaches is what this memory system gives a plain streaming read of
+// that size; the range kernels are judged against it as well as against the published peak.
+#include "skv_internal.h"
+
+namespace skv {
+namespace {
+
+constexpr int kProbeThreads = 256;
+constexpr int kProbeUnroll = 4;
+
+__global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const uint4* __restrict__ src, size_t per_wg,
+                                                                  float* sink) {
+  const uint4* p = src + (size_t)blockIdx.x * per_wg;
+  float acc = 0.f;
+  for (size_t i = threadIdx.x; i < per_wg; i += kProbeThreads * kProbeUnroll) {   // per_wg is a multiple of the stride
+    uint4 v[kProbeUnroll];
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u) v[u] = p[i + (size_t)u * kProbeThreads];
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u) acc += __uint_as_float(v[u].x ^ v[u].y ^ v[u].z ^ v[u].w);
+  }
+  if (acc == 12345.678f) sink[blockIdx.x] = acc;   // practically never: the sum of xor-ed words is not this value
+}
+
+}  // namespace
+
+hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,
+                     static_cast<const uint4*>(src), pieces_per_wg, static_cast<float*>(sink));
+  return hipGetLastError();
+}
+
+}  // namespace skv

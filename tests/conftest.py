@@ -26,3 +26,12 @@ def _library_present():
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(params=[0, 1], ids=["vector", "matrix"])
+def decode_engine(request):
+    """Runs a test once per range kernel over bf16 rows (vector arithmetic, matrix cores)."""
+    from paper_2601_21686_amd import binding
+    before = binding.skv_set_decode_engine(request.param)
+    yield request.param
+    binding.skv_set_decode_engine(before)

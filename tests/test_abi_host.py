@@ -355,3 +355,21 @@ def test_paged_layer_argument_checks():
     Pbig = paged(page_tokens=65536, max_pages=32, n_pages=64)
     assert lib.skv_paged_prefill_attention(C.byref(Pbig), FAKE, 8192, 4096, 128, FAKE, 16, (1 << 20) - 15, 0.0, 0,
                                            None) == B.SKV_ERR_CAPACITY
+
+
+def test_decode_engine_switch():
+    lib = B.lib()
+    before = lib.skv_set_decode_engine(1)
+    assert lib.skv_set_decode_engine(-1) == 1          # anything but 0 or 1 changes nothing
+    assert lib.skv_set_decode_engine(7) == 1
+    assert lib.skv_set_decode_engine(0) == 1
+    assert lib.skv_set_decode_engine(before) == 0
+
+
+def test_read_probe_argument_checks():
+    lib = B.lib()
+    n = C.c_size_t(0)
+    assert lib.skv_probe_stream_read(None, 1 << 20, 4, FAKE, C.byref(n), None) == B.SKV_ERR_NULL
+    assert lib.skv_probe_stream_read(FAKE + 4, 1 << 20, 4, FAKE, C.byref(n), None) == B.SKV_ERR_ALIGN
+    assert lib.skv_probe_stream_read(FAKE, 1 << 20, 0, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE
+    assert lib.skv_probe_stream_read(FAKE, 1000, 4, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE    # less than a slice each

@@ -8,7 +8,7 @@ import torch
 from paper_2601_21686_amd import binding as B
 from _helpers import TOL, Pair, vec_rel_err
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("decode_engine")]
 
 
 def _filled_pair(seed, batch, hq, hkv, r_k, r_v, n, capacity=None, **kw):
