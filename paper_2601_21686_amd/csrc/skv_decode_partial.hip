@@ -760,27 +760,35 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   }
 }
 
-#if !SKV_Q8
 // ---------------------------------------------------------------------------------------------------
 // The same range on the matrix cores.
 //
 // With G query heads per KV head the scores and the mix are products of a [G x r] block with the streamed
 // rows: 2 G (r_K + r_V) multiply-adds per cache row, which at G = 4 keeps the vector pipe almost as busy as
-// the memory system.  Here both products run as 16x16x16 bf16 matrix instructions with the query heads in
-// 4 of the 16 columns (the matrix pipe has two orders of magnitude to spare at this arithmetic intensity),
-// and the vector pipe is left with the softmax and the operand conversions.
+// the memory system (and, over a quantised cache, busier: there the vector kernel is bound by arithmetic).
+// Here both products run as 16x16x16 bf16 matrix instructions with the query heads in 4 of the 16 columns
+// (the matrix pipe has two orders of magnitude to spare at this arithmetic intensity), and the vector pipe
+// is left with the softmax and the operand conversions.
 //
 //   S^T [keys x queries]   = K_down [keys x r_K] . Q~^T          A = cache rows as they are loaded
 //   O^T [r_V x queries]   += V_down^T [r_V x keys] . P^T         B = 2^(S^T - m): the accumulator layout of the
 //                                                                 first product is the B layout of the second
 // A wave works on tiles of 32 consecutive rows by itself (wave w of the workgroup takes tiles w, w + 4, ...
 // of the range): no workgroup barrier in the loop.  Lane (m = lane % 16, g = lane / 16) loads the g-th
-// quarter of key row m of each 16-row block (contiguous, r_K / 2 bytes), which is the A operand if the
-// contraction index is enumerated as channel = g r_K / 4 + 4 step + i; Q~ is laid out to match.  Value
-// rows go through a per-wave LDS region, transposed on the way ([channel][key], 8-key runs per 16-byte
-// store), and come back as A operands of the second product.  float32 operands (Q~, the weights) are
-// split into two bf16 terms (x ~ hi + lo, relative error 2^-17), two products each, so the 2e-3 bound of
-// the vector kernel holds.
+// quarter of key row m of each 16-row block (contiguous), which is the A operand if the contraction index
+// is enumerated as channel = g r_K / 4 + 4 step + i; Q~ is laid out to match.  Value rows go through a
+// per-wave LDS region, transposed on the way ([channel][key], 8-key runs per 16-byte store), and come back
+// as A operands of the second product.  float32 operands (Q~, the weights) are split into two bf16 terms
+// (x ~ hi + lo, relative error 2^-17), two products each, so the 2e-3 bound of the vector kernel holds.
+//
+// Quantised caches (Sec. 4.3).  Integer codes are exact in bf16, so they enter the products as they are
+// and the ranges stay outside: key scales are already folded into Q~ (the key zero point shifts every
+// score of a query alike and drops out); a value row j contributes (p_j scale_j) code_j + p_j zero_j per
+// 64-channel group, i.e. the weights of the second product are p_j scale_j (one B operand per group) and
+// sum_j p_j zero_j is kept beside the normaliser.  8-bit codes are converted byte by byte
+// (v_cvt_f32_ubyteN, then the high halves of two results packed).  4-bit codes n become the bf16 number
+// 16 + n, whose bit pattern is 0x4180 + 8 n (one shift-or per pair): for keys the extra 16 sum_c q~_c is
+// one more constant per query; for values it is taken back through the zero term (zero_j - 16 scale_j).
 // ---------------------------------------------------------------------------------------------------
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -801,6 +809,17 @@ __device__ __forceinline__ void split4(const float (&x)[4], uint2& hi, uint2& lo
   lo.x = pack_bf16_pair(x[0] - bf16_lo(hi.x), x[1] - bf16_hi(hi.x));
   lo.y = pack_bf16_pair(x[2] - bf16_lo(hi.y), x[3] - bf16_hi(hi.y));
 }
+// the high halves of two float32 numbers as a bf16 pair (exact when both are bf16 numbers already)
+__device__ __forceinline__ uint32_t high_halves(float lo, float hi) {
+  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+template <int N>
+__device__ __forceinline__ float byte_to_f32(uint32_t w) { return (float)((w >> (8 * N)) & 0xffu); }
+// two 4-bit codes (bits 0..3 of bytes NL of lo and NH of hi ... see callers) as bf16 numbers 16 + n
+constexpr float kNibbleOffset = 16.f;
+__device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_0_and_2) {
+  return (pair_in_bytes_0_and_2 << 3) | 0x41804180u;
+}
 
 #ifndef SKV_MMA_DEPTH
 #define SKV_MMA_DEPTH 1          // tiles a wave has requested ahead of the one it computes on (1 or 2)
@@ -813,18 +832,25 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   static_assert(FMT == kFmt, "format tag must match the build");
   constexpr int KSTEPS = RK / 16;                // contraction steps of the score product
   constexpr int VBLOCKS = RV / 16;               // 16-channel blocks of the mix
-  constexpr int VUNITS = 4 * (RV / 2);           // (8-row group, channel pair) units of a value tile
+  constexpr int NG = (RV + 63) / 64;             // 64-channel groups of a value row (quantisation groups)
+  // raw words per lane: a quarter of a key row per 16-row block; value tiles as units of 8 rows by one word
+  constexpr int KRAW = RK / 4 / kElemsPerDword;  // bf16: RK / 8, 8-bit: RK / 16, 4-bit: RK / 32
+  constexpr int VWORDS = RV / kElemsPerDword;    // words in a value row
+  constexpr int VUNITS = 4 * VWORDS;
   constexpr int VPL = (VUNITS + 63) / 64;        // units per lane
   constexpr int VP = kMmaVPitch;
+  static_assert(KRAW >= 1 && (RK / 4) % kElemsPerDword == 0, "rank not supported by this format");
 
   // The projection scratch is needed before the first tile only, the value tiles after it: one region.
-  constexpr int kProjBytes = kProjectThreads * GT * 8 * (int)sizeof(float);
+  constexpr int kProjBytes = SKV_Q8 ? 0 : kProjectThreads * GT * 8 * (int)sizeof(float);
   constexpr int kTileBytes = 4 * RV * VP * (int)sizeof(uint16_t);           // per wave: value tile, [channel][row]
   __shared__ __attribute__((aligned(16))) unsigned char scratch_s[kProjBytes > kTileBytes ? kProjBytes : kTileBytes];
   __shared__ float red[4 * GT * (RV + 2)];
+#if !SKV_Q8
   __shared__ float px_s[GT * SKV_HEAD_DIM];
   __shared__ float py_s[GT * SKV_HEAD_DIM];
   float* ppart_s = reinterpret_cast<float*>(scratch_s);
+#endif
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -847,10 +873,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   const int kv = bkv % p.n_kv_heads;
   const int b = bkv / p.n_kv_heads;
   const int hq0 = kv * p.group + pass * GT;
+#if !SKV_Q8
   if (fresh) {
     fresh_rows_block<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s);
     return;
   }
+#endif
   int t0, t1;
   range_of_split((int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add, p.n_stream, split, &t0, &t1);
 
@@ -876,14 +904,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   const int64_t flat0 = ((int64_t)b * p.n_kv_heads + kv) * p.capacity;
   auto tile_base = [&](int row) -> int64_t { return flat0 + row; };
 #endif
-  const uint16_t* kc = reinterpret_cast<const uint16_t*>(p.k_cache);
-  const uint16_t* vc = reinterpret_cast<const uint16_t*>(p.v_cache);
 
-  // ---- tile loads: keys straight into operand layout, values as (8 rows x channel pair) units ------------
+  // ---- tile loads: key quarters as they lie in memory, values as (8 rows x one word) units ----------------
   const int n_tiles = (t1 - t0 + kMmaTileRows - 1) / kMmaTileRows;
   struct TileRegsM {
-    uint2 k[2][KSTEPS];
+    uint32_t k[2][KRAW];
     uint32_t v[VPL][8];
+#if SKV_Q8
+    uint32_t vm[NG][2][4];                       // (scale | zero << 16) of rows 16 kb + 4 g + i, per group
+#endif
   };
   auto issue_tile = [&](int tile, TileRegsM& tr) {
     const int row0 = t0 + tile * kMmaTileRows;
@@ -893,41 +922,107 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     for (int kb = 0; kb < 2; ++kb) {
       int r = 16 * kb + lm;
       r = r < last ? r : last;
-      const uint16_t* src = kc + (base + r) * RK + g * (RK / 4);
-      if constexpr (RK % 32 == 0) {
+      const uint32_t* src = p.k_cache + (base + r) * (RK / kElemsPerDword) + g * KRAW;
+      if constexpr (KRAW % 4 == 0) {
 #pragma unroll
-        for (int k2 = 0; k2 < KSTEPS / 2; ++k2) {
-          const uint4 w = *reinterpret_cast<const uint4*>(src + 8 * k2);
-          tr.k[kb][2 * k2] = make_uint2(w.x, w.y);
-          tr.k[kb][2 * k2 + 1] = make_uint2(w.z, w.w);
+        for (int k4 = 0; k4 < KRAW / 4; ++k4) {
+          const uint4 w = *reinterpret_cast<const uint4*>(src + 4 * k4);
+          tr.k[kb][4 * k4] = w.x; tr.k[kb][4 * k4 + 1] = w.y; tr.k[kb][4 * k4 + 2] = w.z; tr.k[kb][4 * k4 + 3] = w.w;
+        }
+      } else if constexpr (KRAW % 2 == 0) {
+#pragma unroll
+        for (int k2 = 0; k2 < KRAW / 2; ++k2) {
+          const uint2 w = *reinterpret_cast<const uint2*>(src + 2 * k2);
+          tr.k[kb][2 * k2] = w.x; tr.k[kb][2 * k2 + 1] = w.y;
         }
       } else {
 #pragma unroll
-        for (int ks = 0; ks < KSTEPS; ++ks) tr.k[kb][ks] = *reinterpret_cast<const uint2*>(src + 4 * ks);
+        for (int k1 = 0; k1 < KRAW; ++k1) tr.k[kb][k1] = src[k1];
       }
     }
 #pragma unroll
     for (int u = 0; u < VPL; ++u) {
       const int i = lane + 64 * u;
       if (VUNITS % 64 == 0 || i < VUNITS) {
-        const int cp = i % (RV / 2), kg = i / (RV / 2);
+        const int cw = i % VWORDS, kg = i / VWORDS;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           int r = 8 * kg + e;
           r = r < last ? r : last;
-          tr.v[u][e] = *reinterpret_cast<const uint32_t*>(vc + (base + r) * RV + 2 * cp);
+          tr.v[u][e] = p.v_cache[(base + r) * VWORDS + cw];
         }
       }
     }
+#if SKV_Q8
+#pragma unroll
+    for (int gq = 0; gq < NG; ++gq)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          int r = 16 * kb + 4 * g + i;
+          r = r < last ? r : last;
+          tr.vm[gq][kb][i] = p.v_meta[(base + r) * NG + gq];
+        }
+#endif
   };
-  // the value tile into this wave's LDS region, transposed: channel c, rows 8 kg .. 8 kg + 7 as one 16-byte run
+  // the A operand of contraction step ks of key block kb
+  auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint2 {
+#if SKV_QBITS == 8
+    const uint32_t w = tr.k[kb][ks];                             // 4 codes
+    return make_uint2(high_halves(byte_to_f32<0>(w), byte_to_f32<1>(w)), high_halves(byte_to_f32<2>(w), byte_to_f32<3>(w)));
+#elif SKV_QBITS == 4
+    const uint32_t w = tr.k[kb][ks >> 1] >> (16 * (ks & 1));     // bytes 0, 1: 4 codes, the even channel in the low half
+    const uint32_t ev = w & 0x0f0fu, od = (w >> 4) & 0x0f0fu;
+    return make_uint2(nibbles_to_bf16_pair((ev & 0xffu) | ((od & 0xffu) << 16)),
+                      nibbles_to_bf16_pair((ev >> 8) | ((od >> 8) << 16)));
+#else
+    return make_uint2(tr.k[kb][2 * ks], tr.k[kb][2 * ks + 1]);
+#endif
+  };
+  // the value tile into this wave's LDS region as bf16, transposed: channel c, rows 8 kg .. 8 kg + 7 as one 16-byte run
   uint16_t* vt = reinterpret_cast<uint16_t*>(scratch_s) + wave * (RV * VP);
   auto store_values = [&](const TileRegsM& tr) {
 #pragma unroll
     for (int u = 0; u < VPL; ++u) {
       const int i = lane + 64 * u;
       if (VUNITS % 64 == 0 || i < VUNITS) {
-        const int cp = i % (RV / 2), kg = i / (RV / 2);
+        const int cw = i % VWORDS, kg = i / VWORDS;
+#if SKV_QBITS == 8
+        // a word holds channels 4 cw .. 4 cw + 3 of one row
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          uint32_t o[4];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t w0 = tr.v[u][2 * e2], w1 = tr.v[u][2 * e2 + 1];
+            const float f0 = c == 0 ? byte_to_f32<0>(w0) : c == 1 ? byte_to_f32<1>(w0) : c == 2 ? byte_to_f32<2>(w0) : byte_to_f32<3>(w0);
+            const float f1 = c == 0 ? byte_to_f32<0>(w1) : c == 1 ? byte_to_f32<1>(w1) : c == 2 ? byte_to_f32<2>(w1) : byte_to_f32<3>(w1);
+            o[e2] = high_halves(f0, f1);
+          }
+          *reinterpret_cast<uint4*>(vt + (4 * cw + c) * VP + 8 * kg) = uint4{o[0], o[1], o[2], o[3]};
+        }
+#elif SKV_QBITS == 4
+        // a word holds channels 8 cw .. 8 cw + 7 of one row: even ones in the low halves of its bytes
+        uint32_t ev[8], od[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          ev[e] = tr.v[u][e] & 0x0f0f0f0fu;
+          od[e] = (tr.v[u][e] >> 4) & 0x0f0f0f0fu;
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          uint32_t o[4];
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const uint32_t a = (c & 1) ? od[2 * e2] : ev[2 * e2], bb = (c & 1) ? od[2 * e2 + 1] : ev[2 * e2 + 1];
+            const int sh = 8 * (c >> 1);
+            o[e2] = nibbles_to_bf16_pair(((a >> sh) & 0xffu) | (((bb >> sh) & 0xffu) << 16));
+          }
+          *reinterpret_cast<uint4*>(vt + (8 * cw + c) * VP + 8 * kg) = uint4{o[0], o[1], o[2], o[3]};
+        }
+#else
+        // a word holds channels 2 cw, 2 cw + 1 of one row
         uint4 even, odd;
         even.x = __builtin_amdgcn_perm(tr.v[u][1], tr.v[u][0], 0x05040100u);
         even.y = __builtin_amdgcn_perm(tr.v[u][3], tr.v[u][2], 0x05040100u);
@@ -937,8 +1032,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
         odd.y = __builtin_amdgcn_perm(tr.v[u][3], tr.v[u][2], 0x07060302u);
         odd.z = __builtin_amdgcn_perm(tr.v[u][5], tr.v[u][4], 0x07060302u);
         odd.w = __builtin_amdgcn_perm(tr.v[u][7], tr.v[u][6], 0x07060302u);
-        *reinterpret_cast<uint4*>(vt + (2 * cp) * VP + 8 * kg) = even;
-        *reinterpret_cast<uint4*>(vt + (2 * cp + 1) * VP + 8 * kg) = odd;
+        *reinterpret_cast<uint4*>(vt + (2 * cw) * VP + 8 * kg) = even;
+        *reinterpret_cast<uint4*>(vt + (2 * cw + 1) * VP + 8 * kg) = odd;
+#endif
       }
     }
   };
@@ -954,6 +1050,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #endif
   const float* qsrc;
   float qscale;
+#if !SKV_Q8
   if (p.q != nullptr) {
     ProjectPieces pp;
     project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
@@ -963,8 +1060,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
     qsrc = py_s;
     qscale = p.scale_log2e;
-  } else {
-    qsrc = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;          // already scaled
+  } else
+#endif
+  {
+    qsrc = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;          // already scaled (and, quantised, times the key scales)
     qscale = 1.f;
   }
   uint2 qhi[KSTEPS], qlo[KSTEPS];
@@ -978,8 +1077,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 
   // ---- stream this wave's tiles -------------------------------------------------------------------
   // Per lane: query column lm, rows 4 g + i of each 16-row block.  m_ref is the softmax reference of the
-  // column (log2 units; the same in the four lanes of a column), l this lane's share of the normaliser.
+  // column (log2 units; the same in the four lanes of a column), l this lane's share of the normaliser,
+  // zsum (quantised) its share of sum_j p_j zero_j per group.
   float m_ref = 0.f, l = 0.f;
+  float zsum[NG];
+#pragma unroll
+  for (int gq = 0; gq < NG; ++gq) zsum[gq] = 0.f;
   bool first = true;
   f32x4 oacc[VBLOCKS];
 #pragma unroll
@@ -995,11 +1098,25 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
       sc[kb] = f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
-        sc[kb] = mfma16(tr.k[kb][ks], qhi[ks], sc[kb]);
-        sc[kb] = mfma16(tr.k[kb][ks], qlo[ks], sc[kb]);
+        const uint2 a = key_operand(tr, kb, ks);
+        sc[kb] = mfma16(a, qhi[ks], sc[kb]);
+        sc[kb] = mfma16(a, qlo[ks], sc[kb]);
       }
     }
     store_values(tr);
+#if SKV_Q8
+    float vscale[NG][2][4], vzero[NG][2][4];
+#pragma unroll
+    for (int gq = 0; gq < NG; ++gq)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          vscale[gq][kb][i] = bf16_lo(tr.vm[gq][kb][i]);
+          vzero[gq][kb][i] = bf16_hi(tr.vm[gq][kb][i]);
+          if (SKV_QBITS == 4) vzero[gq][kb][i] = fmaf(-kNibbleOffset, vscale[gq][kb][i], vzero[gq][kb][i]);
+        }
+#endif
     __builtin_amdgcn_wave_barrier();
     if (tile + 4 * SKV_MMA_DEPTH < n_tiles) issue_tile(tile + 4 * SKV_MMA_DEPTH, tr);
     // rows past the end of the range do not count
@@ -1019,12 +1136,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
       m_ref = first ? mx : m_ref + mx;
       l *= f;
 #pragma unroll
+      for (int gq = 0; gq < NG; ++gq) zsum[gq] *= f;
+#pragma unroll
       for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] *= f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) sc[kb] -= mx;
     }
     first = false;
-    uint2 phi[2], plo[2];
+    // the weights as B operands: one pair per 64-channel group when rows carry their own value scales
+    uint2 phi[NG][2], plo[NG][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       float x[4];
@@ -1033,15 +1153,30 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
         x[i] = fast_exp2(sc[kb][i]);
         l += x[i];
       }
-      split4(x, phi[kb], plo[kb]);
+#if SKV_Q8
+#pragma unroll
+      for (int gq = 0; gq < NG; ++gq) {
+        float xs[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          xs[i] = x[i] * vscale[gq][kb][i];
+          zsum[gq] = fmaf(x[i], vzero[gq][kb][i], zsum[gq]);
+        }
+        split4(xs, phi[gq][kb], plo[gq][kb]);
+      }
+#else
+      split4(x, phi[0][kb], plo[0][kb]);
+#endif
     }
 #pragma unroll
     for (int cb = 0; cb < VBLOCKS; ++cb)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const uint2 a = *reinterpret_cast<const uint2*>(vt + (16 * cb + lm) * VP + 16 * kb + 4 * g);
-        oacc[cb] = mfma16(a, phi[kb], oacc[cb]);
-        oacc[cb] = mfma16(a, plo[kb], oacc[cb]);
+        constexpr int kNoGroup = 0;
+        const int gq = SKV_Q8 ? (16 * cb) / 64 : kNoGroup;
+        oacc[cb] = mfma16(a, phi[gq][kb], oacc[cb]);
+        oacc[cb] = mfma16(a, plo[gq][kb], oacc[cb]);
       }
     __builtin_amdgcn_wave_barrier();
   };
@@ -1054,15 +1189,27 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   for (int tile = wave; tile < n_tiles; tile += 4) process(tile, ta);
 #endif
 
-  // ---- the four lanes of a column hold shares of l; then merge the 4 waves through LDS, in wave order ----
+  // ---- the four lanes of a column hold shares of l (and of the zero sums); then merge the 4 waves through
+  //      LDS, in wave order ------------------------------------------------------------------------
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
+#if SKV_Q8
+#pragma unroll
+  for (int gq = 0; gq < NG; ++gq) {
+    zsum[gq] += __shfl_xor(zsum[gq], 16);
+    zsum[gq] += __shfl_xor(zsum[gq], 32);
+  }
+#endif
   if (lm < GT) {
     float* r = red + (wave * GT + lm) * (RV + 2);
 #pragma unroll
     for (int cb = 0; cb < VBLOCKS; ++cb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) r[16 * cb + 4 * g + i] = oacc[cb][i];
+      for (int i = 0; i < 4; ++i) {
+        float a = oacc[cb][i];
+        if (SKV_Q8) a += zsum[(16 * cb) / 64];                   // every channel of a group receives the group's zero sum
+        r[16 * cb + 4 * g + i] = a;
+      }
     if (g == 0) {
       r[RV] = first ? kNegBig : m_ref;                           // a wave without tiles: the neutral element
       r[RV + 1] = l;
@@ -1089,7 +1236,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     }
   }
 }
-#endif  // !SKV_Q8
+
 
 template <int RK, int RV>
 hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
@@ -1098,7 +1245,6 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const int fresh_rows = p.T_new > 0 ? (cols + p.n_stream - 1) / p.n_stream : 0;
   const dim3 grid((unsigned)p.n_stream, (unsigned)(cols + fresh_rows));
   const dim3 block(kDecodeThreads);
-#if !SKV_Q8
   if (p.engine == 1) {
     switch (heads) {
       case 1: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
@@ -1108,7 +1254,6 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
     }
     return hipGetLastError();
   }
-#endif
   switch (heads) {
     case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;

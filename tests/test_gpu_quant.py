@@ -10,7 +10,7 @@ from paper_2601_21686_amd import binding as B
 from paper_2601_21686_amd import synth
 from _helpers import TOL, vec_rel_err
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("decode_engine")]
 
 
 def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
