@@ -58,8 +58,9 @@ def parse_args():
     ap.add_argument("--ranks", default="", help="--mode prefill/append: override the workload's ranks, as r_k,r_v")
     ap.add_argument("--lengths", default="1.0,0.5,0.25,0.03125",
                     help="--mode varlen: per-sequence context lengths as fractions of the workload's context, cycled over the batch")
-    ap.add_argument("--engine", choices=("vector", "matrix"), default="vector",
-                    help="range kernel over bf16 rows: vector arithmetic (default) or matrix cores")
+    ap.add_argument("--engine", choices=("auto", "vector", "matrix"), default="auto",
+                    help="range kernel: chosen by shape (default: matrix cores for groups of 8 query heads, vector "
+                         "arithmetic otherwise), or forced")
     ap.add_argument("--mode", choices=("bench", "kernel", "copy", "read", "append", "prefill", "varlen"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
@@ -109,7 +110,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
-    B.skv_set_decode_engine(1 if args.engine == "matrix" else 0)
+    B.skv_set_decode_engine({"vector": 0, "matrix": 1, "auto": 2}[args.engine])
     if args.mode == "read":
         # what a kernel that only reads gets from this memory system, by working-set size: the yardstick beside
         # the published peak (sizes up to the 256 MiB last-level cache are partly served from it when re-read)
@@ -546,7 +547,7 @@ def main():
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant, "engine": args.engine,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" and not q8) else "decode_partial_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and HQ // HKV == 8)) else "decode_partial_kernel",
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(wl.name, args.cache), "bytes_per_launch": kern_bytes,

@@ -519,12 +519,14 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* paged, const void*
                                        int64_t n_prev, float scale, int32_t mode, void* stream);
 
 /*
- * Which kernel streams the bf16 cache in the decode calls (contiguous and paged; the quantised
- * formats have their own): 0 = vector arithmetic, 1 = matrix cores (the query heads of a group as
- * columns of 16x16x16 bf16 products, float32 operands split into two bf16 terms).  Both compute
- * App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in speed only.
- * Process-wide and not synchronised: set it before issuing work.  Returns the previous value;
- * any other argument changes nothing (a way to read the current value).
+ * Which kernel streams the cache in the decode calls: 0 = vector arithmetic, 1 = matrix cores (the
+ * query heads of a group as columns of 16x16x16 bf16 products, float32 operands split into two bf16
+ * terms, integer codes of the quantised formats taken as they are), 2 = chosen by shape (the default:
+ * the matrix kernel for groups of eight query heads per KV head, which it serves in ONE pass over the
+ * cache where the vector kernel needs two; the vector kernel otherwise -- the two are equally fast
+ * there).  Both compute App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in
+ * speed only.  Process-wide and not synchronised: set it before issuing work.  Returns the previous
+ * value; any other argument changes nothing (a way to read the current value).
  */
 int32_t skv_set_decode_engine(int32_t engine);
 

@@ -472,7 +472,8 @@ def skv_probe_stream_read(src: torch.Tensor, workgroups: int, sink: torch.Tensor
 
 
 def skv_set_decode_engine(engine: int) -> int:
-    """0 = vector arithmetic, 1 = matrix cores; returns the previous choice (any other value: no change)."""
+    """0 = vector arithmetic, 1 = matrix cores, 2 = by shape (default); returns the previous choice (any other
+    value: no change)."""
     return int(lib().skv_set_decode_engine(int(engine)))
 
 

@@ -376,6 +376,20 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
 // them at rows [cur_len, cur_len + T_new), and attends them with the group's projected queries.  The
 // result is one more partial (m, l, a~) for the combine kernel, so the streaming workgroups never
 // have to wait for these rows to land in the cache.
+// The projection of a pass's GT query rows.  The scratch of project_rows_finish grows with the row count; it
+// is sized for four rows, so eight go in two halves (the basis pieces are held in registers across both).
+template <int GT>
+__device__ __forceinline__ void project_query_rows(const ProjectPieces& pp, int r, const float* x_s, float* part_s,
+                                                   float* y_s) {
+  if constexpr (GT <= 4) {
+    project_rows_finish<GT>(pp, r, x_s, part_s, y_s);
+  } else {
+    static_assert(GT == 8, "one, two, four or eight query heads per pass");
+    project_rows_finish<4>(pp, r, x_s, part_s, y_s);
+    project_rows_finish<4>(pp, r, x_s + 4 * SKV_HEAD_DIM, part_s, y_s + 4 * r);
+  }
+}
+
 template <int RK, int RV, int GT>
 __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, int kv, int pass, int hq0,
                                                  float* x_s, float* part_s, float* y_s) {
@@ -393,7 +407,7 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
     const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
     for (int i = tid; i < GT * D; i += kDecodeThreads) x_s[i] = bf16_to_f32(qptr[i]);
     __syncthreads();
-    project_rows_finish<GT>(pp, RK, x_s, part_s, y_s);
+    project_query_rows<GT>(pp, RK, x_s, part_s, y_s);
     for (int i = tid; i < GT * RK; i += kDecodeThreads) qt_s[i] = y_s[i] * p.scale_log2e;
   }
   float m = kNegBig, l = 0.f;                    // thread g < GT: softmax state of head g
@@ -842,7 +856,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   static_assert(KRAW >= 1 && (RK / 4) % kElemsPerDword == 0, "rank not supported by this format");
 
   // The projection scratch is needed before the first tile only, the value tiles after it: one region.
-  constexpr int kProjBytes = SKV_Q8 ? 0 : kProjectThreads * GT * 8 * (int)sizeof(float);
+  constexpr int kProjBytes = SKV_Q8 ? 0 : kProjectThreads * (GT < 4 ? GT : 4) * 8 * (int)sizeof(float);
   constexpr int kTileBytes = 4 * RV * VP * (int)sizeof(uint16_t);           // per wave: value tile, [channel][row]
   __shared__ __attribute__((aligned(16))) unsigned char scratch_s[kProjBytes > kTileBytes ? kProjBytes : kTileBytes];
   __shared__ float red[4 * GT * (RV + 2)];
@@ -1057,7 +1071,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
     for (int i = tid; i < GT * SKV_HEAD_DIM; i += kDecodeThreads) px_s[i] = bf16_to_f32(qptr[i]);
     __syncthreads();
-    project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
+    project_query_rows<GT>(pp, RK, px_s, ppart_s, py_s);
     qsrc = py_s;
     qscale = p.scale_log2e;
   } else
@@ -1250,6 +1264,7 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
       case 1: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
       case 2: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
       case 4: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 4, kFmt>), grid, block, 0, stream, p); break;
+      case 8: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 8, kFmt>), grid, block, 0, stream, p); break;
       default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

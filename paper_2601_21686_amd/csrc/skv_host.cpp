@@ -26,8 +26,20 @@ bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; 
 // 8 or 16 ranges per (sequence, KV head) are the fastest, 32 and 64 are slower.
 constexpr int kTargetWorkgroups = 512;
 
-// Which range kernel streams bf16 rows: 0 = vector arithmetic, 1 = matrix cores (process-wide, see skv.h).
-int g_decode_engine = 0;
+// Which range kernel streams the cache: 0 = vector arithmetic, 1 = matrix cores, 2 = by shape (process-wide,
+// see skv.h).  By shape: the matrix kernel where it saves a pass over the cache (eight query heads per KV
+// head), the vector kernel elsewhere (the two are equally fast there).
+int g_decode_engine = 2;
+int decode_engine_for(int group) {
+  if (g_decode_engine == 2) return group == 8 ? 1 : 0;
+  return g_decode_engine;
+}
+
+// Query heads of a KV group one workgroup of the range kernel serves.  The vector kernel takes up to four (a
+// group of eight streams the cache twice); the matrix kernel has the columns for all eight in one pass.
+int decode_heads_per_pass(int group) {
+  return (decode_engine_for(group) == 1 && group == 8) ? 8 : heads_per_pass(group);
+}
 
 // need_bases = false: the folded-weights entry points, which never touch p_k / p_v.
 skv_status check_layer(const skv_layer* L, bool need_bases = true) {
@@ -93,7 +105,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->seq_lens = nullptr;
   p->len_add = 0;
   p->pages = PageMap{nullptr, 0, 0, 0};
-  p->engine = g_decode_engine;
+  p->engine = decode_engine_for(L->n_q_heads / L->n_kv_heads);
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
@@ -152,7 +164,7 @@ bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx
     return true;
   }
   const int64_t quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
-  const int64_t columns = (int64_t)batch * n_kv_heads * (group / heads_per_pass(group));
+  const int64_t columns = (int64_t)batch * n_kv_heads * (group / decode_heads_per_pass(group));
   int64_t s = (kTargetWorkgroups + columns - 1) / (columns > 0 ? columns : 1);
   if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
   if (s > quanta) s = quanta;                 // never a range without rows
@@ -198,7 +210,7 @@ skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgrou
 
 int32_t skv_set_decode_engine(int32_t engine) {
   const int32_t before = g_decode_engine;
-  if (engine == 0 || engine == 1) g_decode_engine = engine;
+  if (engine >= 0 && engine <= 2) g_decode_engine = engine;
   return before;
 }
 
@@ -350,7 +362,7 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
   if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
   decode_partial_launcher launch = q8 ? partial_q_launcher_for(bits, L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }
@@ -381,7 +393,7 @@ skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int
   if (pages) p.pages = *pages;
   decode_partial_launcher launch = pages ? paged_partial_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }
@@ -480,7 +492,7 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const int gq = L->n_q_heads / L->n_kv_heads;
   // (the fused launch adds up to one grid row per column: stay inside the grid's y limit)
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
   if (T > 0 && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
     // The usual decode step, two launches: context ranges over the rows already cached, plus one
     // workgroup per (sequence, KV head) that projects, stores and attends the new rows; then the merge.
@@ -916,7 +928,7 @@ skv_status step_lens(const skv_layer* L, const void* k_new, const void* v_new, i
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   const int gq = L->n_q_heads / L->n_kv_heads;
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / heads_per_pass(gq)) <= 65535;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
   if (T <= kFusedStepMaxTokens && max_cur_len > 0 && grid_ok) {
     int32_t s_old = 0;
     if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;

@@ -360,10 +360,12 @@ def test_paged_layer_argument_checks():
 def test_decode_engine_switch():
     lib = B.lib()
     before = lib.skv_set_decode_engine(1)
-    assert lib.skv_set_decode_engine(-1) == 1          # anything but 0 or 1 changes nothing
+    assert before == 2                                  # the default: chosen by shape
+    assert lib.skv_set_decode_engine(-1) == 1          # anything but 0, 1, 2 changes nothing
     assert lib.skv_set_decode_engine(7) == 1
     assert lib.skv_set_decode_engine(0) == 1
     assert lib.skv_set_decode_engine(before) == 0
+    assert lib.skv_set_decode_engine(-1) == 2
 
 
 def test_read_probe_argument_checks():
