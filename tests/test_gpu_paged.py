@@ -269,3 +269,38 @@ def test_table_entries_outside_the_pool_are_clamped():
     want = O.paged_decode_attention(P.ora, cache, _f64(q), [200, 200])
     assert vec_rel_err(out.cpu().numpy(), want) <= TOL
     assert vec_rel_err(out.cpu().numpy(), O.paged_decode_attention(P.ora, P.cache, _f64(q), [200, 200])) > TOL
+
+
+def test_paged_decode_steps_in_a_hip_graph_replay_identically():
+    # a serving loop replays captured steps with the lengths and the block table on the device: capture three
+    # steps over a shuffled table, replay with eager work in between, compare every replay with the eager run
+    lens, steps = [900, 63, 500, 1], 3
+    P = PagedPair(("pg-graph",), 4, 8, 2, 64, 64, 64, 16)
+    P.fill(14, lens)
+    kn, vn = P.raw_kv(15, steps)
+    qs = [P.queries(20 + s) for s in range(steps)]
+    ws = P.gpu.workspace()
+    lens_dev = [_lens_t([n + s for n in lens]) for s in range(steps)]
+    eager = torch.empty((steps, 4, 8, 128), dtype=torch.float32, device="cuda")
+    for s in range(steps):
+        B.skv_paged_decode_step(P.gpu, kn[:, s:s + 1], vn[:, s:s + 1], lens_dev[s], max(lens) + s, qs[s], eager[s], 0.0, ws)
+    torch.cuda.synchronize()
+    pool_after = P.gpu.k_pool.clone()
+    outs = torch.zeros_like(eager)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            for s in range(steps):
+                B.skv_paged_decode_step(P.gpu, kn[:, s:s + 1], vn[:, s:s + 1], lens_dev[s], max(lens) + s, qs[s], outs[s],
+                                        0.0, ws)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        outs.fill_(float("nan"))
+        ws.random_(0, 255)                                # eager work between replays: scribble over the workspace
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, eager), rep
+        assert torch.equal(P.gpu.k_pool.view(torch.int16), pool_after.view(torch.int16)), rep
