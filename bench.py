@@ -481,7 +481,8 @@ def main():
     li_big = sorted(range(wl.n_layers), key=lambda i: ranks_k[i] + ranks_v[i])[wl.n_layers // 2]
     Lr = layers[li_big]
     n_roof = wl.n_ctx
-    splits = args.splits if args.splits > 0 else B.skv_decode_default_splits(Lr, n_roof)
+    default_splits = {0: B.skv_decode_default_splits, 8: B.skv_q8_decode_default_splits, 4: B.skv_q4_decode_default_splits}[qbits]
+    splits = args.splits if args.splits > 0 else default_splits(Lr, n_roof)
     if q8 or folded:
         # these variants keep the projected queries in the workspace (prepared by a small launch)
         (QF[qbits][2] if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
@@ -547,7 +548,7 @@ def main():
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant, "engine": args.engine,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and HQ // HKV == 8)) else "decode_partial_kernel",
+        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8))) else "decode_partial_kernel",
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(wl.name, args.cache), "bytes_per_launch": kern_bytes,

@@ -328,6 +328,9 @@ skv_status skv_q8_decode_partial(const skv_q8_layer* layer, int64_t n_ctx, int32
                                  void* workspace, size_t workspace_bytes, void* stream);
 /* Bytes the quantised cache of one layer holds for n tokens (codes + value metadata). */
 size_t skv_q8_cache_bytes(const skv_q8_layer* layer, int64_t n_tokens);
+/* The number of context ranges the calls above choose for n_ctx tokens (as skv_decode_default_splits;
+ * the quantised formats may plan more ranges than the bf16 cache).  0 for an invalid layer or n_ctx. */
+int32_t skv_q8_decode_default_splits(const skv_q8_layer* layer, int64_t n_ctx);
 
 /*
  * The same with 4-bit codes (the paper lowers the bit width further, Sec. 4.3):
@@ -355,6 +358,7 @@ skv_status skv_q4_decode_project_query(const skv_q4_layer* layer, const void* q,
 skv_status skv_q4_decode_partial(const skv_q4_layer* layer, int64_t n_ctx, int32_t n_splits,
                                  void* workspace, size_t workspace_bytes, void* stream);
 size_t skv_q4_cache_bytes(const skv_q4_layer* layer, int64_t n_tokens);
+int32_t skv_q4_decode_default_splits(const skv_q4_layer* layer, int64_t n_ctx);
 
 /*
  * Sequential budgeted rank selection (Sec. 3.5 Eqs. 15-17; App. B Alg. 2).

@@ -29,9 +29,9 @@ EXPORTS = (
     "skv_decode_partial", "skv_decode_combine", "skv_decode_partial_q",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
-    "skv_q8_decode_project_query", "skv_q8_decode_partial",
+    "skv_q8_decode_project_query", "skv_q8_decode_partial", "skv_q8_decode_default_splits",
     "skv_q4_project_append", "skv_q4_decode_attention", "skv_q4_decode_step", "skv_q4_cache_bytes",
-    "skv_q4_decode_project_query", "skv_q4_decode_partial",
+    "skv_q4_decode_project_query", "skv_q4_decode_partial", "skv_q4_decode_default_splits",
     "skv_append_projected", "skv_decode_attention_folded", "skv_decode_step_folded",
     "skv_padded_rank", "skv_pad_basis", "skv_orthonormalize",
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
@@ -120,6 +120,9 @@ def lib() -> C.CDLL:
     L.skv_q8_decode_partial.restype = C.c_int
     L.skv_q8_cache_bytes.argtypes = [QP, i64]
     L.skv_q8_cache_bytes.restype = sz
+    for w in ("q8", "q4"):
+        getattr(L, f"skv_{w}_decode_default_splits").argtypes = [QP, i64]
+        getattr(L, f"skv_{w}_decode_default_splits").restype = i32
     for w in ("q4",):
         getattr(L, f"skv_{w}_project_append").argtypes = [QP, vp, vp, i64, i64, i64, i32, i64, vp]
         getattr(L, f"skv_{w}_decode_attention").argtypes = [QP, vp, vp, i64, C.c_float, vp, sz, vp]
@@ -731,3 +734,10 @@ skv_q8_decode_project_query, skv_q4_decode_project_query = (_bind(_q_decode_proj
                                                             _bind(_q_decode_project_query, 4))
 skv_q8_decode_partial, skv_q4_decode_partial = _bind(_q_decode_partial, 8), _bind(_q_decode_partial, 4)
 skv_q8_cache_bytes, skv_q4_cache_bytes = _bind(_q_cache_bytes, 8), _bind(_q_cache_bytes, 4)
+
+
+def _q_default_splits(bits, layer: QuantLayer, n_ctx: int) -> int:
+    return int(_qfn(layer, "decode_default_splits", bits)(_ref(layer), int(n_ctx)))
+
+
+skv_q8_decode_default_splits, skv_q4_decode_default_splits = _bind(_q_default_splits, 8), _bind(_q_default_splits, 4)

@@ -823,6 +823,21 @@ __device__ __forceinline__ void split4(const float (&x)[4], uint2& hi, uint2& lo
   lo.x = pack_bf16_pair(x[0] - bf16_lo(hi.x), x[1] - bf16_hi(hi.x));
   lo.y = pack_bf16_pair(x[2] - bf16_lo(hi.y), x[3] - bf16_hi(hi.y));
 }
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+// the 32-deep form: lane (m, g) supplies A[m][8 g .. 8 g + 7] and B[8 g .. 8 g + 7][n]; per multiply-add it
+// occupies the matrix pipe about a third as long as the 16-deep one (measured), which matters where the
+// kernel is bound by instruction issue (the quantised caches)
+__device__ __forceinline__ f32x4 mfma16w(uint4 a, uint4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ void split8w(const float (&x)[8], uint4& hi, uint4& lo) {
+  uint2 h0, l0, h1, l1;
+  const float a[4] = {x[0], x[1], x[2], x[3]}, b[4] = {x[4], x[5], x[6], x[7]};
+  split4(a, h0, l0);
+  split4(b, h1, l1);
+  hi = uint4{h0.x, h0.y, h1.x, h1.y};
+  lo = uint4{l0.x, l0.y, l1.x, l1.y};
+}
 // the high halves of two float32 numbers as a bf16 pair (exact when both are bf16 numbers already)
 __device__ __forceinline__ uint32_t high_halves(float lo, float hi) {
   return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
@@ -844,7 +859,13 @@ constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel
 template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
-  constexpr int KSTEPS = RK / 16;                // contraction steps of the score product
+  // Quantised builds (ranks are multiples of 32 there) use the 32-deep matrix instruction: the contraction index
+  // of the first product is then enumerated as channel = g r_K / 4 + 8 step + i, and the 32 rows of a tile are
+  // ONE contraction of the second product, position 8 g + 4 b + i standing for row 16 b + 4 g + i (the rows whose
+  // scores lane (n, g) holds after the first product).
+  constexpr bool WIDE = SKV_Q8 != 0;
+  static_assert(!WIDE || RK % 32 == 0, "the 32-deep form needs ranks that are multiples of 32");
+  constexpr int KSTEPS = WIDE ? RK / 32 : RK / 16;   // contraction steps of the score product
   constexpr int VBLOCKS = RV / 16;               // 16-channel blocks of the mix
   constexpr int NG = (RV + 63) / 64;             // 64-channel groups of a value row (quantisation groups)
   // raw words per lane: a quarter of a key row per 16-row block; value tiles as units of 8 rows by one word
@@ -981,19 +1002,26 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #endif
   };
   // the A operand of contraction step ks of key block kb
-  auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint2 {
 #if SKV_QBITS == 8
-    const uint32_t w = tr.k[kb][ks];                             // 4 codes
-    return make_uint2(high_halves(byte_to_f32<0>(w), byte_to_f32<1>(w)), high_halves(byte_to_f32<2>(w), byte_to_f32<3>(w)));
-#elif SKV_QBITS == 4
-    const uint32_t w = tr.k[kb][ks >> 1] >> (16 * (ks & 1));     // bytes 0, 1: 4 codes, the even channel in the low half
-    const uint32_t ev = w & 0x0f0fu, od = (w >> 4) & 0x0f0fu;
-    return make_uint2(nibbles_to_bf16_pair((ev & 0xffu) | ((od & 0xffu) << 16)),
-                      nibbles_to_bf16_pair((ev >> 8) | ((od >> 8) << 16)));
-#else
-    return make_uint2(tr.k[kb][2 * ks], tr.k[kb][2 * ks + 1]);
-#endif
+  auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint4 {
+    const uint32_t w0 = tr.k[kb][2 * ks], w1 = tr.k[kb][2 * ks + 1];   // 8 codes
+    return uint4{high_halves(byte_to_f32<0>(w0), byte_to_f32<1>(w0)), high_halves(byte_to_f32<2>(w0), byte_to_f32<3>(w0)),
+                 high_halves(byte_to_f32<0>(w1), byte_to_f32<1>(w1)), high_halves(byte_to_f32<2>(w1), byte_to_f32<3>(w1))};
   };
+#elif SKV_QBITS == 4
+  auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint4 {
+    const uint32_t w = tr.k[kb][ks];                             // 8 codes: the even channel in the low half of a byte
+    const uint32_t ev = w & 0x0f0f0f0fu, od = (w >> 4) & 0x0f0f0f0fu;
+    return uint4{nibbles_to_bf16_pair((ev & 0xffu) | ((od & 0xffu) << 16)),
+                 nibbles_to_bf16_pair(((ev >> 8) & 0xffu) | (((od >> 8) & 0xffu) << 16)),
+                 nibbles_to_bf16_pair(((ev >> 16) & 0xffu) | (((od >> 16) & 0xffu) << 16)),
+                 nibbles_to_bf16_pair((ev >> 24) | ((od >> 24) << 16))};
+  };
+#else
+  auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint2 {
+    return make_uint2(tr.k[kb][2 * ks], tr.k[kb][2 * ks + 1]);
+  };
+#endif
   // the value tile into this wave's LDS region as bf16, transposed: channel c, rows 8 kg .. 8 kg + 7 as one 16-byte run
   uint16_t* vt = reinterpret_cast<uint16_t*>(scratch_s) + wave * (RV * VP);
   auto store_values = [&](const TileRegsM& tr) {
@@ -1014,7 +1042,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
             const float f1 = c == 0 ? byte_to_f32<0>(w1) : c == 1 ? byte_to_f32<1>(w1) : c == 2 ? byte_to_f32<2>(w1) : byte_to_f32<3>(w1);
             o[e2] = high_halves(f0, f1);
           }
-          *reinterpret_cast<uint4*>(vt + (4 * cw + c) * VP + 8 * kg) = uint4{o[0], o[1], o[2], o[3]};
+          uint16_t* dst = vt + (4 * cw + c) * VP + 16 * (kg & 1) + 4 * (kg >> 1);   // rows 8 kg + e at 16 (kg % 2) + 8 (e / 4) + 4 (kg / 2) + e % 4
+          *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
+          *reinterpret_cast<uint2*>(dst + 8) = make_uint2(o[2], o[3]);
         }
 #elif SKV_QBITS == 4
         // a word holds channels 8 cw .. 8 cw + 7 of one row: even ones in the low halves of its bytes
@@ -1033,7 +1063,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
             const int sh = 8 * (c >> 1);
             o[e2] = nibbles_to_bf16_pair(((a >> sh) & 0xffu) | (((bb >> sh) & 0xffu) << 16));
           }
-          *reinterpret_cast<uint4*>(vt + (8 * cw + c) * VP + 8 * kg) = uint4{o[0], o[1], o[2], o[3]};
+          uint16_t* dst = vt + (8 * cw + c) * VP + 16 * (kg & 1) + 4 * (kg >> 1);
+          *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
+          *reinterpret_cast<uint2*>(dst + 8) = make_uint2(o[2], o[3]);
         }
 #else
         // a word holds channels 2 cw, 2 cw + 1 of one row
@@ -1080,6 +1112,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     qsrc = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;          // already scaled (and, quantised, times the key scales)
     qscale = 1.f;
   }
+#if SKV_Q8
+  uint4 qhi[KSTEPS], qlo[KSTEPS];
+#pragma unroll
+  for (int ks = 0; ks < KSTEPS; ++ks) {
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = lm < GT ? qsrc[lm * RK + g * (RK / 4) + 8 * ks + i] * qscale : 0.f;
+    split8w(x, qhi[ks], qlo[ks]);
+  }
+#else
   uint2 qhi[KSTEPS], qlo[KSTEPS];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) {
@@ -1088,6 +1130,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     for (int i = 0; i < 4; ++i) x[i] = lm < GT ? qsrc[lm * RK + g * (RK / 4) + 4 * ks + i] * qscale : 0.f;
     split4(x, qhi[ks], qlo[ks]);
   }
+#endif
 
   // ---- stream this wave's tiles -------------------------------------------------------------------
   // Per lane: query column lm, rows 4 g + i of each 16-row block.  m_ref is the softmax reference of the
@@ -1112,9 +1155,15 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
       sc[kb] = f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
+#if SKV_Q8
+        const uint4 a = key_operand(tr, kb, ks);
+        sc[kb] = mfma16w(a, qhi[ks], sc[kb]);
+        sc[kb] = mfma16w(a, qlo[ks], sc[kb]);
+#else
         const uint2 a = key_operand(tr, kb, ks);
         sc[kb] = mfma16(a, qhi[ks], sc[kb]);
         sc[kb] = mfma16(a, qlo[ks], sc[kb]);
+#endif
       }
     }
     store_values(tr);
@@ -1158,7 +1207,37 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     }
     first = false;
     // the weights as B operands: one pair per 64-channel group when rows carry their own value scales
-    uint2 phi[NG][2], plo[NG][2];
+#if SKV_Q8
+    float x[2][4];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[kb][i] = fast_exp2(sc[kb][i]);
+        l += x[kb][i];
+      }
+    uint4 phi[NG], plo[NG];
+#pragma unroll
+    for (int gq = 0; gq < NG; ++gq) {
+      float xs[8];
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          xs[4 * kb + i] = x[kb][i] * vscale[gq][kb][i];
+          zsum[gq] = fmaf(x[kb][i], vzero[gq][kb][i], zsum[gq]);
+        }
+      split8w(xs, phi[gq], plo[gq]);
+    }
+#pragma unroll
+    for (int cb = 0; cb < VBLOCKS; ++cb) {
+      const uint4 a = *reinterpret_cast<const uint4*>(vt + (16 * cb + lm) * VP + 8 * g);
+      const int gq = (16 * cb) / 64;
+      oacc[cb] = mfma16w(a, phi[gq], oacc[cb]);
+      oacc[cb] = mfma16w(a, plo[gq], oacc[cb]);
+    }
+#else
+    uint2 phi[2], plo[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       float x[4];
@@ -1167,31 +1246,17 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
         x[i] = fast_exp2(sc[kb][i]);
         l += x[i];
       }
-#if SKV_Q8
-#pragma unroll
-      for (int gq = 0; gq < NG; ++gq) {
-        float xs[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          xs[i] = x[i] * vscale[gq][kb][i];
-          zsum[gq] = fmaf(x[i], vzero[gq][kb][i], zsum[gq]);
-        }
-        split4(xs, phi[gq][kb], plo[gq][kb]);
-      }
-#else
-      split4(x, phi[0][kb], plo[0][kb]);
-#endif
+      split4(x, phi[kb], plo[kb]);
     }
 #pragma unroll
     for (int cb = 0; cb < VBLOCKS; ++cb)
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const uint2 a = *reinterpret_cast<const uint2*>(vt + (16 * cb + lm) * VP + 16 * kb + 4 * g);
-        constexpr int kNoGroup = 0;
-        const int gq = SKV_Q8 ? (16 * cb) / 64 : kNoGroup;
-        oacc[cb] = mfma16(a, phi[gq][kb], oacc[cb]);
-        oacc[cb] = mfma16(a, plo[gq][kb], oacc[cb]);
+        oacc[cb] = mfma16(a, phi[kb], oacc[cb]);
+        oacc[cb] = mfma16(a, plo[kb], oacc[cb]);
       }
+#endif
     __builtin_amdgcn_wave_barrier();
   };
 #if SKV_MMA_DEPTH == 2

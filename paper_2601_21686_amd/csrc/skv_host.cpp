@@ -30,8 +30,10 @@ constexpr int kTargetWorkgroups = 512;
 // see skv.h).  By shape: the matrix kernel where it saves a pass over the cache (eight query heads per KV
 // head), the vector kernel elsewhere (the two are equally fast there).
 int g_decode_engine = 2;
-int decode_engine_for(int group) {
-  if (g_decode_engine == 2) return group == 8 ? 1 : 0;
+// bits: 0 for bf16 rows, else the width of the quantised codes (there the matrix kernel needs fewer vector
+// instructions per row, which is what bounds both kernels: measured 31.4 against 35.2 us at 8 bits)
+int decode_engine_for(int group, int bits = 0) {
+  if (g_decode_engine == 2) return (group == 8 || bits != 0) ? 1 : 0;
   return g_decode_engine;
 }
 
@@ -156,7 +158,7 @@ skv_status check_decode_common(const skv_layer* L, int32_t n_splits, const void*
 }  // namespace
 
 bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx, int32_t want,
-                 int32_t* n_splits) {
+                 int32_t* n_splits, int bits) {
   if (n_ctx < 1 || n_ctx > std::numeric_limits<int32_t>::max() - kRangeQuantum) return false;
   if (want > 0) {
     if (want > SKV_MAX_SPLITS) return false;
@@ -165,7 +167,10 @@ bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx
   }
   const int64_t quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
   const int64_t columns = (int64_t)batch * n_kv_heads * (group / decode_heads_per_pass(group));
-  int64_t s = (kTargetWorkgroups + columns - 1) / (columns > 0 ? columns : 1);
+  // the matrix kernel over a quantised cache is bound by instruction issue, which more resident waves help
+  // (measured best at 24..32 ranges for b4/32K where the bf16 kernels want 8..16)
+  const int64_t target = (bits != 0 && decode_engine_for(group, bits) == 1) ? 3 * kTargetWorkgroups / 2 : kTargetWorkgroups;
+  int64_t s = (target + columns - 1) / (columns > 0 ? columns : 1);
   if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
   if (s > quanta) s = quanta;                 // never a range without rows
   if (s < 1) s = 1;
@@ -263,12 +268,12 @@ skv_status check_query_stage(const skv_layer* L, const void* q, float scale, con
 }
 
 skv_status check_partial_stage(const skv_layer* L, int64_t n_ctx, int32_t n_splits,
-                               const void* workspace, size_t workspace_bytes, int32_t* s_out) {
+                               const void* workspace, size_t workspace_bytes, int32_t* s_out, int bits = 0) {
   skv_status st = check_layer(L);
   if (st != SKV_OK) return st;
   if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
   if (n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, n_splits, s_out))
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, n_splits, s_out, bits))
     return SKV_ERR_SHAPE;
   return check_decode_common(L, *s_out, workspace, workspace_bytes);
 }
@@ -359,7 +364,10 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
   DecodeParams p;
   fill_decode_params(L, &p, s, workspace);
   p.n_ctx = (int32_t)n_ctx;
-  if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
+  if (q8) {
+    p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
+    p.engine = decode_engine_for(p.group, bits);
+  }
   decode_partial_launcher launch = q8 ? partial_q_launcher_for(bits, L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
@@ -716,12 +724,21 @@ skv_status q_decode_project_query(const skv_q8_layer* Q, int bits, const void* q
   return SKV_OK;
 }
 
+int32_t q_default_splits(const skv_q8_layer* Q, int bits, int64_t n_ctx) {
+  if (check_q_layer(Q, bits) != SKV_OK) return 0;
+  const skv_layer* L = &Q->base;
+  if (n_ctx < 1 || n_ctx > L->capacity) return 0;
+  int32_t s = 0;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, bits)) return 0;
+  return s;
+}
+
 skv_status q_decode_partial(const skv_q8_layer* Q, int bits, int64_t n_ctx, int32_t n_splits, void* workspace,
                             size_t workspace_bytes, void* stream) {
   skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   int32_t s = 0;
-  st = check_partial_stage(&Q->base, n_ctx, n_splits, workspace, workspace_bytes, &s);
+  st = check_partial_stage(&Q->base, n_ctx, n_splits, workspace, workspace_bytes, &s, bits);
   if (st != SKV_OK) return st;
   return run_partial(&Q->base, n_ctx, s, workspace, stream, Q, bits);
 }
@@ -741,7 +758,7 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   if (st != SKV_OK) return st;
   const int64_t n_ctx = cur_len + T;
   int32_t s = 0;
-  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s, bits);
   if (st != SKV_OK) return st;
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
@@ -782,6 +799,9 @@ skv_status skv_q4_decode_attention(const skv_q4_layer* Q, const void* q, void* o
                                    void* workspace, size_t workspace_bytes, void* stream) {
   return q_decode_step(Q, 4, nullptr, nullptr, 0, 0, 0, 0, n_ctx, q, out, scale, workspace, workspace_bytes, stream);
 }
+
+int32_t skv_q8_decode_default_splits(const skv_q8_layer* Q, int64_t n_ctx) { return q_default_splits(Q, 8, n_ctx); }
+int32_t skv_q4_decode_default_splits(const skv_q4_layer* Q, int64_t n_ctx) { return q_default_splits(Q, 4, n_ctx); }
 
 skv_status skv_q8_decode_project_query(const skv_q8_layer* Q, const void* q, float scale, void* workspace,
                                        size_t workspace_bytes, void* stream) {

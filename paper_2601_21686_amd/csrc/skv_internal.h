@@ -149,7 +149,7 @@ constexpr int kDecodeThreads = 256;
 // Number of context ranges for n_ctx tokens.  want <= 0: heuristic.  Returns false if `want`
 // is out of range.
 bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx,
-                 int32_t want, int32_t* n_splits);
+                 int32_t want, int32_t* n_splits, int bits = 0);
 
 // Rows [t0, t1) of range `split` out of n_splits over n_ctx rows: whole quanta, dealt as evenly
 // as possible (the first `rem` ranges get one more); empty when t0 >= t1.
