@@ -40,10 +40,10 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch step by step instead of replaying a captured graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches of the decode range kernel for the roofline leg")
-    ap.add_argument("--cache", choices=("bf16", "q8", "q4", "paged"), default="bf16",
+    ap.add_argument("--cache", choices=("bf16", "q8", "q4", "paged", "paged_q8", "paged_q4"), default="bf16",
                     help="bf16: the benchmarked configuration; q8 / q4: the 8- or 4-bit quantised compressed cache "
                          "(keys with static per-head group ranges, values with per-token group ranges); "
-                         "paged: bf16 rows in a pool of pages behind a shuffled block table")
+                         "paged: bf16 rows in a pool of pages behind a shuffled block table; paged_q8 / paged_q4: integer codes in such pages")
     ap.add_argument("--page-tokens", type=int, default=64, help="--cache paged: rows per page (a power of two >= 64)")
     ap.add_argument("--variant", choices=("explicit", "folded"), default="explicit",
                     help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
@@ -339,8 +339,8 @@ def main():
     cap = wl.n_ctx + K + 8
     assert n0 >= 1
 
-    qbits = {"bf16": 0, "q8": 8, "q4": 4, "paged": 0}[args.cache]
-    paged = args.cache == "paged"
+    qbits = {"bf16": 0, "q8": 8, "q4": 4, "paged": 0, "paged_q8": 8, "paged_q4": 4}[args.cache]
+    paged = args.cache.startswith("paged")
     q8 = qbits != 0                                  # any quantised cache
     QF = {8: (B.skv_q8_project_append, B.skv_q8_decode_step, B.skv_q8_decode_project_query, B.skv_q8_decode_partial),
           4: (B.skv_q4_project_append, B.skv_q4_decode_step, B.skv_q4_decode_project_query, B.skv_q4_decode_partial)}
@@ -385,8 +385,7 @@ def main():
             lo, hi = lo - 0.5 * span, hi + 0.5 * span
             ksc, kzr = ((hi - lo) / float(2 ** qbits - 1)).contiguous(), lo.contiguous()
             k_ranges.append((ksc, kzr))
-            layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap, qbits))
-        elif paged:
+        if paged:
             # a pool with a few spare pages; the table is a seeded shuffle, so consecutive logical pages of a
             # sequence are scattered over the pool
             pt = args.page_tokens
@@ -394,7 +393,10 @@ def main():
             n_pages = Bt * per_seq + 16
             order = np.random.default_rng(synth.stable_seed(wl.name, li, "pages")).permutation(n_pages)
             table = torch.from_numpy(order[:Bt * per_seq].reshape(Bt, per_seq).astype(np.int32)).to(dev)
-            layers.append(B.PagedLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), pt, n_pages, table))
+            layers.append(B.PagedLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), pt, n_pages, table, bits=qbits,
+                                       k_scale=ksc if q8 else None, k_zero=kzr if q8 else None))
+        elif q8:
+            layers.append(B.QuantLayer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), ksc, kzr, cap, qbits))
         else:
             layers.append(B.Layer(Bt, HQ, HKV, pk.to(dev), pv.to(dev), cap))
 
@@ -482,14 +484,21 @@ def main():
     Lr = layers[li_big]
     n_roof = wl.n_ctx
     default_splits = {0: B.skv_decode_default_splits, 8: B.skv_q8_decode_default_splits, 4: B.skv_q4_decode_default_splits}[qbits]
-    splits = args.splits if args.splits > 0 else default_splits(Lr, n_roof)
-    if q8 or folded:
+    if paged and q8:
+        # no separate stage calls over quantised pages: the whole attention call is timed
+        splits = B.skv_paged_decode_default_splits(Lr, n_roof)
+        tmp_out = torch.empty((Bt, HQ, d), dtype=torch.float32, device=dev)
+        partial_fn = lambda L_, n_, s_, ws_: B.skv_paged_decode_attention(L_, qs[0, li_big], tmp_out, None, n_, 0.0, ws_)
+    elif q8 or folded:
+        splits = args.splits if args.splits > 0 else default_splits(Lr, n_roof)
         # these variants keep the projected queries in the workspace (prepared by a small launch)
         (QF[qbits][2] if q8 else B.skv_decode_project_query)(Lr, qs[0, li_big], 0.0, ws)
         partial_fn = QF[qbits][3] if q8 else B.skv_decode_partial
     elif paged:
+        splits = args.splits if args.splits > 0 else B.skv_paged_decode_default_splits(Lr, n_roof)
         partial_fn = lambda L_, n_, s_, ws_: B.skv_paged_decode_partial_q(L_, qs[0, li_big], None, n_, s_, 0.0, ws_)
     else:
+        splits = args.splits if args.splits > 0 else default_splits(Lr, n_roof)
         # the launch the decode step makes: every workgroup projects its head group's queries itself
         partial_fn = lambda L_, n_, s_, ws_: B.skv_decode_partial_q(L_, qs[0, li_big], n_, s_, 0.0, ws_)
     for _ in range(10):
@@ -544,11 +553,13 @@ def main():
                    "n_ctx_first_step": wl.n_ctx, "n_layers": wl.n_layers,
                    "r_k": ranks_k if wl.n_layers > 1 else ranks_k[0],
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
-                   "cache": f"{qbits}-bit codes, group 64" if q8 else (f"bf16, pages of {args.page_tokens} rows, shuffled block table" if paged else "bf16"), "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
+                   "cache": (f"{qbits}-bit codes, group 64" if q8 else "bf16") + (f", pages of {args.page_tokens} rows, shuffled block table" if paged else ""), "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
                    "variant": args.variant, "engine": args.engine,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
-        "roofline": {"bound": "hbm", "kernel": "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8))) else "decode_partial_kernel",
+        "roofline": {"bound": "hbm", "kernel": ("projection + decode_partial_mma_kernel + merge (the whole attention call: no stage calls over quantised pages)" if (paged and q8)
+                                else "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8)))
+                                else "decode_partial_kernel"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": read_traffic(wl.name, args.cache), "bytes_per_launch": kern_bytes,

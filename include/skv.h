@@ -489,8 +489,15 @@ skv_status skv_orthonormalize(const void* a, int32_t n_bases, int32_t r, int32_t
  * skv_paged_decode_step      as skv_decode_step_varlen
  * skv_paged_prefill_attention as skv_prefill_attention (one n_prev for the whole batch);
  *                            n_prev + T at most 1048576 rows (CAPACITY beyond)
- * skv_paged_pool_bytes       bytes of both pools: n_pages * n_kv_heads * page_tokens * (r_k + r_v) * 2
- *                            (0 for an invalid description)
+ * skv_paged_pool_bytes       bytes of the pools: n_pages * n_kv_heads * page_tokens * (r_k + r_v) * 2 for bf16
+ *                            rows, codes plus value ranges for the quantised formats (0 for an invalid
+ *                            description)
+ * Quantised pages (code_bits = 8 or 4): the pools hold integer codes exactly as skv_q8_layer /
+ * skv_q4_layer describe them (k_cache / v_cache: codes [n_pages][n_kv_heads][page_tokens][r bits / 8
+ * bytes]; v_meta one word per row and group, laid out like the code pools; k_scale / k_zero static),
+ * and append, decode attention and decode step work as skv_q8_* / skv_q4_* do, with the same rank
+ * rules (RANK otherwise).  skv_paged_decode_partial_q and skv_paged_prefill_attention are offered
+ * over bf16 pages only (SHAPE).
  * Errors: those of the calls named, plus SHAPE (page_tokens not a power of two >= 64, n_pages or
  * max_pages_per_seq < 1), CAPACITY (capacity != page_tokens * max_pages_per_seq), NULL / ALIGN
  * (block_table missing or not 4-byte aligned).
@@ -501,9 +508,15 @@ typedef struct {
   int32_t page_tokens;
   int32_t n_pages;
   int32_t max_pages_per_seq;
+  int32_t code_bits;     /* 0: bf16 rows; 8 or 4: the quantised formats of skv_q8_layer / skv_q4_layer */
+  const float* k_scale;  /* code_bits != 0: as in skv_q8_layer                                         */
+  const float* k_zero;
+  void* v_meta;          /* code_bits != 0: device uint32 [n_pages][n_kv_heads][page_tokens][groups of r_v] */
 } skv_paged_layer;
 
 size_t skv_paged_pool_bytes(const skv_paged_layer* paged);
+/* The number of context ranges the decode calls choose for n_ctx tokens (0 for an invalid description or n_ctx). */
+int32_t skv_paged_decode_default_splits(const skv_paged_layer* paged, int64_t n_ctx);
 skv_status skv_paged_project_append(const skv_paged_layer* paged, const void* k_new, const void* v_new,
                                     int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
                                     const int32_t* cur_lens, int64_t max_cur_len, void* stream);

@@ -378,6 +378,53 @@ def paged_prefill_attention(layer: OracleLayer, cache: OraclePagedCache, q: np.n
     return prefill_attention(paged_as_contiguous(layer, cache, [n_prev + T] * layer.batch), q, n_prev, scale, rows)
 
 
+@dataclass
+class OraclePagedQuantCache:
+    """The four arrays of a quantised cache as page pools [n_pages, n_kv_heads, page_tokens, ...]
+    (codes one per byte, value ranges as bf16 bit patterns) plus the block table."""
+    k_codes: np.ndarray
+    v_codes: np.ndarray
+    v_scale_bits: np.ndarray
+    v_zero_bits: np.ndarray
+    block_table: np.ndarray
+    page_tokens: int
+
+
+def _paged_quant_pools(cache: "OraclePagedQuantCache"):
+    return ("k_codes", cache.k_codes), ("v_codes", cache.v_codes), ("v_scale_bits", cache.v_scale_bits), \
+           ("v_zero_bits", cache.v_zero_bits)
+
+
+def paged_quant_project_append(layer: "OracleQuantLayer", cache: OraclePagedQuantCache, k_new: np.ndarray,
+                               v_new: np.ndarray, cur_lens) -> None:
+    """quant_project_append into quantised pages: sequence b's T new rows become its rows
+    [cur_lens[b], cur_lens[b] + T).  `layer` supplies shapes, bases, the static key ranges and the width."""
+    T = np.asarray(k_new).shape[1]
+    tmp = new_quant_layer(layer.batch, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.p_k, layer.p_v,
+                          layer.k_scale, layer.k_zero, max(1, T), layer.bits)
+    quant_project_append(tmp, k_new, v_new, 0)
+    for b in range(layer.batch):
+        for name, pool in _paged_quant_pools(cache):
+            paged_store_rows(pool, cache.block_table[b], cache.page_tokens, int(cur_lens[b]), getattr(tmp, name)[b, :, :T])
+
+
+def paged_quant_decode_attention(layer: "OracleQuantLayer", cache: OraclePagedQuantCache, q: np.ndarray, seq_lens,
+                                 scale: float | None = None) -> np.ndarray:
+    """quant_decode_attention per sequence over the rows its block table names; zeros for an empty sequence."""
+    q = np.asarray(q, np.float64)
+    out = np.zeros(q.shape, np.float64)
+    for b in range(layer.batch):
+        n_b = int(seq_lens[b])
+        if n_b == 0:
+            continue
+        one = new_quant_layer(1, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.p_k, layer.p_v,
+                              layer.k_scale, layer.k_zero, n_b, layer.bits)
+        for name, pool in _paged_quant_pools(cache):
+            getattr(one, name)[0] = paged_rows(pool, cache.block_table[b], cache.page_tokens, n_b)
+        out[b] = quant_decode_attention(one, q[b:b + 1], n_b, scale)[0]
+    return out
+
+
 # --------------------------------------------------------------------------
 # Sec. 3.4 "Overheads": projections folded into the attention linear weights
 # --------------------------------------------------------------------------

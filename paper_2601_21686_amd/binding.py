@@ -37,7 +37,7 @@ EXPORTS = (
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
-    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read", "skv_paged_decode_default_splits",
 )
 
 
@@ -64,7 +64,8 @@ class skv_q8_layer(C.Structure):
 
 class skv_paged_layer(C.Structure):
     _fields_ = [("layer", skv_layer), ("block_table", C.c_void_p), ("page_tokens", C.c_int32),
-                ("n_pages", C.c_int32), ("max_pages_per_seq", C.c_int32)]
+                ("n_pages", C.c_int32), ("max_pages_per_seq", C.c_int32), ("code_bits", C.c_int32),
+                ("k_scale", C.c_void_p), ("k_zero", C.c_void_p), ("v_meta", C.c_void_p)]
 
 
 _lib = None
@@ -156,6 +157,8 @@ def lib() -> C.CDLL:
     PP = C.POINTER(skv_paged_layer)
     L.skv_paged_pool_bytes.argtypes = [PP]
     L.skv_paged_pool_bytes.restype = sz
+    L.skv_paged_decode_default_splits.argtypes = [PP, i64]
+    L.skv_paged_decode_default_splits.restype = i32
     L.skv_paged_project_append.argtypes = [PP, vp, vp, i64, i64, i64, i32, vp, i64, vp]
     L.skv_paged_project_append.restype = C.c_int
     L.skv_paged_decode_attention.argtypes = [PP, vp, vp, vp, i64, C.c_float, vp, sz, vp]
@@ -484,35 +487,49 @@ def skv_set_decode_engine(engine: int) -> int:
 
 
 class PagedLayer:
-    """A layer whose compressed rows live in page pools [n_pages, n_kv_heads, page_tokens, r] addressed
-    through block_table (int32 CUDA [batch, max_pages_per_seq]).  The pools are allocated here
-    (uninitialised) unless passed in."""
+    """A layer whose compressed rows live in page pools [n_pages, n_kv_heads, page_tokens, ...] addressed
+    through block_table (int32 CUDA [batch, max_pages_per_seq]).  bits = 0: bf16 rows; 8 or 4: integer codes
+    (uint8 pools of r * bits / 8 bytes per row, v_meta int32 [..., groups of r_v], static key ranges k_scale /
+    k_zero as for QuantLayer).  The pools are allocated here (uninitialised) unless passed in."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, page_tokens, n_pages, block_table,
-                 k_pool=None, v_pool=None):
+                 k_pool=None, v_pool=None, bits=0, k_scale=None, k_zero=None):
         dev = p_k.device
         assert p_k.dtype == torch.bfloat16 and p_v.dtype == torch.bfloat16
         assert p_k.is_contiguous() and p_v.is_contiguous()
         assert block_table.dtype == torch.int32 and block_table.is_cuda and block_table.is_contiguous()
         assert block_table.dim() == 2 and block_table.shape[0] == batch
+        assert bits in (0, 8, 4)
         self.batch, self.n_q_heads, self.n_kv_heads = int(batch), int(n_q_heads), int(n_kv_heads)
-        self.page_tokens, self.n_pages = int(page_tokens), int(n_pages)
+        self.page_tokens, self.n_pages, self.bits = int(page_tokens), int(n_pages), int(bits)
         self.max_pages_per_seq = int(block_table.shape[1])
         self.capacity = self.page_tokens * self.max_pages_per_seq
         self.r_k, self.r_v = int(p_k.shape[2]), int(p_v.shape[2])
         self.p_k, self.p_v, self.block_table = p_k, p_v, block_table
+        if bits:
+            wk, wv, dt = self.r_k * bits // 8, self.r_v * bits // 8, torch.uint8
+        else:
+            wk, wv, dt = self.r_k, self.r_v, torch.bfloat16
         if k_pool is None:
-            k_pool = torch.empty((n_pages, n_kv_heads, page_tokens, self.r_k), dtype=torch.bfloat16, device=dev)
+            k_pool = torch.empty((n_pages, n_kv_heads, page_tokens, wk), dtype=dt, device=dev)
         if v_pool is None:
-            v_pool = torch.empty((n_pages, n_kv_heads, page_tokens, self.r_v), dtype=torch.bfloat16, device=dev)
-        assert k_pool.is_contiguous() and v_pool.is_contiguous()
+            v_pool = torch.empty((n_pages, n_kv_heads, page_tokens, wv), dtype=dt, device=dev)
+        assert k_pool.is_contiguous() and v_pool.is_contiguous() and k_pool.dtype == dt and v_pool.dtype == dt
         self.k_pool, self.v_pool = k_pool, v_pool
+        self.v_meta = self.k_scale = self.k_zero = None
+        if bits:
+            self.k_scale = k_scale.to(device=dev, dtype=torch.float32).contiguous()
+            self.k_zero = k_zero.to(device=dev, dtype=torch.float32).contiguous()
+            self.v_meta = torch.empty((n_pages, n_kv_heads, page_tokens, (self.r_v + 63) // 64), dtype=torch.int32,
+                                      device=dev)
         base = skv_layer(self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v,
                          self.capacity, k_pool.data_ptr(), v_pool.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
                          0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
                          0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
         self.c = skv_paged_layer(base, block_table.data_ptr(), self.page_tokens, self.n_pages,
-                                 self.max_pages_per_seq)
+                                 self.max_pages_per_seq, self.bits,
+                                 self.k_scale.data_ptr() if bits else None, self.k_zero.data_ptr() if bits else None,
+                                 self.v_meta.data_ptr() if bits else None)
         self._ws = None
 
     def workspace(self) -> torch.Tensor:
@@ -527,6 +544,10 @@ def _lens_ptr(t, batch: int):
         return None
     _lens_ok(t, batch)
     return t.data_ptr()
+
+
+def skv_paged_decode_default_splits(layer: PagedLayer, n_ctx: int) -> int:
+    return int(lib().skv_paged_decode_default_splits(C.byref(layer.c), int(n_ctx)))
 
 
 def skv_paged_pool_bytes(layer: PagedLayer) -> int:

@@ -65,6 +65,11 @@ def _jobs():
         jobs.append((f"skv_decode_partial_q8_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=8"],
                      DEVICE_FLAGS))
+    for bits, ranks in ((8, Q8_KEY_RANKS), (4, Q4_KEY_RANKS)):   # quantised rows in pages (matrix-core kernel only)
+        for rk in ranks:
+            jobs.append((f"skv_decode_partial_paged_q{bits}_rk{rk}.o",
+                         ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}",
+                          f"-DSKV_QBITS={bits}", "-DSKV_PAGED=1"], DEVICE_FLAGS))
     for rk in Q4_KEY_RANKS:
         jobs.append((f"skv_decode_partial_q4_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=4"],

@@ -41,9 +41,8 @@
 #ifndef SKV_PAGED
 #define SKV_PAGED 0                 // 1: the caches are page pools addressed through a block table (bf16 rows only)
 #endif
-#if SKV_PAGED && SKV_QBITS != 0
-#error "the paged build streams bf16 rows"
-#endif
+// Quantised rows in pages are served by the matrix-core kernel only: such a build leaves the vector kernel out.
+#define SKV_VECTOR_KERNEL (!(SKV_PAGED && SKV_QBITS != 0))
 #if SKV_QBITS != 0 && SKV_QBITS != 8 && SKV_QBITS != 4
 #error "SKV_QBITS must be 0, 8 or 4"
 #endif
@@ -60,10 +59,10 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // of the first 64 channels and the j-th eighth of the rest.
 #if SKV_QBITS == 8
 constexpr int kElemsPerDword = 4;                // one byte per channel
-constexpr int kFmt = 1;
+constexpr int kFmt = SKV_PAGED ? 4 : 1;
 #elif SKV_QBITS == 4
 constexpr int kElemsPerDword = 8;                // two channels per byte, the even one in the low half
-constexpr int kFmt = 2;
+constexpr int kFmt = SKV_PAGED ? 5 : 2;
 #else
 constexpr int kElemsPerDword = 2;                // bf16
 constexpr int kFmt = SKV_PAGED ? 3 : 0;
@@ -473,8 +472,9 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
 }
 #endif
 
+#if SKV_VECTOR_KERNEL
 // FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes, 2: 4-bit codes,
-// 3: bf16 rows in pages).
+// 3: bf16 rows in pages, 4 and 5: 8- and 4-bit codes in pages).
 template <int RK, int RV, int GT, int FMT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
@@ -774,6 +774,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   }
 }
 
+#endif  // SKV_VECTOR_KERNEL
+
 // ---------------------------------------------------------------------------------------------------
 // The same range on the matrix cores.
 //
@@ -845,7 +847,7 @@ __device__ __forceinline__ uint32_t high_halves(float lo, float hi) {
 template <int N>
 __device__ __forceinline__ float byte_to_f32(uint32_t w) { return (float)((w >> (8 * N)) & 0xffu); }
 // two 4-bit codes (bits 0..3 of bytes NL of lo and NH of hi ... see callers) as bf16 numbers 16 + n
-constexpr float kNibbleOffset = 16.f;
+[[maybe_unused]] constexpr float kNibbleOffset = 16.f;
 __device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_0_and_2) {
   return (pair_in_bytes_0_and_2 << 3) | 0x41804180u;
 }
@@ -1334,6 +1336,7 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
     }
     return hipGetLastError();
   }
+#if SKV_VECTOR_KERNEL
   switch (heads) {
     case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
     case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
@@ -1341,6 +1344,9 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
+#else
+  return hipErrorInvalidValue;                   // this build holds the matrix-core kernel only
+#endif
 }
 
 template <int RK>
@@ -1366,7 +1372,11 @@ hipError_t launch_rk(int r_v, int heads, const DecodeParams& p, hipStream_t stre
 
 #define SKV_CAT2(a, b) a##b
 #define SKV_CAT(a, b) SKV_CAT2(a, b)
-#if SKV_QBITS == 8
+#if SKV_QBITS == 8 && SKV_PAGED
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_paged_q8_rk, SKV_RK)
+#elif SKV_QBITS == 4 && SKV_PAGED
+#define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_paged_q4_rk, SKV_RK)
+#elif SKV_QBITS == 8
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q8_rk, SKV_RK)
 #elif SKV_QBITS == 4
 #define SKV_LAUNCHER_NAME SKV_CAT(launch_decode_partial_q4_rk, SKV_RK)

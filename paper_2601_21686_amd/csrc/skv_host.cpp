@@ -358,17 +358,43 @@ decode_partial_launcher partial_q_launcher_for(int bits, int r_k) {
   return nullptr;
 }
 
+decode_partial_launcher paged_partial_q_launcher_for(int bits, int r_k) {
+  if (bits == 4) {
+    switch (r_k) {
+      case 64: return launch_decode_partial_paged_q4_rk64;
+      case 128: return launch_decode_partial_paged_q4_rk128;
+    }
+    return nullptr;
+  }
+  switch (r_k) {
+    case 32: return launch_decode_partial_paged_q8_rk32;
+    case 64: return launch_decode_partial_paged_q8_rk64;
+    case 96: return launch_decode_partial_paged_q8_rk96;
+    case 128: return launch_decode_partial_paged_q8_rk128;
+  }
+  return nullptr;
+}
+
 // q8: the quantised layer the call is for, or null for the bf16 cache.
 skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* workspace, void* stream,
-                       const skv_q8_layer* q8 = nullptr, int bits = 8) {
+                       const skv_q8_layer* q8 = nullptr, int bits = 8, const int32_t* seq_lens = nullptr,
+                       int32_t len_add = 0, const PageMap* pages = nullptr) {
   DecodeParams p;
   fill_decode_params(L, &p, s, workspace);
   p.n_ctx = (int32_t)n_ctx;
+  p.seq_lens = seq_lens;
+  p.len_add = len_add;
   if (q8) {
     p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
     p.engine = decode_engine_for(p.group, bits);
   }
-  decode_partial_launcher launch = q8 ? partial_q_launcher_for(bits, L->r_k) : partial_launcher_for(L->r_k);
+  if (pages) {                                   // quantised rows in pages: the matrix-core kernel only
+    p.pages = *pages;
+    p.engine = 1;
+  }
+  decode_partial_launcher launch = !q8     ? partial_launcher_for(L->r_k)
+                                   : pages ? paged_partial_q_launcher_for(bits, L->r_k)
+                                           : partial_q_launcher_for(bits, L->r_k);
   if (!launch) return SKV_ERR_RANK;
   if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
@@ -701,13 +727,17 @@ size_t q_cache_bytes(const skv_q8_layer* Q, int bits, int64_t n_tokens) {
 }
 
 skv_status q_project_append(const skv_q8_layer* Q, int bits, const void* k_new, const void* v_new, int64_t stride_b,
-                            int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, void* stream) {
+                            int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, void* stream,
+                            const int32_t* cur_lens = nullptr, const PageMap* pages = nullptr) {
   skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
   st = check_append(&Q->base, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
   if (st != SKV_OK || T == 0) return st;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
   AppendParams p;
   fill_q_append(Q, bits, &p, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  p.cur_lens = cur_lens;
+  if (pages) p.pages = *pages;
   if (launch_append(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;   // few rows: vector path; a chunk: matrix cores
   return SKV_OK;
 }
@@ -746,9 +776,11 @@ skv_status q_decode_partial(const skv_q8_layer* Q, int bits, int64_t n_ctx, int3
 // T = 0: attention only
 skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, const void* v_new, int64_t stride_b,
                          int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q, void* out,
-                         float scale, void* workspace, size_t workspace_bytes, void* stream) {
+                         float scale, void* workspace, size_t workspace_bytes, void* stream,
+                         const int32_t* cur_lens = nullptr, const PageMap* pages = nullptr) {
   skv_status st = check_q_layer(Q, bits);
   if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
   const skv_layer* L = &Q->base;
   if (T > 0 || k_new || v_new) {
     st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
@@ -765,12 +797,16 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   DecodeParams qp;
   fill_q_query(Q, &qp, q, scale, workspace);
   AppendParams ap;
-  if (T > 0) fill_q_append(Q, bits, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (T > 0) {
+    fill_q_append(Q, bits, &ap, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+    ap.cur_lens = cur_lens;
+    if (pages) ap.pages = *pages;
+  }
   const bool few = T > 0 && (int64_t)L->batch * T <= kVectorAppendMaxRows;
   if (T > 0 && !few && launch_append(ap, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
   if (launch_project(few ? &ap : nullptr, &qp, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
-  st = run_partial(L, n_ctx, s, workspace, stream, Q, bits);
+  st = run_partial(L, n_ctx, s, workspace, stream, Q, bits, cur_lens, T, pages);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
 }
@@ -882,6 +918,16 @@ skv_status run_folded_attention(const skv_layer* L, void* out_low, int64_t n_ctx
 
 namespace {
 
+// The quantised layer a paged description with integer codes stands for (its arrays are the pools).
+skv_q8_layer paged_quant_view(const skv_paged_layer* P) {
+  skv_q8_layer Q;
+  Q.base = P->layer;
+  Q.k_scale = P->k_scale;
+  Q.k_zero = P->k_zero;
+  Q.v_meta = P->v_meta;
+  return Q;
+}
+
 // The paged layer's checks; fills the device-side description of its page table.
 skv_status check_paged(const skv_paged_layer* P, PageMap* pm) {
   if (!P) return SKV_ERR_NULL;
@@ -893,6 +939,12 @@ skv_status check_paged(const skv_paged_layer* P, PageMap* pm) {
   if (pt < kRangeQuantum || pt > (1 << 20) || (pt & (pt - 1))) return SKV_ERR_SHAPE;   // a power of two, >= 64
   if (P->n_pages < 1 || P->max_pages_per_seq < 1) return SKV_ERR_SHAPE;
   if (P->layer.capacity != (int64_t)pt * P->max_pages_per_seq) return SKV_ERR_CAPACITY;
+  if (P->code_bits != 0 && P->code_bits != 8 && P->code_bits != 4) return SKV_ERR_SHAPE;
+  if (P->code_bits != 0) {
+    const skv_q8_layer Q = paged_quant_view(P);
+    const skv_status sq = check_q_layer(&Q, P->code_bits);
+    if (sq != SKV_OK) return sq;
+  }
   int shift = 0;
   while ((1 << shift) < pt) ++shift;
   *pm = PageMap{P->block_table, P->max_pages_per_seq, shift, P->n_pages};
@@ -1045,7 +1097,19 @@ skv_status skv_decode_step_varlen(const skv_layer* L, const void* k_new, const v
 size_t skv_paged_pool_bytes(const skv_paged_layer* P) {
   PageMap pm;
   if (check_paged(P, &pm) != SKV_OK) return 0;
-  return (size_t)P->n_pages * P->layer.n_kv_heads * (size_t)P->page_tokens * (size_t)(P->layer.r_k + P->layer.r_v) * 2u;
+  const size_t rows = (size_t)P->n_pages * P->layer.n_kv_heads * (size_t)P->page_tokens;
+  if (P->code_bits == 0) return rows * (size_t)(P->layer.r_k + P->layer.r_v) * 2u;
+  return rows * ((size_t)(P->layer.r_k + P->layer.r_v) * (size_t)P->code_bits / 8u + 4u * (size_t)((P->layer.r_v + 63) / 64));
+}
+
+int32_t skv_paged_decode_default_splits(const skv_paged_layer* P, int64_t n_ctx) {
+  PageMap pm;
+  if (check_paged(P, &pm) != SKV_OK) return 0;
+  const skv_layer* L = &P->layer;
+  if (n_ctx < 1 || n_ctx > L->capacity) return 0;
+  int32_t s = 0;
+  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, P->code_bits)) return 0;
+  return s;
 }
 
 skv_status skv_paged_project_append(const skv_paged_layer* P, const void* k_new, const void* v_new, int64_t stride_b,
@@ -1054,6 +1118,11 @@ skv_status skv_paged_project_append(const skv_paged_layer* P, const void* k_new,
   PageMap pm;
   const skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
+  if (P->code_bits != 0) {
+    const skv_q8_layer Q = paged_quant_view(P);
+    return q_project_append(&Q, P->code_bits, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len, stream,
+                            cur_lens, &pm);
+  }
   return append_lens(&P->layer, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, stream, &pm);
 }
 
@@ -1063,6 +1132,11 @@ skv_status skv_paged_decode_attention(const skv_paged_layer* P, const void* q, v
   PageMap pm;
   const skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
+  if (P->code_bits != 0) {
+    const skv_q8_layer Q = paged_quant_view(P);
+    return q_decode_step(&Q, P->code_bits, nullptr, nullptr, 0, 0, 0, 0, max_len, q, out, scale, workspace,
+                         workspace_bytes, stream, seq_lens, &pm);
+  }
   return attention_lens(&P->layer, q, out, seq_lens, max_len, scale, workspace, workspace_bytes, stream, &pm);
 }
 
@@ -1072,6 +1146,7 @@ skv_status skv_paged_decode_partial_q(const skv_paged_layer* P, const void* q, c
   PageMap pm;
   skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
+  if (P->code_bits != 0) return SKV_ERR_SHAPE;             // offered over bf16 pages only
   const skv_layer* L = &P->layer;
   st = check_query_stage(L, q, scale, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
@@ -1089,6 +1164,12 @@ skv_status skv_paged_decode_step(const skv_paged_layer* P, const void* k_new, co
   PageMap pm;
   const skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
+  if (P->code_bits != 0) {
+    if (T < 1) return SKV_ERR_SHAPE;                     // a step appends at least one row per sequence
+    const skv_q8_layer Q = paged_quant_view(P);
+    return q_decode_step(&Q, P->code_bits, k_new, v_new, stride_b, stride_t, stride_h, T, max_cur_len, q, out, scale,
+                         workspace, workspace_bytes, stream, cur_lens, &pm);
+  }
   return step_lens(&P->layer, k_new, v_new, stride_b, stride_t, stride_h, T, cur_lens, max_cur_len, q, out, scale,
                    workspace, workspace_bytes, stream, &pm);
 }
@@ -1099,6 +1180,7 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* P, const void* q, 
   PageMap pm;
   skv_status st = check_paged(P, &pm);
   if (st != SKV_OK) return st;
+  if (P->code_bits != 0) return SKV_ERR_SHAPE;             // offered over bf16 pages only
   st = check_prefill(&P->layer, false, q, out, T, n_prev, scale, mode);
   if (st != SKV_OK || T == 0) return st;
   if (n_prev + (int64_t)T > kPagedPrefillMaxRows) return SKV_ERR_CAPACITY;   // the kernel's table of tile starts

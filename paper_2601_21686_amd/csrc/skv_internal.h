@@ -189,6 +189,12 @@ hipError_t launch_decode_partial_q8_rk96(int, int, const DecodeParams&, hipStrea
 hipError_t launch_decode_partial_q8_rk128(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q4_rk64(int, int, const DecodeParams&, hipStream_t);
 hipError_t launch_decode_partial_q4_rk128(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q8_rk32(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q8_rk64(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q8_rk96(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q8_rk128(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q4_rk64(int, int, const DecodeParams&, hipStream_t);
+hipError_t launch_decode_partial_paged_q4_rk128(int, int, const DecodeParams&, hipStream_t);
 
 // sched: 0 = the default schedule for the shape, 1 = keys and values staged together, 2 = keys a tile ahead
 typedef hipError_t (*prefill_launcher)(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream);

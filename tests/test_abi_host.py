@@ -375,3 +375,28 @@ def test_read_probe_argument_checks():
     assert lib.skv_probe_stream_read(FAKE + 4, 1 << 20, 4, FAKE, C.byref(n), None) == B.SKV_ERR_ALIGN
     assert lib.skv_probe_stream_read(FAKE, 1 << 20, 0, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE
     assert lib.skv_probe_stream_read(FAKE, 1000, 4, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE    # less than a slice each
+
+
+def test_paged_quantised_argument_checks():
+    lib = B.lib()
+    big = 1 << 30
+
+    def paged(bits, k_scale=FAKE, k_zero=FAKE, v_meta=FAKE, **kw):
+        return B.skv_paged_layer(_layer(capacity=64 * 16, **kw), FAKE, 64, 100, 16, bits, k_scale, k_zero, v_meta)
+
+    att = lambda p: lib.skv_paged_decode_attention(C.byref(p), FAKE, FAKE, None, 2000, 0.0, FAKE, big, None)
+    assert att(paged(8)) == B.SKV_ERR_CAPACITY                       # a valid description: fails on the length only
+    assert att(paged(3)) == B.SKV_ERR_SHAPE                          # widths: 0, 8, 4
+    assert att(paged(8, k_scale=None)) == B.SKV_ERR_NULL
+    assert att(paged(8, v_meta=FAKE + 2)) == B.SKV_ERR_ALIGN
+    assert att(paged(8, r_k=48, p_k_head_stride=128 * 48)) == B.SKV_ERR_RANK     # 8-bit ranks: multiples of 32
+    assert att(paged(4, r_v=96, p_v_head_stride=128 * 96)) == B.SKV_ERR_RANK     # 4-bit ranks: multiples of 64
+    assert lib.skv_paged_pool_bytes(C.byref(paged(8))) == 100 * 8 * 64 * (64 + 64 + 4)
+    assert lib.skv_paged_pool_bytes(C.byref(paged(4))) == 100 * 8 * 64 * (32 + 32 + 4)
+    lib.skv_set_decode_engine(2)
+    assert lib.skv_paged_decode_default_splits(C.byref(paged(0)), 1024) == 16      # 512 workgroups over 32 columns
+    assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 1024) == 16      # 24 wanted, 16 quanta of 64 rows there
+    assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 2000) == 0
+    # chunk attention and the separate first launch are offered over bf16 pages only
+    assert lib.skv_paged_prefill_attention(C.byref(paged(8)), FAKE, 8192, 4096, 128, FAKE, 16, 0, 0.0, 0, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_paged_decode_partial_q(C.byref(paged(8)), FAKE, None, 0.0, 100, 0, FAKE, big, None) == B.SKV_ERR_SHAPE

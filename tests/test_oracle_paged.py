@@ -105,3 +105,35 @@ def test_results_do_not_depend_on_which_pool_page_holds_a_row():
     # ... but a swap that moves rows across the causal boundary changes it
     swapped.block_table[0, [0, 2]] = swapped.block_table[0, [2, 0]]
     assert not np.allclose(O.paged_prefill_attention(layer, swapped, qc, 17)[0], same[0])
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_paged_quantised_functions_equal_the_contiguous_quantised_layer(bits):
+    # quantised pages: the same codes and value ranges, found through the table
+    batch, hq, hkv, pt, r = 2, 4, 2, 8, 64
+    _, pk = synth.orthonormal_bases(synth.stable_seed("pq", "pk"), hkv, 128, r)
+    _, pv = synth.orthonormal_bases(synth.stable_seed("pq", "pv"), hkv, 128, r)
+    f = lambda t: O.bf16_bits_to_f64(synth.torch_bf16_to_bits(t))
+    ks, kz = np.full((hkv, 1), 0.05, np.float32), np.full((hkv, 1), -5.0, np.float32)
+    flat = O.new_quant_layer(batch, hq, hkv, 128, f(pk), f(pv), ks, kz, 32, bits)
+    rng = np.random.default_rng(5)
+    table = rng.permutation(12)[:8].reshape(2, 4)
+    shape = (12, hkv, pt)
+    cache = O.OraclePagedQuantCache(np.zeros(shape + (r,), np.uint8), np.zeros(shape + (r,), np.uint8),
+                                    np.zeros(shape + (1,), np.uint16), np.zeros(shape + (1,), np.uint16), table, pt)
+    n = 27
+    k, v = rng.standard_normal((batch, n, hkv, 128)), rng.standard_normal((batch, n, hkv, 128))
+    O.quant_project_append(flat, k, v, 0)
+    cur = np.zeros(batch, int)
+    for a, b_ in ((0, 5), (5, 18), (18, 27)):
+        O.paged_quant_project_append(flat, cache, k[:, a:b_], v[:, a:b_], cur)
+        cur += b_ - a
+    for b in range(batch):
+        assert np.array_equal(O.paged_rows(cache.k_codes, table[b], pt, n), flat.k_codes[b, :, :n])
+        assert np.array_equal(O.paged_rows(cache.v_codes, table[b], pt, n), flat.v_codes[b, :, :n])
+        assert np.array_equal(O.paged_rows(cache.v_scale_bits, table[b], pt, n), flat.v_scale_bits[b, :, :n])
+        assert np.array_equal(O.paged_rows(cache.v_zero_bits, table[b], pt, n), flat.v_zero_bits[b, :, :n])
+    q = rng.standard_normal((batch, hq, 128))
+    got = O.paged_quant_decode_attention(flat, cache, q, [27, 9])
+    assert np.array_equal(got[0], O.quant_decode_attention(flat, q, 27)[0])
+    assert np.array_equal(got[1], O.quant_decode_attention(flat, q, 9)[1])
