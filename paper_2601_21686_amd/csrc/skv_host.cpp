@@ -111,6 +111,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->scale_log2e = 0.f;
   p->lift = 1;
   p->k_scale = nullptr;
+  p->k_zero = nullptr;
   p->v_meta = nullptr;
   char* ws = static_cast<char*>(workspace);
   p->qt = reinterpret_cast<float*>(ws);
@@ -773,6 +774,40 @@ skv_status q_decode_partial(const skv_q8_layer* Q, int bits, int64_t n_ctx, int3
   return run_partial(&Q->base, n_ctx, s, workspace, stream, Q, bits);
 }
 
+// One launch for the ranges of a quantised cache with the queries projected inside it and, when T_new > 0, the
+// new rows quantised, stored and attended by extra workgroups (matrix-core kernel only).
+skv_status run_partial_fused_q(const skv_q8_layer* Q, int bits, const void* q, float scale, int64_t n_ctx,
+                               int32_t s_stream, const void* k_new, const void* v_new, int64_t stride_b,
+                               int64_t stride_t, int64_t stride_h, int32_t T_new, void* workspace, void* stream,
+                               const int32_t* seq_lens, const PageMap* pages) {
+  const skv_layer* L = &Q->base;
+  DecodeParams p;
+  const int32_t total = s_stream + (T_new > 0 ? 1 : 0);
+  fill_decode_params(L, &p, total, workspace);
+  p.n_stream = s_stream;
+  p.n_ctx = (int32_t)n_ctx;
+  p.q = static_cast<const uint16_t*>(q);
+  p.scale_log2e = scale_log2e_of(scale);
+  p.k_new = static_cast<const uint16_t*>(k_new);
+  p.v_new = static_cast<const uint16_t*>(v_new);
+  p.stride_b = stride_b;
+  p.stride_t = stride_t;
+  p.stride_h = stride_h;
+  p.cur_len = n_ctx;
+  p.T_new = T_new;
+  p.seq_lens = seq_lens;
+  p.k_scale = Q->k_scale;
+  p.k_zero = Q->k_zero;
+  p.v_meta = static_cast<const uint32_t*>(Q->v_meta);
+  p.engine = 1;
+  if (pages) p.pages = *pages;
+  decode_partial_launcher launch = pages ? paged_partial_q_launcher_for(bits, L->r_k) : partial_q_launcher_for(bits, L->r_k);
+  if (!launch) return SKV_ERR_RANK;
+  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+    return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
 // T = 0: attention only
 skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, const void* v_new, int64_t stride_b,
                          int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q, void* out,
@@ -794,6 +829,26 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   if (st != SKV_OK) return st;
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
+  // With the matrix-core kernel a step is two launches, as over the bf16 cache: the range kernel projects the
+  // queries itself, and for a few new tokens extra workgroups quantise, store and attend them.
+  const int gq = L->n_q_heads / L->n_kv_heads;
+  const bool matrix = pages != nullptr || decode_engine_for(gq, bits) == 1;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
+  if (matrix && T == 0) {
+    st = run_partial_fused_q(Q, bits, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, cur_lens, pages);
+    if (st != SKV_OK) return st;
+    return run_combine(L, out, s, workspace, stream);
+  }
+  if (matrix && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
+    int32_t s_old = 0;
+    if (!plan_splits(L->batch, L->n_kv_heads, gq, cur_len, 0, &s_old, bits)) return SKV_ERR_SHAPE;
+    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
+    st = run_partial_fused_q(Q, bits, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
+                             stream, cur_lens, pages);
+    if (st != SKV_OK) return st;
+    return run_combine(L, out, s_old + 1, workspace, stream);
+  }
   DecodeParams qp;
   fill_q_query(Q, &qp, q, scale, workspace);
   AppendParams ap;

@@ -44,6 +44,7 @@ struct DecodeParams {
   float* qt;                 // [batch][n_q_heads][r_k]: projected query times scale*log2(e)
   // 8-bit quantised cache only (null otherwise)
   const float* k_scale;      // [n_kv_heads][groups of r_k]: static key scales, folded into qt
+  const float* k_zero;       // the matching zero points: only a fused step over a quantised cache needs them (new rows)
   const uint32_t* v_meta;    // [batch][n_kv_heads][capacity][groups of r_v]: bf16 scale | bf16 zero << 16
   float* out;                // [batch][n_q_heads][128]
   int64_t capacity;
