@@ -169,17 +169,31 @@ def main():
         sc = synth.channel_scales(synth.stable_seed(wl.name, 0, "sk"), wl.n_kv_heads, wl.head_dim)
         k = synth.kv_activations(1, wl.batch, T, wl.n_kv_heads, wl.head_dim, sc, dev)
         v = synth.kv_activations(2, wl.batch, T, wl.n_kv_heads, wl.head_dim, sc, dev)
-        for _ in range(3):
+        for _ in range(5):
             append(L, k, v, wl.n_ctx - T)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        iters = max(1, args.kernel_iters // 10)
+        iters = max(1, args.kernel_iters)            # enqueued back to back: the queue never runs dry
         e0.record()
         for _ in range(iters):
             append(L, k, v, wl.n_ctx - T)
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / iters
+        # yardstick: a plain kernel that reads two bytes per byte written, sized to this append's input
+        in_bytes = wl.batch * T * wl.n_kv_heads * wl.head_dim * 2
+        pa = torch.empty(in_bytes // 4, dtype=torch.int32, device=dev).fill_(1)
+        pb, pc = pa.clone(), torch.empty_like(pa)
+        mix_each = 0
+        for _ in range(5):
+            mix_each = B.skv_probe_stream_mix(pa, pb, pc, 2048)
+        e0.record()
+        for _ in range(iters):
+            B.skv_probe_stream_mix(pa, pb, pc, 2048)
+        e1.record()
+        torch.cuda.synchronize()
+        mix_us = e0.elapsed_time(e1) * 1e3 / iters
+        mix_gbps = 3 * mix_each / mix_us / 1e3
         out_row = (rk + rv) * 2 if not abits else (rk + rv) * abits // 8 + 4 * ((rv + 63) // 64)
         nbytes = wl.batch * T * wl.n_kv_heads * (2 * wl.head_dim * 2 + out_row)
         flops = 2 * wl.batch * T * wl.n_kv_heads * wl.head_dim * (rk + rv)
@@ -187,7 +201,9 @@ def main():
                           "us_per_launch": round(us, 2), "bytes_per_launch": nbytes, "flops_per_launch": flops,
                           "achieved_GBps": round(nbytes / us / 1e3, 1), "frac_of_hbm_peak": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4),
                           "achieved_TFLOPs": round(flops / us / 1e6, 1), "frac_of_bf16_mfma_peak": round(flops / us / 1e6 / 2500.0, 4),
-                          "launches": iters + 3}))
+                          "plain_mix": {"kernel": "stream_mix_kernel", "bytes": 3 * mix_each, "us_per_launch": round(mix_us, 2),
+                                        "GBps": round(mix_gbps, 1), "append_vs_plain_mix": round(nbytes / us / 1e3 / mix_gbps, 4)},
+                          "launches": iters + 5}))
         return
     if args.mode == "varlen":
         # decode steps (append one token per sequence at its own position, attend its own context) over a batch

@@ -559,6 +559,18 @@ int32_t skv_set_decode_engine(int32_t engine);
 skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgroups, void* sink,
                                  size_t* bytes_read, void* stream);
 
+/*
+ * A second measuring stick: one launch that reads two buffers and writes a third (c = a ^ b), two bytes
+ * read for each byte written, the traffic mix of the chunk append (Sec. 2.1 Eq. 1 at r_k + r_v = head
+ * size).  The first *bytes_each <= bytes bytes of each buffer take part (whole multiples of
+ * workgroups * 16 KiB), each workgroup a contiguous slice.
+ *   a, b  device, 16-byte aligned, at least `bytes` long, read
+ *   c     device, 16-byte aligned, at least `bytes` long, overwritten; must not overlap a or b
+ * Errors: NULL, ALIGN, SHAPE (workgroups outside [1, 65535], or bytes below workgroups * 16 KiB), HIP.
+ */
+skv_status skv_probe_stream_mix(const void* a, const void* b, void* c, size_t bytes, int32_t workgroups,
+                                size_t* bytes_each, void* stream);
+
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */
 size_t skv_cache_bytes(const skv_layer* layer, int64_t n_tokens);

@@ -37,7 +37,7 @@ EXPORTS = (
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
-    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read", "skv_paged_decode_default_splits",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read", "skv_probe_stream_mix", "skv_paged_decode_default_splits",
 )
 
 
@@ -171,6 +171,8 @@ def lib() -> C.CDLL:
     L.skv_paged_prefill_attention.restype = C.c_int
     L.skv_probe_stream_read.argtypes = [vp, sz, i32, vp, C.POINTER(C.c_size_t), vp]
     L.skv_probe_stream_read.restype = C.c_int
+    L.skv_probe_stream_mix.argtypes = [vp, vp, vp, sz, i32, C.POINTER(C.c_size_t), vp]
+    L.skv_probe_stream_mix.restype = C.c_int
     L.skv_set_decode_engine.argtypes = [i32]
     L.skv_set_decode_engine.restype = i32
     L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
@@ -474,6 +476,17 @@ def skv_probe_stream_read(src: torch.Tensor, workgroups: int, sink: torch.Tensor
     n = C.c_size_t(0)
     _check(lib().skv_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), int(workgroups),
                                        sink.data_ptr(), C.byref(n), _stream_ptr(stream)), "skv_probe_stream_read")
+    return int(n.value)
+
+
+def skv_probe_stream_mix(a: torch.Tensor, b: torch.Tensor, c: torch.Tensor, workgroups: int, stream=None) -> int:
+    """One launch c = a ^ b over three contiguous CUDA tensors of one size; returns the bytes taken from each."""
+    nbytes = a.numel() * a.element_size()
+    for t in (a, b, c):
+        assert t.is_cuda and t.is_contiguous() and t.numel() * t.element_size() == nbytes
+    n = C.c_size_t(0)
+    _check(lib().skv_probe_stream_mix(a.data_ptr(), b.data_ptr(), c.data_ptr(), nbytes, int(workgroups),
+                                      C.byref(n), _stream_ptr(stream)), "skv_probe_stream_mix")
     return int(n.value)
 
 

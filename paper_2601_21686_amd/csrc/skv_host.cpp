@@ -214,6 +214,19 @@ skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgrou
   return SKV_OK;
 }
 
+skv_status skv_probe_stream_mix(const void* a, const void* b, void* c, size_t bytes, int32_t workgroups,
+                                size_t* bytes_each, void* stream) {
+  if (!a || !b || !c || !bytes_each) return SKV_ERR_NULL;
+  if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return SKV_ERR_ALIGN;
+  if (workgroups < 1 || workgroups > 65535) return SKV_ERR_SHAPE;
+  const size_t stride = 1024;                                        // 256 lanes x 4 pieces in flight
+  const size_t per_wg = bytes / 16 / (size_t)workgroups / stride * stride;
+  if (per_wg == 0) return SKV_ERR_SHAPE;
+  *bytes_each = per_wg * (size_t)workgroups * 16;
+  if (launch_stream_mix(a, b, c, per_wg, workgroups, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
 int32_t skv_set_decode_engine(int32_t engine) {
   const int32_t before = g_decode_engine;
   if (engine >= 0 && engine <= 2) g_decode_engine = engine;

@@ -219,6 +219,8 @@ hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipSt
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 // reads workgroups * pieces_per_wg 16-byte pieces (pieces_per_wg a multiple of 1024), writes nothing
 hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream);
+hipError_t launch_stream_mix(const void* a, const void* b, void* c, size_t pieces_per_wg, int workgroups,
+                             hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)
 hipError_t launch_pad_basis(const void* src, void* dst, int r, int r_pad, int64_t rows, hipStream_t stream);
 // out bf16 [n][128][r_out]: leading r columns of the orthonormal factor of a float32 [n][128][128], zero columns behind

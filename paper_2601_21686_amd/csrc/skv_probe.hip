@@ -1,4 +1,4 @@
-// A measuring stick, not part of the attention path: a kernel that only reads.  Every workgroup streams a
+// Measuring sticks, not part of the attention path.  First a kernel that only reads.  Every workgroup streams a
 // contiguous slice with four 16-byte loads in flight per lane and writes nothing (one guarded store that never
 // fires keeps the loads alive).  What it reaches is what this memory system gives a plain streaming read of
 // that size; the range kernels are judged against it as well as against the published peak.
@@ -24,7 +24,32 @@ __global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const uint4*
   if (acc == 12345.678f) sink[blockIdx.x] = acc;   // practically never: the sum of xor-ed words is not this value
 }
 
+// The same for a stream that reads two bytes for each byte it writes, the mix of the chunk append at
+// ranks that add up to the head size: c = a ^ b over contiguous slices.
+__global__ __launch_bounds__(kProbeThreads) void stream_mix_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b,
+                                                                 uint4* __restrict__ c, size_t per_wg) {
+  const size_t base = (size_t)blockIdx.x * per_wg;
+  for (size_t i = threadIdx.x; i < per_wg; i += kProbeThreads * kProbeUnroll) {   // per_wg is a multiple of the stride
+    uint4 x[kProbeUnroll], y[kProbeUnroll];
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u) {
+      x[u] = a[base + i + (size_t)u * kProbeThreads];
+      y[u] = b[base + i + (size_t)u * kProbeThreads];
+    }
+#pragma unroll
+    for (int u = 0; u < kProbeUnroll; ++u)
+      c[base + i + (size_t)u * kProbeThreads] = make_uint4(x[u].x ^ y[u].x, x[u].y ^ y[u].y, x[u].z ^ y[u].z, x[u].w ^ y[u].w);
+  }
+}
+
 }  // namespace
+
+hipError_t launch_stream_mix(const void* a, const void* b, void* c, size_t pieces_per_wg, int workgroups,
+                             hipStream_t stream) {
+  hipLaunchKernelGGL(stream_mix_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,
+                     static_cast<const uint4*>(a), static_cast<const uint4*>(b), static_cast<uint4*>(c), pieces_per_wg);
+  return hipGetLastError();
+}
 
 hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream) {
   hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,

@@ -377,6 +377,15 @@ def test_read_probe_argument_checks():
     assert lib.skv_probe_stream_read(FAKE, 1000, 4, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE    # less than a slice each
 
 
+def test_mix_probe_argument_checks():
+    lib = B.lib()
+    n = C.c_size_t(0)
+    assert lib.skv_probe_stream_mix(FAKE, None, FAKE, 1 << 20, 4, C.byref(n), None) == B.SKV_ERR_NULL
+    assert lib.skv_probe_stream_mix(FAKE, FAKE, FAKE + 8, 1 << 20, 4, C.byref(n), None) == B.SKV_ERR_ALIGN
+    assert lib.skv_probe_stream_mix(FAKE, FAKE, FAKE, 1 << 20, 70000, C.byref(n), None) == B.SKV_ERR_SHAPE
+    assert lib.skv_probe_stream_mix(FAKE, FAKE, FAKE, 1000, 4, C.byref(n), None) == B.SKV_ERR_SHAPE   # less than a slice each
+
+
 def test_paged_quantised_argument_checks():
     lib = B.lib()
     big = 1 << 30
