@@ -26,6 +26,9 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang"
 # The chunk attention keeps its matrix-core accumulators in ordinary vector registers (they are
 # read by the softmax right after each product), which saves the copies out of the accumulation file.
 PREFILL_FLAGS = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+# The matrix-core range kernel feeds its score accumulators to the softmax and rescales its mix
+# accumulators in place: the same form saves it about 80 register copies per 32-row tile.
+DECODE_FLAGS = PREFILL_FLAGS
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
           "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
 
@@ -48,7 +51,7 @@ def _jobs():
     for rk in KEY_RANKS:
         jobs.append((f"skv_decode_partial_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}"],
-                     DEVICE_FLAGS))
+                     DEVICE_FLAGS + DECODE_FLAGS))
     for rk in KEY_RANKS:
         jobs.append((f"skv_prefill_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_prefill.hip"), f"-DSKV_RK={rk}"],
@@ -60,20 +63,20 @@ def _jobs():
     for rk in KEY_RANKS:                  # the same range kernel addressing its rows through a page table
         jobs.append((f"skv_decode_partial_paged_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_PAGED=1"],
-                     DEVICE_FLAGS))
+                     DEVICE_FLAGS + DECODE_FLAGS))
     for rk in Q8_KEY_RANKS:
         jobs.append((f"skv_decode_partial_q8_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=8"],
-                     DEVICE_FLAGS))
+                     DEVICE_FLAGS + DECODE_FLAGS))
     for bits, ranks in ((8, Q8_KEY_RANKS), (4, Q4_KEY_RANKS)):   # quantised rows in pages (matrix-core kernel only)
         for rk in ranks:
             jobs.append((f"skv_decode_partial_paged_q{bits}_rk{rk}.o",
                          ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}",
-                          f"-DSKV_QBITS={bits}", "-DSKV_PAGED=1"], DEVICE_FLAGS))
+                          f"-DSKV_QBITS={bits}", "-DSKV_PAGED=1"], DEVICE_FLAGS + DECODE_FLAGS))
     for rk in Q4_KEY_RANKS:
         jobs.append((f"skv_decode_partial_q4_rk{rk}.o",
                      ["-x", "hip", os.path.join(CSRC, "skv_decode_partial.hip"), f"-DSKV_RK={rk}", "-DSKV_QBITS=4"],
-                     DEVICE_FLAGS))
+                     DEVICE_FLAGS + DECODE_FLAGS))
     return jobs
 
 
