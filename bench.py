@@ -116,7 +116,7 @@ def main():
         # the published peak (sizes up to the 256 MiB last-level cache are partly served from it when re-read)
         sink = torch.zeros(65536, dtype=torch.float32, device=dev)
         rows = []
-        for mib in (64, 128, 256, 512, 1024, 2048):
+        for mib in (64, 128, 256, 512, 1024, 2048, 4096, 8192):
             src = torch.empty(mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
             best = None
             for wgs in (512, 2048):
