@@ -61,6 +61,11 @@ def parse_args():
     ap.add_argument("--engine", choices=("auto", "vector", "matrix"), default="auto",
                     help="range kernel: chosen by shape (default: matrix cores for groups of 8 query heads, vector "
                          "arithmetic otherwise), or forced")
+    ap.add_argument("--cache-reads", choices=("auto", "size", "stream", "plain"), default="auto",
+                    help="how the range kernels load cache rows: streaming loads, ordinary loads, size = the library's "
+                         "default (streaming when one launch covers clearly more than the 256 MiB last-level cache); "
+                         "auto = what a caller that knows its model does: streaming when the layers of one step "
+                         "together exceed that cache, else the library's default")
     ap.add_argument("--mode", choices=("bench", "kernel", "copy", "read", "append", "prefill", "varlen"), default="bench",
                     help="bench: the full run; kernel: only the decode range kernel launches (for counter runs); "
                          "copy: a plain 1 GiB device copy, to calibrate the HBM byte counters; "
@@ -111,6 +116,7 @@ def main():
     torch.cuda.set_device(0)
 
     B.skv_set_decode_engine({"vector": 0, "matrix": 1, "auto": 2}[args.engine])
+    B.skv_set_cache_reads({"stream": 0, "plain": 1, "size": 2, "auto": 2}[args.cache_reads])
     if args.mode == "read":
         # what a kernel that only reads gets from this memory system, by working-set size: the yardstick beside
         # the published peak (sizes up to the 256 MiB last-level cache are partly served from it when re-read)
@@ -382,6 +388,14 @@ def main():
             return (ranks_k[li] + ranks_v[li]) * qbits // 8 + 4 * ((ranks_v[li] + 63) // 64)
         return 2 * (ranks_k[li] + ranks_v[li])
 
+    # A caller knows its model: when the layers of one step together exceed the last-level cache, no row can
+    # be found there again on the next step, whatever a single launch covers.
+    step_cache_bytes = sum(Bt * HKV * wl.n_ctx * row_bytes(li) for li in range(wl.n_layers))
+    cache_reads = args.cache_reads
+    if cache_reads == "auto":
+        cache_reads = "stream" if (wl.n_layers > 1 and step_cache_bytes > (288 << 20)) else "size"
+        B.skv_set_cache_reads({"stream": 0, "size": 2}[cache_reads])
+
     layers, scales, k_ranges = [], [], []
     for li in range(wl.n_layers):
         _, pk = synth.orthonormal_bases(synth.stable_seed(wl.name, li, "pk"), HKV, d, ranks_k[li])
@@ -571,7 +585,7 @@ def main():
                    "r_v": ranks_v if wl.n_layers > 1 else ranks_v[0],
                    "cache": (f"{qbits}-bit codes, group 64" if q8 else "bf16") + (f", pages of {args.page_tokens} rows, shuffled block table" if paged else ""), "step": ("place 1 projected token/sequence + attention in the compressed space, every layer" if folded
                             else "append 1 token/sequence + decode attention, every layer (skv_decode_step)"),
-                   "variant": args.variant, "engine": args.engine,
+                   "variant": args.variant, "engine": args.engine, "cache_reads": cache_reads,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
         "roofline": {"bound": "hbm", "kernel": ("projection + decode_partial_mma_kernel + merge (the whole attention call: no stage calls over quantised pages)" if (paged and q8)
                                 else "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8)))

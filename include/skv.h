@@ -548,10 +548,22 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* paged, const void*
 int32_t skv_set_decode_engine(int32_t engine);
 
 /*
+ * How the range kernels of the decode calls read cache rows (D2/D4: every row of the compressed cache is
+ * read once per step, Sec. 2.1 Eq. 2 with App. A.1 Eq. 18).  0 = streaming (non-temporal) loads: right when
+ * the rows will not be found in a cache on the next step, as in a model whose layers together exceed the
+ * last-level cache; 1 = ordinary loads; 2 (default) = by size: streaming when the rows one launch covers
+ * add up to more than 288 MiB (clearly more than the 256 MiB last-level cache), ordinary otherwise.  Results do not depend on it.  Process-wide and not
+ * synchronised: set it before issuing work.  Returns the previous value; any other argument changes
+ * nothing (a way to read the current value).
+ */
+int32_t skv_set_cache_reads(int32_t mode);
+
+/*
  * A measuring stick for the benchmark, no part of the method: one launch that only READS.  The first
  * *bytes_read <= bytes bytes of src (whole multiples of workgroups * 16 KiB) are streamed, each
  * workgroup a contiguous slice, and nothing is written.  Timing it tells what a plain streaming read of
- * that size reaches on the machine at hand, which the range kernels are compared with.
+ * that size reaches on the machine at hand, which the range kernels are compared with.  It uses the kind of
+ * load a range kernel over that many bytes would use (skv_set_cache_reads).
  *   src   device, 16-byte aligned, at least `bytes` long
  *   sink  device float32 [workgroups]: never written in practice, must be valid
  * Errors: NULL, ALIGN, SHAPE (workgroups outside [1, 65535], or bytes below workgroups * 16 KiB), HIP.

@@ -37,7 +37,7 @@ EXPORTS = (
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
-    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_probe_stream_read", "skv_probe_stream_mix", "skv_paged_decode_default_splits",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_set_cache_reads", "skv_probe_stream_read", "skv_probe_stream_mix", "skv_paged_decode_default_splits",
 )
 
 
@@ -175,6 +175,8 @@ def lib() -> C.CDLL:
     L.skv_probe_stream_mix.restype = C.c_int
     L.skv_set_decode_engine.argtypes = [i32]
     L.skv_set_decode_engine.restype = i32
+    L.skv_set_cache_reads.argtypes = [i32]
+    L.skv_set_cache_reads.restype = i32
     L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
     L.skv_orthonormalize.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
@@ -494,6 +496,12 @@ def skv_set_decode_engine(engine: int) -> int:
     """0 = vector arithmetic, 1 = matrix cores, 2 = by shape (default); returns the previous choice (any other
     value: no change)."""
     return int(lib().skv_set_decode_engine(int(engine)))
+
+
+def skv_set_cache_reads(mode: int) -> int:
+    """0 = streaming loads, 1 = ordinary loads, 2 = by size (default); returns the previous choice (any other
+    value: no change)."""
+    return int(lib().skv_set_cache_reads(int(mode)))
 
 
 # ---- paged cache -------------------------------------------------------------------------------

@@ -83,7 +83,7 @@ __device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_
 constexpr int kMmaTileRows = 32;                 // rows a wave takes at a time
 constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel (bf16 elements; 80 bytes)
 
-template <int RK, int RV, int GT, int FMT>
+template <int RK, int RV, int GT, int FMT, bool NT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
   // Quantised builds (ranks are multiples of 32 there) use the 32-deep matrix instruction: the contraction index
@@ -180,47 +180,50 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     const int row0 = t0 + tile * kMmaTileRows;
     const int64_t base = tile_base(row0);
     if (row0 + kMmaTileRows <= t1) {
-      // A whole tile (all but the last of a range): one address per stream and lane, the rest are constant offsets.
-      const uint32_t* ksrc = p.k_cache + (base + lm) * (RK / kElemsPerDword) + g * KRAW;
+      // A whole tile (all but the last of a range): one address per stream and lane, the rest are constant
+      // offsets; streaming or ordinary loads as the launch asks (NT).
+      {
+        const uint32_t* ksrc = p.k_cache + (base + lm) * (RK / kElemsPerDword) + g * KRAW;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const uint32_t* src = ksrc + 16 * kb * (RK / kElemsPerDword);
-        if constexpr (KRAW % 4 == 0) {
+        for (int kb = 0; kb < 2; ++kb) {
+          const uint32_t* src = ksrc + 16 * kb * (RK / kElemsPerDword);
+          if constexpr (KRAW % 4 == 0) {
 #pragma unroll
-          for (int k4 = 0; k4 < KRAW / 4; ++k4) {
-            const uint4 w = *reinterpret_cast<const uint4*>(src + 4 * k4);
-            tr.k[kb][4 * k4] = w.x; tr.k[kb][4 * k4 + 1] = w.y; tr.k[kb][4 * k4 + 2] = w.z; tr.k[kb][4 * k4 + 3] = w.w;
+            for (int k4 = 0; k4 < KRAW / 4; ++k4) {
+              const u32x4 w = load_cache<NT>(reinterpret_cast<const u32x4*>(src + 4 * k4));
+              tr.k[kb][4 * k4] = w.x; tr.k[kb][4 * k4 + 1] = w.y; tr.k[kb][4 * k4 + 2] = w.z; tr.k[kb][4 * k4 + 3] = w.w;
+            }
+          } else if constexpr (KRAW % 2 == 0) {
+#pragma unroll
+            for (int k2 = 0; k2 < KRAW / 2; ++k2) {
+              const u32x2 w = load_cache<NT>(reinterpret_cast<const u32x2*>(src + 2 * k2));
+              tr.k[kb][2 * k2] = w.x; tr.k[kb][2 * k2 + 1] = w.y;
+            }
+          } else {
+#pragma unroll
+            for (int k1 = 0; k1 < KRAW; ++k1) tr.k[kb][k1] = load_cache<NT>(src + k1);
           }
-        } else if constexpr (KRAW % 2 == 0) {
+        }
 #pragma unroll
-          for (int k2 = 0; k2 < KRAW / 2; ++k2) {
-            const uint2 w = *reinterpret_cast<const uint2*>(src + 2 * k2);
-            tr.k[kb][2 * k2] = w.x; tr.k[kb][2 * k2 + 1] = w.y;
+        for (int u = 0; u < VPL; ++u) {
+          const int i = lane + 64 * u;
+          if (VUNITS % 64 == 0 || i < VUNITS) {
+            const int cw = i % VWORDS, kg = i / VWORDS;
+            const uint32_t* vsrc = p.v_cache + (base + 8 * kg) * VWORDS + cw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tr.v[u][e] = load_cache<NT>(vsrc + e * VWORDS);
           }
-        } else {
-#pragma unroll
-          for (int k1 = 0; k1 < KRAW; ++k1) tr.k[kb][k1] = src[k1];
         }
-      }
-#pragma unroll
-      for (int u = 0; u < VPL; ++u) {
-        const int i = lane + 64 * u;
-        if (VUNITS % 64 == 0 || i < VUNITS) {
-          const int cw = i % VWORDS, kg = i / VWORDS;
-          const uint32_t* vsrc = p.v_cache + (base + 8 * kg) * VWORDS + cw;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) tr.v[u][e] = vsrc[e * VWORDS];
-        }
-      }
 #if SKV_Q8
-      const uint32_t* msrc = p.v_meta + (base + 4 * g) * NG;
+        const uint32_t* msrc = p.v_meta + (base + 4 * g) * NG;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+          for (int i = 0; i < 4; ++i)
 #pragma unroll
-          for (int gq = 0; gq < NG; ++gq) tr.vm[gq][kb][i] = msrc[(16 * kb + i) * NG + gq];
+            for (int gq = 0; gq < NG; ++gq) tr.vm[gq][kb][i] = load_cache<NT>(msrc + (16 * kb + i) * NG + gq);
 #endif
+      }
       return;
     }
     const int last = t1 - 1 - row0;                              // rows past it re-read it; their weights are zero

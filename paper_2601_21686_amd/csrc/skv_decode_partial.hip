@@ -93,40 +93,41 @@ struct RowMap {
   __device__ static constexpr int group_of_slot(int i) { return i < CA ? 0 : 1; }
 };
 
-#ifndef SKV_NT
-#define SKV_NT 0                 // 1: non-temporal loads of the cache (measured slightly slower)
-#endif
-#if SKV_NT
-#define SKV_LOAD(p) __builtin_nontemporal_load(p)
-#else
-#define SKV_LOAD(p) (*(p))
-#endif
+// Cache rows are loaded either with ordinary loads or, when the launch's rows cannot be found in a
+// cache again anyway (see DecodeParams::stream_loads), with streaming (non-temporal) ones.  The kind is a
+// template parameter of the range kernels: a run-time branch at the point of issue costs the steady-state
+// loop its exact wait counts (measured: 10-25 % slower).
+template <bool NT, typename T>
+__device__ __forceinline__ T load_cache(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int N>
+template <int N, bool NT>
 __device__ __forceinline__ void load_dwords(const uint32_t* p, uint32_t* w) {
   if constexpr (N == 1) {
-    w[0] = SKV_LOAD(p);
+    w[0] = load_cache<NT>(p);
   } else if constexpr (N == 2) {
-    const u32x2 v = SKV_LOAD(reinterpret_cast<const u32x2*>(p));
+    const u32x2 v = load_cache<NT>(reinterpret_cast<const u32x2*>(p));
     w[0] = v.x; w[1] = v.y;
   } else if constexpr (N == 3) {
-    w[0] = SKV_LOAD(p);
-    w[1] = SKV_LOAD(p + 1);
-    w[2] = SKV_LOAD(p + 2);
+    w[0] = load_cache<NT>(p);
+    w[1] = load_cache<NT>(p + 1);
+    w[2] = load_cache<NT>(p + 2);
   } else if constexpr (N == 4) {
-    const u32x4 v = SKV_LOAD(reinterpret_cast<const u32x4*>(p));
+    const u32x4 v = load_cache<NT>(reinterpret_cast<const u32x4*>(p));
     w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
   }
 }
 
-template <int R>
+template <int R, bool NT = false>
 __device__ __forceinline__ void load_row(const uint32_t* row, int j, uint32_t (&w)[RowMap<R>::DPL]) {
   using M = RowMap<R>;
-  load_dwords<M::DA>(row + j * M::DA, &w[0]);
-  if constexpr (M::DB > 0) load_dwords<M::DB>(row + M::SEG_B_DW + j * M::DB, &w[M::DA]);
+  load_dwords<M::DA, NT>(row + j * M::DA, &w[0]);
+  if constexpr (M::DB > 0) load_dwords<M::DB, NT>(row + M::SEG_B_DW + j * M::DB, &w[M::DA]);
 }
 
 template <int R>
@@ -199,7 +200,7 @@ struct TileRegs {
 // Requests 8*U rows of a wave.  row0 is this lane's first row; the lane's rows
 // are row0 + 8u.  With MASKED, rows >= t_end are redirected to row t_end-1 so
 // that nothing outside [0, n_ctx) is ever read.
-template <int RK, int RV, int U, bool MASKED>
+template <int RK, int RV, int U, bool MASKED, bool NT = false>
 __device__ __forceinline__ void issue_rows(const uint32_t* __restrict__ kbase,
                                            const uint32_t* __restrict__ vbase,
                                            const uint32_t* __restrict__ mbase, int row0, int t_end,
@@ -208,16 +209,16 @@ __device__ __forceinline__ void issue_rows(const uint32_t* __restrict__ kbase,
   for (int u = 0; u < U; ++u) {
     int row = row0 + 8 * u;
     if constexpr (MASKED) row = row < t_end ? row : t_end - 1;
-    load_row<RK>(kbase + (int64_t)row * RowMap<RK>::ROW_DW, j, t.kw[u]);
+    load_row<RK, NT>(kbase + (int64_t)row * RowMap<RK>::ROW_DW, j, t.kw[u]);
   }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int row = row0 + 8 * u;
     if constexpr (MASKED) row = row < t_end ? row : t_end - 1;
-    load_row<RV>(vbase + (int64_t)row * RowMap<RV>::ROW_DW, j, t.vw[u]);
+    load_row<RV, NT>(vbase + (int64_t)row * RowMap<RV>::ROW_DW, j, t.vw[u]);
 #if SKV_Q8
 #pragma unroll
-    for (int g = 0; g < RowMap<RV>::NG; ++g) t.vm[u][g] = SKV_LOAD(mbase + (int64_t)row * RowMap<RV>::NG + g);
+    for (int g = 0; g < RowMap<RV>::NG; ++g) t.vm[u][g] = load_cache<NT>(mbase + (int64_t)row * RowMap<RV>::NG + g);
 #endif
   }
 }
@@ -377,7 +378,7 @@ __device__ __forceinline__ void consume_rows(const TileRegs<RK, RV, U>& t, int r
 #if SKV_VECTOR_KERNEL
 // FMT only names the cache format in the kernel's symbol (0: bf16 rows, 1: 8-bit codes, 2: 4-bit codes,
 // 3: bf16 rows in pages, 4 and 5: 8- and 4-bit codes in pages).
-template <int RK, int RV, int GT, int FMT>
+template <int RK, int RV, int GT, int FMT, bool NT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
   using KM = RowMap<RK>;
@@ -466,8 +467,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     }
     const int page = __builtin_amdgcn_readlane(held, rel - held_first);
     const int64_t blk = ((int64_t)page * p.n_kv_heads + kv) << p.pages.page_shift;
-    issue_rows<RK, RV, U, false>(p.k_cache + blk * KM::ROW_DW, p.v_cache + blk * VM::ROW_DW, nullptr,
-                                 (r & page_rows_mask) + oct, 0, j, t);
+    issue_rows<RK, RV, U, false, NT>(p.k_cache + blk * KM::ROW_DW, p.v_cache + blk * VM::ROW_DW, nullptr,
+                                     (r & page_rows_mask) + oct, 0, j, t);
   };
   // the ragged tail: rows clamped to the last valid one, each looked up by itself
   auto issue_tail = [&](int row0, Tile& t) {
@@ -489,7 +490,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   const uint32_t* mbase = nullptr;
 #endif
   auto issue_full = [&](int tile_row, Tile& t) {
-    issue_rows<RK, RV, U, false>(kbase, vbase, mbase, tile_row + lane_row, t1, j, t);
+    issue_rows<RK, RV, U, false, NT>(kbase, vbase, mbase, tile_row + lane_row, t1, j, t);
   };
   auto issue_tail = [&](int row0, Tile& t) { issue_rows<RK, RV, U, true>(kbase, vbase, mbase, row0, t1, j, t); };
 #endif
@@ -681,6 +682,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 
 #include "skv_decode_mma.inl"
 
+// launches KERNEL<RK, RV, HEADS, format, kind of cache load>
+#define SKV_LAUNCH_BY_LOADS(KERNEL, HEADS)                                                           \
+  do {                                                                                               \
+    if (p.stream_loads) hipLaunchKernelGGL((KERNEL<RK, RV, HEADS, kFmt, true>), grid, block, 0, stream, p);  \
+    else hipLaunchKernelGGL((KERNEL<RK, RV, HEADS, kFmt, false>), grid, block, 0, stream, p);       \
+  } while (0)
+
 template <int RK, int RV>
 hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const int passes = p.group / heads;
@@ -690,19 +698,19 @@ hipError_t launch_rv(int heads, const DecodeParams& p, hipStream_t stream) {
   const dim3 block(kDecodeThreads);
   if (p.engine == 1) {
     switch (heads) {
-      case 1: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
-      case 2: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
-      case 4: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 4, kFmt>), grid, block, 0, stream, p); break;
-      case 8: hipLaunchKernelGGL((decode_partial_mma_kernel<RK, RV, 8, kFmt>), grid, block, 0, stream, p); break;
+      case 1: SKV_LAUNCH_BY_LOADS(decode_partial_mma_kernel, 1); break;
+      case 2: SKV_LAUNCH_BY_LOADS(decode_partial_mma_kernel, 2); break;
+      case 4: SKV_LAUNCH_BY_LOADS(decode_partial_mma_kernel, 4); break;
+      case 8: SKV_LAUNCH_BY_LOADS(decode_partial_mma_kernel, 8); break;
       default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
   }
 #if SKV_VECTOR_KERNEL
   switch (heads) {
-    case 1: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 1, kFmt>), grid, block, 0, stream, p); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 2, kFmt>), grid, block, 0, stream, p); break;
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<RK, RV, 4, kFmt>), grid, block, 0, stream, p); break;
+    case 1: SKV_LAUNCH_BY_LOADS(decode_partial_kernel, 1); break;
+    case 2: SKV_LAUNCH_BY_LOADS(decode_partial_kernel, 2); break;
+    case 4: SKV_LAUNCH_BY_LOADS(decode_partial_kernel, 4); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

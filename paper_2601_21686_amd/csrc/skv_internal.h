@@ -71,6 +71,8 @@ struct DecodeParams {
                              // clamp(seq_lens[b], 0, n_ctx - len_add) + len_add
   PageMap pages;             // paged cache: k_cache / v_cache are the pools
   int32_t engine;            // range kernel over bf16 rows: 0 = vector arithmetic, 1 = matrix cores
+  int32_t stream_loads;      // 1: the full tiles of the range kernel are read with streaming (non-temporal) loads,
+                             // for rows that will not be found in a cache again anyway; 0: ordinary loads
   float scale_log2e;         // softmax scale times log2(e)
   int32_t lift;              // combine: 1 = multiply by P_V^T into out [..][128]; 0 = leave rank-r_v coordinates in out [..][r_v]
 };
@@ -218,7 +220,8 @@ hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipSt
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 // reads workgroups * pieces_per_wg 16-byte pieces (pieces_per_wg a multiple of 1024), writes nothing
-hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream);
+hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, bool streaming,
+                              hipStream_t stream);
 hipError_t launch_stream_mix(const void* a, const void* b, void* c, size_t pieces_per_wg, int workgroups,
                              hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)

@@ -10,14 +10,21 @@ namespace {
 constexpr int kProbeThreads = 256;
 constexpr int kProbeUnroll = 4;
 
-__global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const uint4* __restrict__ src, size_t per_wg,
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// NT: streaming (non-temporal) loads, as the range kernels use them for rows that exceed the last-level cache.
+template <bool NT>
+__global__ __launch_bounds__(kProbeThreads) void stream_read_kernel(const u32x4* __restrict__ src, size_t per_wg,
                                                                   float* sink) {
-  const uint4* p = src + (size_t)blockIdx.x * per_wg;
+  const u32x4* p = src + (size_t)blockIdx.x * per_wg;
   float acc = 0.f;
   for (size_t i = threadIdx.x; i < per_wg; i += kProbeThreads * kProbeUnroll) {   // per_wg is a multiple of the stride
-    uint4 v[kProbeUnroll];
+    u32x4 v[kProbeUnroll];
 #pragma unroll
-    for (int u = 0; u < kProbeUnroll; ++u) v[u] = p[i + (size_t)u * kProbeThreads];
+    for (int u = 0; u < kProbeUnroll; ++u) {
+      if constexpr (NT) v[u] = __builtin_nontemporal_load(p + i + (size_t)u * kProbeThreads);
+      else v[u] = p[i + (size_t)u * kProbeThreads];
+    }
 #pragma unroll
     for (int u = 0; u < kProbeUnroll; ++u) acc += __uint_as_float(v[u].x ^ v[u].y ^ v[u].z ^ v[u].w);
   }
@@ -51,9 +58,14 @@ hipError_t launch_stream_mix(const void* a, const void* b, void* c, size_t piece
   return hipGetLastError();
 }
 
-hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, hipStream_t stream) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,
-                     static_cast<const uint4*>(src), pieces_per_wg, static_cast<float*>(sink));
+hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, bool streaming,
+                              hipStream_t stream) {
+  if (streaming)
+    hipLaunchKernelGGL(stream_read_kernel<true>, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,
+                       static_cast<const u32x4*>(src), pieces_per_wg, static_cast<float*>(sink));
+  else
+    hipLaunchKernelGGL(stream_read_kernel<false>, dim3((unsigned)workgroups), dim3(kProbeThreads), 0, stream,
+                       static_cast<const u32x4*>(src), pieces_per_wg, static_cast<float*>(sink));
   return hipGetLastError();
 }
 

@@ -28,10 +28,14 @@ def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
 
 
-@pytest.fixture(params=[0, 1], ids=["vector", "matrix"])
+@pytest.fixture(params=[(0, 2), (1, 2), (0, 0), (1, 0)], ids=["vector", "matrix", "vector-streamed", "matrix-streamed"])
 def decode_engine(request):
-    """Runs a test once per range kernel over bf16 rows (vector arithmetic, matrix cores)."""
+    """Runs a test once per range kernel over bf16 rows (vector arithmetic, matrix cores) and per kind of
+    cache load (chosen by size, which means ordinary loads at test sizes; streaming loads forced)."""
     from paper_2601_21686_amd import binding
-    before = binding.skv_set_decode_engine(request.param)
-    yield request.param
+    engine, reads = request.param
+    before = binding.skv_set_decode_engine(engine)
+    before_reads = binding.skv_set_cache_reads(reads)
+    yield engine
     binding.skv_set_decode_engine(before)
+    binding.skv_set_cache_reads(before_reads)

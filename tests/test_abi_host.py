@@ -368,6 +368,17 @@ def test_decode_engine_switch():
     assert lib.skv_set_decode_engine(-1) == 2
 
 
+def test_cache_read_mode_switch():
+    lib = B.lib()
+    before = lib.skv_set_cache_reads(0)
+    assert before == 2                                  # by size unless told otherwise
+    assert lib.skv_set_cache_reads(-1) == 0             # anything but 0, 1, 2 changes nothing
+    assert lib.skv_set_cache_reads(3) == 0
+    assert lib.skv_set_cache_reads(1) == 0
+    assert lib.skv_set_cache_reads(before) == 1
+    assert lib.skv_set_cache_reads(-1) == 2
+
+
 def test_read_probe_argument_checks():
     lib = B.lib()
     n = C.c_size_t(0)
