@@ -253,3 +253,20 @@ def test_decode_steps_captured_in_a_hip_graph_replay_identically():
         torch.cuda.synchronize()
         assert torch.equal(outs, eager), rep
         assert torch.equal(P.gpu.k_cache.view(torch.int16), cache_after.view(torch.int16)), rep
+
+
+@pytest.mark.parametrize("r_k,r_v,hq,hkv", [(64, 64, 8, 2), (48, 80, 4, 4), (32, 128, 16, 2)])
+def test_kind_of_cache_load_does_not_change_a_bit(r_k, r_v, hq, hkv):
+    """Streaming and ordinary loads fetch the same bytes: outputs agree bit for bit, per engine."""
+    n = 2100
+    P = _filled_pair(("loads", r_k, r_v), 2, hq, hkv, r_k, r_v, n)
+    q = P.queries(3)
+    before = B.skv_set_cache_reads(1)
+    try:
+        plain = P.gpu_decode(q, n)
+        B.skv_set_cache_reads(0)
+        streamed = P.gpu_decode(q, n)
+    finally:
+        B.skv_set_cache_reads(before)
+    assert np.array_equal(plain, streamed)
+    assert vec_rel_err(plain, P.oracle_decode(q, n)) <= TOL
