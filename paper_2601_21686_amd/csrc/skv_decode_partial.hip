@@ -171,9 +171,34 @@ __device__ __forceinline__ float octet_sum(float x) {
   return x;
 }
 
+// Sum / maximum over the 8 lanes that sit 8, 16 and 32 apart (the same slot of the wave's 8 octets); every
+// lane receives the same bits.  The exchanges are vector instructions: a rotation by 8 inside a row of 16
+// lanes, then the swaps of odd and even rows and of the two halves of the wave.  (The same tree as three
+// shuffles, with the same bits, without the round trips through the LDS pipeline: the end-of-range merge
+// of 40-odd values per lane took 2.4 us with shuffles.)
+__device__ __forceinline__ float rows_pair(float x, bool take_max) {
+  const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return take_max ? fmaxf(__uint_as_float(r.x), __uint_as_float(r.y)) : __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+__device__ __forceinline__ float halves_pair(float x, bool take_max) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return take_max ? fmaxf(__uint_as_float(r.x), __uint_as_float(r.y)) : __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+__device__ __forceinline__ float octets_sum(float x) {
+  x += dpp_f32<0x128>(x);          // row_ror:8: lane i <-> i ^ 8
+  return halves_pair(rows_pair(x, false), false);
+}
+__device__ __forceinline__ float octets_max(float x) {
+  x = fmaxf(x, dpp_f32<0x128>(x));
+  return halves_pair(rows_pair(x, true), true);
+}
+
 // Build-time tunables (defaults are the measured best on MI355X).
 #ifndef SKV_DW_IN_FLIGHT
 #define SKV_DW_IN_FLIGHT 8       // dwords of keys (and of values) one lane requests per tile
+#endif
+#ifndef SKV_EARLY_TILES
+#define SKV_EARLY_TILES 6        // tiles requested before the in-kernel query projection (>= 2; 4: +1 us, 8: the same)
 #endif
 #ifndef SKV_PIPELINE
 #define SKV_PIPELINE 1           // tiles requested ahead of the one being computed on (>= 1)
@@ -500,8 +525,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   //      here: q~ = (q P_K) * scale * log2(e), the same sums as the projection kernel.  Either way the
   //      first tile of the range is requested before the queries are waited for. -----------------
   float qreg[GT][KM::CPL];
-  Tile tb;                                       // second tile of the range, when requested early
-  bool pre2 = false;
+  // Tiles 1 .. kEarlyTiles-1 of the range, requested together with tile 0 ahead of the query projection:
+  // the projection takes about as long as four tiles take to arrive at the steady rate.
+  constexpr int kEarlyTiles = SKV_EARLY_TILES;
+  Tile early[kEarlyTiles - 1];
+  bool pre = false;
 #if !SKV_Q8
   if (p.q != nullptr) {
     ProjectPieces pp;
@@ -512,9 +540,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
       if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) qraw[k] = qptr[tid + k * kDecodeThreads];
     if (n_full > 0) issue_full(t0, ta);
-    // the projection below takes about as long as a round trip to HBM: keep a second tile on its way
-    pre2 = SKV_PIPELINE == 1 && n_full >= 3;
-    if (pre2) issue_full(t0 + ROWS_PER_WG, tb);
+    pre = SKV_PIPELINE == 1 && n_full >= kEarlyTiles + 1;
+    if (pre) {
+#pragma unroll
+      for (int k = 1; k < kEarlyTiles; ++k) issue_full(t0 + k * ROWS_PER_WG, early[k - 1]);
+    }
 #pragma unroll
     for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
       if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) px_s[tid + k * kDecodeThreads] = bf16_to_f32(qraw[k]);
@@ -575,12 +605,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
       if (k < n_full) issue_full(t0 + k * ROWS_PER_WG, ring[k]);
     int i = 0;
     if constexpr (NBUF == 2) {
-      if (pre2) {                                   // tiles 0 and 1 are both on their way (n_full >= 3)
-        ring[1] = tb;
+      if (pre) {                                    // tiles 0 .. kEarlyTiles-1 are on their way (n_full > kEarlyTiles)
         consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
-        issue_full(t0 + 2 * ROWS_PER_WG, ring[0]);
-        consume_rows<RK, RV, GT, U, false>(ring[1], 0, t1, qd, qreg, m, l, acc, zacc);
-        i = 2;                                      // ring[0] holds tile 2: the loop's invariant
+#pragma unroll
+        for (int k = 1; k < kEarlyTiles; ++k) {
+          if (k == kEarlyTiles - 1) issue_full(t0 + kEarlyTiles * ROWS_PER_WG, ring[0]);
+          consume_rows<RK, RV, GT, U, false>(early[k - 1], 0, t1, qd, qreg, m, l, acc, zacc);
+        }
+        i = kEarlyTiles;                            // ring[0] holds that tile: the loop's invariant
       }
     }
     if constexpr (NBUF > 1) {
@@ -620,27 +652,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   // ---- merge the 8 octet streams of the wave (lanes 8, 16, 32 apart) ---------------------
 #pragma unroll
   for (int a = 0; a < HL; ++a) {
-    float mw = m[a];
-    mw = fmaxf(mw, __shfl_xor(mw, 8));
-    mw = fmaxf(mw, __shfl_xor(mw, 16));
-    mw = fmaxf(mw, __shfl_xor(mw, 32));
+    const float mw = octets_max(m[a]);
     const float f = fast_exp2(m[a] - mw);
-    float lg = l[a] * f;
-    lg += __shfl_xor(lg, 8);
-    lg += __shfl_xor(lg, 16);
-    lg += __shfl_xor(lg, 32);
-    l[a] = lg;
+    l[a] = octets_sum(l[a] * f);
     m[a] = mw;
 #pragma unroll
     for (int half = 0; half < (HS::kSplit ? 2 : 1); ++half) {
       const float fh = half == 0 ? f : dpp_f32<0x141>(f);   // slot HL+a: the mirror lane's head
 #pragma unroll
       for (int i = 0; i < VM::CPL; ++i) {
-        float x = acc[half * HL + a][i] * fh;
-        x += __shfl_xor(x, 8);
-        x += __shfl_xor(x, 16);
-        x += __shfl_xor(x, 32);
-        acc[half * HL + a][i] = x;
+        acc[half * HL + a][i] = octets_sum(acc[half * HL + a][i] * fh);
       }
     }
   }
