@@ -28,6 +28,8 @@
 // an octet each finish half of the query heads; each octet runs its own
 // online-softmax stream and streams are merged once at the end.
 // The projected query q~ comes from the projection kernel (skv_project.hip) or is computed here.
+// Both range kernels exist with ordinary and with streaming (non-temporal) loads of the cache rows
+// (last template argument); the launcher picks per launch (DecodeParams::stream_loads).
 //
 // Parts: this file holds the cache-format description, the vector-arithmetic range kernel and the
 // launchers; skv_decode_fresh.inl the extra workgroups of a fused decode step (the new rows);
