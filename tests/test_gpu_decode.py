@@ -270,3 +270,21 @@ def test_kind_of_cache_load_does_not_change_a_bit(r_k, r_v, hq, hkv):
         B.skv_set_cache_reads(before)
     assert np.array_equal(plain, streamed)
     assert vec_rel_err(plain, P.oracle_decode(q, n)) <= TOL
+
+
+@pytest.mark.parametrize("r,tile_rows", [(16, 256), (64, 64), (128, 32)])
+@pytest.mark.parametrize("tiles", [5, 6, 7, 8])
+@pytest.mark.parametrize("extra", [0, 1, -1])
+def test_ranges_around_the_early_request_depth(r, tile_rows, tiles, extra):
+    """The range kernel that projects its queries itself requests several tiles before the projection when the
+    range is long enough; ranges of just below, at and above that length, with and without a ragged tail, in one
+    range and in three."""
+    n = tile_rows * tiles + (extra if extra >= 0 else tile_rows - 1)
+    P = _filled_pair(("early", r), 1, 4, 1, r, r, 3 * n)
+    q = P.queries(5)
+    for n_splits, n_ctx in ((1, n), (3, 3 * n)):
+        out = torch.empty((1, 4, 128), dtype=torch.float32, device="cuda")
+        B.skv_decode_partial_q(P.gpu, q, n_ctx, n_splits)
+        B.skv_decode_combine(P.gpu, out, n_splits)
+        torch.cuda.synchronize()
+        assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
