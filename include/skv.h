@@ -534,6 +534,22 @@ skv_status skv_paged_decode_step(const skv_paged_layer* paged, const void* k_new
 skv_status skv_paged_prefill_attention(const skv_paged_layer* paged, const void* q, int64_t q_stride_b,
                                        int64_t q_stride_t, int64_t q_stride_h, void* out, int32_t T,
                                        int64_t n_prev, float scale, int32_t mode, void* stream);
+/*
+ * The folded-weights variant (Sec. 3.4 "Overheads") over bf16 pages: as skv_append_projected,
+ * skv_decode_attention_folded and skv_decode_step_folded (same arguments, layouts and errors; the bases of
+ * paged->layer may be NULL), with the rows of sequence b at [cur_lens[b], cur_lens[b] + T) resp.
+ * [0, seq_lens[b]) of its pages; cur_lens / seq_lens as in the paged calls above (NULL: every sequence at
+ * max_cur_len / max_len).  SHAPE for quantised pages.
+ */
+skv_status skv_paged_append_projected(const skv_paged_layer* paged, const void* k_low, const void* v_low, int32_t T,
+                                      const int32_t* cur_lens, int64_t max_cur_len, void* stream);
+skv_status skv_paged_decode_attention_folded(const skv_paged_layer* paged, const void* q_low, void* out_low,
+                                             const int32_t* seq_lens, int64_t max_len, float scale,
+                                             void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_paged_decode_step_folded(const skv_paged_layer* paged, const void* k_low, const void* v_low, int32_t T,
+                                        const int32_t* cur_lens, int64_t max_cur_len, const void* q_low,
+                                        void* out_low, float scale, void* workspace, size_t workspace_bytes,
+                                        void* stream);
 
 /*
  * Which kernel streams the cache in the decode calls: 0 = vector arithmetic, 1 = matrix cores (the

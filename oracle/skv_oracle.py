@@ -471,6 +471,32 @@ def decode_attention_folded(layer: OracleLayer, q_low: np.ndarray, n_ctx: int,
     return out
 
 
+def paged_append_projected(layer: OracleLayer, cache: OraclePagedCache, k_low: np.ndarray, v_low: np.ndarray,
+                           cur_lens) -> None:
+    """append_projected into the paged cache: the T already-projected rows of sequence b become its rows
+    [cur_lens[b], cur_lens[b] + T)."""
+    T = np.asarray(k_low).shape[1]
+    tmp = new_layer(layer.batch, layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.p_k, layer.p_v,
+                    max(1, T), layer.store)
+    append_projected(tmp, k_low, v_low, 0)
+    for b in range(layer.batch):
+        paged_store_rows(cache.k_pool, cache.block_table[b], cache.page_tokens, int(cur_lens[b]), tmp.k_cache[b, :, :T])
+        paged_store_rows(cache.v_pool, cache.block_table[b], cache.page_tokens, int(cur_lens[b]), tmp.v_cache[b, :, :T])
+
+
+def paged_decode_attention_folded(layer: OracleLayer, cache: OraclePagedCache, q_low: np.ndarray, seq_lens,
+                                  scale: float | None = None) -> np.ndarray:
+    """decode_attention_folded over the rows the block table names, sequence b over its first seq_lens[b]
+    rows (zeros for a sequence without rows)."""
+    q_low = np.asarray(q_low, np.float64)
+    flat = paged_as_contiguous(layer, cache, seq_lens)
+    out = np.zeros((layer.batch, layer.n_q_heads, layer.r_v), np.float64)
+    for b in range(layer.batch):
+        if int(seq_lens[b]) > 0:
+            out[b] = decode_attention_folded(_one_sequence(flat, b), q_low[b:b + 1], int(seq_lens[b]), scale)[0]
+    return out
+
+
 # --------------------------------------------------------------------------
 # App. A.1 Eq. 18 with a whole chunk of queries (prefill over the compressed cache)
 # --------------------------------------------------------------------------

@@ -38,6 +38,7 @@ EXPORTS = (
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
     "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_set_cache_reads", "skv_probe_stream_read", "skv_probe_stream_mix", "skv_paged_decode_default_splits",
+    "skv_paged_append_projected", "skv_paged_decode_attention_folded", "skv_paged_decode_step_folded",
 )
 
 
@@ -169,6 +170,12 @@ def lib() -> C.CDLL:
     L.skv_paged_decode_step.restype = C.c_int
     L.skv_paged_prefill_attention.argtypes = [PP, vp, i64, i64, i64, vp, i32, i64, C.c_float, i32, vp]
     L.skv_paged_prefill_attention.restype = C.c_int
+    L.skv_paged_append_projected.argtypes = [PP, vp, vp, i32, vp, i64, vp]
+    L.skv_paged_append_projected.restype = C.c_int
+    L.skv_paged_decode_attention_folded.argtypes = [PP, vp, vp, vp, i64, C.c_float, vp, sz, vp]
+    L.skv_paged_decode_attention_folded.restype = C.c_int
+    L.skv_paged_decode_step_folded.argtypes = [PP, vp, vp, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
+    L.skv_paged_decode_step_folded.restype = C.c_int
     L.skv_probe_stream_read.argtypes = [vp, sz, i32, vp, C.POINTER(C.c_size_t), vp]
     L.skv_probe_stream_read.restype = C.c_int
     L.skv_probe_stream_mix.argtypes = [vp, vp, vp, sz, i32, C.POINTER(C.c_size_t), vp]
@@ -615,6 +622,39 @@ def skv_paged_decode_step(layer: PagedLayer, k_new: torch.Tensor, v_new: torch.T
                                        int(k_new.shape[1]), _lens_ptr(cur_lens, layer.batch), int(max_cur_len),
                                        q.data_ptr(), out.data_ptr(), float(scale), ws.data_ptr(),
                                        ws.numel() * ws.element_size(), _stream_ptr(stream)), "skv_paged_decode_step")
+
+
+def skv_paged_append_projected(layer: PagedLayer, k_low: torch.Tensor, v_low: torch.Tensor, cur_lens,
+                               max_cur_len: int, stream=None) -> None:
+    """k_low: bf16 CUDA [batch, T, n_kv_heads, r_k] contiguous, v_low likewise with r_v; cur_lens: int32 CUDA
+    [batch] or None."""
+    assert k_low.dtype == torch.bfloat16 and v_low.dtype == torch.bfloat16
+    assert k_low.is_contiguous() and v_low.is_contiguous()
+    _check(lib().skv_paged_append_projected(C.byref(layer.c), k_low.data_ptr(), v_low.data_ptr(), int(k_low.shape[1]),
+                                            _lens_ptr(cur_lens, layer.batch), int(max_cur_len), _stream_ptr(stream)),
+           "skv_paged_append_projected")
+
+
+def skv_paged_decode_attention_folded(layer: PagedLayer, q_low: torch.Tensor, out_low: torch.Tensor, seq_lens,
+                                      max_len: int, scale: float = 0.0, workspace: torch.Tensor | None = None,
+                                      stream=None) -> None:
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_paged_decode_attention_folded(C.byref(layer.c), q_low.data_ptr(), out_low.data_ptr(),
+                                                   _lens_ptr(seq_lens, layer.batch), int(max_len), float(scale),
+                                                   ws.data_ptr(), ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_paged_decode_attention_folded")
+
+
+def skv_paged_decode_step_folded(layer: PagedLayer, k_low: torch.Tensor, v_low: torch.Tensor, cur_lens,
+                                 max_cur_len: int, q_low: torch.Tensor, out_low: torch.Tensor, scale: float = 0.0,
+                                 workspace: torch.Tensor | None = None, stream=None) -> None:
+    assert k_low.is_contiguous() and v_low.is_contiguous()
+    ws = layer.workspace() if workspace is None else workspace
+    _check(lib().skv_paged_decode_step_folded(C.byref(layer.c), k_low.data_ptr(), v_low.data_ptr(), int(k_low.shape[1]),
+                                              _lens_ptr(cur_lens, layer.batch), int(max_cur_len), q_low.data_ptr(),
+                                              out_low.data_ptr(), float(scale), ws.data_ptr(),
+                                              ws.numel() * ws.element_size(), _stream_ptr(stream)),
+           "skv_paged_decode_step_folded")
 
 
 def skv_paged_prefill_attention(layer: PagedLayer, q: torch.Tensor, out: torch.Tensor, n_prev: int,

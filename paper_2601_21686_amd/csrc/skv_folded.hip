@@ -11,6 +11,7 @@ namespace {
 // Tasks of one launch, chosen by blockIdx.y + first_task: 0 places key rows, 1 places value
 // rows, 2 scales the projected queries.
 //   0, 1: one 16-byte piece per thread, rows [b][t][h][r] packed -> cache [b][h][cur_len + t][r]
+//         (or the page the block table names for that row)
 //   2:    q~ = q_low * scale * log2(e), float32, into the workspace
 __global__ __launch_bounds__(256) void folded_kernel(const AppendParams p, const DecodeParams dp, const int first_task) {
   const int task = (int)blockIdx.y + first_task;
@@ -33,7 +34,7 @@ __global__ __launch_bounds__(256) void folded_kernel(const AppendParams p, const
     const int64_t bt = row / p.n_kv_heads;
     const int t = (int)(bt % p.T);
     const int64_t b = bt / p.T;
-    const int64_t drow = (b * p.n_kv_heads + h) * p.capacity + clamped_len(p.cur_lens, (int)b, p.cur_len) + t;
+    const int64_t drow = cache_row(p.pages, p.capacity, p.n_kv_heads, (int)b, h, clamped_len(p.cur_lens, (int)b, p.cur_len) + t);
     dst[drow * pieces + piece] = src[i];
   }
 }

@@ -426,11 +426,11 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
     p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
     p.engine = decode_engine_for(p.group, bits);
   }
-  if (pages) {                                   // quantised rows in pages: the matrix-core kernel only
+  if (pages) {
     p.pages = *pages;
-    p.engine = 1;
+    if (q8) p.engine = 1;                        // quantised rows in pages: the matrix-core kernel only
   }
-  decode_partial_launcher launch = !q8     ? partial_launcher_for(L->r_k)
+  decode_partial_launcher launch = !q8     ? (pages ? paged_partial_launcher_for(L->r_k) : partial_launcher_for(L->r_k))
                                    : pages ? paged_partial_q_launcher_for(bits, L->r_k)
                                            : partial_q_launcher_for(bits, L->r_k);
   if (!launch) return SKV_ERR_RANK;
@@ -997,8 +997,9 @@ skv_status check_folded_decode(const skv_layer* L, const void* q_low, const void
 
 // Range kernel, then the merge of the ranges without the lift: out_low stays in rank-r_V coordinates.
 skv_status run_folded_attention(const skv_layer* L, void* out_low, int64_t n_ctx, int32_t s, void* workspace,
-                                void* stream) {
-  const skv_status st = run_partial(L, n_ctx, s, workspace, stream);
+                                void* stream, const int32_t* seq_lens = nullptr, int32_t len_add = 0,
+                                const PageMap* pages = nullptr) {
+  const skv_status st = run_partial(L, n_ctx, s, workspace, stream, nullptr, 8, seq_lens, len_add, pages);
   if (st != SKV_OK) return st;
   DecodeParams cp;
   fill_decode_params(L, &cp, s, workspace);
@@ -1023,9 +1024,9 @@ skv_q8_layer paged_quant_view(const skv_paged_layer* P) {
 }
 
 // The paged layer's checks; fills the device-side description of its page table.
-skv_status check_paged(const skv_paged_layer* P, PageMap* pm) {
+skv_status check_paged(const skv_paged_layer* P, PageMap* pm, bool need_bases = true) {
   if (!P) return SKV_ERR_NULL;
-  const skv_status st = check_layer(&P->layer);
+  const skv_status st = check_layer(&P->layer, need_bases);
   if (st != SKV_OK) return st;
   if (!P->block_table) return SKV_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(P->block_table) & 3u) return SKV_ERR_ALIGN;
@@ -1281,6 +1282,75 @@ skv_status skv_paged_prefill_attention(const skv_paged_layer* P, const void* q, 
   st = check_q_strides(q_stride_b, q_stride_t, q_stride_h);
   if (st != SKV_OK) return st;
   return run_prefill(&P->layer, false, q, q_stride_b, q_stride_t, q_stride_h, out, T, n_prev, scale, mode, stream, &pm);
+}
+
+// Folded-weights variant over bf16 pages: rows arrive projected, queries projected, outputs stay in rank-r_V
+// coordinates; only where a row lives differs from the contiguous calls.
+skv_status skv_paged_append_projected(const skv_paged_layer* P, const void* k_low, const void* v_low, int32_t T,
+                                      const int32_t* cur_lens, int64_t max_cur_len, void* stream) {
+  PageMap pm;
+  skv_status st = check_paged(P, &pm, false);
+  if (st != SKV_OK) return st;
+  if (P->code_bits != 0) return SKV_ERR_SHAPE;             // offered over bf16 pages only
+  st = check_folded_append(&P->layer, k_low, v_low, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  if (T == 0) return SKV_OK;
+  AppendParams p;
+  fill_append_params(&P->layer, &p, k_low, v_low, 0, 0, 0, T, max_cur_len);
+  p.cur_lens = cur_lens;
+  p.pages = pm;
+  if (launch_copy_projected(p, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return SKV_OK;
+}
+
+skv_status skv_paged_decode_attention_folded(const skv_paged_layer* P, const void* q_low, void* out_low,
+                                             const int32_t* seq_lens, int64_t max_len, float scale, void* workspace,
+                                             size_t workspace_bytes, void* stream) {
+  PageMap pm;
+  skv_status st = check_paged(P, &pm, false);
+  if (st != SKV_OK) return st;
+  if (P->code_bits != 0) return SKV_ERR_SHAPE;
+  const skv_layer* L = &P->layer;
+  int32_t s = 0;
+  st = check_folded_decode(L, q_low, out_low, max_len, scale, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return SKV_ERR_ALIGN;
+  DecodeParams qp;
+  fill_query_params(L, &qp, q_low, scale, workspace);
+  if (launch_scale_query(qp, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
+  return run_folded_attention(L, out_low, max_len, s, workspace, stream, seq_lens, 0, &pm);
+}
+
+skv_status skv_paged_decode_step_folded(const skv_paged_layer* P, const void* k_low, const void* v_low, int32_t T,
+                                        const int32_t* cur_lens, int64_t max_cur_len, const void* q_low,
+                                        void* out_low, float scale, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+  PageMap pm;
+  skv_status st = check_paged(P, &pm, false);
+  if (st != SKV_OK) return st;
+  if (P->code_bits != 0) return SKV_ERR_SHAPE;
+  const skv_layer* L = &P->layer;
+  st = check_folded_append(L, k_low, v_low, T, max_cur_len);
+  if (st != SKV_OK) return st;
+  if (reinterpret_cast<uintptr_t>(cur_lens) & 3u) return SKV_ERR_ALIGN;
+  const int64_t n_ctx = max_cur_len + T;
+  int32_t s = 0;
+  st = check_folded_decode(L, q_low, out_low, n_ctx, scale, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  hipStream_t hs = static_cast<hipStream_t>(stream);
+  DecodeParams qp;
+  fill_query_params(L, &qp, q_low, scale, workspace);
+  if (T > 0) {
+    AppendParams ap;
+    fill_append_params(L, &ap, k_low, v_low, 0, 0, 0, T, max_cur_len);
+    ap.cur_lens = cur_lens;
+    ap.pages = pm;
+    if (launch_folded_prepare(ap, qp, hs) != hipSuccess) return SKV_ERR_HIP;
+  } else if (launch_scale_query(qp, hs) != hipSuccess) {
+    return SKV_ERR_HIP;
+  }
+  return run_folded_attention(L, out_low, n_ctx, s, workspace, stream, cur_lens, T, &pm);
 }
 
 int32_t skv_padded_rank(int32_t r) {

@@ -397,6 +397,29 @@ def test_mix_probe_argument_checks():
     assert lib.skv_probe_stream_mix(FAKE, FAKE, FAKE, 1000, 4, C.byref(n), None) == B.SKV_ERR_SHAPE   # less than a slice each
 
 
+def test_paged_folded_argument_checks():
+    lib = B.lib()
+    big = 1 << 30
+    P = B.skv_paged_layer(_layer(capacity=64 * 16, p_k=None, p_v=None), FAKE, 64, 100, 16)     # no bases needed
+    app = lambda p, T, cur: lib.skv_paged_append_projected(C.byref(p), FAKE, FAKE, T, None, cur, None)
+    assert app(P, 0, 10) == B.SKV_OK
+    assert app(P, 4, 1021) == B.SKV_ERR_CAPACITY
+    assert app(P, -1, 0) == B.SKV_ERR_SHAPE
+    assert lib.skv_paged_append_projected(C.byref(P), None, FAKE, 4, None, 0, None) == B.SKV_ERR_NULL
+    assert lib.skv_paged_append_projected(C.byref(P), FAKE, FAKE, 4, FAKE + 2, 0, None) == B.SKV_ERR_ALIGN
+    att = lambda p, n, ws=big: lib.skv_paged_decode_attention_folded(C.byref(p), FAKE, FAKE, None, n, 0.0, FAKE, ws, None)
+    assert att(P, 0) == B.SKV_ERR_CAPACITY
+    assert att(P, 1025) == B.SKV_ERR_CAPACITY
+    assert att(P, 100, 64) == B.SKV_ERR_WORKSPACE
+    Q = B.skv_paged_layer(_layer(capacity=64 * 16), FAKE, 64, 100, 16, 8, FAKE, FAKE, FAKE)
+    assert app(Q, 4, 0) == B.SKV_ERR_SHAPE                                                  # bf16 pages only
+    assert att(Q, 100) == B.SKV_ERR_SHAPE
+    assert lib.skv_paged_decode_step_folded(C.byref(Q), FAKE, FAKE, 1, None, 10, FAKE, FAKE, 0.0, FAKE, big, None) == B.SKV_ERR_SHAPE
+    assert lib.skv_paged_decode_step_folded(C.byref(P), FAKE, FAKE, 1, None, 1024, FAKE, FAKE, 0.0, FAKE, big, None) == B.SKV_ERR_CAPACITY
+    bad = B.skv_paged_layer(_layer(capacity=64 * 16, p_k=None, p_v=None), FAKE, 48, 100, 16)
+    assert app(bad, 4, 0) == B.SKV_ERR_SHAPE                                                # page size not a power of two
+
+
 def test_paged_quantised_argument_checks():
     lib = B.lib()
     big = 1 << 30

@@ -304,3 +304,61 @@ def test_paged_decode_steps_in_a_hip_graph_replay_identically():
         torch.cuda.synchronize()
         assert torch.equal(outs, eager), rep
         assert torch.equal(P.gpu.k_pool.view(torch.int16), pool_after.view(torch.int16)), rep
+
+
+@pytest.mark.parametrize("r_k,r_v,hq,hkv", [(64, 64, 8, 2), (48, 80, 4, 4), (32, 128, 16, 2)])
+@pytest.mark.parametrize("page_tokens", [64, 128])
+def test_paged_folded_variant_places_rows_exactly_and_matches_the_oracle(r_k, r_v, hq, hkv, page_tokens):
+    # rows and queries arrive projected (what a model with folded weights hands over); outputs stay in rank-r_V
+    # coordinates.  Placement is a copy, so the pools must match bit for bit; rows nobody wrote keep the sentinel.
+    batch, lens, T = 3, [0, 70, 300], 37
+    P = PagedPair(("pg-fold", r_k, r_v, page_tokens), batch, hq, hkv, r_k, r_v, page_tokens, 8)
+    P.fill(9, lens)
+    g = torch.Generator(device="cuda").manual_seed(7)
+    k_low = torch.randn((batch, T, hkv, r_k), generator=g, device="cuda").to(torch.bfloat16)
+    v_low = torch.randn((batch, T, hkv, r_v), generator=g, device="cuda").to(torch.bfloat16)
+    q_low = torch.randn((batch, hq, r_k), generator=g, device="cuda").to(torch.bfloat16)
+    B.skv_paged_append_projected(P.gpu, k_low, v_low, _lens_t(lens), max(lens))
+    torch.cuda.synchronize()
+    O.paged_append_projected(P.ora, P.cache, _f64(k_low), _f64(v_low), lens)
+    gk, gv = P.pool_bits()
+    for got, want in ((gk, P.cache.k_pool), (gv, P.cache.v_pool)):
+        written = ~np.isnan(want)
+        assert np.all(got[~written] == SENTINEL)
+        rows_new = np.zeros(want.shape[:3], bool)               # the rows this call placed: exact copies
+        for b in range(batch):
+            for t in range(lens[b], lens[b] + T):
+                rows_new[P.table[b, t // page_tokens], :, t % page_tokens] = True
+        assert np.array_equal(got[rows_new], O.f64_to_bf16_bits(want[rows_new]))
+    cur = [n + T for n in lens]
+    out_low = torch.full((batch, hq, r_v), float("nan"), dtype=torch.float32, device="cuda")
+    for seq in (cur, [5, 0, 211]):
+        B.skv_paged_decode_attention_folded(P.gpu, q_low, out_low, _lens_t(seq), max(seq))
+        torch.cuda.synchronize()
+        want = O.paged_decode_attention_folded(P.ora, P.cache, _f64(q_low), seq)
+        got = out_low.cpu().numpy()
+        live = [b for b in range(batch) if seq[b] > 0]
+        assert vec_rel_err(got[live], want[live]) <= TOL
+        assert all(np.all(got[b] == 0.0) for b in range(batch) if seq[b] == 0)
+    # a step: one more projected row per sequence, then attention over it as well
+    k1 = torch.randn((batch, 1, hkv, r_k), generator=g, device="cuda").to(torch.bfloat16)
+    v1 = torch.randn((batch, 1, hkv, r_v), generator=g, device="cuda").to(torch.bfloat16)
+    B.skv_paged_decode_step_folded(P.gpu, k1, v1, _lens_t(cur), max(cur), q_low, out_low)
+    torch.cuda.synchronize()
+    O.paged_append_projected(P.ora, P.cache, _f64(k1), _f64(v1), cur)
+    want = O.paged_decode_attention_folded(P.ora, P.cache, _f64(q_low), [c + 1 for c in cur])
+    assert vec_rel_err(out_low.cpu().numpy(), want) <= TOL
+
+
+def test_paged_folded_uniform_length_equals_the_contiguous_folded_call():
+    P = PagedPair(("pg-fold-u",), 2, 8, 2, 64, 64, 64, 8)
+    n = 333
+    P.fill(4, [n, n])
+    L = P.contiguous_gpu([n, n])
+    g = torch.Generator(device="cuda").manual_seed(3)
+    q_low = torch.randn((2, 8, 64), generator=g, device="cuda").to(torch.bfloat16)
+    out, ref = (torch.empty((2, 8, 64), dtype=torch.float32, device="cuda") for _ in range(2))
+    B.skv_paged_decode_attention_folded(P.gpu, q_low, out, None, n)
+    B.skv_decode_attention_folded(L, q_low, ref, n)
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref)

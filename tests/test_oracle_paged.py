@@ -77,6 +77,36 @@ def test_paged_append_and_attention_equal_the_contiguous_layer(store):
     assert np.array_equal(O.paged_prefill_attention(layer, cache, qc, 21), O.prefill_attention(layer, qc, 21))
 
 
+def test_paged_folded_functions_equal_the_contiguous_ones_and_the_explicit_path():
+    # rows handed over already projected land where the projecting append puts them, and attention in the
+    # compressed space over the pages equals the contiguous one; lifted, it is the explicit attention
+    batch, hq, hkv, pt, r_k, r_v = 2, 4, 2, 8, 32, 48
+    layer, cache, rng = _setup(("paged-folded",), batch, hq, hkv, r_k, r_v, pt, 16, 4, "f64")
+    n = 21
+    k = rng.standard_normal((batch, n, hkv, 128))
+    v = rng.standard_normal((batch, n, hkv, 128))
+    O.project_append(layer, k, v, 0)
+    k_low = np.einsum("bthd,hdc->bthc", k, layer.p_k)
+    v_low = np.einsum("bthd,hdc->bthc", v, layer.p_v)
+    cur = np.zeros(batch, int)
+    for a, b_ in ((0, 7), (7, 8), (8, 21)):
+        O.paged_append_projected(layer, cache, k_low[:, a:b_], v_low[:, a:b_], cur)
+        cur += b_ - a
+    flat = O.paged_as_contiguous(layer, cache, [n, n])
+    assert np.allclose(flat.k_cache[:, :, :n], layer.k_cache[:, :, :n], rtol=0, atol=1e-12)
+    assert np.allclose(flat.v_cache[:, :, :n], layer.v_cache[:, :, :n], rtol=0, atol=1e-12)
+    q = rng.standard_normal((batch, hq, 128))
+    q_low = np.einsum("bgd,gdc->bgc", q, np.repeat(layer.p_k, hq // hkv, axis=0))
+    lens = [21, 6]
+    got = O.paged_decode_attention_folded(layer, cache, q_low, lens)
+    for b in range(batch):
+        want = O.decode_attention_folded(O._one_sequence(flat, b), q_low[b:b + 1], lens[b])[0]
+        assert np.array_equal(got[b], want)
+    lifted = np.einsum("bgc,gdc->bgd", got, np.repeat(layer.p_v, hq // hkv, axis=0))
+    assert np.allclose(lifted, O.decode_attention_varlen(layer, q, lens), rtol=1e-11, atol=1e-13)
+    assert np.all(O.paged_decode_attention_folded(layer, cache, q_low, [0, 3])[0] == 0.0)
+
+
 def test_results_do_not_depend_on_which_pool_page_holds_a_row():
     batch, hq, hkv, pt = 2, 4, 2, 8
     layer, cache, rng = _setup(("relabel",), batch, hq, hkv, 32, 32, pt, 12, 3)
