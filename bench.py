@@ -553,12 +553,13 @@ def main():
     probe_bytes = min(max(int(kern_bytes), 1 << 24), 2 << 30)
     probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).random_(0, 255)
     probe_sink = torch.zeros(4096, dtype=torch.float32, device=dev)
+    probe_wgs = max(1, min(2048, probe_bytes // 16384))        # a workgroup's slice is at least one 16 KiB stride
     for _ in range(5):
-        probe_n = B.skv_probe_stream_read(probe_src, 2048, probe_sink)
+        probe_n = B.skv_probe_stream_read(probe_src, probe_wgs, probe_sink)
     torch.cuda.synchronize()
     e0.record()
     for _ in range(20):
-        B.skv_probe_stream_read(probe_src, 2048, probe_sink)
+        B.skv_probe_stream_read(probe_src, probe_wgs, probe_sink)
     e1.record()
     torch.cuda.synchronize()
     probe_us = e0.elapsed_time(e1) * 1e3 / 20

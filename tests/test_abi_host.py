@@ -134,11 +134,14 @@ def test_default_split_plan():
     assert lib.skv_decode_default_splits(C.byref(L), 1) == 1
     assert lib.skv_decode_default_splits(C.byref(L), 64) == 1
     assert lib.skv_decode_default_splits(C.byref(L), 65) == 2
-    assert lib.skv_decode_default_splits(C.byref(L), 1000) == 16
+    assert lib.skv_decode_default_splits(C.byref(L), 1000) == 8           # one workgroup per CU below 1024 rows each
+    assert lib.skv_decode_default_splits(C.byref(L), 8192) == 8           # two workgroups per CU only with 1024 rows each
     mha = _layer(n_q_heads=32, n_kv_heads=32, batch=8, capacity=1 << 20)
     assert lib.skv_decode_default_splits(C.byref(mha), 131072) == 2
     one = _layer(batch=1, capacity=1 << 20)
-    assert lib.skv_decode_default_splits(C.byref(one), 1024) == 16
+    assert lib.skv_decode_default_splits(C.byref(one), 1024) == 8
+    assert lib.skv_decode_default_splits(C.byref(one), 4096) == 32
+    assert lib.skv_decode_default_splits(C.byref(one), 32768) == 32
     assert lib.skv_decode_default_splits(C.byref(one), 1 << 20) == 64
 
 
@@ -437,7 +440,7 @@ def test_paged_quantised_argument_checks():
     assert lib.skv_paged_pool_bytes(C.byref(paged(8))) == 100 * 8 * 64 * (64 + 64 + 4)
     assert lib.skv_paged_pool_bytes(C.byref(paged(4))) == 100 * 8 * 64 * (32 + 32 + 4)
     lib.skv_set_decode_engine(2)
-    assert lib.skv_paged_decode_default_splits(C.byref(paged(0)), 1024) == 16      # 512 workgroups over 32 columns
+    assert lib.skv_paged_decode_default_splits(C.byref(paged(0)), 1024) == 8       # bf16 rows: one workgroup per CU below 1024 rows each
     assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 1024) == 16      # 24 wanted, 16 quanta of 64 rows there
     assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 2000) == 0
     # chunk attention and the separate first launch are offered over bf16 pages only
