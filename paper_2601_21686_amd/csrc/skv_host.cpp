@@ -1,5 +1,6 @@
 // Host layer of the C ABI: argument checks, launch planning, rank selection.
 // No device code here.
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <limits>
@@ -190,15 +191,17 @@ bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx
   if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
   if (s > quanta) s = quanta;                 // never a range without rows
   if (s < 1) s = 1;
-  if (bits == 0) {
-    // Short ranges do not pay: a workgroup's start-up (query projection, first round trip) and its merge cost
-    // about as much as streaming a thousand rows.  Two workgroups per CU only when each still has 1024 rows,
-    // and no range of a single 64-row tile while more than a quarter of the CUs stay busy (measured for one
-    // sequence, 64/64: 32K rows 22.3 us in 32 ranges against 24.4 in 64; 4K rows 11.8 in 32 against 14.4 in 64;
-    // four sequences of 8K rows: 21.5 in 8 against 22.2 in 16).
-    while (s > 1 && quanta / s < 16 && s * columns > kTargetWorkgroups / 2) s = (s + 1) / 2;
-    while (s > 1 && quanta / s < 2 && s * columns > kTargetWorkgroups / 8) s = (s + 1) / 2;
-  }
+  // Short ranges do not pay: a workgroup's start-up (query projection, first round trip) and its merge cost
+  // about as much as streaming a thousand rows.  More than one workgroup per CU only while each still has
+  // 1024 rows, and no range of a single 64-row tile while more than a quarter of the CUs stay busy (measured
+  // for one sequence, 64/64: 32K rows 22.3 us in 32 ranges against 24.4 in 64; 4K rows 11.9 in 32 against 14.4
+  // in 64; four sequences of 8K rows: 21.1 in 8 against 22.4 in 16; 8-bit codes, one sequence of 16K rows:
+  // 18.0 in 32 against 21.8 in 96).
+  const int64_t one_per_cu = std::max<int64_t>(1, (kTargetWorkgroups / 2) / (columns > 0 ? columns : 1));
+  const int64_t by_rows = quanta / 16;
+  if (s > by_rows) s = std::max(by_rows, std::min(s, one_per_cu));
+  while (s > 1 && quanta / s < 2 && s * columns > kTargetWorkgroups / 8) s = (s + 1) / 2;
+  if (s < 1) s = 1;
   *n_splits = (int32_t)s;
   return true;
 }

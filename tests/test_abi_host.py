@@ -441,7 +441,7 @@ def test_paged_quantised_argument_checks():
     assert lib.skv_paged_pool_bytes(C.byref(paged(4))) == 100 * 8 * 64 * (32 + 32 + 4)
     lib.skv_set_decode_engine(2)
     assert lib.skv_paged_decode_default_splits(C.byref(paged(0)), 1024) == 8       # bf16 rows: one workgroup per CU below 1024 rows each
-    assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 1024) == 16      # 24 wanted, 16 quanta of 64 rows there
+    assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 1024) == 8       # 24 wanted; one workgroup per CU below 1024 rows each
     assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 2000) == 0
     # chunk attention and the separate first launch are offered over bf16 pages only
     assert lib.skv_paged_prefill_attention(C.byref(paged(8)), FAKE, 8192, 4096, 128, FAKE, 16, 0, 0.0, 0, None) == B.SKV_ERR_SHAPE
