@@ -200,7 +200,10 @@ __device__ __forceinline__ float octets_max(float x) {
 #define SKV_DW_IN_FLIGHT 8       // dwords of keys (and of values) one lane requests per tile
 #endif
 #ifndef SKV_EARLY_TILES
-#define SKV_EARLY_TILES 6        // tiles requested before the in-kernel query projection (>= 2; 4: +1 us, 8: the same)
+#define SKV_EARLY_TILES 6        // tiles a long range requests before the in-kernel query projection (>= 2)
+#endif
+#ifndef SKV_EARLY_FROM
+#define SKV_EARLY_FROM 24        // a range is long from this many whole tiles; a shorter one requests two
 #endif
 #ifndef SKV_PIPELINE
 #define SKV_PIPELINE 1           // tiles requested ahead of the one being computed on (>= 1)
@@ -527,36 +530,59 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   //      here: q~ = (q P_K) * scale * log2(e), the same sums as the projection kernel.  Either way the
   //      first tile of the range is requested before the queries are waited for. -----------------
   float qreg[GT][KM::CPL];
-  // Tiles 1 .. kEarlyTiles-1 of the range, requested together with tile 0 ahead of the query projection:
-  // the projection takes about as long as four tiles take to arrive at the steady rate.
+  // Tiles 1 .. kEarlyTiles-1 of a long range, requested together with tile 0 ahead of the query projection:
+  // the projection takes about as long as four tiles take to arrive at the steady rate.  A wave cannot go on
+  // to the projection before its requests are accepted, which under load is not much sooner than they are
+  // served, so a range of few tiles, where the projection is a visible share of the whole, requests only two.
   constexpr int kEarlyTiles = SKV_EARLY_TILES;
+  constexpr int kEarlyFrom = SKV_EARLY_FROM;
+  static_assert(kEarlyTiles >= 2 && kEarlyFrom > kEarlyTiles, "a long range holds more tiles than it requests early");
   Tile early[kEarlyTiles - 1];
-  bool pre = false;
+  bool pre = false, pre2 = false;
 #if !SKV_Q8
   if (p.q != nullptr) {
     ProjectPieces pp;
     project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
+    // Every lane requests its share of the raw queries without a condition (a lane beyond the last element
+    // repeats an earlier one and keeps nothing): a request under a condition is waited for where the
+    // condition ends, ahead of the cache rows that should already be on their way by then.
     const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
-    uint16_t qraw[(GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads];
+    constexpr int kQElems = GT * SKV_HEAD_DIM;
+    constexpr int kQPerLane = (kQElems + kDecodeThreads - 1) / kDecodeThreads;
+    uint16_t qraw[kQPerLane];
 #pragma unroll
-    for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
-      if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) qraw[k] = qptr[tid + k * kDecodeThreads];
-    if (n_full > 0) issue_full(t0, ta);
-    pre = SKV_PIPELINE == 1 && n_full >= kEarlyTiles + 1;
+    for (int k = 0; k < kQPerLane; ++k) qraw[k] = qptr[(tid + k * kDecodeThreads) % kQElems];
+    // The rest of the projection, once for each way the range starts: the waits for the basis and the queries
+    // count the requests made after them, and a count is only exact where the path to it is a single one.
+    auto finish = [&]() {
+#pragma unroll
+      for (int k = 0; k < kQPerLane; ++k)
+        if (tid + k * kDecodeThreads < kQElems) px_s[tid + k * kDecodeThreads] = bf16_to_f32(qraw[k]);
+      __syncthreads();
+      project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        const float* qh = py_s + HeadSplit<GT>::head_of_slot(g, j >> 2) * RK;
+#pragma unroll
+        for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = qh[KM::chan(j, i)] * p.scale_log2e;
+      }
+    };
+    pre = SKV_PIPELINE == 1 && n_full >= kEarlyFrom;
+    pre2 = SKV_PIPELINE == 1 && !pre && n_full >= 3;
     if (pre) {
+      issue_full(t0, ta);
 #pragma unroll
       for (int k = 1; k < kEarlyTiles; ++k) issue_full(t0 + k * ROWS_PER_WG, early[k - 1]);
-    }
-#pragma unroll
-    for (int k = 0; k < (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads; ++k)
-      if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) px_s[tid + k * kDecodeThreads] = bf16_to_f32(qraw[k]);
-    __syncthreads();
-    project_rows_finish<GT>(pp, RK, px_s, ppart_s, py_s);
-#pragma unroll
-    for (int g = 0; g < GT; ++g) {
-      const float* qh = py_s + HeadSplit<GT>::head_of_slot(g, j >> 2) * RK;
-#pragma unroll
-      for (int i = 0; i < KM::CPL; ++i) qreg[g][i] = qh[KM::chan(j, i)] * p.scale_log2e;
+      finish();
+    } else if (pre2) {
+      issue_full(t0, ta);
+      issue_full(t0 + ROWS_PER_WG, early[0]);
+      finish();
+    } else if (n_full > 0) {
+      issue_full(t0, ta);
+      finish();
+    } else {
+      finish();
     }
   } else
 #endif
@@ -607,7 +633,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
       if (k < n_full) issue_full(t0 + k * ROWS_PER_WG, ring[k]);
     int i = 0;
     if constexpr (NBUF == 2) {
-      if (pre) {                                    // tiles 0 .. kEarlyTiles-1 are on their way (n_full > kEarlyTiles)
+      if (pre) {                                    // tiles 0 .. kEarlyTiles-1 are on their way (n_full >= kEarlyFrom)
         consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
 #pragma unroll
         for (int k = 1; k < kEarlyTiles; ++k) {
@@ -615,6 +641,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
           consume_rows<RK, RV, GT, U, false>(early[k - 1], 0, t1, qd, qreg, m, l, acc, zacc);
         }
         i = kEarlyTiles;                            // ring[0] holds that tile: the loop's invariant
+      } else if (pre2) {                            // tiles 0 and 1 are on their way (n_full >= 3)
+        consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
+        issue_full(t0 + 2 * ROWS_PER_WG, ring[0]);
+        consume_rows<RK, RV, GT, U, false>(early[0], 0, t1, qd, qreg, m, l, acc, zacc);
+        i = 2;
       }
     }
     if constexpr (NBUF > 1) {

@@ -273,12 +273,12 @@ def test_kind_of_cache_load_does_not_change_a_bit(r_k, r_v, hq, hkv):
 
 
 @pytest.mark.parametrize("r,tile_rows", [(16, 256), (64, 64), (128, 32)])
-@pytest.mark.parametrize("tiles", [5, 6, 7, 8])
+@pytest.mark.parametrize("tiles", [1, 2, 3, 4, 7, 23, 24, 25, 31])
 @pytest.mark.parametrize("extra", [0, 1, -1])
 def test_ranges_around_the_early_request_depth(r, tile_rows, tiles, extra):
-    """The range kernel that projects its queries itself requests several tiles before the projection when the
-    range is long enough; ranges of just below, at and above that length, with and without a ragged tail, in one
-    range and in three."""
+    """The range kernel that projects its queries itself requests tiles before the projection: one for a range
+    of one or two whole tiles, two from three tiles on, six from twenty-four on.  Ranges of just below, at and
+    above those lengths, with and without a ragged tail, in one range and in three."""
     n = tile_rows * tiles + (extra if extra >= 0 else tile_rows - 1)
     P = _filled_pair(("early", r), 1, 4, 1, r, r, 3 * n)
     q = P.queries(5)
