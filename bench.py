@@ -589,7 +589,7 @@ def main():
                    "variant": args.variant, "engine": args.engine, "cache_reads": cache_reads,
                    "launch": "hip graph replay" if use_graph else "per-call launches"},
         "roofline": {"bound": "hbm", "kernel": ("projection + decode_partial_mma_kernel + merge (the whole attention call: no stage calls over quantised pages)" if (paged and q8)
-                                else "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8)))
+                                else "decode_partial_mma_kernel" if (args.engine == "matrix" or (args.engine == "auto" and (HQ // HKV == 8 or q8 or (HQ // HKV == 4 and rk in (32, 64) and rv in (32, 64)))))
                                 else "decode_partial_kernel"),
                      "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),

@@ -556,8 +556,9 @@ skv_status skv_paged_decode_step_folded(const skv_paged_layer* paged, const void
  * query heads of a group as columns of 16x16x16 bf16 products, float32 operands split into two bf16
  * terms, integer codes of the quantised formats taken as they are), 2 = chosen by shape (the default:
  * the matrix kernel for groups of eight query heads per KV head, which it serves in ONE pass over the
- * cache where the vector kernel needs two; the vector kernel otherwise -- the two are equally fast
- * there).  Both compute App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in
+ * cache where the vector kernel needs two, for the quantised formats, and for bf16 layers with groups of
+ * four whose ranks are both 32 or 64, where it measured 2-5 % faster; the vector kernel otherwise,
+ * which is the faster one at the other ranks and without grouping).  Both compute App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in
  * speed only.  Process-wide and not synchronised: set it before issuing work.  Returns the previous
  * value; any other argument changes nothing (a way to read the current value).
  */

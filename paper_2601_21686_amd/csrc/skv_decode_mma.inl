@@ -83,6 +83,11 @@ __device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_
 constexpr int kMmaTileRows = 32;                 // rows a wave takes at a time
 constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel (bf16 elements; 80 bytes)
 
+// An empty statement that the compiler keeps in its place among the memory requests, and through which a
+// requested word passes: whatever needs the word is scheduled after the requests that precede the statement.
+__device__ __forceinline__ void keep_after_requests(float& x) { asm volatile("" : "+v"(x) : : "memory"); }
+__device__ __forceinline__ void keep_after_requests(uint32_t& x) { asm volatile("" : "+v"(x) : : "memory"); }
+
 template <int RK, int RV, int GT, int FMT, bool NT>
 __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
@@ -362,44 +367,75 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   // ---- projected queries as B operands: column lm is query head lm of the pass (zero beyond GT) ---------
   // SKV_MMA_DEPTH tiles per wave on their way while the queries are prepared, and from then on (one register
   // set each).  Measured: a second set is slower at every shape tried (45.1 against 43.5 us at b4/32K, 64/64).
+  // The requests go out in an order and a shape that keep the waits exact: first the few words the queries
+  // need (from the workspace, or the basis pieces and raw queries of the in-kernel projection), then the
+  // wave's first tile, without a condition (a wave with no tile of its own requests the range's last one and
+  // never looks at it).  A request made under a condition is waited for where the paths join again, and
+  // requests return in order, so the other way round the queries would wait for the whole tile.
   TileRegsM ta;
-  if (wave < n_tiles) issue_tile(wave, ta);
+  const bool from_workspace = p.q == nullptr;
+  constexpr int QW = SKV_Q8 ? 8 : 4;                              // query channels per contraction step and lane
+  const int lmq = lm < GT ? lm : 0;                               // a lane beyond the pass's heads reads head 0 and keeps zero
+  float xq[KSTEPS][QW];
+  ProjectPieces pp;
+  constexpr int kQElems = GT * SKV_HEAD_DIM;
+  constexpr int kQPerLane = (kQElems + kDecodeThreads - 1) / kDecodeThreads;
+  uint32_t qraw[kQPerLane];                                      // one raw query element each, in a register of its own
+  if (from_workspace) {
+    // already scaled (and, quantised, times the key scales)
+    const float* qt = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK + lmq * RK + g * (RK / 4);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int i = 0; i < QW; ++i) xq[ks][i] = qt[QW * ks + i];
+  } else {
+    project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
+    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
+#pragma unroll
+    for (int k = 0; k < kQPerLane; ++k) qraw[k] = qptr[(tid + k * kDecodeThreads) % kQElems];
+  }
+  issue_tile(wave < n_tiles ? wave : n_tiles - 1, ta);
 #if SKV_MMA_DEPTH == 2
   TileRegsM tb;
   if (wave + 4 < n_tiles) issue_tile(wave + 4, tb);
 #endif
-  const float* qsrc;
-  float qscale;
-  if (p.q != nullptr) {
-    ProjectPieces pp;
-    project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, pp);
-    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * SKV_HEAD_DIM;
-    for (int i = tid; i < GT * SKV_HEAD_DIM; i += kDecodeThreads) px_s[i] = bf16_to_f32(qptr[i]);
+  // Nothing that needs the words requested above may be scheduled ahead of the tile's requests (an empty
+  // statement the compiler must keep in place, through which those words pass).
+  if (from_workspace) {
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int i = 0; i < QW; ++i) keep_after_requests(xq[ks][i]);
+  } else {
+#pragma unroll
+    for (int k = 0; k < kQPerLane; ++k) keep_after_requests(qraw[k]);
+  }
+  float qscale = 1.f;
+  if (!from_workspace) {
+#pragma unroll
+    for (int k = 0; k < kQPerLane; ++k)
+      if (tid + k * kDecodeThreads < kQElems) px_s[tid + k * kDecodeThreads] = bf16_to_f32((uint16_t)qraw[k]);
     __syncthreads();
     project_query_rows<GT>(pp, RK, px_s, ppart_s, py_s);
-    qsrc = py_s;
+    const float* qh = py_s + lmq * RK + g * (RK / 4);
+#pragma unroll
+    for (int ks = 0; ks < KSTEPS; ++ks)
+#pragma unroll
+      for (int i = 0; i < QW; ++i) xq[ks][i] = qh[QW * ks + i];
     qscale = p.scale_log2e;
-  } else {
-    qsrc = p.qt + ((int64_t)b * p.n_q_heads + hq0) * RK;          // already scaled (and, quantised, times the key scales)
-    qscale = 1.f;
   }
   // quantised keys: <q~, code * scale + zero> = <q~ * scale, code> + const; the constant drops out of the softmax
   // (queries taken from the workspace carry the key scales already)
 #if SKV_Q8
   auto key_scale_of = [&](int channel) -> float {
-    return p.q != nullptr ? p.k_scale[kv * ((RK + 63) / 64) + (channel >> 6)] : 1.f;
+    return from_workspace ? 1.f : p.k_scale[kv * ((RK + 63) / 64) + (channel >> 6)];
   };
-#endif
-#if SKV_Q8
   uint4 qhi[KSTEPS], qlo[KSTEPS];
 #pragma unroll
   for (int ks = 0; ks < KSTEPS; ++ks) {
     float x[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int c = g * (RK / 4) + 8 * ks + i;
-      x[i] = lm < GT ? qsrc[lm * RK + c] * qscale * key_scale_of(c) : 0.f;
-    }
+    for (int i = 0; i < 8; ++i) x[i] = lm < GT ? xq[ks][i] * qscale * key_scale_of(g * (RK / 4) + 8 * ks + i) : 0.f;
     split8w(x, qhi[ks], qlo[ks]);
   }
 #else
@@ -408,7 +444,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   for (int ks = 0; ks < KSTEPS; ++ks) {
     float x[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) x[i] = lm < GT ? qsrc[lm * RK + g * (RK / 4) + 4 * ks + i] * qscale : 0.f;
+    for (int i = 0; i < 4; ++i) x[i] = lm < GT ? xq[ks][i] * qscale : 0.f;
     split4(x, qhi[ks], qlo[ks]);
   }
 #endif

@@ -37,6 +37,17 @@ int decode_engine_for(int group, int bits = 0) {
   if (g_decode_engine == 2) return (group == 8 || bits != 0) ? 1 : 0;
   return g_decode_engine;
 }
+// The same for a bf16 layer of known ranks.  By shape, groups of four with both ranks 32 or 64 also take the
+// matrix kernel: measured 2-5 % ahead of the vector kernel there with either kind of load (b4/32K 64/64: 40.3
+// against 41.3 us per launch on one machine) and level at short contexts; level or behind at ranks 48, 80, 96,
+// 128 (128/128 with streaming loads: 107 against 93 us), behind without grouping, and behind by 5-9 % for
+// groups of two below 8K rows.
+int decode_engine_for_layer(const skv_layer* L) {
+  const int group = L->n_q_heads / L->n_kv_heads;
+  if (g_decode_engine != 2 || group == 8) return decode_engine_for(group);
+  const bool small_pow2 = (L->r_k == 32 || L->r_k == 64) && (L->r_v == 32 || L->r_v == 64);
+  return (group == 4 && small_pow2) ? 1 : 0;
+}
 
 // How the range kernels read cache rows: 0 = streaming loads, 1 = ordinary loads, 2 = by size (process-wide,
 // see skv.h).  By size: a launch whose rows add up to clearly more than the 256 MiB last-level cache cannot
@@ -122,7 +133,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->seq_lens = nullptr;
   p->len_add = 0;
   p->pages = PageMap{nullptr, 0, 0, 0};
-  p->engine = decode_engine_for(L->n_q_heads / L->n_kv_heads);
+  p->engine = decode_engine_for_layer(L);
   p->stream_loads = 0;
   p->scale_log2e = 0.f;
   p->lift = 1;
