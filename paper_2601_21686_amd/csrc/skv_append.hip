@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
   uint16_t* pt_s = reinterpret_cast<uint16_t*>(lds_raw);                             // [channel][d], r rows
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar: the tile loop below branches as a wave
   const int lane = tid & 63;
   const int h = blockIdx.y;
   const int which = blockIdx.z;                  // 0: keys, 1: values
@@ -112,11 +112,8 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
   uint8_t* stage = lds_raw + r * (kLdsPitch * 2) + wave * (kTokensPerWave * pitch + kTokensPerWave * 8);
   int64_t* row_s = reinterpret_cast<int64_t*>(stage + kTokensPerWave * pitch);
 
-  // the first tile is requested before the basis is staged
   int m0 = blockIdx.x * kTokensPerWg + wave * kTokensPerWave;
   TokenFrags<kTilesPerWave> fa, fb;
-  if (m0 < M) load_token_frags<STREAM>(p, x, h, m0, M, lrow, lk, fa);
-  if (m0 + stride < M) load_token_frags<STREAM>(p, x, h, m0 + stride, M, lrow, lk, fb);
 
   // basis [d][c] -> LDS [c][d]
   // Thread = (row d of the basis, one of two 8-channel pieces per round); all pieces are requested
@@ -128,6 +125,12 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
 #pragma unroll
     for (int k = 0; k < 8; ++k)
       if (k < rounds) v[k] = *reinterpret_cast<const uint4*>(basis + d * r + (2 * k + (tid >> 7)) * 8);
+    // The wave's first two tiles are requested behind the basis and without a condition (rows past the end
+    // re-read the last row): requests return in order and a wait counts the requests made since, so the
+    // basis is staged while the token rows are on their way.  Requested ahead of the basis, or under a
+    // condition, the staging waited for every token row (5-6 us into the launch).
+    load_token_frags<STREAM>(p, x, h, m0, M, lrow, lk, fa);
+    load_token_frags<STREAM>(p, x, h, m0 + stride, M, lrow, lk, fb);
 #pragma unroll
     for (int k = 0; k < 8; ++k)
       if (k < rounds) {
@@ -145,16 +148,19 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
   // Two register sets of token fragments take turns: a set is requested again, two tiles ahead,
   // right after the rows computed from it have been sent off, so requests of this wave are
   // outstanding all the time.
-  auto process = [&](TokenFrags<kTilesPerWave>& cur, const int m0) {
-    {                                              // where this wave's 64 token rows go (-1: past the end)
-      const int tok = m0 + lane;
-      int64_t row = -1;
-      if (lane < kTokensPerWave && tok < M) {
-        const int b = tok / p.T, t = tok % p.T;
-        row = cache_row(p.pages, p.capacity, p.n_kv_heads, b, h, clamped_len(p.cur_lens, b, p.cur_len) + t);
-      }
-      if (lane < kTokensPerWave) row_s[lane] = row;
+  // Where the wave's token rows [m, m + kTokensPerWave) go (-1: past the end).  With per-sequence lengths or
+  // pages this reads a table, under a condition; it is called where no request of token rows has been made
+  // since the last wait, because a request under a condition makes every later wait a wait for everything.
+  auto plan_rows = [&](const int m) {
+    const int tok = m + lane;
+    int64_t row = -1;
+    if (lane < kTokensPerWave && tok < M) {
+      const int b = tok / p.T, t = tok % p.T;
+      row = cache_row(p.pages, p.capacity, p.n_kv_heads, b, h, clamped_len(p.cur_lens, b, p.cur_len) + t);
     }
+    if (lane < kTokensPerWave) row_s[lane] = row;
+  };
+  auto process = [&](TokenFrags<kTilesPerWave>& cur, const int m0) {
     // Sends `ppr` 16-byte pieces of every staged row to the cache, 1 KB of consecutive bytes per
     // store instruction when the tokens are consecutive rows.  Streaming stores: the rows are not
     // read again here and should not displace the chunk being read in the caches.
@@ -278,13 +284,21 @@ __global__ __launch_bounds__(256) void append_mfma_kernel(const AppendParams p) 
       const int row_bytes = QBITS == 8 ? r : r >> 1;
       flush(reinterpret_cast<uint8_t*>(cache), row_bytes, row_bytes >> 4);
     }
+    // The next tile's destination rows (the last flush has read this tile's), then this set's next token
+    // rows, as the last thing, so that they stay on their way while the other set is worked on.  (Requested
+    // without a condition they cost more than the exact waits gain: a wave of a 4096-token chunk has two tiles
+    // and would request four.)
+    plan_rows(m0 + stride);
     if (m0 + 2 * stride < M) load_token_frags<STREAM>(p, x, h, m0 + 2 * stride, M, lrow, lk, cur);
   };
   if (m0 >= M) return;                           // no barrier below this point
+  plan_rows(m0);
+  // Two tiles per turn and one way out: with a way out between the two, the paths that meet at the top of
+  // the loop differ in what they have requested last, and the wait there becomes a wait for everything.  A
+  // second tile past the end computes on re-read rows and stores nothing (its destination rows are all -1).
   while (true) {
     process(fa, m0);
     m0 += stride;
-    if (m0 >= M) break;
     process(fb, m0);
     m0 += stride;
     if (m0 >= M) break;
