@@ -56,6 +56,16 @@ def test_append_values_and_placement(batch, T, cur, r_k, r_v):
     _check_append(P, k, v, cur, T)
 
 
+@pytest.mark.parametrize("batch,T,cur", [(2, 20000, 3), (1, 49153, 0)])
+def test_append_of_a_chunk_that_gives_waves_three_tiles(batch, T, cur):
+    """The chunk kernel runs at most 64 workgroups per head, each wave taking every 16384th block of 64 tokens in
+    turns of two: 40000 rows give some waves three tiles (a second turn whose second tile lies past the end) and
+    the others two; 49153 rows give one wave a fourth tile of a single row."""
+    P = Pair(("app-long", batch, T), batch, 8, 4, 48, 80, cur + T + 9, fill_bits=SENTINEL)
+    k, v = P.raw_kv(1, T)
+    _check_append(P, k, v, cur, T)
+
+
 @pytest.mark.parametrize("batch,T", [(2, 3), (2, 200)])
 def test_append_is_bit_exact_with_selection_bases(batch, T):
     # bases that pick +-channels: the cache must be an exact copy of those channels
