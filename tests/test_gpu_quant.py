@@ -86,7 +86,8 @@ class QPair:
 
 
 @pytest.mark.parametrize("bits,r_k,r_v", CASES)
-@pytest.mark.parametrize("batch,T,cur", [(2, 1, 5), (1, 40, 0), (2, 100, 7), (3, 333, 0)])   # the last two: matrix-core chunk path
+@pytest.mark.parametrize("batch,T,cur", [(2, 1, 5), (1, 40, 0), (2, 100, 7), (3, 333, 0),   # the last three: matrix-core chunk path;
+                                         (1, 20500, 0)])   # 20500 rows: some waves take three tiles, in two turns of the kernel's loop
 def test_quantised_append_codes_and_ranges(bits, r_k, r_v, batch, T, cur):
     append_fn = _fns(bits)[0]
     P = QPair(("qapp", r_k, r_v, T), batch, 8, 4, r_k, r_v, cur + T + 3, bits)
