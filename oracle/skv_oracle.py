@@ -659,10 +659,13 @@ def layer_ranks(n_layers: int, head_dim: int, rho: float, cand_k, cand_v, delta)
 #     next to the codes as two bf16 numbers;
 #   * code = clamp(round_half_even((x - zero) / scale), 0, 2^bits - 1),
 #     x_hat = code * scale + zero.
-# A code is an integer decided by floating point, so the decision is taken in
-# the precision the GPU kernel uses: float32 (IEEE subtraction and division)
-# on the float32-rounded projection.  Attention then runs, in float64, on the
-# dequantised rows exactly as on a bf16 cache.
+# Sec. 4.3 fixes no precision for the quantiser, so it is evaluated as the
+# plain definition in float64 on the float64 projection: minimum, maximum,
+# subtraction, division and round-half-even all in float64.  Only what the
+# cache FORMAT stores is narrower: static key ranges are float32 numbers,
+# per-row value ranges are bf16 numbers (rounded once, from float64).
+# Attention then runs, in float64, on the dequantised rows exactly as on a
+# bf16 cache.
 
 GROUP = 64
 
@@ -673,54 +676,58 @@ def group_slices(r: int):
 
 
 def calibrate_static_range(y: np.ndarray, bits: int = 8):
-    """(scale, zero) float32 per channel group from sample rows y [n, r]:
-    zero = min, scale = (max - min) / (2^bits - 1); a flat group gets scale 1."""
-    y32 = np.asarray(y, np.float64).astype(np.float32)
-    levels = np.float32(2 ** bits - 1)
+    """(scale, zero) per channel group from sample rows y [n, r]:
+    zero = min, scale = (max - min) / (2^bits - 1), computed in float64 and
+    stored as float32 (the format of static key ranges); a flat group gets scale 1."""
+    y = np.asarray(y, np.float64)
+    levels = float(2 ** bits - 1)
     sc, zr = [], []
-    for g in group_slices(y32.shape[1]):
-        lo, hi = y32[:, g].min(), y32[:, g].max()
-        s = np.float32(hi - lo) / levels
+    for g in group_slices(y.shape[1]):
+        lo, hi = y[:, g].min(), y[:, g].max()
+        s = np.float32((hi - lo) / levels)
         sc.append(s if s > 0 else np.float32(1.0))
-        zr.append(lo)
+        zr.append(np.float32(lo))
     return np.array(sc, np.float32), np.array(zr, np.float32)
 
 
 def quantize_static(y: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: int = 8) -> np.ndarray:
-    """Codes (uint8) of rows y [n, r] under fixed per-group (scale, zero) float32."""
-    y32 = np.asarray(y, np.float64).astype(np.float32)
-    out = np.empty(y32.shape, np.uint8)
-    top = np.float32(2 ** bits - 1)
-    for gi, g in enumerate(group_slices(y32.shape[1])):
-        t = (y32[:, g] - np.float32(zero[gi])) / np.float32(scale[gi])        # float32 throughout
-        out[:, g] = np.clip(np.rint(t), np.float32(0), top).astype(np.uint8)
+    """Codes (uint8) of rows y [n, r] under fixed per-group (scale, zero):
+    clamp(round_half_even((y - zero) / scale), 0, 2^bits - 1) in float64."""
+    y = np.asarray(y, np.float64)
+    out = np.empty(y.shape, np.uint8)
+    top = float(2 ** bits - 1)
+    for gi, g in enumerate(group_slices(y.shape[1])):
+        t = (y[:, g] - float(zero[gi])) / float(scale[gi])
+        out[:, g] = np.clip(np.rint(t), 0.0, top).astype(np.uint8)
     return out
 
 
 def quantize_dynamic(y: np.ndarray, bits: int = 8):
     """Per-row, per-group quantisation.  Returns (codes uint8 [n, r],
     scale bits uint16 [n, n_groups], zero bits uint16 [n, n_groups]); scale and
-    zero are bf16: zero = bf16(min), scale = bf16((max - min) / (2^bits - 1)),
-    replaced by 1 when that is 0."""
-    y32 = np.asarray(y, np.float64).astype(np.float32)
-    n, r = y32.shape
+    zero are stored as bf16: zero = bf16(min), scale = bf16((max - min) / (2^bits - 1))
+    (replaced by 1 when that is 0), each rounded once from its float64 value; the
+    codes are then clamp(round_half_even((y - zero) / scale)) in float64 with the
+    STORED zero and scale, so that code * scale + zero is the nearest level."""
+    y = np.asarray(y, np.float64)
+    n, r = y.shape
     groups = group_slices(r)
     codes = np.empty((n, r), np.uint8)
     sb = np.empty((n, len(groups)), np.uint16)
     zb = np.empty((n, len(groups)), np.uint16)
-    levels = np.float32(2 ** bits - 1)
+    levels = float(2 ** bits - 1)
     for gi, g in enumerate(groups):
-        lo = y32[:, g].min(axis=1)
-        hi = y32[:, g].max(axis=1)
-        s_bits = f64_to_bf16_bits(((hi - lo) / levels).astype(np.float64))     # float32 quotient, then bf16
-        s = bf16_bits_to_f64(s_bits).astype(np.float32)
+        lo = y[:, g].min(axis=1)
+        hi = y[:, g].max(axis=1)
+        s_bits = f64_to_bf16_bits((hi - lo) / levels)
+        s = bf16_bits_to_f64(s_bits)
         flat = s == 0
         s_bits = np.where(flat, np.uint16(0x3F80), s_bits)
-        s = np.where(flat, np.float32(1.0), s)
-        z_bits = f64_to_bf16_bits(lo.astype(np.float64))
-        z = bf16_bits_to_f64(z_bits).astype(np.float32)
-        t = (y32[:, g] - z[:, None]) / s[:, None]
-        codes[:, g] = np.clip(np.rint(t), np.float32(0), levels).astype(np.uint8)
+        s = np.where(flat, 1.0, s)
+        z_bits = f64_to_bf16_bits(lo)
+        z = bf16_bits_to_f64(z_bits)
+        t = (y[:, g] - z[:, None]) / s[:, None]
+        codes[:, g] = np.clip(np.rint(t), 0.0, levels).astype(np.uint8)
         sb[:, gi], zb[:, gi] = s_bits, z_bits
     return codes, sb, zb
 

@@ -84,6 +84,18 @@ class QPair:
     def oracle_decode(self, q, n, scale=None):
         return O.quant_decode_attention(self.ora, O.bf16_bits_to_f64(synth.torch_bf16_to_bits(q)), n, scale)
 
+    def oracle_layer_over_gpu_cache(self, n):
+        """An oracle layer whose rows [0, n) are the codes and value ranges the GPU stored (same bases, same
+        static key ranges): what the oracle's attention gives on exactly those cache bytes."""
+        lay = O.new_quant_layer(self.batch, self.hq, self.hkv, 128, self.pk64, self.pv64, self.ora.k_scale,
+                                self.ora.k_zero, self.capacity, self.bits)
+        lay.k_codes[:, :, :n] = unpack_codes(self.gpu.k_cache[:, :, :n].cpu().numpy(), self.bits)
+        lay.v_codes[:, :, :n] = unpack_codes(self.gpu.v_cache[:, :, :n].cpu().numpy(), self.bits)
+        meta = self.gpu.v_meta[:, :, :n].cpu().numpy().view(np.uint32)
+        lay.v_scale_bits[:, :, :n] = (meta & 0xffff).astype(np.uint16)
+        lay.v_zero_bits[:, :, :n] = (meta >> 16).astype(np.uint16)
+        return lay
+
 
 @pytest.mark.parametrize("bits,r_k,r_v", CASES)
 @pytest.mark.parametrize("batch,T,cur", [(2, 1, 5), (1, 40, 0), (2, 100, 7), (3, 333, 0),   # the last three: matrix-core chunk path;
@@ -159,7 +171,12 @@ def test_quantised_decode_matches_oracle_on_identical_cache_bytes(bits, r_k, r_v
 
 @pytest.mark.parametrize("bits", [8, 4])
 def test_quantised_decode_steps_end_to_end(bits):
-    # append through the library, then a few fused decode steps; both sides keep their own caches
+    # Append through the library, then a few fused decode steps; both sides keep their own caches.  A code is
+    # an integer decided by floating point: the library decides it in float32 on a float32 sum, the oracle in
+    # float64, so a few codes sit one apart.  The end-to-end statement is therefore made of two facts, each
+    # held to its own bar: (1) the cache the library built is the oracle's up to such flips (codes at most one
+    # apart, on fewer than 1 % of the entries; value ranges equal on more than 98 % of the rows), and (2) on
+    # the very bytes the library stored, its attention output is the oracle's within the stated 2e-3.
     append_fn, _, step_fn, _, _, bytes_fn = _fns(bits)
     n0, steps = 900, 3
     P = QPair(("qe2e",), 2, 8, 2, 64, 64, n0 + steps, bits)
@@ -173,8 +190,17 @@ def test_quantised_decode_steps_end_to_end(bits):
         step_fn(P.gpu, k1, v1, n0 + s, q, out)
         torch.cuda.synchronize()
         P.oracle_append(k1, v1, n0 + s)
-        # A handful of codes may differ by one between the two caches.  One step of an 8-bit code is well
-        # inside the tolerance; one step of a 4-bit code is 1/15 of a group's range, so there the bound is the
-        # effect of such flips (fewer than 1 % of the codes, each weighted by its row's softmax weight).
-        assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n0 + s + 1)) <= (TOL if bits == 8 else 2e-2)
+        n = n0 + s + 1
+        mine = P.oracle_layer_over_gpu_cache(n)
+        dk = np.abs(mine.k_codes[:, :, :n].astype(int) - P.ora.k_codes[:, :, :n].astype(int))
+        dv = np.abs(mine.v_codes[:, :, :n].astype(int) - P.ora.v_codes[:, :, :n].astype(int))
+        same = (mine.v_scale_bits[:, :, :n] == P.ora.v_scale_bits[:, :, :n]) & (mine.v_zero_bits[:, :, :n] == P.ora.v_zero_bits[:, :, :n])
+        assert dk.max() <= 1 and (dk > 0).mean() < 0.01
+        assert same.mean() > 0.98
+        assert dv[same[..., 0]].max() <= 1 and (dv[same[..., 0]] > 0).mean() < 0.01
+        q64 = O.bf16_bits_to_f64(synth.torch_bf16_to_bits(q))
+        assert vec_rel_err(out.cpu().numpy(), O.quant_decode_attention(mine, q64, n)) <= TOL
+        if bits == 8:
+            # one step of an 8-bit code is well inside the tolerance: each side on its own cache as well
+            assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n)) <= TOL
     assert bytes_fn(P.gpu, 1000) == 2 * 2 * 1000 * (128 * bits // 8 + 4)

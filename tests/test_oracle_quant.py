@@ -78,7 +78,7 @@ def test_dynamic_round_trip_error_bound_and_monotone_codes():
     s = O.bf16_bits_to_f64(sb)
     z = O.bf16_bits_to_f64(zb)
     back = O.dequantize(codes, s, z)
-    y32 = y.astype(np.float32).astype(np.float64)
+    y32 = y                                    # the definition works on the float64 rows themselves
     for gi, g in enumerate(O.group_slices(128)):
         lo, hi = y32[:, g].min(1), y32[:, g].max(1)
         # zero is bf16(lo), scale is bf16((hi-lo)/255): both within 2^-8 relative of the exact values
@@ -139,21 +139,67 @@ def test_eight_bit_cache_stays_close_to_the_unquantised_cache():
 
 
 def test_quant_append_places_rows_and_leaves_the_rest():
+    # Selection bases (P = columns of the identity) make the projection a copy of chosen channels, so every
+    # code and range below is worked out by hand.  Keys: scale 0.5, zero -2 -> code = rne((x + 2) / 0.5).
     B, HKV, d, r, cap, T, cur = 2, 2, 128, 32, 10, 3, 4
-    P64, Pbf = synth.orthonormal_bases(9, HKV, d, r)
-    L = O.new_quant_layer(B, HKV, HKV, d, P64, P64, np.ones((HKV, 1)), np.zeros((HKV, 1)), cap)
+    pick = [(7 * c + 3) % d for c in range(r)]                       # channel c of a row = input channel pick[c]
+    P = np.zeros((HKV, d, r))
+    for h in range(HKV):
+        P[h, pick, np.arange(r)] = 1.0
+    L = O.new_quant_layer(B, HKV, HKV, d, P, P, np.full((HKV, 1), 0.5), np.full((HKV, 1), -2.0), cap)
     L.k_codes[:] = 77
     L.v_codes[:] = 78
-    rng = np.random.default_rng(5)
-    K = rng.standard_normal((B, T, HKV, d)) * 20
-    O.quant_project_append(L, K, K, cur)
+    L.v_scale_bits[:] = 0x1234
+    L.v_zero_bits[:] = 0x4321
+    hand_in = [-2.0, -1.75, -1.5, -0.75, 0.0, 0.124, 10.0, 125.5, 125.75, 300.0, -9.0, 1.25]
+    hand_code = [0, 0, 1, 2, 4, 4, 24, 255, 255, 255, 0, 6]
+    #  (x+2)/.5:  0, .5->0, 1, 2.5->2, 4, 4.248->4, 24, 255, 255.5->clamp, clamp, clamp at 0, 6.5->6
+    K = np.zeros((B, T, HKV, d))
+    V = np.zeros((B, T, HKV, d))
+    want_k = np.zeros((B, HKV, T, r), np.uint8)
+    want_v = np.zeros((B, HKV, T, r), np.uint8)
+    want_s = np.zeros((B, HKV, T), np.float64)
+    want_z = np.zeros((B, HKV, T), np.float64)
+    for b in range(B):
+        for t in range(T):
+            for h in range(HKV):
+                rot = 5 * b + 3 * t + h
+                for c in range(r):
+                    K[b, t, h, pick[c]] = hand_in[(c + rot) % len(hand_in)]
+                    want_k[b, h, t, c] = hand_code[(c + rot) % len(hand_in)]
+                # values: a row spanning [z, z + 255 s] with s a power of two and entries on the grid z + n s,
+                # plus entries a quarter step above a level (round down) and three quarters above (round up)
+                s_, z_ = 2.0 ** -(1 + (rot % 3)), float(rot % 4) - 1.5
+                n_ = [(37 * c + rot) % 256 for c in range(r)]
+                n_[0], n_[1] = 0, 255
+                frac = [0.0, 0.25, 0.75, 0.0][rot % 4]
+                for c in range(r):
+                    off = frac if 2 <= c < r - 1 and n_[c] < 255 else 0.0
+                    V[b, t, h, pick[c]] = z_ + (n_[c] + off) * s_
+                    want_v[b, h, t, c] = n_[c] + (1 if off > 0.5 else 0)
+                want_s[b, h, t], want_z[b, h, t] = s_, z_
+    K[:, :, :, [p_ for p_ in range(d) if p_ not in pick]] = 999.0            # channels the basis does not select
+    O.quant_project_append(L, K, V, cur)
     rest = np.ones(cap, bool)
     rest[cur:cur + T] = False
     assert np.all(L.k_codes[:, :, rest] == 77) and np.all(L.v_codes[:, :, rest] == 78)
-    for b in range(B):
-        for h in range(HKV):
-            want = np.clip(np.rint((K[b, :, h] @ P64[h]).astype(np.float32)), 0, 255)
-            assert np.array_equal(L.k_codes[b, h, cur:cur + T], want.astype(np.uint8))
+    assert np.all(L.v_scale_bits[:, :, rest] == 0x1234) and np.all(L.v_zero_bits[:, :, rest] == 0x4321)
+    assert np.array_equal(L.k_codes[:, :, cur:cur + T], want_k)
+    assert np.array_equal(L.v_codes[:, :, cur:cur + T], want_v)
+    assert np.array_equal(O.bf16_bits_to_f64(L.v_scale_bits[:, :, cur:cur + T, 0]), want_s)
+    assert np.array_equal(O.bf16_bits_to_f64(L.v_zero_bits[:, :, cur:cur + T, 0]), want_z)
+
+
+def test_codes_are_decided_in_float64():
+    # Inputs a hair on either side of a rounding boundary that float32 cannot tell apart: the definition is
+    # evaluated in float64, so they receive different codes.
+    eps = 2.0 ** -40
+    y = np.array([[1.5 - eps, 1.5 + eps, 2.5 - eps, 2.5 + eps, 0.0, 255.0]])
+    got = O.quantize_static(y, np.array([1.0], np.float32), np.array([0.0], np.float32))
+    assert got.tolist() == [[1, 2, 2, 3, 0, 255]]
+    cd, sb, zb = O.quantize_dynamic(y)
+    assert O.bf16_bits_to_f64(sb)[0, 0] == 1.0 and O.bf16_bits_to_f64(zb)[0, 0] == 0.0
+    assert cd.tolist() == [[1, 2, 2, 3, 0, 255]]
 
 
 def test_four_bit_codes_by_hand_and_round_trip():
