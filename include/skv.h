@@ -4,9 +4,10 @@
  *
  * C ABI.  Plain pointers and sizes only.  Every pointer marked "device" is GPU
  * memory owned by the caller; "host" is ordinary process memory.  The library
- * owns no memory, keeps no state between calls, never allocates and never
- * synchronises: GPU work is enqueued on the hipStream_t passed as `stream`
- * (NULL = the default stream) and the call returns at once.  All arguments are
+ * owns no memory, keeps no state between calls (everything a call depends on
+ * is in its arguments), never allocates and never synchronises: GPU work is
+ * enqueued on the hipStream_t passed as `stream` (NULL = the default stream)
+ * and the call returns at once.  All arguments are
  * checked on the host before anything is launched; when a call returns an
  * error nothing has been written.  The return value is the only error channel.
  *
@@ -59,7 +60,31 @@ typedef enum {
  *            the key basis across heads and keeps value bases per head,
  *            Sec. 3.3 "Head sharing"); otherwise at least head_dim * r.
  * The bf16 numbers stored in p_k / p_v are the basis: nothing re-orthonormalises.
+ *   flags    hints for the decode calls, 0 = every choice left to the library.  They never change what is
+ *            computed (App. A.1 Eq. 18 to the same 2e-3 bound), only how fast; a value with unknown bits
+ *            set is SKV_ERR_SHAPE.
+ *            SKV_READS_*: how the range kernels load cache rows (every row of the compressed cache is
+ *              read once per step, Sec. 2.1 Eq. 2 inside Eq. 18).  SKV_READS_BY_SIZE (0): streaming
+ *              (non-temporal) loads when the rows one launch covers add up to more than 288 MiB, clearly
+ *              more than the 256 MiB last-level cache, ordinary loads otherwise.  SKV_READS_STREAMING: the
+ *              caller knows that the rows will not be found in a cache at the next step, whatever one
+ *              launch covers -- the layers of a model whose caches together exceed the last-level cache
+ *              should all carry it.  SKV_READS_CACHED: ordinary loads always.
+ *            SKV_ENGINE_*: which range kernel streams the cache.  SKV_ENGINE_BY_SHAPE (0): the library's
+ *              choice for the shape (what skv_decode_engine_for reports); SKV_ENGINE_VECTOR: vector
+ *              arithmetic; SKV_ENGINE_MATRIX: matrix cores (the query heads of a group as columns of
+ *              16x16 bf16 products, float32 operands split into two bf16 terms, integer codes of the
+ *              quantised formats taken as they are).  For tuning and tests; quantised pages run on the
+ *              matrix kernel whatever the flag says.
  */
+#define SKV_READS_BY_SIZE 0u
+#define SKV_READS_STREAMING 1u
+#define SKV_READS_CACHED 2u
+#define SKV_READS_MASK 3u
+#define SKV_ENGINE_BY_SHAPE 0u
+#define SKV_ENGINE_VECTOR 4u
+#define SKV_ENGINE_MATRIX 8u
+#define SKV_ENGINE_MASK 12u
 typedef struct {
   int32_t batch, n_q_heads, n_kv_heads, head_dim;
   int32_t r_k, r_v;
@@ -70,6 +95,8 @@ typedef struct {
   const void* p_v;
   int64_t p_k_head_stride;
   int64_t p_v_head_stride;
+  uint32_t flags;
+  uint32_t reserved;       /* must be 0 */
 } skv_layer;
 
 /*
@@ -125,6 +152,18 @@ size_t skv_decode_workspace_bytes(const skv_layer* layer);
 /* The number of context ranges skv_decode_attention uses for this shape
  * (1..SKV_MAX_SPLITS); 0 if the arguments are invalid. */
 int32_t skv_decode_default_splits(const skv_layer* layer, int64_t n_ctx);
+
+/* Which range kernel the decode calls run for this layer (D2-D4: scores, online softmax and value mix of
+ * App. A.1 Eq. 18 in the factored form): 0 = vector arithmetic (decode_partial_kernel), 1 = matrix cores
+ * (decode_partial_mma_kernel); -1 for an invalid layer or code width.  code_bits: 0 for bf16 rows, 8 or 4
+ * for the quantised formats.  The layer's SKV_ENGINE_* flag decides when set; by shape the matrix kernel
+ * takes groups of eight query heads per KV head (one pass over the cache where the vector kernel needs
+ * two), the quantised formats, and bf16 layers with groups of four whose ranks are both 32 or 64; the
+ * vector kernel everything else.  Host only. */
+int32_t skv_decode_engine_for(const skv_layer* layer, int32_t code_bits);
+/* 1 if the range kernel of a decode call over n_ctx rows reads the cache with streaming loads, 0 for
+ * ordinary loads (the layer's SKV_READS_* flag, or by size), -1 for invalid arguments.  Host only. */
+int32_t skv_decode_streams_rows(const skv_layer* layer, int64_t n_ctx, int32_t code_bits);
 
 /* Rows [*first_row, *end_row) of the cache that context range `range` of `n_splits` covers
  * when n_ctx rows are attended (host only).  Ranges are runs of whole 64-row quanta, dealt as
@@ -550,55 +589,6 @@ skv_status skv_paged_decode_step_folded(const skv_paged_layer* paged, const void
                                         const int32_t* cur_lens, int64_t max_cur_len, const void* q_low,
                                         void* out_low, float scale, void* workspace, size_t workspace_bytes,
                                         void* stream);
-
-/*
- * Which kernel streams the cache in the decode calls: 0 = vector arithmetic, 1 = matrix cores (the
- * query heads of a group as columns of 16x16x16 bf16 products, float32 operands split into two bf16
- * terms, integer codes of the quantised formats taken as they are), 2 = chosen by shape (the default:
- * the matrix kernel for groups of eight query heads per KV head, which it serves in ONE pass over the
- * cache where the vector kernel needs two, for the quantised formats, and for bf16 layers with groups of
- * four whose ranks are both 32 or 64, where it measured 2-5 % faster; the vector kernel otherwise,
- * which is the faster one at the other ranks and without grouping).  Both compute App. A.1 Eq. 18 in the factored form to the same 2e-3 bound; they differ in
- * speed only.  Process-wide and not synchronised: set it before issuing work.  Returns the previous
- * value; any other argument changes nothing (a way to read the current value).
- */
-int32_t skv_set_decode_engine(int32_t engine);
-
-/*
- * How the range kernels of the decode calls read cache rows (D2/D4: every row of the compressed cache is
- * read once per step, Sec. 2.1 Eq. 2 with App. A.1 Eq. 18).  0 = streaming (non-temporal) loads: right when
- * the rows will not be found in a cache on the next step, as in a model whose layers together exceed the
- * last-level cache; 1 = ordinary loads; 2 (default) = by size: streaming when the rows one launch covers
- * add up to more than 288 MiB (clearly more than the 256 MiB last-level cache), ordinary otherwise.  Results do not depend on it.  Process-wide and not
- * synchronised: set it before issuing work.  Returns the previous value; any other argument changes
- * nothing (a way to read the current value).
- */
-int32_t skv_set_cache_reads(int32_t mode);
-
-/*
- * A measuring stick for the benchmark, no part of the method: one launch that only READS.  The first
- * *bytes_read <= bytes bytes of src (whole multiples of workgroups * 16 KiB) are streamed, each
- * workgroup a contiguous slice, and nothing is written.  Timing it tells what a plain streaming read of
- * that size reaches on the machine at hand, which the range kernels are compared with.  It uses the kind of
- * load a range kernel over that many bytes would use (skv_set_cache_reads).
- *   src   device, 16-byte aligned, at least `bytes` long
- *   sink  device float32 [workgroups]: never written in practice, must be valid
- * Errors: NULL, ALIGN, SHAPE (workgroups outside [1, 65535], or bytes below workgroups * 16 KiB), HIP.
- */
-skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgroups, void* sink,
-                                 size_t* bytes_read, void* stream);
-
-/*
- * A second measuring stick: one launch that reads two buffers and writes a third (c = a ^ b), two bytes
- * read for each byte written, the traffic mix of the chunk append (Sec. 2.1 Eq. 1 at r_k + r_v = head
- * size).  The first *bytes_each <= bytes bytes of each buffer take part (whole multiples of
- * workgroups * 16 KiB), each workgroup a contiguous slice.
- *   a, b  device, 16-byte aligned, at least `bytes` long, read
- *   c     device, 16-byte aligned, at least `bytes` long, overwritten; must not overlap a or b
- * Errors: NULL, ALIGN, SHAPE (workgroups outside [1, 65535], or bytes below workgroups * 16 KiB), HIP.
- */
-skv_status skv_probe_stream_mix(const void* a, const void* b, void* c, size_t bytes, int32_t workgroups,
-                                size_t* bytes_each, void* stream);
 
 /* Bytes of compressed cache one layer holds for n tokens (Sec. 2.1 Eq. 3 times
  * the uncompressed size): batch * n_kv_heads * n * (r_k + r_v) * 2. */

@@ -14,6 +14,7 @@ import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libskv.so")
+PROBE_LIB_PATH = os.path.join(_PKG, "libskv_probe.so")     # the benchmark's plain streaming kernels (include/skv_probe.h)
 
 SKV_OK = 0
 SKV_ERR_NULL, SKV_ERR_SHAPE, SKV_ERR_RANK, SKV_ERR_CAPACITY = 1, 2, 3, 4
@@ -22,6 +23,13 @@ SKV_HEAD_DIM = 128
 SKV_MAX_SPLITS = 256
 SKV_PREFILL_EXACT, SKV_PREFILL_FAST = 0, 1
 SKV_PREFILL_SCHED_TOGETHER, SKV_PREFILL_SCHED_AHEAD = 0x10, 0x20
+# skv_layer.flags
+SKV_READS_BY_SIZE, SKV_READS_STREAMING, SKV_READS_CACHED = 0, 1, 2
+SKV_ENGINE_BY_SHAPE, SKV_ENGINE_VECTOR, SKV_ENGINE_MATRIX = 0, 4, 8
+
+# flags given to layers constructed without an explicit `flags` argument (a Python-side default of this
+# binding, read when a layer object is built; the library itself keeps no state)
+DEFAULT_LAYER_FLAGS = 0
 
 EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
@@ -37,9 +45,10 @@ EXPORTS = (
     "skv_decode_attention_varlen", "skv_project_append_varlen", "skv_decode_step_varlen",
     "skv_prefill_attention", "skv_prefill_attention_folded", "skv_prefill_step", "skv_prefill_tile_tokens",
     "skv_paged_pool_bytes", "skv_paged_project_append", "skv_paged_decode_attention", "skv_paged_decode_step",
-    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_set_decode_engine", "skv_set_cache_reads", "skv_probe_stream_read", "skv_probe_stream_mix", "skv_paged_decode_default_splits",
+    "skv_paged_prefill_attention", "skv_paged_decode_partial_q", "skv_decode_engine_for", "skv_decode_streams_rows", "skv_paged_decode_default_splits",
     "skv_paged_append_projected", "skv_paged_decode_attention_folded", "skv_paged_decode_step_folded",
 )
+PROBE_EXPORTS = ("skv_probe_stream_read", "skv_probe_stream_mix")
 
 
 class SkvError(RuntimeError):
@@ -56,6 +65,7 @@ class skv_layer(C.Structure):
         ("k_cache", C.c_void_p), ("v_cache", C.c_void_p),
         ("p_k", C.c_void_p), ("p_v", C.c_void_p),
         ("p_k_head_stride", C.c_int64), ("p_v_head_stride", C.c_int64),
+        ("flags", C.c_uint32), ("reserved", C.c_uint32),
     ]
 
 
@@ -176,14 +186,10 @@ def lib() -> C.CDLL:
     L.skv_paged_decode_attention_folded.restype = C.c_int
     L.skv_paged_decode_step_folded.argtypes = [PP, vp, vp, i32, vp, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_paged_decode_step_folded.restype = C.c_int
-    L.skv_probe_stream_read.argtypes = [vp, sz, i32, vp, C.POINTER(C.c_size_t), vp]
-    L.skv_probe_stream_read.restype = C.c_int
-    L.skv_probe_stream_mix.argtypes = [vp, vp, vp, sz, i32, C.POINTER(C.c_size_t), vp]
-    L.skv_probe_stream_mix.restype = C.c_int
-    L.skv_set_decode_engine.argtypes = [i32]
-    L.skv_set_decode_engine.restype = i32
-    L.skv_set_cache_reads.argtypes = [i32]
-    L.skv_set_cache_reads.restype = i32
+    L.skv_decode_engine_for.argtypes = [LP, i32]
+    L.skv_decode_engine_for.restype = i32
+    L.skv_decode_streams_rows.argtypes = [LP, i64, i32]
+    L.skv_decode_streams_rows.restype = i32
     L.skv_orthonormalize.argtypes = [vp, i32, i32, i32, vp, vp]
     L.skv_orthonormalize.restype = C.c_int
     L.skv_padded_rank.argtypes = [i32]
@@ -193,6 +199,27 @@ def lib() -> C.CDLL:
     L.skv_status_string.argtypes = [C.c_int]
     L.skv_status_string.restype = C.c_char_p
     _lib = L
+    return L
+
+
+_probe_lib = None
+
+
+def probe_lib() -> C.CDLL:
+    """Opens libskv_probe.so (the benchmark's plain streaming kernels) once."""
+    global _probe_lib
+    if _probe_lib is not None:
+        return _probe_lib
+    if not os.path.exists(PROBE_LIB_PATH):
+        raise FileNotFoundError(
+            f"{PROBE_LIB_PATH} not found: build it with `python -m paper_2601_21686_amd.build`")
+    L = C.CDLL(PROBE_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    L.skv_probe_stream_read.argtypes = [vp, sz, i32, i32, vp, C.POINTER(C.c_size_t), vp]
+    L.skv_probe_stream_read.restype = C.c_int
+    L.skv_probe_stream_mix.argtypes = [vp, vp, vp, sz, i32, C.POINTER(C.c_size_t), vp]
+    L.skv_probe_stream_mix.restype = C.c_int
+    _probe_lib = L
     return L
 
 
@@ -219,7 +246,7 @@ class Layer:
     """
 
     def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, capacity,
-                 k_cache=None, v_cache=None, head_dim=SKV_HEAD_DIM):
+                 k_cache=None, v_cache=None, head_dim=SKV_HEAD_DIM, flags=None):
         dev = p_k.device
         assert p_k.dtype == torch.bfloat16 and p_v.dtype == torch.bfloat16
         assert p_k.is_contiguous() and p_v.is_contiguous()
@@ -237,7 +264,8 @@ class Layer:
             self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.r_k, self.r_v,
             self.capacity, k_cache.data_ptr(), v_cache.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
             0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
-            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2],
+            DEFAULT_LAYER_FLAGS if flags is None else int(flags), 0)
         self._ws = None
 
     def workspace(self) -> torch.Tensor:
@@ -256,7 +284,7 @@ class QuantLayer:
     holding a bf16 scale (low half) and a bf16 zero (high half) per value row and group.
     """
 
-    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, k_scale, k_zero, capacity, bits=8):
+    def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, k_scale, k_zero, capacity, bits=8, flags=None):
         dev = p_k.device
         assert bits in (8, 4)
         self.bits = int(bits)
@@ -274,7 +302,8 @@ class QuantLayer:
             self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v, self.capacity,
             self.k_cache.data_ptr(), self.v_cache.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
             0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
-            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+            0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2],
+            DEFAULT_LAYER_FLAGS if flags is None else int(flags), 0)
         self.c = skv_q8_layer(base, self.k_scale.data_ptr(), self.k_zero.data_ptr(), self.v_meta.data_ptr())
         self._ws = None
 
@@ -479,12 +508,15 @@ def skv_decode_step_varlen(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_
                                         _stream_ptr(stream)), "skv_decode_step_varlen")
 
 
-def skv_probe_stream_read(src: torch.Tensor, workgroups: int, sink: torch.Tensor, stream=None) -> int:
-    """One read-only launch over src (a contiguous CUDA tensor); returns the bytes it read."""
+def skv_probe_stream_read(src: torch.Tensor, workgroups: int, sink: torch.Tensor, streaming: bool = False,
+                          stream=None) -> int:
+    """One read-only launch over src (a contiguous CUDA tensor), with streaming or ordinary loads; returns the
+    bytes it read."""
     assert src.is_cuda and src.is_contiguous() and sink.dtype == torch.float32 and sink.numel() >= workgroups
     n = C.c_size_t(0)
-    _check(lib().skv_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), int(workgroups),
-                                       sink.data_ptr(), C.byref(n), _stream_ptr(stream)), "skv_probe_stream_read")
+    _check(probe_lib().skv_probe_stream_read(src.data_ptr(), src.numel() * src.element_size(), int(workgroups),
+                                             1 if streaming else 0, sink.data_ptr(), C.byref(n), _stream_ptr(stream)),
+           "skv_probe_stream_read")
     return int(n.value)
 
 
@@ -494,21 +526,30 @@ def skv_probe_stream_mix(a: torch.Tensor, b: torch.Tensor, c: torch.Tensor, work
     for t in (a, b, c):
         assert t.is_cuda and t.is_contiguous() and t.numel() * t.element_size() == nbytes
     n = C.c_size_t(0)
-    _check(lib().skv_probe_stream_mix(a.data_ptr(), b.data_ptr(), c.data_ptr(), nbytes, int(workgroups),
-                                      C.byref(n), _stream_ptr(stream)), "skv_probe_stream_mix")
+    _check(probe_lib().skv_probe_stream_mix(a.data_ptr(), b.data_ptr(), c.data_ptr(), nbytes, int(workgroups),
+                                            C.byref(n), _stream_ptr(stream)), "skv_probe_stream_mix")
     return int(n.value)
 
 
-def skv_set_decode_engine(engine: int) -> int:
-    """0 = vector arithmetic, 1 = matrix cores, 2 = by shape (default); returns the previous choice (any other
-    value: no change)."""
-    return int(lib().skv_set_decode_engine(int(engine)))
+def _layer_struct(layer) -> skv_layer:
+    c = layer.c
+    return c if isinstance(c, skv_layer) else (c.base if isinstance(c, skv_q8_layer) else c.layer)
 
 
-def skv_set_cache_reads(mode: int) -> int:
-    """0 = streaming loads, 1 = ordinary loads, 2 = by size (default); returns the previous choice (any other
-    value: no change)."""
-    return int(lib().skv_set_cache_reads(int(mode)))
+def skv_decode_engine_for(layer) -> int:
+    """The range kernel the decode calls run for this layer object: 0 = vector arithmetic, 1 = matrix cores."""
+    bits = int(getattr(layer, "bits", 0))
+    if isinstance(layer.c, skv_paged_layer) and bits:
+        return 1                                   # quantised pages: the matrix kernel only
+    return int(lib().skv_decode_engine_for(C.byref(_layer_struct(layer)), bits))
+
+
+def skv_decode_streams_rows(layer, n_ctx: int) -> bool:
+    """Whether the range kernel of a decode call over n_ctx rows of this layer reads with streaming loads."""
+    r = int(lib().skv_decode_streams_rows(C.byref(_layer_struct(layer)), int(n_ctx), int(getattr(layer, "bits", 0))))
+    if r < 0:
+        raise SkvError(SKV_ERR_SHAPE, "skv_decode_streams_rows")
+    return bool(r)
 
 
 # ---- paged cache -------------------------------------------------------------------------------
@@ -521,7 +562,7 @@ class PagedLayer:
     k_zero as for QuantLayer).  The pools are allocated here (uninitialised) unless passed in."""
 
     def __init__(self, batch, n_q_heads, n_kv_heads, p_k, p_v, page_tokens, n_pages, block_table,
-                 k_pool=None, v_pool=None, bits=0, k_scale=None, k_zero=None):
+                 k_pool=None, v_pool=None, bits=0, k_scale=None, k_zero=None, flags=None):
         dev = p_k.device
         assert p_k.dtype == torch.bfloat16 and p_v.dtype == torch.bfloat16
         assert p_k.is_contiguous() and p_v.is_contiguous()
@@ -553,7 +594,8 @@ class PagedLayer:
         base = skv_layer(self.batch, self.n_q_heads, self.n_kv_heads, SKV_HEAD_DIM, self.r_k, self.r_v,
                          self.capacity, k_pool.data_ptr(), v_pool.data_ptr(), p_k.data_ptr(), p_v.data_ptr(),
                          0 if p_k.shape[0] == 1 else p_k.shape[1] * p_k.shape[2],
-                         0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2])
+                         0 if p_v.shape[0] == 1 else p_v.shape[1] * p_v.shape[2],
+                         DEFAULT_LAYER_FLAGS if flags is None else int(flags), 0)
         self.c = skv_paged_layer(base, block_table.data_ptr(), self.page_tokens, self.n_pages,
                                  self.max_pages_per_seq, self.bits,
                                  self.k_scale.data_ptr() if bits else None, self.k_zero.data_ptr() if bits else None,

@@ -15,6 +15,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libskv.so")
+PROBE_OUT = os.path.join(PKG, "libskv_probe.so")     # the benchmark's plain streaming kernels: a library of their own
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 KEY_RANKS = (16, 32, 48, 64, 80, 96, 112, 128)
@@ -80,7 +81,30 @@ def _jobs():
     return jobs
 
 
-def build(verbose: bool = True, workers: int | None = None) -> str:
+def _up_to_date(out: str, cmd_line: str) -> bool:
+    """True if the object exists, was made by the same command and is newer than every file it was made from
+    (as listed by the compiler's dependency output)."""
+    dep, tag = out + ".d", out + ".cmd"
+    if not (os.path.exists(out) and os.path.exists(dep) and os.path.exists(tag)):
+        return False
+    with open(tag) as f:
+        if f.read() != cmd_line:
+            return False
+    with open(dep) as f:
+        words = f.read().replace("\\\n", " ").split()
+    t = os.path.getmtime(out)
+    for w in words:
+        if w.endswith(":"):
+            continue
+        if not os.path.exists(w) or os.path.getmtime(w) > t:
+            return False
+    return True
+
+
+def build(verbose: bool = True, workers: int | None = None, incremental: bool = False) -> str:
+    """Compiles every source and links the libraries.  incremental: objects whose sources, headers and
+    command line have not changed since they were made are kept (a developer's shortcut; the default
+    compiles everything)."""
     hipcc = _hipcc()
     os.makedirs(BUILD_DIR, exist_ok=True)
     workers = workers or min(8, os.cpu_count() or 1)
@@ -88,10 +112,18 @@ def build(verbose: bool = True, workers: int | None = None) -> str:
     def compile_one(job):
         obj, src_args, extra = job
         out = os.path.join(BUILD_DIR, obj)
-        cmd = [hipcc, "-c", *COMMON, *extra, *src_args, "-o", out]
+        cmd = [hipcc, "-c", *COMMON, *extra, *src_args, "-MD", "-MF", out + ".d", "-o", out]
+        if incremental and _up_to_date(out, " ".join(cmd)):
+            if verbose:
+                print(f"[build] {obj} (up to date)", flush=True)
+            return out
+        if os.path.exists(out + ".cmd"):
+            os.remove(out + ".cmd")
         res = subprocess.run(cmd, capture_output=True, text=True)
         if res.returncode != 0:
             raise RuntimeError(f"compile failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
+        with open(out + ".cmd", "w") as f:
+            f.write(" ".join(cmd))
         if verbose:
             err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
             print(f"[build] {obj}" + (f"\n{err}" if err else ""), flush=True)
@@ -99,15 +131,18 @@ def build(verbose: bool = True, workers: int | None = None) -> str:
 
     with ThreadPoolExecutor(max_workers=workers) as ex:
         objs = list(ex.map(compile_one, _jobs()))
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", OUT, *objs]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError(f"link failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
-    if verbose:
-        print(f"[build] linked {OUT}", flush=True)
+    probe_objs = [o for o in objs if os.path.basename(o) == "skv_probe.o"]
+    objs = [o for o in objs if o not in probe_objs]
+    for out, members in ((OUT, objs), (PROBE_OUT, probe_objs)):
+        cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out, *members]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"link failed: {' '.join(cmd)}\n{res.stdout}\n{res.stderr}")
+        if verbose:
+            print(f"[build] linked {out}", flush=True)
     return OUT
 
 
 if __name__ == "__main__":
-    build()
+    build(incremental="--incremental" in sys.argv[1:])
     sys.exit(0)

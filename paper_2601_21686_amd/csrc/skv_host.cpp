@@ -27,46 +27,46 @@ bool rank_ok(int32_t r) { return r >= 16 && r <= SKV_HEAD_DIM && (r % 16) == 0; 
 // 8 or 16 ranges per (sequence, KV head) are the fastest, 32 and 64 are slower.
 constexpr int kTargetWorkgroups = 512;
 
-// Which range kernel streams the cache: 0 = vector arithmetic, 1 = matrix cores, 2 = by shape (process-wide,
-// see skv.h).  By shape: the matrix kernel where it saves a pass over the cache (eight query heads per KV
-// head), the vector kernel elsewhere (the two are equally fast there).
-int g_decode_engine = 2;
-// bits: 0 for bf16 rows, else the width of the quantised codes (there the matrix kernel needs fewer vector
-// instructions per row, which is what bounds both kernels: measured 31.4 against 35.2 us at 8 bits)
-int decode_engine_for(int group, int bits = 0) {
-  if (g_decode_engine == 2) return (group == 8 || bits != 0) ? 1 : 0;
-  return g_decode_engine;
-}
-// The same for a bf16 layer of known ranks.  By shape, groups of four with both ranks 32 or 64 also take the
-// matrix kernel: measured 2-5 % ahead of the vector kernel there with either kind of load (b4/32K 64/64: 40.3
-// against 41.3 us per launch on one machine) and level at short contexts; level or behind at ranks 48, 80, 96,
-// 128 (128/128 with streaming loads: 107 against 93 us), behind without grouping, and behind by 5-9 % for
-// groups of two below 8K rows.
-int decode_engine_for_layer(const skv_layer* L) {
+// Which range kernel streams the cache of this layer: 0 = vector arithmetic, 1 = matrix cores.  The layer's
+// SKV_ENGINE_* flag decides when set.  By shape, the matrix kernel where it saves a pass over the cache (eight
+// query heads per KV head) and over the quantised formats (bits = width of the codes, 0 for bf16 rows: there it
+// needs fewer vector instructions per row, which is what bounds both kernels: measured 31.4 against 35.2 us at
+// 8 bits); for bf16 rows in groups of four with both ranks 32 or 64 as well: measured 2-5 % ahead of the vector
+// kernel there with either kind of load (b4/32K 64/64: 40.3 against 41.3 us per launch on one machine) and level
+// at short contexts; level or behind at ranks 48, 80, 96, 128 (128/128 with streaming loads: 107 against 93 us),
+// behind without grouping, and behind by 5-9 % for groups of two below 8K rows.  Quantised rows in pages are
+// served by the matrix kernel only.
+int engine_for(const skv_layer* L, int bits = 0, bool paged_codes = false) {
+  if (paged_codes) return 1;
+  const uint32_t want = L->flags & SKV_ENGINE_MASK;
   const int group = L->n_q_heads / L->n_kv_heads;
-  if (g_decode_engine != 2 || group == 8) return decode_engine_for(group);
+  if (want == SKV_ENGINE_VECTOR) return 0;
+  if (want == SKV_ENGINE_MATRIX) return 1;
+  if (group == 8 || bits != 0) return 1;
   const bool small_pow2 = (L->r_k == 32 || L->r_k == 64) && (L->r_v == 32 || L->r_v == 64);
   return (group == 4 && small_pow2) ? 1 : 0;
 }
 
-// How the range kernels read cache rows: 0 = streaming loads, 1 = ordinary loads, 2 = by size (process-wide,
-// see skv.h).  By size: a launch whose rows add up to clearly more than the 256 MiB last-level cache cannot
+// How the range kernels read cache rows: 1 = streaming loads, 0 = ordinary loads.  The layer's SKV_READS_* flag
+// decides when set.  By size: a launch whose rows add up to clearly more than the 256 MiB last-level cache cannot
 // find them there on the next step and reads them with streaming loads (measured 8-10 % faster from 0.4 to
 // 10 GB per launch); one that fits, or nearly fits, keeps ordinary loads (rows re-read step after step are
 // partly served from that cache: at 256 MiB ordinary loads are 2 % ahead, at 288 MiB streaming ones 1 %,
-// at 384 MiB 10 %).
-int g_cache_reads = 2;
+// at 384 MiB 10 %).  A caller whose layers together exceed that cache sets SKV_READS_STREAMING on each.
 constexpr int64_t kStreamAboveBytes = 288ll << 20;
 int32_t stream_loads_for(const skv_layer* L, int64_t n_ctx, int bits = 0) {
-  if (g_cache_reads != 2) return g_cache_reads == 0 ? 1 : 0;
+  const uint32_t want = L->flags & SKV_READS_MASK;
+  if (want == SKV_READS_STREAMING) return 1;
+  if (want == SKV_READS_CACHED) return 0;
   const int64_t row_bits = (int64_t)(L->r_k + L->r_v) * (bits ? bits : 16);
   return (int64_t)L->batch * L->n_kv_heads * n_ctx * row_bits / 8 > kStreamAboveBytes ? 1 : 0;
 }
 
 // Query heads of a KV group one workgroup of the range kernel serves.  The vector kernel takes up to four (a
 // group of eight streams the cache twice); the matrix kernel has the columns for all eight in one pass.
-int decode_heads_per_pass(int group) {
-  return (decode_engine_for(group) == 1 && group == 8) ? 8 : heads_per_pass(group);
+int decode_heads_per_pass(const skv_layer* L, int bits = 0, bool paged_codes = false) {
+  const int group = L->n_q_heads / L->n_kv_heads;
+  return (group == 8 && engine_for(L, bits, paged_codes) == 1) ? 8 : heads_per_pass(group);
 }
 
 // need_bases = false: the folded-weights entry points, which never touch p_k / p_v.
@@ -82,6 +82,8 @@ skv_status check_layer(const skv_layer* L, bool need_bases = true) {
   // one grid row per (sequence, KV head, pass) in the streaming launch: the grid's y limit
   if ((int64_t)L->batch * L->n_kv_heads * (g / heads_per_pass(g)) > 65535) return SKV_ERR_SHAPE;
   if (!rank_ok(L->r_k) || !rank_ok(L->r_v)) return SKV_ERR_RANK;
+  if ((L->flags & ~(SKV_READS_MASK | SKV_ENGINE_MASK)) || L->reserved != 0) return SKV_ERR_SHAPE;
+  if ((L->flags & SKV_READS_MASK) == SKV_READS_MASK || (L->flags & SKV_ENGINE_MASK) == SKV_ENGINE_MASK) return SKV_ERR_SHAPE;
   if (L->capacity < 1 || L->capacity > std::numeric_limits<int32_t>::max()) return SKV_ERR_CAPACITY;
   const int64_t sk = L->p_k_head_stride, sv = L->p_v_head_stride;
   if (need_bases && sk != 0 && sk < (int64_t)SKV_HEAD_DIM * L->r_k) return SKV_ERR_SHAPE;
@@ -133,7 +135,7 @@ void fill_decode_params(const skv_layer* L, DecodeParams* p, int32_t n_splits, v
   p->seq_lens = nullptr;
   p->len_add = 0;
   p->pages = PageMap{nullptr, 0, 0, 0};
-  p->engine = decode_engine_for_layer(L);
+  p->engine = engine_for(L);
   p->stream_loads = 0;
   p->scale_log2e = 0.f;
   p->lift = 1;
@@ -185,8 +187,8 @@ skv_status check_decode_common(const skv_layer* L, int32_t n_splits, const void*
 
 }  // namespace
 
-bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx, int32_t want,
-                 int32_t* n_splits, int bits) {
+bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_splits, int bits, bool paged_codes) {
+  const int32_t batch = L->batch, n_kv_heads = L->n_kv_heads, group = L->n_q_heads / L->n_kv_heads;
   if (n_ctx < 1 || n_ctx > std::numeric_limits<int32_t>::max() - kRangeQuantum) return false;
   if (want > 0) {
     if (want > SKV_MAX_SPLITS) return false;
@@ -194,10 +196,10 @@ bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx
     return true;
   }
   const int64_t quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
-  const int64_t columns = (int64_t)batch * n_kv_heads * (group / decode_heads_per_pass(group));
+  const int64_t columns = (int64_t)batch * n_kv_heads * (group / decode_heads_per_pass(L, bits, paged_codes));
   // the matrix kernel over a quantised cache is bound by instruction issue, which more resident waves help
   // (measured best at 24..32 ranges for b4/32K where the bf16 kernels want 8..16)
-  const int64_t target = (bits != 0 && decode_engine_for(group, bits) == 1) ? 3 * kTargetWorkgroups / 2 : kTargetWorkgroups;
+  const int64_t target = (bits != 0 && engine_for(L, bits, paged_codes) == 1) ? 3 * kTargetWorkgroups / 2 : kTargetWorkgroups;
   int64_t s = (target + columns - 1) / (columns > 0 ? columns : 1);
   if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
   if (s > quanta) s = quanta;                 // never a range without rows
@@ -238,45 +240,17 @@ const char* skv_status_string(skv_status s) {
   return "SKV_ERR_UNKNOWN";
 }
 
-skv_status skv_probe_stream_read(const void* src, size_t bytes, int32_t workgroups, void* sink, size_t* bytes_read,
-                                 void* stream) {
-  if (!src || !sink || !bytes_read) return SKV_ERR_NULL;
-  if (!aligned16(src) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return SKV_ERR_ALIGN;
-  if (workgroups < 1 || workgroups > 65535) return SKV_ERR_SHAPE;
-  const size_t stride = 1024;                                        // 256 lanes x 4 pieces in flight
-  const size_t per_wg = bytes / 16 / (size_t)workgroups / stride * stride;
-  if (per_wg == 0) return SKV_ERR_SHAPE;
-  *bytes_read = per_wg * (size_t)workgroups * 16;
-  // the same kind of load a range kernel over that many bytes would use
-  const bool streaming = g_cache_reads == 0 || (g_cache_reads == 2 && (int64_t)*bytes_read > kStreamAboveBytes);
-  if (launch_stream_read(src, per_wg, workgroups, sink, streaming, static_cast<hipStream_t>(stream)) != hipSuccess)
-    return SKV_ERR_HIP;
-  return SKV_OK;
+int32_t skv_decode_engine_for(const skv_layer* L, int32_t code_bits) {
+  if (check_layer(L, false) != SKV_OK) return -1;
+  if (code_bits != 0 && code_bits != 8 && code_bits != 4) return -1;
+  return engine_for(L, code_bits);
 }
 
-skv_status skv_probe_stream_mix(const void* a, const void* b, void* c, size_t bytes, int32_t workgroups,
-                                size_t* bytes_each, void* stream) {
-  if (!a || !b || !c || !bytes_each) return SKV_ERR_NULL;
-  if (!aligned16(a) || !aligned16(b) || !aligned16(c)) return SKV_ERR_ALIGN;
-  if (workgroups < 1 || workgroups > 65535) return SKV_ERR_SHAPE;
-  const size_t stride = 1024;                                        // 256 lanes x 4 pieces in flight
-  const size_t per_wg = bytes / 16 / (size_t)workgroups / stride * stride;
-  if (per_wg == 0) return SKV_ERR_SHAPE;
-  *bytes_each = per_wg * (size_t)workgroups * 16;
-  if (launch_stream_mix(a, b, c, per_wg, workgroups, static_cast<hipStream_t>(stream)) != hipSuccess) return SKV_ERR_HIP;
-  return SKV_OK;
-}
-
-int32_t skv_set_cache_reads(int32_t mode) {
-  const int32_t before = g_cache_reads;
-  if (mode >= 0 && mode <= 2) g_cache_reads = mode;
-  return before;
-}
-
-int32_t skv_set_decode_engine(int32_t engine) {
-  const int32_t before = g_decode_engine;
-  if (engine >= 0 && engine <= 2) g_decode_engine = engine;
-  return before;
+int32_t skv_decode_streams_rows(const skv_layer* L, int64_t n_ctx, int32_t code_bits) {
+  if (check_layer(L, false) != SKV_OK) return -1;
+  if (code_bits != 0 && code_bits != 8 && code_bits != 4) return -1;
+  if (n_ctx < 1 || n_ctx > L->capacity) return -1;
+  return stream_loads_for(L, n_ctx, code_bits);
 }
 
 size_t skv_cache_bytes(const skv_layer* L, int64_t n_tokens) {
@@ -306,7 +280,7 @@ int32_t skv_decode_default_splits(const skv_layer* L, int64_t n_ctx) {
   if (check_layer(L) != SKV_OK) return 0;
   if (n_ctx < 1 || n_ctx > L->capacity) return 0;
   int32_t s = 0;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s)) return 0;
+  if (!plan_splits(L, n_ctx, 0, &s)) return 0;
   return s;
 }
 
@@ -328,12 +302,13 @@ skv_status check_query_stage(const skv_layer* L, const void* q, float scale, con
 }
 
 skv_status check_partial_stage(const skv_layer* L, int64_t n_ctx, int32_t n_splits,
-                               const void* workspace, size_t workspace_bytes, int32_t* s_out, int bits = 0) {
+                               const void* workspace, size_t workspace_bytes, int32_t* s_out, int bits = 0,
+                               bool paged_codes = false) {
   skv_status st = check_layer(L);
   if (st != SKV_OK) return st;
   if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
   if (n_splits > SKV_MAX_SPLITS) return SKV_ERR_SHAPE;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, n_splits, s_out, bits))
+  if (!plan_splits(L, n_ctx, n_splits, s_out, bits, paged_codes))
     return SKV_ERR_SHAPE;
   return check_decode_common(L, *s_out, workspace, workspace_bytes);
 }
@@ -444,20 +419,17 @@ skv_status run_partial(const skv_layer* L, int64_t n_ctx, int32_t s, void* works
   p.n_ctx = (int32_t)n_ctx;
   p.seq_lens = seq_lens;
   p.len_add = len_add;
-  p.stream_loads = stream_loads_for(L, n_ctx, q8 ? bits : 0);
-  if (q8) {
-    p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
-    p.engine = decode_engine_for(p.group, bits);
-  }
-  if (pages) {
-    p.pages = *pages;
-    if (q8) p.engine = 1;                        // quantised rows in pages: the matrix-core kernel only
-  }
+  const int cbits = q8 ? bits : 0;
+  const bool paged_codes = q8 && pages;          // quantised rows in pages: the matrix-core kernel only
+  p.stream_loads = stream_loads_for(L, n_ctx, cbits);
+  p.engine = engine_for(L, cbits, paged_codes);
+  if (q8) p.v_meta = static_cast<const uint32_t*>(q8->v_meta);
+  if (pages) p.pages = *pages;
   decode_partial_launcher launch = !q8     ? (pages ? paged_partial_launcher_for(L->r_k) : partial_launcher_for(L->r_k))
                                    : pages ? paged_partial_q_launcher_for(bits, L->r_k)
                                            : partial_q_launcher_for(bits, L->r_k);
   if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, decode_heads_per_pass(L, cbits, paged_codes), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }
@@ -489,7 +461,7 @@ skv_status run_partial_fused(const skv_layer* L, const void* q, float scale, int
   if (pages) p.pages = *pages;
   decode_partial_launcher launch = pages ? paged_partial_launcher_for(L->r_k) : partial_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, decode_heads_per_pass(L), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }
@@ -588,12 +560,12 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
   hipStream_t hs = static_cast<hipStream_t>(stream);
   const int gq = L->n_q_heads / L->n_kv_heads;
   // (the fused launch adds up to one grid row per column: stay inside the grid's y limit)
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(L)) <= 65535;
   if (T > 0 && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
     // The usual decode step, two launches: context ranges over the rows already cached, plus one
     // workgroup per (sequence, KV head) that projects, stores and attends the new rows; then the merge.
     int32_t s_old = 0;
-    if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (!plan_splits(L, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
     if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused(L, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
@@ -821,7 +793,7 @@ int32_t q_default_splits(const skv_q8_layer* Q, int bits, int64_t n_ctx) {
   const skv_layer* L = &Q->base;
   if (n_ctx < 1 || n_ctx > L->capacity) return 0;
   int32_t s = 0;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, bits)) return 0;
+  if (!plan_splits(L, n_ctx, 0, &s, bits)) return 0;
   return s;
 }
 
@@ -865,7 +837,7 @@ skv_status run_partial_fused_q(const skv_q8_layer* Q, int bits, const void* q, f
   if (pages) p.pages = *pages;
   decode_partial_launcher launch = pages ? paged_partial_q_launcher_for(bits, L->r_k) : partial_q_launcher_for(bits, L->r_k);
   if (!launch) return SKV_ERR_RANK;
-  if (launch(L->r_v, decode_heads_per_pass(p.group), p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, decode_heads_per_pass(L, bits, pages != nullptr), p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }
@@ -887,15 +859,16 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   if (st != SKV_OK) return st;
   const int64_t n_ctx = cur_len + T;
   int32_t s = 0;
-  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s, bits);
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s, bits, pages != nullptr);
   if (st != SKV_OK) return st;
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   // With the matrix-core kernel a step is two launches, as over the bf16 cache: the range kernel projects the
   // queries itself, and for a few new tokens extra workgroups quantise, store and attend them.
   const int gq = L->n_q_heads / L->n_kv_heads;
-  const bool matrix = pages != nullptr || decode_engine_for(gq, bits) == 1;
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
+  const bool paged_codes = pages != nullptr;
+  const bool matrix = engine_for(L, bits, paged_codes) == 1;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(L, bits, paged_codes)) <= 65535;
   if (matrix && T == 0) {
     st = run_partial_fused_q(Q, bits, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream, cur_lens, pages);
     if (st != SKV_OK) return st;
@@ -903,7 +876,7 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   }
   if (matrix && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
     int32_t s_old = 0;
-    if (!plan_splits(L->batch, L->n_kv_heads, gq, cur_len, 0, &s_old, bits)) return SKV_ERR_SHAPE;
+    if (!plan_splits(L, cur_len, 0, &s_old, bits, paged_codes)) return SKV_ERR_SHAPE;
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
     if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused_q(Q, bits, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
@@ -1014,7 +987,7 @@ skv_status check_folded_decode(const skv_layer* L, const void* q_low, const void
   if (!aligned16(q_low) || !aligned16(out_low) || !aligned16(workspace)) return SKV_ERR_ALIGN;
   if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
   if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, s_out)) return SKV_ERR_SHAPE;
+  if (!plan_splits(L, n_ctx, 0, s_out)) return SKV_ERR_SHAPE;
   return check_decode_common(L, *s_out, workspace, workspace_bytes);
 }
 
@@ -1118,10 +1091,10 @@ skv_status step_lens(const skv_layer* L, const void* k_new, const void* v_new, i
   st = check_combine_stage(L, out, s, workspace, workspace_bytes);
   if (st != SKV_OK) return st;
   const int gq = L->n_q_heads / L->n_kv_heads;
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(gq)) <= 65535;
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(L)) <= 65535;
   if (T <= kFusedStepMaxTokens && max_cur_len > 0 && grid_ok) {
     int32_t s_old = 0;
-    if (!plan_splits(L->batch, L->n_kv_heads, gq, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (!plan_splits(L, max_cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
     if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused(L, q, scale, max_cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
@@ -1226,7 +1199,7 @@ int32_t skv_paged_decode_default_splits(const skv_paged_layer* P, int64_t n_ctx)
   const skv_layer* L = &P->layer;
   if (n_ctx < 1 || n_ctx > L->capacity) return 0;
   int32_t s = 0;
-  if (!plan_splits(L->batch, L->n_kv_heads, L->n_q_heads / L->n_kv_heads, n_ctx, 0, &s, P->code_bits)) return 0;
+  if (!plan_splits(L, n_ctx, 0, &s, P->code_bits, P->code_bits != 0)) return 0;
   return s;
 }
 

@@ -149,10 +149,11 @@ inline int prefill_tile_tokens(int group) { return 32 * (4 / heads_per_pass(grou
 constexpr int kRangeQuantum = 64;
 constexpr int kDecodeThreads = 256;
 
-// Number of context ranges for n_ctx tokens.  want <= 0: heuristic.  Returns false if `want`
+// Number of context ranges for n_ctx tokens of this layer (bits: 0 for bf16 rows, else the width of the
+// quantised codes; paged_codes: quantised rows in pages).  want <= 0: heuristic.  Returns false if `want`
 // is out of range.
-bool plan_splits(int32_t batch, int32_t n_kv_heads, int32_t group, int64_t n_ctx,
-                 int32_t want, int32_t* n_splits, int bits = 0);
+bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_splits, int bits = 0,
+                 bool paged_codes = false);
 
 // Rows [t0, t1) of range `split` out of n_splits over n_ctx rows: whole quanta, dealt as evenly
 // as possible (the first `rem` ranges get one more); empty when t0 >= t1.
@@ -219,11 +220,6 @@ hipError_t launch_prefill_paged_rk112(int, int, int, const PrefillParams&, hipSt
 hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
-// reads workgroups * pieces_per_wg 16-byte pieces (pieces_per_wg a multiple of 1024), writes nothing
-hipError_t launch_stream_read(const void* src, size_t pieces_per_wg, int workgroups, void* sink, bool streaming,
-                              hipStream_t stream);
-hipError_t launch_stream_mix(const void* a, const void* b, void* c, size_t pieces_per_wg, int workgroups,
-                             hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)
 hipError_t launch_pad_basis(const void* src, void* dst, int r, int r_pad, int64_t rows, hipStream_t stream);
 // out bf16 [n][128][r_out]: leading r columns of the orthonormal factor of a float32 [n][128][128], zero columns behind

@@ -28,14 +28,16 @@ def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
 
 
-@pytest.fixture(params=[(0, 2), (1, 2), (0, 0), (1, 0)], ids=["vector", "matrix", "vector-streamed", "matrix-streamed"])
+@pytest.fixture(params=["vector", "matrix", "vector-streamed", "matrix-streamed"])
 def decode_engine(request):
     """Runs a test once per range kernel over bf16 rows (vector arithmetic, matrix cores) and per kind of
-    cache load (chosen by size, which means ordinary loads at test sizes; streaming loads forced)."""
+    cache load (chosen by size, which means ordinary loads at test sizes; streaming loads forced).  The
+    choice travels in the flags word of every layer the test builds (the binding's default for new layers)."""
     from paper_2601_21686_amd import binding
-    engine, reads = request.param
-    before = binding.skv_set_decode_engine(engine)
-    before_reads = binding.skv_set_cache_reads(reads)
-    yield engine
-    binding.skv_set_decode_engine(before)
-    binding.skv_set_cache_reads(before_reads)
+    flags = binding.SKV_ENGINE_MATRIX if request.param.startswith("matrix") else binding.SKV_ENGINE_VECTOR
+    if request.param.endswith("streamed"):
+        flags |= binding.SKV_READS_STREAMING
+    before = binding.DEFAULT_LAYER_FLAGS
+    binding.DEFAULT_LAYER_FLAGS = flags
+    yield 1 if request.param.startswith("matrix") else 0
+    binding.DEFAULT_LAYER_FLAGS = before

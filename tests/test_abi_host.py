@@ -16,8 +16,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libskv.so not built")
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "skv.h")).read()
+def _declared_functions(header="skv.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(skv_[a-z_0-9]+)\s*\(", text)))
 
@@ -28,6 +28,19 @@ def test_library_exports_every_declared_function():
     lib = B.lib()
     for n in names:
         assert hasattr(lib, n), n
+
+
+def test_every_header_is_covered_and_the_probe_library_exports_its_own():
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["skv.h", "skv_probe.h"]
+    names = _declared_functions("skv_probe.h")
+    assert set(names) == set(B.PROBE_EXPORTS)
+    probe = B.probe_lib()
+    for n in names:
+        assert hasattr(probe, n), n
+    # the product library holds the method only: no yardstick kernels, no process-wide switches
+    lib = B.lib()
+    for n in list(B.PROBE_EXPORTS) + ["skv_set_decode_engine", "skv_set_cache_reads"]:
+        assert not hasattr(lib, n), n
 
 
 def test_status_strings():
@@ -360,39 +373,57 @@ def test_paged_layer_argument_checks():
                                            None) == B.SKV_ERR_CAPACITY
 
 
-def test_decode_engine_switch():
+def test_layer_flags_are_validated_and_steer_the_choices():
     lib = B.lib()
-    before = lib.skv_set_decode_engine(1)
-    assert before == 2                                  # the default: chosen by shape
-    assert lib.skv_set_decode_engine(-1) == 1          # anything but 0, 1, 2 changes nothing
-    assert lib.skv_set_decode_engine(7) == 1
-    assert lib.skv_set_decode_engine(0) == 1
-    assert lib.skv_set_decode_engine(before) == 0
-    assert lib.skv_set_decode_engine(-1) == 2
-
-
-def test_cache_read_mode_switch():
-    lib = B.lib()
-    before = lib.skv_set_cache_reads(0)
-    assert before == 2                                  # by size unless told otherwise
-    assert lib.skv_set_cache_reads(-1) == 0             # anything but 0, 1, 2 changes nothing
-    assert lib.skv_set_cache_reads(3) == 0
-    assert lib.skv_set_cache_reads(1) == 0
-    assert lib.skv_set_cache_reads(before) == 1
-    assert lib.skv_set_cache_reads(-1) == 2
+    big = 1 << 30
+    att = lambda L: lib.skv_decode_attention(C.byref(L), FAKE, FAKE, 100, 0.0, FAKE, big, None)
+    # unknown bits, both bits of a field, or a non-zero reserved word: rejected before anything is launched
+    assert att(_layer(flags=16)) == B.SKV_ERR_SHAPE
+    assert att(_layer(flags=0x80000000)) == B.SKV_ERR_SHAPE
+    assert att(_layer(flags=B.SKV_READS_STREAMING | B.SKV_READS_CACHED)) == B.SKV_ERR_SHAPE
+    assert att(_layer(flags=B.SKV_ENGINE_VECTOR | B.SKV_ENGINE_MATRIX)) == B.SKV_ERR_SHAPE
+    assert att(_layer(reserved=1)) == B.SKV_ERR_SHAPE
+    assert lib.skv_decode_workspace_bytes(C.byref(_layer(flags=16))) == 0
+    assert lib.skv_decode_engine_for(C.byref(_layer(flags=16)), 0) == -1
+    # the engine by shape (32 query heads over 8 KV heads in _layer's default: groups of four) ...
+    eng = lambda bits=0, **kw: lib.skv_decode_engine_for(C.byref(_layer(**kw)), bits)
+    assert eng() == 1                                                        # 64/64, groups of four: matrix cores
+    assert eng(r_k=48, p_k_head_stride=128 * 48) == 0                        # other ranks: vector arithmetic
+    assert eng(r_v=128, p_v_head_stride=128 * 128) == 0
+    assert eng(n_q_heads=8) == 0                                             # no grouping
+    assert eng(n_q_heads=64) == 1                                            # groups of eight: one pass on the matrix cores
+    assert eng(8, r_k=96, p_k_head_stride=128 * 96) == 1                     # quantised codes
+    assert eng(4, n_q_heads=8) == 1
+    assert eng(3) == -1
+    # ... and forced by the layer's flag, whatever the shape
+    assert eng(flags=B.SKV_ENGINE_VECTOR) == 0
+    assert eng(8, flags=B.SKV_ENGINE_VECTOR) == 0
+    assert eng(n_q_heads=8, flags=B.SKV_ENGINE_MATRIX) == 1
+    # groups of eight: the vector kernel streams the cache twice (twice the columns, half the ranges)
+    auto8, vec8 = _layer(n_q_heads=64, capacity=1 << 16), _layer(n_q_heads=64, capacity=1 << 16, flags=B.SKV_ENGINE_VECTOR)
+    assert lib.skv_decode_default_splits(C.byref(auto8), 1 << 16) == 2 * lib.skv_decode_default_splits(C.byref(vec8), 1 << 16)
+    # the kind of load: by size (288 MiB of rows per launch), or as the flag says
+    rows = lambda n, **kw: lib.skv_decode_streams_rows(C.byref(_layer(capacity=1 << 20, **kw)), n, 0)
+    assert rows(32768) == 0                                                  # 4 x 8 x 32768 x 256 B = 256 MiB
+    assert rows(40000) == 1                                                  # 312 MiB
+    assert rows(100, flags=B.SKV_READS_STREAMING) == 1
+    assert rows(1 << 20, flags=B.SKV_READS_CACHED) == 0
+    assert rows(0) == -1 and rows((1 << 20) + 1) == -1
+    assert lib.skv_decode_streams_rows(C.byref(_layer(capacity=1 << 20)), 70000, 8) == 0     # half the bytes per row
+    assert lib.skv_decode_streams_rows(C.byref(_layer(capacity=1 << 20)), 80000, 8) == 1
 
 
 def test_read_probe_argument_checks():
-    lib = B.lib()
+    lib = B.probe_lib()
     n = C.c_size_t(0)
-    assert lib.skv_probe_stream_read(None, 1 << 20, 4, FAKE, C.byref(n), None) == B.SKV_ERR_NULL
-    assert lib.skv_probe_stream_read(FAKE + 4, 1 << 20, 4, FAKE, C.byref(n), None) == B.SKV_ERR_ALIGN
-    assert lib.skv_probe_stream_read(FAKE, 1 << 20, 0, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE
-    assert lib.skv_probe_stream_read(FAKE, 1000, 4, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE    # less than a slice each
+    assert lib.skv_probe_stream_read(None, 1 << 20, 4, 0, FAKE, C.byref(n), None) == B.SKV_ERR_NULL
+    assert lib.skv_probe_stream_read(FAKE + 4, 1 << 20, 4, 0, FAKE, C.byref(n), None) == B.SKV_ERR_ALIGN
+    assert lib.skv_probe_stream_read(FAKE, 1 << 20, 0, 1, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE
+    assert lib.skv_probe_stream_read(FAKE, 1000, 4, 1, FAKE, C.byref(n), None) == B.SKV_ERR_SHAPE    # less than a slice each
 
 
 def test_mix_probe_argument_checks():
-    lib = B.lib()
+    lib = B.probe_lib()
     n = C.c_size_t(0)
     assert lib.skv_probe_stream_mix(FAKE, None, FAKE, 1 << 20, 4, C.byref(n), None) == B.SKV_ERR_NULL
     assert lib.skv_probe_stream_mix(FAKE, FAKE, FAKE + 8, 1 << 20, 4, C.byref(n), None) == B.SKV_ERR_ALIGN
@@ -439,7 +470,6 @@ def test_paged_quantised_argument_checks():
     assert att(paged(4, r_v=96, p_v_head_stride=128 * 96)) == B.SKV_ERR_RANK     # 4-bit ranks: multiples of 64
     assert lib.skv_paged_pool_bytes(C.byref(paged(8))) == 100 * 8 * 64 * (64 + 64 + 4)
     assert lib.skv_paged_pool_bytes(C.byref(paged(4))) == 100 * 8 * 64 * (32 + 32 + 4)
-    lib.skv_set_decode_engine(2)
     assert lib.skv_paged_decode_default_splits(C.byref(paged(0)), 1024) == 8       # bf16 rows: one workgroup per CU below 1024 rows each
     assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 1024) == 8       # 24 wanted; one workgroup per CU below 1024 rows each
     assert lib.skv_paged_decode_default_splits(C.byref(paged(8)), 2000) == 0

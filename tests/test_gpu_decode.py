@@ -261,13 +261,11 @@ def test_kind_of_cache_load_does_not_change_a_bit(r_k, r_v, hq, hkv):
     n = 2100
     P = _filled_pair(("loads", r_k, r_v), 2, hq, hkv, r_k, r_v, n)
     q = P.queries(3)
-    before = B.skv_set_cache_reads(1)
-    try:
-        plain = P.gpu_decode(q, n)
-        B.skv_set_cache_reads(0)
-        streamed = P.gpu_decode(q, n)
-    finally:
-        B.skv_set_cache_reads(before)
+    engine = P.gpu.c.flags & (B.SKV_ENGINE_VECTOR | B.SKV_ENGINE_MATRIX)
+    P.gpu.c.flags = engine | B.SKV_READS_CACHED
+    plain = P.gpu_decode(q, n)
+    P.gpu.c.flags = engine | B.SKV_READS_STREAMING
+    streamed = P.gpu_decode(q, n)
     assert np.array_equal(plain, streamed)
     assert vec_rel_err(plain, P.oracle_decode(q, n)) <= TOL
 

@@ -9,11 +9,12 @@ from paper_2601_21686_amd import binding as B
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("streaming", [False, True])
 @pytest.mark.parametrize("n_bytes,workgroups", [(1 << 22, 64), ((1 << 22) + 40000, 100), (16384 * 7, 7)])
-def test_read_probe_covers_whole_slices_and_writes_nothing(n_bytes, workgroups):
+def test_read_probe_covers_whole_slices_and_writes_nothing(n_bytes, workgroups, streaming):
     src = torch.ones(n_bytes // 4, dtype=torch.int32, device="cuda")
     sink = torch.full((workgroups,), -7.0, dtype=torch.float32, device="cuda")
-    n = B.skv_probe_stream_read(src, workgroups, sink)
+    n = B.skv_probe_stream_read(src, workgroups, sink, streaming)
     torch.cuda.synchronize()
     assert 0 < n <= n_bytes and n % (workgroups * 16384) == 0 and n_bytes - n < workgroups * 16384
     assert bool((sink == -7.0).all())
