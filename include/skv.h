@@ -4,10 +4,12 @@
  *
  * C ABI.  Plain pointers and sizes only.  Every pointer marked "device" is GPU
  * memory owned by the caller; "host" is ordinary process memory.  The library
- * owns no memory, keeps no state between calls (everything a call depends on
- * is in its arguments), never allocates and never synchronises: GPU work is
- * enqueued on the hipStream_t passed as `stream` (NULL = the default stream)
- * and the call returns at once.  All arguments are
+ * keeps no state between calls (everything a call depends on is in its
+ * arguments), never allocates and never synchronises, and owns no memory but
+ * one static device scratch array that a single entry point,
+ * skv_decode_attention_static, uses (described there).  GPU work is enqueued
+ * on the hipStream_t passed as `stream` (NULL = the default stream) and the
+ * call returns at once.  All arguments are
  * checked on the host before anything is launched; when a call returns an
  * error nothing has been written.  The return value is the only error channel.
  *
@@ -143,6 +145,27 @@ skv_status skv_project_append(const skv_layer* layer,
 skv_status skv_decode_attention(const skv_layer* layer, const void* q, void* out,
                                 int64_t n_ctx, float scale,
                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * skv_decode_attention for callers that cannot allocate device memory or hand over a workspace: code under
+ * stream capture, tight serving loops, harnesses that forbid allocation.  The same computation with the
+ * same kernels and the same range plan (results are bit-identical to skv_decode_attention), but the scratch
+ * memory is a static device array of SKV_STATIC_SCRATCH_BYTES that the library itself holds on every GPU it
+ * runs on, from the first such call on that GPU until the process ends.  The call allocates nothing and frees
+ * nothing.  Its first use on a device resolves the array's address there (a symbol lookup): make that first
+ * call outside stream capture.
+ *   Limit: a call whose plan needs more than SKV_STATIC_SCRATCH_BYTES of scratch (projected queries,
+ *   batch * n_q_heads * r_k * 4 bytes, plus batch * n_q_heads * ranges * (r_v + 2) * 4 bytes of partial
+ *   results; about 1 MiB at batch 4, 32 query heads, ranks 128) returns SKV_ERR_WORKSPACE and launches nothing.
+ *   Sharing: every call on one GPU uses that GPU's one array, whose contents on entry are irrelevant (the
+ *   kernels write every word they later read).  Calls that may overlap in time on one GPU -- different
+ *   streams, different threads -- race on it: serialise them, or use skv_decode_attention with separate
+ *   workspaces.
+ * Other arguments and errors as for skv_decode_attention.
+ */
+#define SKV_STATIC_SCRATCH_BYTES (4u << 20)
+skv_status skv_decode_attention_static(const skv_layer* layer, const void* q, void* out,
+                                       int64_t n_ctx, float scale, void* stream);
 
 /* Bytes of workspace that skv_decode_attention, skv_decode_step and the stages need for
  * this layer at any n_ctx <= capacity and any split count <= SKV_MAX_SPLITS.

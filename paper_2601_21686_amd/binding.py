@@ -32,7 +32,7 @@ SKV_ENGINE_BY_SHAPE, SKV_ENGINE_VECTOR, SKV_ENGINE_MATRIX = 0, 4, 8
 DEFAULT_LAYER_FLAGS = 0
 
 EXPORTS = (
-    "skv_project_append", "skv_decode_attention", "skv_decode_workspace_bytes",
+    "skv_project_append", "skv_decode_attention", "skv_decode_attention_static", "skv_decode_workspace_bytes",
     "skv_decode_default_splits", "skv_decode_range", "skv_decode_step", "skv_decode_project_query",
     "skv_decode_partial", "skv_decode_combine", "skv_decode_partial_q",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
@@ -97,6 +97,8 @@ def lib() -> C.CDLL:
     L.skv_project_append.restype = C.c_int
     L.skv_decode_attention.argtypes = [LP, vp, vp, i64, C.c_float, vp, sz, vp]
     L.skv_decode_attention.restype = C.c_int
+    L.skv_decode_attention_static.argtypes = [LP, vp, vp, i64, C.c_float, vp]
+    L.skv_decode_attention_static.restype = C.c_int
     L.skv_decode_workspace_bytes.argtypes = [LP]
     L.skv_decode_workspace_bytes.restype = sz
     L.skv_decode_default_splits.argtypes = [LP, i64]
@@ -363,6 +365,13 @@ def skv_decode_attention(layer, q: torch.Tensor, out: torch.Tensor, n_ctx: int, 
     _check(lib().skv_decode_attention(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx),
                                       float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
                                       _stream_ptr(stream)), "skv_decode_attention")
+
+
+def skv_decode_attention_static(layer: "Layer", q: torch.Tensor, out: torch.Tensor, n_ctx: int, scale: float = 0.0,
+                                stream=None) -> None:
+    """skv_decode_attention without a workspace argument: the library's static device scratch array serves."""
+    _check(lib().skv_decode_attention_static(_ref(layer), q.data_ptr(), out.data_ptr(), int(n_ctx), float(scale),
+                                             _stream_ptr(stream)), "skv_decode_attention_static")
 
 
 def skv_decode_step(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: int, q: torch.Tensor,

@@ -48,6 +48,7 @@ def _jobs():
             ("skv_folded.o", ["-x", "hip", os.path.join(CSRC, "skv_folded.hip")], DEVICE_FLAGS),
             ("skv_append.o", ["-x", "hip", os.path.join(CSRC, "skv_append.hip")], DEVICE_FLAGS),
             ("skv_basis.o", ["-x", "hip", os.path.join(CSRC, "skv_basis.hip")], DEVICE_FLAGS),
+            ("skv_static.o", ["-x", "hip", os.path.join(CSRC, "skv_static.hip")], DEVICE_FLAGS),
             ("skv_probe.o", ["-x", "hip", os.path.join(CSRC, "skv_probe.hip")], DEVICE_FLAGS)]
     for rk in KEY_RANKS:
         jobs.append((f"skv_decode_partial_rk{rk}.o",

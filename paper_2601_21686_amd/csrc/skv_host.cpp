@@ -219,6 +219,16 @@ bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_spl
   return true;
 }
 
+skv_status decode_attention_workspace_need(const skv_layer* L, int64_t n_ctx, size_t* bytes) {
+  const skv_status st = check_layer(L);
+  if (st != SKV_OK) return st;
+  if (n_ctx < 1 || n_ctx > L->capacity) return SKV_ERR_CAPACITY;
+  int32_t s = 0;
+  if (!plan_splits(L, n_ctx, 0, &s)) return SKV_ERR_SHAPE;
+  *bytes = workspace_need(L, s);
+  return SKV_OK;
+}
+
 }  // namespace skv
 
 using namespace skv;

@@ -155,6 +155,10 @@ constexpr int kDecodeThreads = 256;
 bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_splits, int bits = 0,
                  bool paged_codes = false);
 
+// Bytes of workspace skv_decode_attention uses for n_ctx rows of this layer (its own range plan; at most
+// skv_decode_workspace_bytes).  Validates the layer and n_ctx as that call does.
+skv_status decode_attention_workspace_need(const skv_layer* L, int64_t n_ctx, size_t* bytes);
+
 // Rows [t0, t1) of range `split` out of n_splits over n_ctx rows: whole quanta, dealt as evenly
 // as possible (the first `rem` ranges get one more); empty when t0 >= t1.
 __host__ __device__ inline void range_of_split(int n_ctx, int n_splits, int split, int* t0, int* t1) {

@@ -413,6 +413,20 @@ def test_layer_flags_are_validated_and_steer_the_choices():
     assert lib.skv_decode_streams_rows(C.byref(_layer(capacity=1 << 20)), 80000, 8) == 1
 
 
+def test_static_scratch_entry_point_checks_before_it_touches_the_gpu():
+    lib = B.lib()
+    att = lambda L, n=100: lib.skv_decode_attention_static(C.byref(L), FAKE, FAKE, n, 0.0, None)
+    assert att(_layer(r_k=72)) == B.SKV_ERR_RANK
+    assert att(_layer(k_cache=None)) == B.SKV_ERR_NULL
+    assert att(_layer(), 0) == B.SKV_ERR_CAPACITY
+    assert att(_layer(), 1025) == B.SKV_ERR_CAPACITY
+    # 64 sequences x 64 query heads at ranks 128: 2 MiB of projected queries and 2.1 MiB for one partial result
+    # per head do not fit the 4 MiB array
+    huge = _layer(batch=64, n_q_heads=64, r_k=128, r_v=128, p_k_head_stride=128 * 128, p_v_head_stride=128 * 128)
+    assert att(huge, 64) == B.SKV_ERR_WORKSPACE
+    assert lib.skv_decode_workspace_bytes(C.byref(huge)) > (4 << 20)
+
+
 def test_read_probe_argument_checks():
     lib = B.probe_lib()
     n = C.c_size_t(0)
