@@ -13,7 +13,8 @@ import os
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libskv.so")
+# SKV_LIBRARY names another build of the library to load instead (the host layer built with sanitizers, say).
+LIB_PATH = os.environ.get("SKV_LIBRARY") or os.path.join(_PKG, "libskv.so")
 PROBE_LIB_PATH = os.path.join(_PKG, "libskv_probe.so")     # the benchmark's plain streaming kernels (include/skv_probe.h)
 
 SKV_OK = 0
@@ -97,8 +98,9 @@ def lib() -> C.CDLL:
     L.skv_project_append.restype = C.c_int
     L.skv_decode_attention.argtypes = [LP, vp, vp, i64, C.c_float, vp, sz, vp]
     L.skv_decode_attention.restype = C.c_int
-    L.skv_decode_attention_static.argtypes = [LP, vp, vp, i64, C.c_float, vp]
-    L.skv_decode_attention_static.restype = C.c_int
+    if hasattr(L, "skv_decode_attention_static"):              # absent from a host-only build
+        L.skv_decode_attention_static.argtypes = [LP, vp, vp, i64, C.c_float, vp]
+        L.skv_decode_attention_static.restype = C.c_int
     L.skv_decode_workspace_bytes.argtypes = [LP]
     L.skv_decode_workspace_bytes.restype = sz
     L.skv_decode_default_splits.argtypes = [LP, i64]

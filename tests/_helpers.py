@@ -19,6 +19,16 @@ def vec_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.max(num / den))
 
 
+def elem_rel_err(got: np.ndarray, want: np.ndarray, floor: float = 1e-3) -> float:
+    """max over elements of |got - want| / max(|want|, floor * ||want||_inf of the element's vector): the plain
+    element-wise relative error, with an absolute floor so that entries near zero do not decide it.  Logged
+    beside vec_rel_err; the tolerance is stated for vec_rel_err."""
+    got = np.asarray(got, np.float64).reshape(-1, got.shape[-1])
+    want = np.asarray(want, np.float64).reshape(-1, want.shape[-1])
+    den = np.maximum(np.abs(want), floor * np.max(np.abs(want), axis=1, keepdims=True))
+    return float(np.max(np.abs(got - want) / den))
+
+
 def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
     """Distance in units of bf16 steps between two arrays of bit patterns."""
     def key(x):

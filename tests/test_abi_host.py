@@ -14,6 +14,9 @@ from paper_2601_21686_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 pytestmark = pytest.mark.skipif(not os.path.exists(B.LIB_PATH), reason="libskv.so not built")
+# A build of the host layer alone (SKV_LIBRARY, see test_host_sanitizers.py) holds no .hip translation unit:
+# the entry point that lives in one is absent there.
+HOST_ONLY = bool(os.environ.get("SKV_LIBRARY"))
 
 
 def _declared_functions(header="skv.h"):
@@ -27,7 +30,7 @@ def test_library_exports_every_declared_function():
     assert set(names) == set(B.EXPORTS)
     lib = B.lib()
     for n in names:
-        assert hasattr(lib, n), n
+        assert hasattr(lib, n) or (HOST_ONLY and n == "skv_decode_attention_static"), n
 
 
 def test_every_header_is_covered_and_the_probe_library_exports_its_own():
@@ -413,6 +416,7 @@ def test_layer_flags_are_validated_and_steer_the_choices():
     assert lib.skv_decode_streams_rows(C.byref(_layer(capacity=1 << 20)), 80000, 8) == 1
 
 
+@pytest.mark.skipif(HOST_ONLY, reason="lives in a .hip translation unit, which a host-only build leaves out")
 def test_static_scratch_entry_point_checks_before_it_touches_the_gpu():
     lib = B.lib()
     att = lambda L, n=100: lib.skv_decode_attention_static(C.byref(L), FAKE, FAKE, n, 0.0, None)

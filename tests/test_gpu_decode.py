@@ -216,7 +216,32 @@ def test_alternating_calls_on_one_workspace_are_bit_stable():
     for i in range(400):
         name = "a" if i % 2 == 0 else "b"
         assert np.array_equal(got[i], got[i % 2]), i                     # same bits as the first call of its kind
-        assert vec_rel_err(got[i], ref[name]) < 1e-5                      # and the two-launch path's values
+        assert np.array_equal(got[i], ref[name]), i                       # which are the bits of the two-launch path
+
+
+@pytest.mark.parametrize("batch,hq,hkv,r_k,r_v,n", [(4, 32, 8, 64, 64, 5000), (1, 8, 8, 48, 80, 700), (2, 8, 4, 128, 32, 1300),
+                                                    (3, 16, 2, 32, 96, 2100), (2, 4, 4, 16, 16, 64), (1, 32, 8, 96, 128, 9000)])
+def test_attention_ignores_what_the_workspace_held(batch, hq, hkv, r_k, r_v, n):
+    """The workspace's contents on entry are irrelevant by contract: random bytes, all ones and the leftovers of
+    other calls must all give the bits of the stage calls (range stage, then the merge launch)."""
+    P = _filled_pair(("scribble", r_k, r_v, n), batch, hq, hkv, r_k, r_v, n)
+    q = P.queries(5)
+    ws = P.gpu.workspace()
+    s = B.skv_decode_default_splits(P.gpu, n)
+    ref = torch.empty((batch, hq, 128), dtype=torch.float32, device="cuda")
+    B.skv_decode_partial_q(P.gpu, q, n, s)
+    B.skv_decode_combine(P.gpu, ref, s)
+    outs = torch.full((24, batch, hq, 128), float("nan"), dtype=torch.float32, device="cuda")
+    for i in range(24):
+        if i % 3 == 0:
+            ws.random_(0, 256)
+        elif i % 3 == 1:
+            ws.fill_(255)
+        B.skv_decode_attention(P.gpu, q, outs[i], n)                      # i % 3 == 2: the previous call's leftovers
+    torch.cuda.synchronize()
+    for i in range(24):
+        assert torch.equal(outs[i], ref), i
+    assert vec_rel_err(ref.cpu().numpy(), P.oracle_decode(q, n)) <= TOL
 
 
 def test_decode_steps_captured_in_a_hip_graph_replay_identically():
