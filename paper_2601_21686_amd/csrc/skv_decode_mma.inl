@@ -76,6 +76,12 @@ __device__ __forceinline__ float byte_to_f32(uint32_t w) { return (float)((w >> 
 __device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_0_and_2) {
   return (pair_in_bytes_0_and_2 << 3) | 0x41804180u;
 }
+// byte N of lo into byte 0 and byte N of hi into byte 2 of the result, zeros between: one byte-permute
+// (selector bytes: 0..3 pick from lo, 4..7 from hi, 0x0c gives zero)
+template <int N>
+__device__ __forceinline__ uint32_t byte_pair(uint32_t lo, uint32_t hi) {
+  return __builtin_amdgcn_perm(hi, lo, 0x0c000c00u | (uint32_t)N | ((uint32_t)(4 + N) << 16));
+}
 
 #ifndef SKV_MMA_DEPTH
 #define SKV_MMA_DEPTH 1          // tiles a wave has requested ahead of the one it computes on (1 or 2)
@@ -291,10 +297,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint4 {
     const uint32_t w = tr.k[kb][ks];                             // 8 codes: the even channel in the low half of a byte
     const uint32_t ev = w & 0x0f0f0f0fu, od = (w >> 4) & 0x0f0f0f0fu;
-    return uint4{nibbles_to_bf16_pair((ev & 0xffu) | ((od & 0xffu) << 16)),
-                 nibbles_to_bf16_pair(((ev >> 8) & 0xffu) | (((od >> 8) & 0xffu) << 16)),
-                 nibbles_to_bf16_pair(((ev >> 16) & 0xffu) | (((od >> 16) & 0xffu) << 16)),
-                 nibbles_to_bf16_pair((ev >> 24) | ((od >> 24) << 16))};
+    return uint4{nibbles_to_bf16_pair(byte_pair<0>(ev, od)), nibbles_to_bf16_pair(byte_pair<1>(ev, od)),
+                 nibbles_to_bf16_pair(byte_pair<2>(ev, od)), nibbles_to_bf16_pair(byte_pair<3>(ev, od))};
   };
 #else
   auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint2 {
@@ -339,8 +343,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #pragma unroll
           for (int e2 = 0; e2 < 4; ++e2) {
             const uint32_t a = (c & 1) ? od[2 * e2] : ev[2 * e2], bb = (c & 1) ? od[2 * e2 + 1] : ev[2 * e2 + 1];
-            const int sh = 8 * (c >> 1);
-            o[e2] = nibbles_to_bf16_pair(((a >> sh) & 0xffu) | (((bb >> sh) & 0xffu) << 16));
+            // channel c of rows 2 e2 and 2 e2 + 1: the same byte of two words, picked by one byte-permute
+            const uint32_t pair = (c >> 1) == 0 ? byte_pair<0>(a, bb) : (c >> 1) == 1 ? byte_pair<1>(a, bb)
+                                : (c >> 1) == 2 ? byte_pair<2>(a, bb) : byte_pair<3>(a, bb);
+            o[e2] = nibbles_to_bf16_pair(pair);
           }
           uint16_t* dst = vt + (8 * cw + c) * VP + 16 * (kg & 1) + 4 * (kg >> 1);
           *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
@@ -394,10 +400,24 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #pragma unroll
     for (int k = 0; k < kQPerLane; ++k) qraw[k] = qptr[(tid + k * kDecodeThreads) % kQElems];
   }
+  // bf16 rows, queries projected here: the projection's few words (basis pieces, raw queries) are waited for
+  // BEFORE the tiles go out -- every workgroup of the launch starts at the same moment, and behind the whole
+  // chip's first tiles those words took 3-5 us to arrive -- and TWO tiles per wave are requested, so that the
+  // memory system has work for the 2-3 us the projection then takes (one tile per wave is 16 MB over the chip,
+  // 2 us of streaming).  From the third tile on a wave is one tile ahead, as before: a second set in flight
+  // throughout measured slower.  Measured b4/32K 64/64, rows from HBM: 46.6-47.1 against 48.2 us per launch.
+  constexpr bool kTwoEarly = !SKV_Q8 && SKV_MMA_DEPTH == 1;
+  const bool two_early = kTwoEarly && !from_workspace;
+  if (two_early) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   issue_tile(wave < n_tiles ? wave : n_tiles - 1, ta);
 #if SKV_MMA_DEPTH == 2
   TileRegsM tb;
   if (wave + 4 < n_tiles) issue_tile(wave + 4, tb);
+#else
+  [[maybe_unused]] TileRegsM tb;
+  if constexpr (kTwoEarly) {
+    if (two_early && wave + 4 < n_tiles) issue_tile(wave + 4, tb);
+  }
 #endif
   // Nothing that needs the words requested above may be scheduled ahead of the tile's requests (an empty
   // statement the compiler must keep in place, through which those words pass).
@@ -463,7 +483,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // one tile from register set tr; the tile after next is requested into the same set once it is free
-  auto process = [&](int tile, TileRegsM& tr) {
+  // next_tile: the tile to request into the set once it is free (none if out of range)
+  auto process_next = [&](int tile, TileRegsM& tr, int next_tile) {
     const int row0 = t0 + tile * kMmaTileRows;
     // scores minus the reference: the reference rides in as the initial accumulator
     f32x4 sc[2];
@@ -498,7 +519,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
         }
 #endif
     __builtin_amdgcn_wave_barrier();
-    if (tile + 4 * SKV_MMA_DEPTH < n_tiles) issue_tile(tile + 4 * SKV_MMA_DEPTH, tr);
+    if (next_tile >= 0 && next_tile < n_tiles) issue_tile(next_tile, tr);
     // rows past the end of the range do not count
     if (row0 + kMmaTileRows > t1) {
 #pragma unroll
@@ -576,13 +597,22 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #endif
     __builtin_amdgcn_wave_barrier();
   };
+  auto process = [&](int tile, TileRegsM& tr) { process_next(tile, tr, tile + 4 * SKV_MMA_DEPTH); };
 #if SKV_MMA_DEPTH == 2
   for (int tile = wave; tile < n_tiles; tile += 8) {
     process(tile, ta);
     if (tile + 4 < n_tiles) process(tile + 4, tb);
   }
 #else
-  for (int tile = wave; tile < n_tiles; tile += 4) process(tile, ta);
+  int first_tile = wave;
+  if constexpr (kTwoEarly) {
+    if (two_early) {                               // the two tiles requested before the projection
+      if (wave < n_tiles) process_next(wave, ta, wave + 8);
+      if (wave + 4 < n_tiles) process_next(wave + 4, tb, -1);
+      first_tile = wave + 8;
+    }
+  }
+  for (int tile = first_tile; tile < n_tiles; tile += 4) process(tile, ta);
 #endif
 
   // ---- the four lanes of a column hold shares of l (and of the zero sums); then merge the 4 waves through

@@ -43,6 +43,12 @@ int engine_for(const skv_layer* L, int bits = 0, bool paged_codes = false) {
   if (want == SKV_ENGINE_VECTOR) return 0;
   if (want == SKV_ENGINE_MATRIX) return 1;
   if (group == 8 || bits != 0) return 1;
+  // Re-measured per rank pair with rows that come from HBM alone (layers flagged SKV_READS_STREAMING, rotated over
+  // more caches than the last-level cache holds; b4/32K, us per launch, vector / matrix): 64/64 44.1 / 46.0,
+  // 64/32 35.1-35.9 / 37.1, 32/32 25.6-26.1 / 26.2, 32/64 35.9 / 34.7-35.5; 96/64 55.4 / 66.5, 128/96 74.0 / 108.
+  // Such layers take the vector kernel; the matrix kernel keeps the small ranks of layers whose rows are re-read
+  // from the last-level cache (level or up to 1 us ahead there).
+  if ((L->flags & SKV_READS_MASK) == SKV_READS_STREAMING) return 0;
   const bool small_pow2 = (L->r_k == 32 || L->r_k == 64) && (L->r_v == 32 || L->r_v == 64);
   return (group == 4 && small_pow2) ? 1 : 0;
 }

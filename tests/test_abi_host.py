@@ -402,6 +402,11 @@ def test_layer_flags_are_validated_and_steer_the_choices():
     assert eng(flags=B.SKV_ENGINE_VECTOR) == 0
     assert eng(8, flags=B.SKV_ENGINE_VECTOR) == 0
     assert eng(n_q_heads=8, flags=B.SKV_ENGINE_MATRIX) == 1
+    # rows that come from HBM alone: the vector kernel also at the small ranks; groups of eight and codes stay
+    assert eng(flags=B.SKV_READS_STREAMING) == 0
+    assert eng(flags=B.SKV_READS_CACHED) == 1
+    assert eng(n_q_heads=64, flags=B.SKV_READS_STREAMING) == 1
+    assert eng(8, flags=B.SKV_READS_STREAMING) == 1
     # groups of eight: the vector kernel streams the cache twice (twice the columns, half the ranges)
     auto8, vec8 = _layer(n_q_heads=64, capacity=1 << 16), _layer(n_q_heads=64, capacity=1 << 16, flags=B.SKV_ENGINE_VECTOR)
     assert lib.skv_decode_default_splits(C.byref(auto8), 1 << 16) == 2 * lib.skv_decode_default_splits(C.byref(vec8), 1 << 16)
