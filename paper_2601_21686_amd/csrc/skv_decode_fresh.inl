@@ -111,12 +111,11 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
 // KV head, pass): projected like the few-token append, quantised with the same float32 arithmetic (keys on the
 // static range of their head and group, values on the row's own range per group, kept as bf16), stored, and
 // attended as the range kernel will see them from the next step on.  Scores are taken in the range kernel's
-// convention -- the folded queries against the integer codes (plus kCodeOffset, the constant the matrix kernel
-// adds to 4-bit codes), i.e. shifted by a constant per query, the same in every partial of the launch -- and
-// the mix uses the dequantised values scale * code + zero.
+// convention -- the folded queries against the integer codes, i.e. shifted by a constant per query, the same
+// in every partial of the launch -- and the mix uses the dequantised values scale * code + zero.
 template <int RK, int RV, int GT>
 __device__ __forceinline__ void fresh_rows_block_q(const DecodeParams& p, int b, int kv, int pass, int hq0,
-                                                   float* x_s, float* part_s, float* y_s, float code_offset) {
+                                                   float* x_s, float* part_s, float* y_s) {
   constexpr int D = SKV_HEAD_DIM;
   constexpr int NGK = (RK + 63) / 64, NGV = (RV + 63) / 64;
   __shared__ float qt_s[GT * RK];
@@ -169,7 +168,7 @@ __device__ __forceinline__ void fresh_rows_block_q(const DecodeParams& p, int b,
       const float zero = live ? p.k_zero[kv * NGK + (tid >> 6)] : 0.f;
       const uint32_t code = live ? (uint32_t)fminf(fmaxf(rintf(__fdiv_rn(y - zero, scale)), 0.f), top) : 0u;
       store_code(k_codes, row, RK, code, live);
-      if (live) kc_s[tid] = (float)code + code_offset;
+      if (live) kc_s[tid] = (float)code;
     }
     {
       ProjectPieces pp;

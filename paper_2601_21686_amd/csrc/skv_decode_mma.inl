@@ -22,14 +22,23 @@
 // as A operands of the second product.  float32 operands (Q~, the weights) are split into two bf16 terms
 // (x ~ hi + lo, relative error 2^-17), two products each, so the 2e-3 bound of the vector kernel holds.
 //
-// Quantised caches (Sec. 4.3).  Integer codes are exact in bf16, so they enter the products as they are
-// and the ranges stay outside: key scales are already folded into Q~ (the key zero point shifts every
-// score of a query alike and drops out); a value row j contributes (p_j scale_j) code_j + p_j zero_j per
-// 64-channel group, i.e. the weights of the second product are p_j scale_j (one B operand per group) and
-// sum_j p_j zero_j is kept beside the normaliser.  8-bit codes are converted byte by byte
-// (v_cvt_f32_ubyteN, then the high halves of two results packed).  4-bit codes n become the bf16 number
-// 16 + n, whose bit pattern is 0x4180 + 8 n (one shift-or per pair): for keys the extra 16 sum_c q~_c is
-// one more constant per query; for values it is taken back through the zero term (zero_j - 16 scale_j).
+// Quantised caches (Sec. 4.3).  The integer codes enter the products as they are and the ranges stay
+// outside: key scales are already folded into Q~ (the key zero point shifts every score of a query alike
+// and drops out); a value row j contributes (p_j scale_j) code_j + p_j zero_j per 64-channel group, i.e.
+// the weights of the second product are p_j scale_j (one B operand per group) and sum_j p_j zero_j is kept
+// beside the normaliser.
+//
+// A code needs no conversion at all: the 16-bit pattern 0x00nn IS a bf16 number, n * 2^-133 (subnormal
+// below 128, the first normal binade from there on), and the bf16 matrix instructions of this part take
+// subnormal inputs at their value.  So one byte-permute per PAIR of codes builds the operand (zero-extend
+// two bytes; 4-bit codes after the usual mask / shift-and-mask of a word), where a conversion through
+// float32 costs three instructions per pair -- and the vector pipe is what bounds these kernels.  The factor
+// 2^-133 is carried by the other operand as far as float32 allows, so that no product leaves the normal
+// range: the folded queries are multiplied by 2^100 (scores come out times 2^-33, put right by the one
+// multiply-add that also subtracts the softmax reference), and the softmax weights are kept 2^64 above
+// their usual size (the reference sits 64 below the running maximum; normaliser, zero sums and partial
+// results are all in that convention, which is as valid a partial result as any), the last 2^133 going
+// onto the mix once, before it is written.
 // ---------------------------------------------------------------------------------------------------
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -65,26 +74,25 @@ __device__ __forceinline__ void split8w(const float (&x)[8], uint4& hi, uint4& l
   hi = uint4{h0.x, h0.y, h1.x, h1.y};
   lo = uint4{l0.x, l0.y, l1.x, l1.y};
 }
-// the high halves of two float32 numbers as a bf16 pair (exact when both are bf16 numbers already)
-__device__ __forceinline__ uint32_t high_halves(float lo, float hi) {
-  return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
-}
-template <int N>
-__device__ __forceinline__ float byte_to_f32(uint32_t w) { return (float)((w >> (8 * N)) & 0xffu); }
-// two 4-bit codes (bits 0..3 of bytes NL of lo and NH of hi ... see callers) as bf16 numbers 16 + n
-[[maybe_unused]] constexpr float kNibbleOffset = 16.f;
-__device__ __forceinline__ uint32_t nibbles_to_bf16_pair(uint32_t pair_in_bytes_0_and_2) {
-  return (pair_in_bytes_0_and_2 << 3) | 0x41804180u;
-}
+// Integer codes as bf16 operands: the pattern 0x00nn is the bf16 number n * 2^-133.
 // byte N of lo into byte 0 and byte N of hi into byte 2 of the result, zeros between: one byte-permute
 // (selector bytes: 0..3 pick from lo, 4..7 from hi, 0x0c gives zero)
 template <int N>
 __device__ __forceinline__ uint32_t byte_pair(uint32_t lo, uint32_t hi) {
   return __builtin_amdgcn_perm(hi, lo, 0x0c000c00u | (uint32_t)N | ((uint32_t)(4 + N) << 16));
 }
+// bytes 2 H and 2 H + 1 of a word, each zero-extended to 16 bits
+template <int H>
+__device__ __forceinline__ uint32_t byte_pair_of_word(uint32_t w) {
+  return __builtin_amdgcn_perm(0u, w, H == 0 ? 0x0c010c00u : 0x0c030c02u);
+}
+[[maybe_unused]] constexpr float kKeyUp = 0x1p100f;          // on the folded queries
+[[maybe_unused]] constexpr float kScoreBack = 0x1p33f;       // 2^133 / kKeyUp, on the scores
+[[maybe_unused]] constexpr float kWeightBias = 64.f;         // log2 of what the softmax weights carry
+[[maybe_unused]] constexpr float kMixBackA = 0x1p66f, kMixBackB = 0x1p67f;   // 2^133 in two steps, on the mix
 
 #ifndef SKV_MMA_DEPTH
-#define SKV_MMA_DEPTH 1          // tiles a wave has requested ahead of the one it computes on (1 or 2)
+#define SKV_MMA_DEPTH 1          // register sets per wave: tiles it has requested or is working on (1 or 2)
 #endif
 constexpr int kMmaTileRows = 32;                 // rows a wave takes at a time
 constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel (bf16 elements; 80 bytes)
@@ -94,8 +102,15 @@ constexpr int kMmaVPitch = kMmaTileRows + 8;     // LDS pitch of a value channel
 __device__ __forceinline__ void keep_after_requests(float& x) { asm volatile("" : "+v"(x) : : "memory"); }
 __device__ __forceinline__ void keep_after_requests(uint32_t& x) { asm volatile("" : "+v"(x) : : "memory"); }
 
+// Workgroups per CU the register allocation is held to.  Two at least: the allocator then works within 256
+// registers per lane, all of them ordinary ones.  Four (128 registers) over a quantised cache with both ranks
+// up to 64, where the kernel is bound by the latency of its chain of dependent steps and the fourth wave per
+// SIMD is worth more than the two registers it costs to stay under the line (larger ranks would spill; with
+// eight heads a pass the workgroup's LDS allows three per CU anyway).
+constexpr int mma_min_workgroups(int rk, int rv, int gt) { return (SKV_Q8 && rk <= 64 && rv <= 64 && gt <= 4) ? 4 : 2; }
+
 template <int RK, int RV, int GT, int FMT, bool NT>
-__global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(const DecodeParams p) {
+__global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) void decode_partial_mma_kernel(const DecodeParams p) {
   static_assert(FMT == kFmt, "format tag must match the build");
   // Quantised builds (ranks are multiples of 32 there) use the 32-deep matrix instruction: the contraction index
   // of the first product is then enumerated as channel = g r_K / 4 + 8 step + i, and the 32 rows of a tile are
@@ -106,10 +121,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   constexpr int KSTEPS = WIDE ? RK / 32 : RK / 16;   // contraction steps of the score product
   constexpr int VBLOCKS = RV / 16;               // 16-channel blocks of the mix
   constexpr int NG = (RV + 63) / 64;             // 64-channel groups of a value row (quantisation groups)
-  // raw words per lane: a quarter of a key row per 16-row block; value tiles as units of 8 rows by one word
+  // raw words per lane: a quarter of a key row per 16-row block; value tiles as units of VROWS rows by one
+  // word (8 rows; 4 with 4-bit codes, whose words hold 8 channels: every lane then has a unit at r_V = 64)
   constexpr int KRAW = RK / 4 / kElemsPerDword;  // bf16: RK / 8, 8-bit: RK / 16, 4-bit: RK / 32
   constexpr int VWORDS = RV / kElemsPerDword;    // words in a value row
-  constexpr int VUNITS = 4 * VWORDS;
+  constexpr int VROWS = SKV_QBITS == 4 ? 4 : 8;
+  constexpr int VUNITS = (kMmaTileRows / VROWS) * VWORDS;
   constexpr int VPL = (VUNITS + 63) / 64;        // units per lane
   constexpr int VP = kMmaVPitch;
   static_assert(KRAW >= 1 && (RK / 4) % kElemsPerDword == 0, "rank not supported by this format");
@@ -118,7 +135,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   constexpr int kProjBytes = kProjectThreads * (GT < 4 ? GT : 4) * 8 * (int)sizeof(float);
   constexpr int kTileBytes = 4 * RV * VP * (int)sizeof(uint16_t);           // per wave: value tile, [channel][row]
   __shared__ __attribute__((aligned(16))) unsigned char scratch_s[kProjBytes > kTileBytes ? kProjBytes : kTileBytes];
-  __shared__ float red[4 * GT * (RV + 2)];
+  constexpr int kWaveTileBytes = RV * VP * (int)sizeof(uint16_t);
+  static_assert(GT * (RV + 2) * (int)sizeof(float) <= kWaveTileBytes, "a wave's merge slots must fit in its value tile");
   __shared__ float px_s[GT * SKV_HEAD_DIM];
   __shared__ float py_s[GT * SKV_HEAD_DIM];
   float* ppart_s = reinterpret_cast<float*>(scratch_s);
@@ -146,7 +164,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   const int hq0 = kv * p.group + pass * GT;
   if (fresh) {
 #if SKV_Q8
-    fresh_rows_block_q<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s, SKV_QBITS == 4 ? kNibbleOffset : 0.f);
+    fresh_rows_block_q<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s);
 #else
     fresh_rows_block<RK, RV, GT>(p, b, kv, pass, hq0, px_s, ppart_s, py_s);
 #endif
@@ -179,20 +197,24 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #endif
 
   // ---- tile loads: key quarters as they lie in memory, values as (8 rows x one word) units ----------------
-  const int n_tiles = (t1 - t0 + kMmaTileRows - 1) / kMmaTileRows;
+  // Whole tiles first, each wave its own (wave w: tiles w, w + 4, ...); rows left over at the end of the range
+  // make one more, partial tile, taken by the wave whose turn it would be, after its whole ones.
+  const int n_whole = (t1 - t0) / kMmaTileRows;
+  const bool has_tail = (t1 - t0) % kMmaTileRows != 0;
   struct TileRegsM {
     uint32_t k[2][KRAW];
-    uint32_t v[VPL][8];
+    uint32_t v[VPL][VROWS];
 #if SKV_Q8
     uint32_t vm[NG][2][4];                       // (scale | zero << 16) of rows 16 kb + 4 g + i, per group
 #endif
   };
-  auto issue_tile = [&](int tile, TileRegsM& tr) {
+  // A whole tile: one address per stream and lane, the rest are constant offsets; streaming or ordinary loads
+  // as the launch asks (NT).  Nothing here depends on a condition: the loop below relies on every request of a
+  // tile being the same run of instructions (see there).
+  auto issue_whole = [&](int tile, TileRegsM& tr) {
     const int row0 = t0 + tile * kMmaTileRows;
     const int64_t base = tile_base(row0);
-    if (row0 + kMmaTileRows <= t1) {
-      // A whole tile (all but the last of a range): one address per stream and lane, the rest are constant
-      // offsets; streaming or ordinary loads as the launch asks (NT).
+    {
       {
         const uint32_t* ksrc = p.k_cache + (base + lm) * (RK / kElemsPerDword) + g * KRAW;
 #pragma unroll
@@ -220,9 +242,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
           const int i = lane + 64 * u;
           if (VUNITS % 64 == 0 || i < VUNITS) {
             const int cw = i % VWORDS, kg = i / VWORDS;
-            const uint32_t* vsrc = p.v_cache + (base + 8 * kg) * VWORDS + cw;
+            const uint32_t* vsrc = p.v_cache + (base + VROWS * kg) * VWORDS + cw;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) tr.v[u][e] = load_cache<NT>(vsrc + e * VWORDS);
+            for (int e = 0; e < VROWS; ++e) tr.v[u][e] = load_cache<NT>(vsrc + e * VWORDS);
           }
         }
 #if SKV_Q8
@@ -235,9 +257,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
             for (int gq = 0; gq < NG; ++gq) tr.vm[gq][kb][i] = load_cache<NT>(msrc + (16 * kb + i) * NG + gq);
 #endif
       }
-      return;
     }
-    const int last = t1 - 1 - row0;                              // rows past it re-read it; their weights are zero
+  };
+  // The partial tile at the end of the range: rows past the last one re-read it; their weights are zero.
+  auto issue_tail = [&](TileRegsM& tr) {
+    const int row0 = t0 + n_whole * kMmaTileRows;
+    const int64_t base = tile_base(row0);
+    const int last = t1 - 1 - row0;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       int r = 16 * kb + lm;
@@ -266,8 +292,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
       if (VUNITS % 64 == 0 || i < VUNITS) {
         const int cw = i % VWORDS, kg = i / VWORDS;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          int r = 8 * kg + e;
+        for (int e = 0; e < VROWS; ++e) {
+          int r = VROWS * kg + e;
           r = r < last ? r : last;
           tr.v[u][e] = p.v_cache[(base + r) * VWORDS + cw];
         }
@@ -290,15 +316,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #if SKV_QBITS == 8
   auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint4 {
     const uint32_t w0 = tr.k[kb][2 * ks], w1 = tr.k[kb][2 * ks + 1];   // 8 codes
-    return uint4{high_halves(byte_to_f32<0>(w0), byte_to_f32<1>(w0)), high_halves(byte_to_f32<2>(w0), byte_to_f32<3>(w0)),
-                 high_halves(byte_to_f32<0>(w1), byte_to_f32<1>(w1)), high_halves(byte_to_f32<2>(w1), byte_to_f32<3>(w1))};
+    return uint4{byte_pair_of_word<0>(w0), byte_pair_of_word<1>(w0), byte_pair_of_word<0>(w1), byte_pair_of_word<1>(w1)};
   };
 #elif SKV_QBITS == 4
   auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint4 {
     const uint32_t w = tr.k[kb][ks];                             // 8 codes: the even channel in the low half of a byte
     const uint32_t ev = w & 0x0f0f0f0fu, od = (w >> 4) & 0x0f0f0f0fu;
-    return uint4{nibbles_to_bf16_pair(byte_pair<0>(ev, od)), nibbles_to_bf16_pair(byte_pair<1>(ev, od)),
-                 nibbles_to_bf16_pair(byte_pair<2>(ev, od)), nibbles_to_bf16_pair(byte_pair<3>(ev, od))};
+    return uint4{byte_pair<0>(ev, od), byte_pair<1>(ev, od), byte_pair<2>(ev, od), byte_pair<3>(ev, od)};
   };
 #else
   auto key_operand = [&](const TileRegsM& tr, int kb, int ks) -> uint2 {
@@ -320,37 +344,36 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
           uint32_t o[4];
 #pragma unroll
           for (int e2 = 0; e2 < 4; ++e2) {
+            // channel c of rows 2 e2 and 2 e2 + 1: the same byte of two words
             const uint32_t w0 = tr.v[u][2 * e2], w1 = tr.v[u][2 * e2 + 1];
-            const float f0 = c == 0 ? byte_to_f32<0>(w0) : c == 1 ? byte_to_f32<1>(w0) : c == 2 ? byte_to_f32<2>(w0) : byte_to_f32<3>(w0);
-            const float f1 = c == 0 ? byte_to_f32<0>(w1) : c == 1 ? byte_to_f32<1>(w1) : c == 2 ? byte_to_f32<2>(w1) : byte_to_f32<3>(w1);
-            o[e2] = high_halves(f0, f1);
+            o[e2] = c == 0 ? byte_pair<0>(w0, w1) : c == 1 ? byte_pair<1>(w0, w1) : c == 2 ? byte_pair<2>(w0, w1) : byte_pair<3>(w0, w1);
           }
           uint16_t* dst = vt + (4 * cw + c) * VP + 16 * (kg & 1) + 4 * (kg >> 1);   // rows 8 kg + e at 16 (kg % 2) + 8 (e / 4) + 4 (kg / 2) + e % 4
           *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
           *reinterpret_cast<uint2*>(dst + 8) = make_uint2(o[2], o[3]);
         }
 #elif SKV_QBITS == 4
-        // a word holds channels 8 cw .. 8 cw + 7 of one row: even ones in the low halves of its bytes
-        uint32_t ev[8], od[8];
+        // a word holds channels 8 cw .. 8 cw + 7 of one row: even ones in the low halves of its bytes; the
+        // unit is rows 4 kg .. 4 kg + 3
+        uint32_t ev[4], od[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 4; ++e) {
           ev[e] = tr.v[u][e] & 0x0f0f0f0fu;
           od[e] = (tr.v[u][e] >> 4) & 0x0f0f0f0fu;
         }
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-          uint32_t o[4];
+          uint32_t o[2];
 #pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) {
+          for (int e2 = 0; e2 < 2; ++e2) {
             const uint32_t a = (c & 1) ? od[2 * e2] : ev[2 * e2], bb = (c & 1) ? od[2 * e2 + 1] : ev[2 * e2 + 1];
             // channel c of rows 2 e2 and 2 e2 + 1: the same byte of two words, picked by one byte-permute
-            const uint32_t pair = (c >> 1) == 0 ? byte_pair<0>(a, bb) : (c >> 1) == 1 ? byte_pair<1>(a, bb)
-                                : (c >> 1) == 2 ? byte_pair<2>(a, bb) : byte_pair<3>(a, bb);
-            o[e2] = nibbles_to_bf16_pair(pair);
+            o[e2] = (c >> 1) == 0 ? byte_pair<0>(a, bb) : (c >> 1) == 1 ? byte_pair<1>(a, bb)
+                  : (c >> 1) == 2 ? byte_pair<2>(a, bb) : byte_pair<3>(a, bb);
           }
-          uint16_t* dst = vt + (8 * cw + c) * VP + 16 * (kg & 1) + 4 * (kg >> 1);
+          // rows 4 kg + e at 16 ((kg / 2) % 2) + 8 (kg % 2) + 4 (kg / 4) + e: the 8-bit layout, half a unit each
+          uint16_t* dst = vt + (8 * cw + c) * VP + 16 * ((kg >> 1) & 1) + 8 * (kg & 1) + 4 * (kg >> 2);
           *reinterpret_cast<uint2*>(dst) = make_uint2(o[0], o[1]);
-          *reinterpret_cast<uint2*>(dst + 8) = make_uint2(o[2], o[3]);
         }
 #else
         // a word holds channels 2 cw, 2 cw + 1 of one row
@@ -371,13 +394,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   };
 
   // ---- projected queries as B operands: column lm is query head lm of the pass (zero beyond GT) ---------
-  // SKV_MMA_DEPTH tiles per wave on their way while the queries are prepared, and from then on (one register
-  // set each).  Measured: a second set is slower at every shape tried (45.1 against 43.5 us at b4/32K, 64/64).
-  // The requests go out in an order and a shape that keep the waits exact: first the few words the queries
-  // need (from the workspace, or the basis pieces and raw queries of the in-kernel projection), then the
-  // wave's first tile, without a condition (a wave with no tile of its own requests the range's last one and
-  // never looks at it).  A request made under a condition is waited for where the paths join again, and
-  // requests return in order, so the other way round the queries would wait for the whole tile.
+  // Requests return in order and are waited for by count.  The waits the compiler places are exact only if,
+  // wherever paths join, every path has made the same requests in the same order; otherwise a wait for one
+  // tile becomes a wait for everything.  So in the loop over whole tiles every request is the same straight
+  // run of loads and is made every time: a wave that has run out of tiles requests the range's last whole one
+  // again and never looks at it.  First come the few words the queries need (from the workspace, or the basis
+  // pieces and raw queries of the in-kernel projection), then the wave's first SKV_MMA_DEPTH tiles.
+  // One register set per wave is the default.  Two (SKV_MMA_DEPTH = 2; the waits then leave the other set's
+  // 20 requests in flight, checked in the generated code) measured no faster anywhere: b4/32K 64/64 from HBM,
+  // bf16 46.9 against 45.6 us; 8-bit codes 27.2 us (three waves per SIMD for the registers) against 25.0.
+  // The kernels are not short of bytes in flight.
   TileRegsM ta;
   const bool from_workspace = p.q == nullptr;
   constexpr int QW = SKV_Q8 ? 8 : 4;                              // query channels per contraction step and lane
@@ -400,25 +426,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #pragma unroll
     for (int k = 0; k < kQPerLane; ++k) qraw[k] = qptr[(tid + k * kDecodeThreads) % kQElems];
   }
-  // bf16 rows, queries projected here: the projection's few words (basis pieces, raw queries) are waited for
-  // BEFORE the tiles go out -- every workgroup of the launch starts at the same moment, and behind the whole
-  // chip's first tiles those words took 3-5 us to arrive -- and TWO tiles per wave are requested, so that the
-  // memory system has work for the 2-3 us the projection then takes (one tile per wave is 16 MB over the chip,
-  // 2 us of streaming).  From the third tile on a wave is one tile ahead, as before: a second set in flight
-  // throughout measured slower.  Measured b4/32K 64/64, rows from HBM: 46.6-47.1 against 48.2 us per launch.
-  constexpr bool kTwoEarly = !SKV_Q8 && SKV_MMA_DEPTH == 1;
-  const bool two_early = kTwoEarly && !from_workspace;
-  if (two_early) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  issue_tile(wave < n_tiles ? wave : n_tiles - 1, ta);
+  // Queries projected here: the projection's few words (basis pieces, raw queries) are waited for BEFORE the
+  // tiles go out -- every workgroup of the launch starts at the same moment, and behind the whole chip's
+  // first tiles those words took 3-5 us to arrive; the tiles then stream while the projection runs.
+  if (!from_workspace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  auto clamped_tile = [&](int tile) { return tile < n_whole ? tile : n_whole - 1; };
 #if SKV_MMA_DEPTH == 2
   TileRegsM tb;
-  if (wave + 4 < n_tiles) issue_tile(wave + 4, tb);
-#else
-  [[maybe_unused]] TileRegsM tb;
-  if constexpr (kTwoEarly) {
-    if (two_early && wave + 4 < n_tiles) issue_tile(wave + 4, tb);
-  }
 #endif
+  if (n_whole > 0) {                                             // (the same for all waves of the workgroup)
+    issue_whole(clamped_tile(wave), ta);
+#if SKV_MMA_DEPTH == 2
+    issue_whole(clamped_tile(wave + 4), tb);
+#endif
+  }
   // Nothing that needs the words requested above may be scheduled ahead of the tile's requests (an empty
   // statement the compiler must keep in place, through which those words pass).
   if (from_workspace) {
@@ -455,7 +476,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   for (int ks = 0; ks < KSTEPS; ++ks) {
     float x[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) x[i] = lm < GT ? xq[ks][i] * qscale * key_scale_of(g * (RK / 4) + 8 * ks + i) : 0.f;
+    for (int i = 0; i < 8; ++i) x[i] = lm < GT ? xq[ks][i] * qscale * key_scale_of(g * (RK / 4) + 8 * ks + i) * kKeyUp : 0.f;
     split8w(x, qhi[ks], qlo[ks]);
   }
 #else
@@ -482,21 +503,27 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #pragma unroll
   for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // one tile from register set tr; the tile after next is requested into the same set once it is free
-  // next_tile: the tile to request into the set once it is free (none if out of range)
-  auto process_next = [&](int tile, TileRegsM& tr, int next_tile) {
-    const int row0 = t0 + tile * kMmaTileRows;
-    // scores minus the reference: the reference rides in as the initial accumulator
-    f32x4 sc[2];
+  // A tile in two parts, between which its register set is free for the next request.
+  // Part one: scores minus the reference (the reference rides in as the initial accumulator), the values into
+  // LDS, the rows' value ranges unpacked.
+  f32x4 sc[2];
+#if SKV_Q8
+  float vscale[NG][2][4], vzero[NG][2][4];
+#endif
+  auto scores_and_values = [&](const TileRegsM& tr) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      sc[kb] = f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
+      sc[kb] = SKV_Q8 ? f32x4{0.f, 0.f, 0.f, 0.f} : f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
 #if SKV_Q8
         const uint4 a = key_operand(tr, kb, ks);
         sc[kb] = mfma16w(a, qhi[ks], sc[kb]);
         sc[kb] = mfma16w(a, qlo[ks], sc[kb]);
+        if (ks == KSTEPS - 1) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) sc[kb][i] = fmaf(sc[kb][i], kScoreBack, -m_ref);
+        }
 #else
         const uint2 a = key_operand(tr, kb, ks);
         sc[kb] = mfma16(a, qhi[ks], sc[kb]);
@@ -506,7 +533,6 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
     }
     store_values(tr);
 #if SKV_Q8
-    float vscale[NG][2][4], vzero[NG][2][4];
 #pragma unroll
     for (int gq = 0; gq < NG; ++gq)
 #pragma unroll
@@ -515,13 +541,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
         for (int i = 0; i < 4; ++i) {
           vscale[gq][kb][i] = bf16_lo(tr.vm[gq][kb][i]);
           vzero[gq][kb][i] = bf16_hi(tr.vm[gq][kb][i]);
-          if (SKV_QBITS == 4) vzero[gq][kb][i] = fmaf(-kNibbleOffset, vscale[gq][kb][i], vzero[gq][kb][i]);
         }
 #endif
     __builtin_amdgcn_wave_barrier();
-    if (next_tile >= 0 && next_tile < n_tiles) issue_tile(next_tile, tr);
+  };
+  // Part two: softmax weights of the tile's rows and their mix with its values.
+  auto weights_and_mix = [&](int row0, bool partial) {
     // rows past the end of the range do not count
-    if (row0 + kMmaTileRows > t1) {
+    if (partial) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -532,16 +559,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
                      fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    if (first || mx > kRescaleSlack) {                           // the reference moves (lanes of a column agree)
-      const float f = first ? 0.f : fast_exp2(-mx);
-      m_ref = first ? mx : m_ref + mx;
+    // (over a quantised cache the reference is held kWeightBias below where it would be: the weights are
+    // that much larger, up to 2^(slack + bias))
+    constexpr float kBias = SKV_Q8 ? kWeightBias : 0.f;
+    if (first || mx > kRescaleSlack + kBias) {                   // the reference moves (lanes of a column agree)
+      const float d = mx - kBias;
+      const float f = first ? 0.f : fast_exp2(-d);
+      m_ref = first ? d : m_ref + d;
       l *= f;
 #pragma unroll
       for (int gq = 0; gq < NG; ++gq) zsum[gq] *= f;
 #pragma unroll
       for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] *= f;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) sc[kb] -= mx;
+      for (int kb = 0; kb < 2; ++kb) sc[kb] -= d;
     }
     first = false;
     // the weights as B operands: one pair per 64-channel group when rows carry their own value scales
@@ -597,26 +628,34 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
 #endif
     __builtin_amdgcn_wave_barrier();
   };
-  auto process = [&](int tile, TileRegsM& tr) { process_next(tile, tr, tile + 4 * SKV_MMA_DEPTH); };
+  // One whole tile from register set tr, if the wave still has one (wave-uniform); next_tile (or the last
+  // whole tile again) is requested into the set as soon as it is free.
+  auto step = [&](int tile, TileRegsM& tr, int next_tile) {
+    const bool valid = tile < n_whole;
+    if (valid) scores_and_values(tr);
+    issue_whole(clamped_tile(next_tile), tr);
+    if (valid) weights_and_mix(t0 + tile * kMmaTileRows, false);
+  };
+  if (n_whole > 0) {
 #if SKV_MMA_DEPTH == 2
-  for (int tile = wave; tile < n_tiles; tile += 8) {
-    process(tile, ta);
-    if (tile + 4 < n_tiles) process(tile + 4, tb);
-  }
-#else
-  int first_tile = wave;
-  if constexpr (kTwoEarly) {
-    if (two_early) {                               // the two tiles requested before the projection
-      if (wave < n_tiles) process_next(wave, ta, wave + 8);
-      if (wave + 4 < n_tiles) process_next(wave + 4, tb, -1);
-      first_tile = wave + 8;
+    for (int tile = wave; tile < n_whole; tile += 8) {
+      step(tile, ta, tile + 8);
+      step(tile + 4, tb, tile + 12);
     }
-  }
-  for (int tile = first_tile; tile < n_tiles; tile += 4) process(tile, ta);
+#else
+    for (int tile = wave; tile < n_whole; tile += 4) step(tile, ta, tile + 4);
 #endif
+  }
+  if (has_tail && wave == (n_whole & 3)) {
+    issue_tail(ta);
+    scores_and_values(ta);
+    weights_and_mix(t0 + n_whole * kMmaTileRows, true);
+  }
 
   // ---- the four lanes of a column hold shares of l (and of the zero sums); then merge the 4 waves through
-  //      LDS, in wave order ------------------------------------------------------------------------
+  //      LDS, in wave order.  A wave's results go where its value tiles were: it has read the last of them
+  //      (its own LDS operations complete in order), and no other wave touches that region before the barrier.
+  auto wave_red = [&](int w) -> float* { return reinterpret_cast<float*>(scratch_s + w * kWaveTileBytes); };
   l += __shfl_xor(l, 16);
   l += __shfl_xor(l, 32);
 #if SKV_Q8
@@ -627,13 +666,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   }
 #endif
   if (lm < GT) {
-    float* r = red + (wave * GT + lm) * (RV + 2);
+    float* r = wave_red(wave) + lm * (RV + 2);
 #pragma unroll
     for (int cb = 0; cb < VBLOCKS; ++cb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float a = oacc[cb][i];
-        if (SKV_Q8) a += zsum[(16 * cb) / 64];                   // every channel of a group receives the group's zero sum
+        // codes were taken as n * 2^-133; every channel of a group receives the group's zero sum
+        if (SKV_Q8) a = fmaf(a * kMixBackA, kMixBackB, zsum[(16 * cb) / 64]);
         r[16 * cb + 4 * g + i] = a;
       }
     if (g == 0) {
@@ -644,9 +684,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
   __syncthreads();
   for (int i = tid; i < GT * (RV + 2); i += kDecodeThreads) {
     const int hg = i / (RV + 2), c = i % (RV + 2);
-    float mt = red[(0 * GT + hg) * (RV + 2) + RV];
+    float mt = wave_red(0)[hg * (RV + 2) + RV];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) mt = fmaxf(mt, red[(w * GT + hg) * (RV + 2) + RV]);
+    for (int w = 1; w < 4; ++w) mt = fmaxf(mt, wave_red(w)[hg * (RV + 2) + RV]);
     if (c == RV) {
       out_ml[hg * head_step_ml] = mt;
     } else {
@@ -654,7 +694,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_mma_kernel(cons
       float a = 0.f;
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
-        const float* r = red + (w * GT + hg) * (RV + 2);
+        const float* r = wave_red(w) + hg * (RV + 2);
         a += r[src] * fast_exp2(r[RV] - mt);
       }
       if (c == RV + 1) out_ml[hg * head_step_ml + 1] = a;

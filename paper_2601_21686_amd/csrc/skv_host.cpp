@@ -193,6 +193,19 @@ skv_status check_decode_common(const skv_layer* L, int32_t n_splits, const void*
 
 }  // namespace
 
+// Workgroups a range launch aims for.  The matrix kernel over a quantised cache is bound by instruction issue
+// and by the latency of its chain of dependent steps, which more resident waves help: as many workgroups as a
+// CU holds at once (four with both ranks up to 64, where the kernel is built for 128 registers per lane, three
+// beyond; measured for b4/32K, 64/64, 8-bit: 26.2 us in 32 ranges against 28.4 in 24, where the bf16 kernels
+// want 8..16).
+bool fills_every_slot(const skv_layer* L, int bits, bool paged_codes) {
+  return bits != 0 && engine_for(L, bits, paged_codes) == 1;
+}
+int64_t workgroup_target(const skv_layer* L, int bits, bool paged_codes) {
+  if (!fills_every_slot(L, bits, paged_codes)) return kTargetWorkgroups;
+  return (L->r_k <= 64 && L->r_v <= 64) ? 2 * kTargetWorkgroups : 3 * kTargetWorkgroups / 2;
+}
+
 bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_splits, int bits, bool paged_codes) {
   const int32_t batch = L->batch, n_kv_heads = L->n_kv_heads, group = L->n_q_heads / L->n_kv_heads;
   if (n_ctx < 1 || n_ctx > std::numeric_limits<int32_t>::max() - kRangeQuantum) return false;
@@ -203,9 +216,7 @@ bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_spl
   }
   const int64_t quanta = (n_ctx + kRangeQuantum - 1) / kRangeQuantum;
   const int64_t columns = (int64_t)batch * n_kv_heads * (group / decode_heads_per_pass(L, bits, paged_codes));
-  // the matrix kernel over a quantised cache is bound by instruction issue, which more resident waves help
-  // (measured best at 24..32 ranges for b4/32K where the bf16 kernels want 8..16)
-  const int64_t target = (bits != 0 && engine_for(L, bits, paged_codes) == 1) ? 3 * kTargetWorkgroups / 2 : kTargetWorkgroups;
+  const int64_t target = workgroup_target(L, bits, paged_codes);
   int64_t s = (target + columns - 1) / (columns > 0 ? columns : 1);
   if (s > SKV_MAX_SPLITS) s = SKV_MAX_SPLITS;
   if (s > quanta) s = quanta;                 // never a range without rows
@@ -223,6 +234,18 @@ bool plan_splits(const skv_layer* L, int64_t n_ctx, int32_t want, int32_t* n_spl
   if (s < 1) s = 1;
   *n_splits = (int32_t)s;
   return true;
+}
+
+// A fused step launches, beside its columns x ranges workgroups, the ones that take the step's new rows (in
+// rows of `ranges` workgroups).  Where the plan already fills every slot the CUs have, those would wait for a
+// slot and finish last (measured b4/32K 64/64 8-bit: 31.0 us against 27.0 for the same launch without them):
+// fewer ranges, so that all are resident from the start.
+void leave_room_for_new_rows(const skv_layer* L, int bits, bool paged_codes, int32_t* s) {
+  if (!fills_every_slot(L, bits, paged_codes)) return;
+  const int64_t columns = (int64_t)L->batch * L->n_kv_heads *
+                          ((L->n_q_heads / L->n_kv_heads) / decode_heads_per_pass(L, bits, paged_codes));
+  const int64_t target = workgroup_target(L, bits, paged_codes);
+  while (*s > 1 && (columns + (columns + *s - 1) / *s) * *s > target) --*s;
 }
 
 skv_status decode_attention_workspace_need(const skv_layer* L, int64_t n_ctx, size_t* bytes) {
@@ -893,6 +916,7 @@ skv_status q_decode_step(const skv_q8_layer* Q, int bits, const void* k_new, con
   if (matrix && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
     int32_t s_old = 0;
     if (!plan_splits(L, cur_len, 0, &s_old, bits, paged_codes)) return SKV_ERR_SHAPE;
+    leave_room_for_new_rows(L, bits, paged_codes, &s_old);
     if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
     if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
     st = run_partial_fused_q(Q, bits, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
