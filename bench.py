@@ -51,8 +51,6 @@ def parse_args():
                     help="explicit: the benchmarked configuration (the library projects keys, values and queries); "
                          "folded: the bases are folded into the model's linear layers (Sec. 3.4), so rows and queries "
                          "arrive projected and the output stays in rank-r_V coordinates")
-    ap.add_argument("--prefill-precision", choices=("exact", "fast"), default="exact",
-                    help="--mode prefill: exact = split-bf16 operands (float32-level accuracy), fast = single bf16 operands")
     ap.add_argument("--prefill-sched", choices=("default", "together", "ahead"), default="default",
                     help="--mode prefill: force one of the kernel's two schedules")
     ap.add_argument("--prefill-chunk", type=int, default=0, help="--mode prefill: tokens in the chunk (0 = the workload's append chunk)")
@@ -309,8 +307,7 @@ def main():
             append(k, v, c0)
         q = synth.chunk_queries(synth.stable_seed(wl.name, "cq"), Bt, T, HQ, d, dev)
         out = torch.empty((Bt, T, HQ, d), dtype=torch.float32, device=dev)
-        pmode = B.SKV_PREFILL_FAST if args.prefill_precision == "fast" else B.SKV_PREFILL_EXACT
-        pmode |= {"default": 0, "together": B.SKV_PREFILL_SCHED_TOGETHER, "ahead": B.SKV_PREFILL_SCHED_AHEAD}[args.prefill_sched]
+        pmode = B.SKV_PREFILL_EXACT | {"default": 0, "together": B.SKV_PREFILL_SCHED_TOGETHER, "ahead": B.SKV_PREFILL_SCHED_AHEAD}[args.prefill_sched]
         iters = max(1, args.kernel_iters // 20)
         for _ in range(2):
             attend()
@@ -328,7 +325,7 @@ def main():
         flops = Bt * HQ * (2 * (rk + rv) * visible + T * 2 * d * (rk + rv))
         nbytes = Bt * HKV * (n_prev + T) * (rk + rv) * 2 + Bt * T * HQ * d * (2 + 4)
         res = {"mode": "prefill", "workload": wl.name, "batch": Bt, "T": T, "n_prev": n_prev, "r_k": rk, "r_v": rv,
-               "precision": args.prefill_precision, "sched": args.prefill_sched, "cache": args.cache, "ms_per_launch": round(ms, 4),
+               "sched": args.prefill_sched, "cache": args.cache, "ms_per_launch": round(ms, 4),
                "chunk_tokens_per_s": round(Bt * T / (ms * 1e-3), 1),
                "roofline": {"bound": "mfma", "kernel": "prefill_kernel", "achieved": round(flops / (ms * 1e-3) / 1e12, 1),
                             "peak": 2500.0, "unit": "TFLOP/s", "frac": round(flops / (ms * 1e-3) / 1e12 / 2500.0, 4),
@@ -356,7 +353,7 @@ def main():
             got = out[b_s, :, kv_s * G:(kv_s + 1) * G].cpu().numpy().astype(np.float64)
             err = max(float(np.max(np.abs(got[t, g] - want[0, t, g])) / np.max(np.abs(want[0, t, g]))) for _, t, g in rows)
             res["parity"] = {"max_rel_err_vs_oracle": err, "rows_checked": len(rows),
-                             "tolerance": 1.5e-2 if (pmode & B.SKV_PREFILL_FAST) else 2e-3}
+                             "tolerance": 2e-3}
             row_flops = sum(2 * (rk + rv) * (n_prev + t + 1) for _, t, _ in rows)
             res["cpu_baseline"] = {"value": round(row_flops / spent / 1e12, 6), "unit": "TFLOP/s (algorithmic)",
                                    "kind": "oracle", "sample": f"{len(rows)} query rows of one (sequence, KV head), {spent:.2f} s"}

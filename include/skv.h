@@ -300,12 +300,12 @@ skv_status skv_decode_step_folded(const skv_layer* layer, const void* k_low, con
  *   out     device float32 [batch][T][n_q_heads][head_dim], packed
  *   T       tokens in the chunk (0 is a no-op);  n_prev + T <= capacity
  *   scale   <= 0 selects 1/sqrt(head_dim)
- *   mode    SKV_PREFILL_EXACT: every float32 intermediate that feeds a bf16
- *           product (projected queries, softmax weights, the normalised mix)
- *           is split into two bf16 terms, so results keep float32-level
- *           accuracy (same 2e-3 bound as the decode step).
- *           SKV_PREFILL_FAST: one bf16 term each (half the matrix work); the
- *           operand rounding of 2^-9 then shows in the output.
+ *   mode    0, or one of the schedule bits below.  (Every float32 intermediate
+ *           that feeds a bf16 product -- projected queries, softmax weights, the
+ *           normalised mix -- is split into two bf16 terms, so results keep
+ *           float32-level accuracy: the 2e-3 bound of the decode step.  There is
+ *           no reduced-precision mode: each of the three, fed as one bf16 term,
+ *           breaks that bound on its own.)
  * skv_prefill_attention_folded is the same in the compressed space (Sec. 3.4
  * "Overheads"): q_low bf16 [batch][T][n_q_heads][r_k] packed, out_low float32
  * [batch][T][n_q_heads][r_v] packed; the bases are not used and may be NULL.
@@ -315,7 +315,6 @@ skv_status skv_decode_step_folded(const skv_layer* layer, const void* k_low, con
  * CAPACITY, ALIGN, HIP.
  */
 #define SKV_PREFILL_EXACT 0
-#define SKV_PREFILL_FAST 1
 /* Optional, OR-ed into mode: force one of the kernel's two schedules instead of the default for
  * the shape (results are identical up to summation order; for tuning and benchmarks).
  * TOGETHER stages a tile's keys and values in one step (fewer live registers, more waves per

@@ -22,7 +22,7 @@ SKV_ERR_NULL, SKV_ERR_SHAPE, SKV_ERR_RANK, SKV_ERR_CAPACITY = 1, 2, 3, 4
 SKV_ERR_ALIGN, SKV_ERR_WORKSPACE, SKV_ERR_BUDGET, SKV_ERR_HIP = 5, 6, 7, 8
 SKV_HEAD_DIM = 128
 SKV_MAX_SPLITS = 256
-SKV_PREFILL_EXACT, SKV_PREFILL_FAST = 0, 1
+SKV_PREFILL_EXACT = 0
 SKV_PREFILL_SCHED_TOGETHER, SKV_PREFILL_SCHED_AHEAD = 0x10, 0x20
 # skv_layer.flags
 SKV_READS_BY_SIZE, SKV_READS_STREAMING, SKV_READS_CACHED = 0, 1, 2

@@ -660,7 +660,7 @@ skv_status check_prefill(const skv_layer* L, bool folded, const void* q, const v
   const skv_status st = check_layer(L, !folded);
   if (st != SKV_OK) return st;
   if (T < 0) return SKV_ERR_SHAPE;
-  if (mode & ~(SKV_PREFILL_FAST | SKV_PREFILL_SCHED_TOGETHER | SKV_PREFILL_SCHED_AHEAD)) return SKV_ERR_SHAPE;
+  if (mode & ~(SKV_PREFILL_SCHED_TOGETHER | SKV_PREFILL_SCHED_AHEAD)) return SKV_ERR_SHAPE;
   if ((mode & SKV_PREFILL_SCHED_TOGETHER) && (mode & SKV_PREFILL_SCHED_AHEAD)) return SKV_ERR_SHAPE;
   if (!(scale == scale) || std::isinf(scale)) return SKV_ERR_SHAPE;
   if (n_prev < 0 || n_prev + (int64_t)T > L->capacity) return SKV_ERR_CAPACITY;
@@ -705,7 +705,7 @@ skv_status run_prefill(const skv_layer* L, bool folded, const void* q, int64_t s
   prefill_launcher launch = pages ? paged_prefill_launcher_for(L->r_k) : prefill_launcher_for(L->r_k);
   if (!launch) return SKV_ERR_RANK;
   const int sched = (mode & SKV_PREFILL_SCHED_TOGETHER) ? 1 : (mode & SKV_PREFILL_SCHED_AHEAD) ? 2 : 0;
-  if (launch(L->r_v, (mode & SKV_PREFILL_FAST) ? 1 : 0, sched, p, static_cast<hipStream_t>(stream)) != hipSuccess)
+  if (launch(L->r_v, sched, p, static_cast<hipStream_t>(stream)) != hipSuccess)
     return SKV_ERR_HIP;
   return SKV_OK;
 }

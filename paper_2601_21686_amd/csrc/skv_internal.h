@@ -205,23 +205,23 @@ hipError_t launch_decode_partial_paged_q4_rk64(int, int, const DecodeParams&, hi
 hipError_t launch_decode_partial_paged_q4_rk128(int, int, const DecodeParams&, hipStream_t);
 
 // sched: 0 = the default schedule for the shape, 1 = keys and values staged together, 2 = keys a tile ahead
-typedef hipError_t (*prefill_launcher)(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream);
-hipError_t launch_prefill_rk16(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk32(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk48(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk64(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk80(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk96(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk112(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_rk128(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk16(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk32(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk48(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk64(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk80(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk96(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk112(int, int, int, const PrefillParams&, hipStream_t);
-hipError_t launch_prefill_paged_rk128(int, int, int, const PrefillParams&, hipStream_t);
+typedef hipError_t (*prefill_launcher)(int r_v, int sched, const PrefillParams& p, hipStream_t stream);
+hipError_t launch_prefill_rk16(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk32(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk48(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk64(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk80(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk96(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk112(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_rk128(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk16(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk32(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk48(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk64(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk80(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk96(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk112(int, int, const PrefillParams&, hipStream_t);
+hipError_t launch_prefill_paged_rk128(int, int, const PrefillParams&, hipStream_t);
 
 hipError_t launch_decode_combine(const DecodeParams& p, hipStream_t stream);
 // dst [rows][r_pad] = src [rows][r] followed by zero columns (bf16 bit patterns)

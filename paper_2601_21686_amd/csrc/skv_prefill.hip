@@ -29,10 +29,13 @@
 //     score block (keys 16 kb + 8 (s/4) + 4 lh + s%4) meet 8 contiguous positions.
 //
 // Precision.  Q~ (a float32 sum over d_h), the probabilities and the normalised
-// mix are float32 numbers that the bf16 matrix cores cannot take directly.  In
-// the default mode each is split into a bf16 head and a bf16 remainder
-// (x ~ hi + lo, relative error 2^-17) and fed as two products; the fast mode
-// feeds the bf16 head only (relative operand error 2^-9).
+// mix are float32 numbers that the bf16 matrix cores cannot take directly.
+// Each is split into a bf16 head and a bf16 remainder (x ~ hi + lo, relative
+// error 2^-17) and fed as two products.  None of the three can do without its
+// remainder: fed as one bf16 term (relative error 2^-9) the probabilities alone
+// put the output 4e-3 .. 2e-2 from the float64 definition (relative to the
+// largest entry of an output vector), the projected queries alone up to 2.5e-3
+// and the normalised mix alone up to 2.2e-3, against a bound of 2e-3.
 #include <type_traits>
 
 #include "skv_device_util.h"
@@ -65,14 +68,13 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// Eight float32 -> bf16 heads (and, if wanted, bf16 remainders).
-template <bool SPLIT>
+// Eight float32 -> bf16 heads and bf16 remainders.
 __device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
-  uint32_t h[4], l[4] = {0u, 0u, 0u, 0u};
+  uint32_t h[4], l[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     h[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
-    if (SPLIT) l[e] = pack_bf16x2(x[2 * e] - bf16_lo(h[e]), x[2 * e + 1] - bf16_hi(h[e]));
+    l[e] = pack_bf16x2(x[2 * e] - bf16_lo(h[e]), x[2 * e + 1] - bf16_hi(h[e]));
   }
   hi = __builtin_bit_cast(bf16x8, uint4{h[0], h[1], h[2], h[3]});
   lo = __builtin_bit_cast(bf16x8, uint4{l[0], l[1], l[2], l[3]});
@@ -92,13 +94,13 @@ __device__ __forceinline__ int swap23(int c) { return (c & ~12) | ((c & 4) << 1)
 // Workgroups per CU the register allocation aims for (waves per SIMD): a wave issues at most
 // one instruction every 8-10 cycles, so both the vector and the matrix pipe stay busy only with
 // several waves resident; 3 where the live state fits in 168 registers without spilling.
-constexpr int prefill_min_blocks(int rk, int rv, bool split, bool pipe) {
+constexpr int prefill_min_blocks(int rk, int rv, bool pipe) {
   // (the paged build needs a few registers more: held to two waves per SIMD rather than left to drop to one)
   return (!pipe && rk + rv <= SKV_MINB3_SUM) ? 3 : (SKV_PAGED ? 2 : 1);
 }
 
-template <int RK, int RV, bool SPLIT, bool PIPE>
-__global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void prefill_kernel(const PrefillParams p) {
+template <int RK, int RV, bool PIPE>
+__global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_kernel(const PrefillParams p) {
   constexpr int KSTEPS = RK / 16;            // contraction steps of the score product
   constexpr int RKB = (RK + 31) / 32;        // 32-channel result blocks of Q~^T
   constexpr int RVB = (RV + 31) / 32;        // 32-channel result blocks of the mix
@@ -309,7 +311,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
       float x[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = qa[ks >> 1][8 * (ks & 1) + e] * p.scale_log2e;
-      split8<SPLIT>(x, qhi[ks], qlo[ks]);
+      split8(x, qhi[ks], qlo[ks]);
     }
   } else {
     const uint16_t* qrow = p.q + (((int64_t)b * p.T + tok_c) * p.n_q_heads + head) * RK;
@@ -323,7 +325,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         x[2 * e] = bf16_lo(w[e]) * p.scale_log2e;
         x[2 * e + 1] = bf16_hi(w[e]) * p.scale_log2e;
       }
-      split8<SPLIT>(x, qhi[ks], qlo[ks]);
+      split8(x, qhi[ks], qlo[ks]);
     }
   }
   // Tiles [0, n_full) are visible to every query row of the workgroup and end before the
@@ -385,7 +387,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         for (int a = 0; a < 2; ++a) {
           const bf16x8 ka = lds_frag(&ks_s[(32 * a + ln) * KP + 16 * ks + 8 * lh]);
           s[a] = mfma32(ka, qhi[ks], ks == 0 ? negm : s[a]);
-          if (SPLIT) s[a] = mfma32(ka, qlo[ks], s[a]);
+          s[a] = mfma32(ka, qlo[ks], s[a]);
         }
       }
     } else {
@@ -395,7 +397,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         for (int ks = 0; ks < KSTEPS; ++ks) {
           const bf16x8 ka = lds_frag(&ks_s[(32 * a + ln) * KP + 16 * ks + 8 * lh]);
           s[a] = mfma32(ka, qhi[ks], ks == 0 ? negm : s[a]);
-          if (SPLIT) s[a] = mfma32(ka, qlo[ks], s[a]);
+          s[a] = mfma32(ka, qlo[ks], s[a]);
         }
       }
     }
@@ -444,14 +446,9 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_exp2f(s[a][8 * kb + e]);
-        split8<SPLIT>(x, phi[2 * a + kb], plo[2 * a + kb]);
-        if (SPLIT) {
+        split8(x, phi[2 * a + kb], plo[2 * a + kb]);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) l_run += x[e];
-        } else {                                        // normalise by the weights actually used
-#pragma unroll
-          for (int e = 0; e < 8; ++e) l_run += (float)phi[2 * a + kb][e];
-        }
+        for (int e = 0; e < 8; ++e) l_run += x[e];
       }
     if (PIPE) {
 #pragma unroll
@@ -460,7 +457,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         for (int vb = 0; vb < RVB; ++vb) {
           const bf16x8 va = lds_frag(&vt_s[(32 * vb + ln) * VP + 16 * st + 8 * lh]);
           oacc[vb] = mfma32(va, phi[st], oacc[vb]);
-          if (SPLIT) oacc[vb] = mfma32(va, plo[st], oacc[vb]);
+          oacc[vb] = mfma32(va, plo[st], oacc[vb]);
         }
     } else {
 #pragma unroll
@@ -469,7 +466,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
         for (int st = 0; st < 4; ++st) {
           const bf16x8 va = lds_frag(&vt_s[(32 * vb + ln) * VP + 16 * st + 8 * lh]);
           oacc[vb] = mfma32(va, phi[st], oacc[vb]);
-          if (SPLIT) oacc[vb] = mfma32(va, plo[st], oacc[vb]);
+          oacc[vb] = mfma32(va, plo[st], oacc[vb]);
         }
     }
   };
@@ -573,7 +570,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = oacc[st >> 1][8 * (st & 1) + e] * inv;
-    split8<SPLIT>(x, ahi[st], alo[st]);
+    split8(x, ahi[st], alo[st]);
   }
   const uint16_t* pv = p.p_v + (int64_t)kv * p.p_v_head_stride;
   float* orow = p.out + (((int64_t)b * p.T + tok_c) * p.n_q_heads + head) * D;
@@ -589,7 +586,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
       const uint2 w1 = *reinterpret_cast<const uint2*>(prow + 16 * st + 8 + 4 * lh);
       const bf16x8 pa = __builtin_bit_cast(bf16x8, uint4{w0.x, w0.y, w1.x, w1.y});
       o = mfma32(pa, ahi[st], o);
-      if (SPLIT) o = mfma32(pa, alo[st], o);
+      o = mfma32(pa, alo[st], o);
     }
     if (row_ok) {
 #pragma unroll
@@ -603,8 +600,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, SPLIT, PIPE)) void p
 // Default schedule per shape: where keeping keys a tile ahead measured faster on MI355X
 // (chunk of 4096 tokens over 28672 cached rows, ranks 32..128); elsewhere its extra live
 // registers cost more than the overlap gains.
-constexpr bool pipe_default(int rk, int rv, bool split) {
-  if (!split) return (rk == 48 || rk == 64) && rv >= 80;
+constexpr bool pipe_default(int rk, int rv) {
   if (rk <= 32) return true;
   if (rk <= 48) return rv >= 80 && rv <= 96;
   if (rk <= 64) return rv >= 48 && rv <= 64;
@@ -612,10 +608,10 @@ constexpr bool pipe_default(int rk, int rv, bool split) {
   return false;
 }
 
-template <int RV, bool SPLIT, bool PIPE>
+template <int RV, bool PIPE>
 hipError_t launch_variant(const PrefillParams& p, hipStream_t stream) {
   const dim3 grid((unsigned)((int64_t)p.n_tiles * p.n_rows_y));
-  auto* kernel = prefill_kernel<SKV_RK, RV, SPLIT, PIPE>;
+  auto* kernel = prefill_kernel<SKV_RK, RV, PIPE>;
   size_t dyn = 0;
 #if SKV_PAGED
   // one table entry per key tile of the longest context of the launch
@@ -631,10 +627,9 @@ hipError_t launch_variant(const PrefillParams& p, hipStream_t stream) {
 }
 
 template <int RV>
-hipError_t launch_rv(int fast, int sched, const PrefillParams& p, hipStream_t stream) {
-  const bool pipe = sched == 1 ? false : sched == 2 ? true : pipe_default(SKV_RK, RV, !fast);
-  if (fast) return pipe ? launch_variant<RV, false, true>(p, stream) : launch_variant<RV, false, false>(p, stream);
-  return pipe ? launch_variant<RV, true, true>(p, stream) : launch_variant<RV, true, false>(p, stream);
+hipError_t launch_rv(int sched, const PrefillParams& p, hipStream_t stream) {
+  const bool pipe = sched == 1 ? false : sched == 2 ? true : pipe_default(SKV_RK, RV);
+  return pipe ? launch_variant<RV, true>(p, stream) : launch_variant<RV, false>(p, stream);
 }
 
 }  // namespace
@@ -647,16 +642,16 @@ hipError_t launch_rv(int fast, int sched, const PrefillParams& p, hipStream_t st
 #else
 #define SKV_PREFILL_LAUNCHER SKV_CAT(launch_prefill_rk, SKV_RK)
 #endif
-hipError_t SKV_PREFILL_LAUNCHER(int r_v, int fast, int sched, const PrefillParams& p, hipStream_t stream) {
+hipError_t SKV_PREFILL_LAUNCHER(int r_v, int sched, const PrefillParams& p, hipStream_t stream) {
   switch (r_v) {
-    case 16: return launch_rv<16>(fast, sched, p, stream);
-    case 32: return launch_rv<32>(fast, sched, p, stream);
-    case 48: return launch_rv<48>(fast, sched, p, stream);
-    case 64: return launch_rv<64>(fast, sched, p, stream);
-    case 80: return launch_rv<80>(fast, sched, p, stream);
-    case 96: return launch_rv<96>(fast, sched, p, stream);
-    case 112: return launch_rv<112>(fast, sched, p, stream);
-    case 128: return launch_rv<128>(fast, sched, p, stream);
+    case 16: return launch_rv<16>(sched, p, stream);
+    case 32: return launch_rv<32>(sched, p, stream);
+    case 48: return launch_rv<48>(sched, p, stream);
+    case 64: return launch_rv<64>(sched, p, stream);
+    case 80: return launch_rv<80>(sched, p, stream);
+    case 96: return launch_rv<96>(sched, p, stream);
+    case 112: return launch_rv<112>(sched, p, stream);
+    case 128: return launch_rv<128>(sched, p, stream);
   }
   return hipErrorInvalidValue;
 }

@@ -18,7 +18,6 @@ pytestmark = pytest.mark.gpu
 # alone bound an output vector's error by 2 * 2^-9 of its scale; the query rounding adds
 # (2^-9 |s|) relative to each weight.  With the scores of these inputs (|s| of a few units)
 # 1.5e-2 is a safe bound; the observed error is a few 1e-3.
-TOL_FAST = 1.5e-2
 
 
 def _filled_pair(seed, batch, hq, hkv, r_k, r_v, n, **kw):
@@ -115,16 +114,15 @@ def test_prefill_strided_queries_scale_and_shared_key_basis():
     assert vec_rel_err(got, want) <= TOL
 
 
-def test_prefill_fast_mode_within_its_own_bound():
+def test_prefill_has_no_reduced_precision_mode():
+    """Bit 0 of mode once selected single-term bf16 operands; it is rejected now (each operand fed as one
+    bf16 term breaks the 2e-3 bound by itself, tests/test_prefill_operand_rounding.py)."""
     n_prev, T = 300, 100
     P = _filled_pair(("pf-fast",), 2, 8, 2, 64, 64, n_prev + T)
     q = _chunk_q(P, 8, T)
-    want = O.prefill_attention(P.ora, _f64(q), n_prev)
-    fast = _gpu_prefill(P, q, n_prev, mode=B.SKV_PREFILL_FAST)
-    exact = _gpu_prefill(P, q, n_prev)
-    assert vec_rel_err(fast, want) <= TOL_FAST
-    assert vec_rel_err(exact, want) <= TOL
-    assert vec_rel_err(exact, want) < vec_rel_err(fast, want)
+    with pytest.raises(B.SkvError) as e:
+        _gpu_prefill(P, q, n_prev, mode=1)
+    assert e.value.code == B.SKV_ERR_SHAPE
 
 
 @pytest.mark.parametrize("r_k,r_v,group", [(64, 64, 4), (48, 80, 2), (128, 32, 1)])
