@@ -181,9 +181,9 @@ int32_t skv_decode_default_splits(const skv_layer* layer, int64_t n_ctx);
  * (decode_partial_mma_kernel); -1 for an invalid layer or code width.  code_bits: 0 for bf16 rows, 8 or 4
  * for the quantised formats.  The layer's SKV_ENGINE_* flag decides when set; by shape the matrix kernel
  * takes groups of eight query heads per KV head (one pass over the cache where the vector kernel needs
- * two), the quantised formats, and bf16 layers with groups of four whose ranks are both 32 or 64 unless
- * the layer is flagged SKV_READS_STREAMING (rows from HBM alone: the vector kernel measured ahead there);
- * the vector kernel everything else.  Host only. */
+ * two), the quantised formats, and bf16 layers with groups of four whose ranks are both 32 or 64 -- of a
+ * layer flagged SKV_READS_STREAMING (rows from HBM alone) only the pairs it was measured ahead at there:
+ * r_v = 128 under r_k = 32 or 64, and 32/64; the vector kernel everything else.  Host only. */
 int32_t skv_decode_engine_for(const skv_layer* layer, int32_t code_bits);
 /* 1 if the range kernel of a decode call over n_ctx rows reads the cache with streaming loads, 0 for
  * ordinary loads (the layer's SKV_READS_* flag, or by size), -1 for invalid arguments.  Host only. */

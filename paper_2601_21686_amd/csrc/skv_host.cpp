@@ -43,12 +43,17 @@ int engine_for(const skv_layer* L, int bits = 0, bool paged_codes = false) {
   if (want == SKV_ENGINE_VECTOR) return 0;
   if (want == SKV_ENGINE_MATRIX) return 1;
   if (group == 8 || bits != 0) return 1;
-  // Re-measured per rank pair with rows that come from HBM alone (layers flagged SKV_READS_STREAMING, rotated over
-  // more caches than the last-level cache holds; b4/32K, us per launch, vector / matrix): 64/64 44.1 / 46.0,
-  // 64/32 35.1-35.9 / 37.1, 32/32 25.6-26.1 / 26.2, 32/64 35.9 / 34.7-35.5; 96/64 55.4 / 66.5, 128/96 74.0 / 108.
-  // Such layers take the vector kernel; the matrix kernel keeps the small ranks of layers whose rows are re-read
-  // from the last-level cache (level or up to 1 us ahead there).
-  if ((L->flags & SKV_READS_MASK) == SKV_READS_STREAMING) return 0;
+  // Measured per rank pair with rows that come from HBM alone (layers flagged SKV_READS_STREAMING, rotated over
+  // more caches than the last-level cache holds; b4/32K, us per launch, vector / matrix): 32/32 26.2 / 26.8,
+  // 32/64 36.3 / 35.2, 32/128 55.6 / 54.4, 48/32 30.9 / 33.0, 48/48 34.9 / 41.5, 48/64 39.5 / 39.3, 64/32 34.9 /
+  // 39.9, 64/64 44.6 / 44.7, 64/96 55.0 / 58.2, 64/128 65.2 / 63.4; 96/64 55.4 / 66.5, 128/96 74.0 / 108.
+  // Such layers take the matrix kernel where it is ahead by more than the 1 us these figures move from machine
+  // to machine; the matrix kernel also keeps the small ranks of layers whose rows are re-read from the
+  // last-level cache (level or up to 1 us ahead there).
+  if ((L->flags & SKV_READS_MASK) == SKV_READS_STREAMING) {
+    const bool ahead = group == 4 && ((L->r_v == 128 && (L->r_k == 32 || L->r_k == 64)) || (L->r_k == 32 && L->r_v == 64));
+    return ahead ? 1 : 0;
+  }
   const bool small_pow2 = (L->r_k == 32 || L->r_k == 64) && (L->r_v == 32 || L->r_v == 64);
   return (group == 4 && small_pow2) ? 1 : 0;
 }

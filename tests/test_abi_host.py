@@ -402,8 +402,12 @@ def test_layer_flags_are_validated_and_steer_the_choices():
     assert eng(flags=B.SKV_ENGINE_VECTOR) == 0
     assert eng(8, flags=B.SKV_ENGINE_VECTOR) == 0
     assert eng(n_q_heads=8, flags=B.SKV_ENGINE_MATRIX) == 1
-    # rows that come from HBM alone: the vector kernel also at the small ranks; groups of eight and codes stay
+    # rows that come from HBM alone: the vector kernel also at most small ranks (the matrix kernel where it was
+    # measured ahead: r_v = 128 under r_k = 32 or 64, and 32/64); groups of eight and codes stay
     assert eng(flags=B.SKV_READS_STREAMING) == 0
+    assert eng(r_v=128, p_v_head_stride=128 * 128, flags=B.SKV_READS_STREAMING) == 1
+    assert eng(r_k=32, p_k_head_stride=128 * 32, flags=B.SKV_READS_STREAMING) == 1
+    assert eng(r_k=32, r_v=32, p_k_head_stride=128 * 32, p_v_head_stride=128 * 32, flags=B.SKV_READS_STREAMING) == 0
     assert eng(flags=B.SKV_READS_CACHED) == 1
     assert eng(n_q_heads=64, flags=B.SKV_READS_STREAMING) == 1
     assert eng(8, flags=B.SKV_READS_STREAMING) == 1
