@@ -68,13 +68,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// x minus one half of a bf16 pair, in one instruction: the two-element dot product of the pair with
+// (-1, -0) or (-0, -1), accumulated onto x.  The difference of a float32 number and its own bf16 head is a
+// float32 number, so whatever rounding the instruction applies the result is the float32 subtraction's
+// (checked bit for bit on the GPU over 4 M values from 2^-100 to 2^11 and zeros).  The multipliers are spelt
+// with -0 rather than +0 on purpose: (-1, +0) is the bit pattern of an inline constant, and in that form the
+// instruction was seen to subtract BOTH halves.
+__device__ __forceinline__ float minus_low_half(uint32_t pair, float x) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x8000bf80u), x, false);
+}
+__device__ __forceinline__ float minus_high_half(uint32_t pair, float x) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0xbf808000u), x, false);
+}
+
 // Eight float32 -> bf16 heads and bf16 remainders.
 __device__ __forceinline__ void split8(const float* x, bf16x8& hi, bf16x8& lo) {
   uint32_t h[4], l[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     h[e] = pack_bf16x2(x[2 * e], x[2 * e + 1]);
-    l[e] = pack_bf16x2(x[2 * e] - bf16_lo(h[e]), x[2 * e + 1] - bf16_hi(h[e]));
+    l[e] = pack_bf16x2(minus_low_half(h[e], x[2 * e]), minus_high_half(h[e], x[2 * e + 1]));
   }
   hi = __builtin_bit_cast(bf16x8, uint4{h[0], h[1], h[2], h[3]});
   lo = __builtin_bit_cast(bf16x8, uint4{l[0], l[1], l[2], l[3]});
@@ -346,10 +359,15 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
   auto vst = [&](int tile) { return smem + (tile & 1) * STAGE + KT * KP; };
   fetch_k(0);
   __syncthreads();                                      // the basis is no longer needed: stages may be written
-  if (RV % 32) {                                        // value channels that do not exist read as zero
+  // Value channels that do not exist read as zero -- except the first of them, which reads as one at every
+  // key position: its row of the mix is then sum_j p_j, the softmax normaliser, computed by the matrix
+  // cores from the very weights the mix uses, and the vector pipe (the bound of this kernel) is spared a
+  // row sum of 32 additions per tile.  (Ranks that fill their last 32-channel block keep the additions.)
+  constexpr bool kRowSumInMix = RV % 32 != 0;
+  if (RV % 32) {
     for (int i = tid; i < 2 * (RVB * 32 - RV) * VP; i += NT) {
       const int s = i / ((RVB * 32 - RV) * VP), o = i % ((RVB * 32 - RV) * VP);
-      smem[s * STAGE + KT * KP + RV * VP + o] = 0;
+      smem[s * STAGE + KT * KP + RV * VP + o] = (o < KT) ? (uint16_t)0x3F80u : (uint16_t)0u;
     }
   }
   if (PIPE) {
@@ -447,8 +465,10 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = __builtin_amdgcn_exp2f(s[a][8 * kb + e]);
         split8(x, phi[2 * a + kb], plo[2 * a + kb]);
+        if (!kRowSumInMix) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) l_run += x[e];
+          for (int e = 0; e < 8; ++e) l_run += x[e];
+        }
       }
     if (PIPE) {
 #pragma unroll
@@ -480,16 +500,28 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
       adjust(s_cur);
     }
     int it = 0;
-    for (; it + 1 < n_full; ++it) {                     // steady state: tiles it and it + 1 wholly visible
+    // steady state: tiles it and it + 1 wholly visible; the scores of tile it are in `cur` on entry, those
+    // of tile it + 1 in `nxt` on exit
+    auto steady = [&](int it, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
       store_k(kst(it + 1));
       store_v(vst(it));
       __syncthreads();
       fetch_k(it + 2);
       load_v(inner_t{}, it + 1);
       if (wave_active) {
-        scores(std::false_type{}, kst(it + 1), (it + 1) * KT, s_nxt);
-        mix(vst(it), s_cur);
-        adjust(s_nxt);
+        scores(std::false_type{}, kst(it + 1), (it + 1) * KT, nxt);
+        mix(vst(it), cur);
+        adjust(nxt);
+      }
+    };
+    // two tiles per turn with the two score sets changing roles: no copy of 32 registers per tile
+    for (; it + 2 < n_full; it += 2) {
+      steady(it, s_cur, s_nxt);
+      steady(it + 1, s_nxt, s_cur);
+    }
+    for (; it + 1 < n_full; ++it) {
+      steady(it, s_cur, s_nxt);
+      if (wave_active) {
         s_cur[0] = s_nxt[0];
         s_cur[1] = s_nxt[1];
       }
@@ -542,7 +574,10 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
   }
 
   if (!wave_active) return;
-  const float l_all = l_run + __shfl_xor(l_run, 32);
+  // the normaliser of this lane's query row: the two lanes' shares, or (row sum in the mix) the accumulator of
+  // channel RV, which is register 8 of the last block in the lane of the lower half
+  static_assert(!kRowSumInMix || RV % 32 == 16, "channel RV is expected at row 16 of its block");
+  const float l_all = kRowSumInMix ? __shfl(oacc[RVB - 1][8], ln) : l_run + __shfl_xor(l_run, 32);
   const float inv = 1.f / l_all;
   const bool row_ok = tok < p.T;
 
