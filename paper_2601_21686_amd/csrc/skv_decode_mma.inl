@@ -52,12 +52,23 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi) {
   const f32x2_t v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+// x minus one half of a bf16 pair in one instruction: the two-element dot product of the pair with (-1, -0)
+// or (-0, -1), accumulated onto x.  The difference of a float32 number and its own bf16 head is a float32
+// number, so the result is the float32 subtraction's bit for bit (checked on the GPU).  The multipliers carry
+// -0, not +0: (-1, +0) is the pattern of an inline constant, and in that form the instruction was seen to
+// subtract both halves.
+__device__ __forceinline__ float minus_low_half(uint32_t pair, float x) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0x8000bf80u), x, false);
+}
+__device__ __forceinline__ float minus_high_half(uint32_t pair, float x) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, 0xbf808000u), x, false);
+}
 // four float32 -> bf16 heads and bf16 remainders, packed as matrix operands
 __device__ __forceinline__ void split4(const float (&x)[4], uint2& hi, uint2& lo) {
   hi.x = pack_bf16_pair(x[0], x[1]);
   hi.y = pack_bf16_pair(x[2], x[3]);
-  lo.x = pack_bf16_pair(x[0] - bf16_lo(hi.x), x[1] - bf16_hi(hi.x));
-  lo.y = pack_bf16_pair(x[2] - bf16_lo(hi.y), x[3] - bf16_hi(hi.y));
+  lo.x = pack_bf16_pair(minus_low_half(hi.x, x[0]), minus_high_half(hi.x, x[1]));
+  lo.y = pack_bf16_pair(minus_low_half(hi.y, x[2]), minus_high_half(hi.y, x[3]));
 }
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 // the 32-deep form: lane (m, g) supplies A[m][8 g .. 8 g + 7] and B[8 g .. 8 g + 7][n]; per multiply-add it
@@ -511,26 +522,31 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
   float vscale[NG][2][4], vzero[NG][2][4];
 #endif
   auto scores_and_values = [&](const TileRegsM& tr) {
+    // (the two 16-row blocks take turns, so that a product never waits for the one just issued)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      sc[kb] = SKV_Q8 ? f32x4{0.f, 0.f, 0.f, 0.f} : f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
+    for (int kb = 0; kb < 2; ++kb) sc[kb] = SKV_Q8 ? f32x4{0.f, 0.f, 0.f, 0.f} : f32x4{-m_ref, -m_ref, -m_ref, -m_ref};
 #pragma unroll
-      for (int ks = 0; ks < KSTEPS; ++ks) {
+    for (int ks = 0; ks < KSTEPS; ++ks) {
 #if SKV_Q8
-        const uint4 a = key_operand(tr, kb, ks);
-        sc[kb] = mfma16w(a, qhi[ks], sc[kb]);
-        sc[kb] = mfma16w(a, qlo[ks], sc[kb]);
-        if (ks == KSTEPS - 1) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) sc[kb][i] = fmaf(sc[kb][i], kScoreBack, -m_ref);
-        }
+      const uint4 a0 = key_operand(tr, 0, ks), a1 = key_operand(tr, 1, ks);
+      sc[0] = mfma16w(a0, qhi[ks], sc[0]);
+      sc[1] = mfma16w(a1, qhi[ks], sc[1]);
+      sc[0] = mfma16w(a0, qlo[ks], sc[0]);
+      sc[1] = mfma16w(a1, qlo[ks], sc[1]);
 #else
-        const uint2 a = key_operand(tr, kb, ks);
-        sc[kb] = mfma16(a, qhi[ks], sc[kb]);
-        sc[kb] = mfma16(a, qlo[ks], sc[kb]);
+      const uint2 a0 = key_operand(tr, 0, ks), a1 = key_operand(tr, 1, ks);
+      sc[0] = mfma16(a0, qhi[ks], sc[0]);
+      sc[1] = mfma16(a1, qhi[ks], sc[1]);
+      sc[0] = mfma16(a0, qlo[ks], sc[0]);
+      sc[1] = mfma16(a1, qlo[ks], sc[1]);
 #endif
-      }
     }
+#if SKV_Q8
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sc[kb][i] = fmaf(sc[kb][i], kScoreBack, -m_ref);
+#endif
     store_values(tr);
 #if SKV_Q8
 #pragma unroll
@@ -557,8 +573,9 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
     }
     float mx = fmaxf(fmaxf(fmaxf(sc[0][0], sc[0][1]), fmaxf(sc[0][2], sc[0][3])),
                      fmaxf(fmaxf(sc[1][0], sc[1][1]), fmaxf(sc[1][2], sc[1][3])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    // over the four lanes of a column (16 and 32 apart): two vector lane swaps, not two trips through the LDS
+    // pipeline -- this maximum sits in the middle of the tile's chain of dependent steps
+    mx = halves_pair(rows_pair(mx, true), true);
     // (over a quantised cache the reference is held kWeightBias below where it would be: the weights are
     // that much larger, up to 2^(slack + bias))
     constexpr float kBias = SKV_Q8 ? kWeightBias : 0.f;
@@ -598,13 +615,13 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
         }
       split8w(xs, phi[gq], plo[gq]);
     }
+    uint4 va[VBLOCKS];
 #pragma unroll
-    for (int cb = 0; cb < VBLOCKS; ++cb) {
-      const uint4 a = *reinterpret_cast<const uint4*>(vt + (16 * cb + lm) * VP + 8 * g);
-      const int gq = (16 * cb) / 64;
-      oacc[cb] = mfma16w(a, phi[gq], oacc[cb]);
-      oacc[cb] = mfma16w(a, plo[gq], oacc[cb]);
-    }
+    for (int cb = 0; cb < VBLOCKS; ++cb) va[cb] = *reinterpret_cast<const uint4*>(vt + (16 * cb + lm) * VP + 8 * g);
+#pragma unroll
+    for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] = mfma16w(va[cb], phi[(16 * cb) / 64], oacc[cb]);
+#pragma unroll
+    for (int cb = 0; cb < VBLOCKS; ++cb) oacc[cb] = mfma16w(va[cb], plo[(16 * cb) / 64], oacc[cb]);
 #else
     uint2 phi[2], plo[2];
 #pragma unroll
@@ -656,13 +673,11 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
   //      LDS, in wave order.  A wave's results go where its value tiles were: it has read the last of them
   //      (its own LDS operations complete in order), and no other wave touches that region before the barrier.
   auto wave_red = [&](int w) -> float* { return reinterpret_cast<float*>(scratch_s + w * kWaveTileBytes); };
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
+  l = halves_pair(rows_pair(l, false), false);
 #if SKV_Q8
 #pragma unroll
   for (int gq = 0; gq < NG; ++gq) {
-    zsum[gq] += __shfl_xor(zsum[gq], 16);
-    zsum[gq] += __shfl_xor(zsum[gq], 32);
+    zsum[gq] = halves_pair(rows_pair(zsum[gq], false), false);
   }
 #endif
   if (lm < GT) {

@@ -101,6 +101,13 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// The maximum of a value and its counterpart 32 lanes away, by a vector lane swap (no trip through LDS).
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float max_with_other_half(float x) {
+  const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+
 // Swap bits 2 and 3 of an index.
 __device__ __forceinline__ int swap23(int c) { return (c & ~12) | ((c & 4) << 1) | ((c & 8) >> 1); }
 
@@ -436,7 +443,7 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[a][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_with_other_half(mx);
     if (__any(mx > thr)) {
       const float dlt = mx > thr ? mx : 0.f;
       const float alpha = thr < 0.f ? 1.f : __builtin_amdgcn_exp2f(-dlt);   // nothing accumulated before the first tile
