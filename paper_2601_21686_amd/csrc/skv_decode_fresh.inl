@@ -16,6 +16,49 @@ __device__ __forceinline__ void project_query_rows(const ProjectPieces& pp, int 
   }
 }
 
+// Everything a new-rows workgroup reads from global memory, requested at once before the first wait: the
+// workgroup runs beside a chip full of streaming ones, where a round trip takes 3-5 us, and as a chain of
+// request, wait, compute (queries, then per new token keys, then values) it lived 20-30 us -- as long as a whole
+// range launch over a quantised cache.  Held in registers: the pieces of both bases (the key basis serves the
+// queries and every new key), the raw queries, and the raw new rows of up to kFusedStepMaxTokens tokens (one
+// element per thread and token).
+template <int GT>
+struct NewRowInputs {
+  static constexpr int kQPerLane = (GT * SKV_HEAD_DIM + kDecodeThreads - 1) / kDecodeThreads;
+  ProjectPieces ppk, ppv;
+  uint32_t qraw[kQPerLane];
+  uint32_t knew[kFusedStepMaxTokens], vnew[kFusedStepMaxTokens];
+};
+template <int RK, int RV, int GT>
+__device__ __forceinline__ void request_new_row_inputs(const DecodeParams& p, int b, int kv, int hq0, NewRowInputs<GT>& in) {
+  constexpr int D = SKV_HEAD_DIM;
+  const int tid = threadIdx.x;
+  project_rows_issue(p.p_k + (int64_t)kv * p.p_k_head_stride, RK, in.ppk);
+  const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
+#pragma unroll
+  for (int k = 0; k < NewRowInputs<GT>::kQPerLane; ++k) in.qraw[k] = qptr[(tid + k * kDecodeThreads) % (GT * D)];
+#pragma unroll
+  for (int t = 0; t < kFusedStepMaxTokens; ++t) {
+    in.knew[t] = 0u;
+    in.vnew[t] = 0u;
+    if (t < p.T_new && tid < D) {
+      const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
+      in.knew[t] = p.k_new[src + tid];
+      in.vnew[t] = p.v_new[src + tid];
+    }
+  }
+  project_rows_issue(p.p_v + (int64_t)kv * p.p_v_head_stride, RV, in.ppv);
+}
+// the raw queries into x_s (synchronised), ready for project_query_rows
+template <int GT>
+__device__ __forceinline__ void stage_queries(const NewRowInputs<GT>& in, float* x_s) {
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int k = 0; k < NewRowInputs<GT>::kQPerLane; ++k)
+    if (tid + k * kDecodeThreads < GT * SKV_HEAD_DIM) x_s[tid + k * kDecodeThreads] = bf16_to_f32((uint16_t)in.qraw[k]);
+  __syncthreads();
+}
+
 #if !SKV_Q8
 // The rows a decode step appends (Sec. 2.1 Eq. 1: k_down = k P_K, v_down = v P_V, rounded to bf16 and
 // cached, Sec. 3.2) and their share of the attention, for one (sequence, KV head, pass): projects the
@@ -32,30 +75,23 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
   __shared__ float vd_s[RV];
   __shared__ float w_s[GT][2];                   // per head: factor of the sums so far, weight of the new row
   const int tid = threadIdx.x;
-  const uint16_t* pk = p.p_k + (int64_t)kv * p.p_k_head_stride;
-  const uint16_t* pv = p.p_v + (int64_t)kv * p.p_v_head_stride;
-  {
-    ProjectPieces pp;
-    project_rows_issue(pk, RK, pp);
-    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
-    for (int i = tid; i < GT * D; i += kDecodeThreads) x_s[i] = bf16_to_f32(qptr[i]);
-    __syncthreads();
-    project_query_rows<GT>(pp, RK, x_s, part_s, y_s);
-    for (int i = tid; i < GT * RK; i += kDecodeThreads) qt_s[i] = y_s[i] * p.scale_log2e;
-  }
+  NewRowInputs<GT> in;
+  request_new_row_inputs<RK, RV, GT>(p, b, kv, hq0, in);
+  stage_queries<GT>(in, x_s);
+  project_query_rows<GT>(in.ppk, RK, x_s, part_s, y_s);
+  for (int i = tid; i < GT * RK; i += kDecodeThreads) qt_s[i] = y_s[i] * p.scale_log2e;
   float m = kNegBig, l = 0.f;                    // thread g < GT: softmax state of head g
   float acc[GT];                                 // thread c < RV: channel c of every head's mix
 #pragma unroll
   for (int g = 0; g < GT; ++g) acc[g] = 0.f;
-  for (int t = 0; t < p.T_new; ++t) {
-    const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
+#pragma unroll
+  for (int t = 0; t < kFusedStepMaxTokens; ++t) {
+    if (t >= p.T_new) break;
     const int64_t row = cache_row(p.pages, p.capacity, p.n_kv_heads, b, kv, clamped_len(p.seq_lens, b, p.cur_len) + t);
     {
-      ProjectPieces pp;
-      project_rows_issue(pk, RK, pp);
-      if (tid < D) x_s[tid] = bf16_to_f32(p.k_new[src + tid]);
+      if (tid < D) x_s[tid] = bf16_to_f32((uint16_t)in.knew[t]);
       __syncthreads();
-      project_rows_finish<1>(pp, RK, x_s, part_s, y_s);
+      project_rows_finish<1>(in.ppk, RK, x_s, part_s, y_s);
       if (tid < RK) {
         const uint32_t bits = f32_to_bf16_bits(y_s[tid]);
         if (pass == 0) p.k_cache_w[row * RK + tid] = (uint16_t)bits;
@@ -63,11 +99,9 @@ __device__ __forceinline__ void fresh_rows_block(const DecodeParams& p, int b, i
       }
     }
     {
-      ProjectPieces pp;
-      project_rows_issue(pv, RV, pp);
-      if (tid < D) x_s[tid] = bf16_to_f32(p.v_new[src + tid]);
+      if (tid < D) x_s[tid] = bf16_to_f32((uint16_t)in.vnew[t]);
       __syncthreads();
-      project_rows_finish<1>(pp, RV, x_s, part_s, y_s);
+      project_rows_finish<1>(in.ppv, RV, x_s, part_s, y_s);
       if (tid < RV) {
         const uint32_t bits = f32_to_bf16_bits(y_s[tid]);
         if (pass == 0) p.v_cache_w[row * RV + tid] = (uint16_t)bits;
@@ -124,21 +158,15 @@ __device__ __forceinline__ void fresh_rows_block_q(const DecodeParams& p, int b,
   __shared__ float w_s[GT][2];
   const int tid = threadIdx.x;
   const float top = (float)((1 << SKV_QBITS) - 1);
-  const uint16_t* pk = p.p_k + (int64_t)kv * p.p_k_head_stride;
-  const uint16_t* pv = p.p_v + (int64_t)kv * p.p_v_head_stride;
+  NewRowInputs<GT> in;
+  request_new_row_inputs<RK, RV, GT>(p, b, kv, hq0, in);
   uint8_t* k_codes = reinterpret_cast<uint8_t*>(p.k_cache_w);
   uint8_t* v_codes = reinterpret_cast<uint8_t*>(p.v_cache_w);
   uint32_t* v_meta = const_cast<uint32_t*>(p.v_meta);
-  {
-    ProjectPieces pp;
-    project_rows_issue(pk, RK, pp);
-    const uint16_t* qptr = p.q + ((int64_t)b * p.n_q_heads + hq0) * D;
-    for (int i = tid; i < GT * D; i += kDecodeThreads) x_s[i] = bf16_to_f32(qptr[i]);
-    __syncthreads();
-    project_query_rows<GT>(pp, RK, x_s, part_s, y_s);
-    for (int i = tid; i < GT * RK; i += kDecodeThreads)
-      qt_s[i] = y_s[i] * p.scale_log2e * p.k_scale[kv * NGK + ((i % RK) >> 6)];
-  }
+  stage_queries<GT>(in, x_s);
+  project_query_rows<GT>(in.ppk, RK, x_s, part_s, y_s);
+  for (int i = tid; i < GT * RK; i += kDecodeThreads)
+    qt_s[i] = y_s[i] * p.scale_log2e * p.k_scale[kv * NGK + ((i % RK) >> 6)];
   // code = clamp(rne((y - zero) / scale), 0, 2^bits - 1), stored 8 bits: one byte per channel; 4 bits: channel 2c in
   // the low half of byte c.  Thread c holds channel c; 64-channel group g is wave g.
   auto store_code = [&](uint8_t* codes, int64_t row, int r, uint32_t code, bool live) {
@@ -153,15 +181,14 @@ __device__ __forceinline__ void fresh_rows_block_q(const DecodeParams& p, int b,
   float acc[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) acc[g] = 0.f;
-  for (int t = 0; t < p.T_new; ++t) {
-    const int64_t src = (int64_t)b * p.stride_b + (int64_t)t * p.stride_t + (int64_t)kv * p.stride_h;
+#pragma unroll
+  for (int t = 0; t < kFusedStepMaxTokens; ++t) {
+    if (t >= p.T_new) break;
     const int64_t row = cache_row(p.pages, p.capacity, p.n_kv_heads, b, kv, clamped_len(p.seq_lens, b, p.cur_len) + t);
     {
-      ProjectPieces pp;
-      project_rows_issue(pk, RK, pp);
-      if (tid < D) x_s[tid] = bf16_to_f32(p.k_new[src + tid]);
+      if (tid < D) x_s[tid] = bf16_to_f32((uint16_t)in.knew[t]);
       __syncthreads();
-      project_rows_finish<1>(pp, RK, x_s, part_s, y_s);
+      project_rows_finish<1>(in.ppk, RK, x_s, part_s, y_s);
       const bool live = tid < RK;
       const float y = live ? y_s[tid] : 0.f;
       const float scale = live ? p.k_scale[kv * NGK + (tid >> 6)] : 1.f;
@@ -171,11 +198,9 @@ __device__ __forceinline__ void fresh_rows_block_q(const DecodeParams& p, int b,
       if (live) kc_s[tid] = (float)code;
     }
     {
-      ProjectPieces pp;
-      project_rows_issue(pv, RV, pp);
-      if (tid < D) x_s[tid] = bf16_to_f32(p.v_new[src + tid]);
+      if (tid < D) x_s[tid] = bf16_to_f32((uint16_t)in.vnew[t]);
       __syncthreads();
-      project_rows_finish<1>(pp, RV, x_s, part_s, y_s);
+      project_rows_finish<1>(in.ppv, RV, x_s, part_s, y_s);
       const bool live = tid < RV;
       const float y = live ? y_s[tid] : 0.f;
       float lo = live ? y : 3.0e38f, hi = live ? y : -3.0e38f;
