@@ -18,6 +18,25 @@ namespace skv {
 namespace {
 
 constexpr int kCombineThreads = SKV_HEAD_DIM;   // one thread per output channel
+
+// The maximum over a wave with vector instructions only (rotations inside a row of 16 lanes, then the swaps of
+// odd and even rows and of the two halves): the kernel is a chain of dependent steps, and six exchanges through
+// the LDS pipeline were a tenth of it.  Every lane receives the maximum.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  x = fmaxf(x, dpp_f32<0x128>(x));               // row_ror:8
+  x = fmaxf(x, dpp_f32<0x124>(x));               // row_ror:4
+  x = fmaxf(x, dpp_f32<0x122>(x));               // row_ror:2
+  x = fmaxf(x, dpp_f32<0x121>(x));               // row_ror:1
+  const u32x2_t a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+  const u32x2_t b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
 constexpr int kPreload = 8;                     // partial-mix values per thread requested up front
 constexpr int kMlPerThread = SKV_MAX_SPLITS / kCombineThreads;
 
@@ -67,8 +86,7 @@ __global__ __launch_bounds__(kCombineThreads) void decode_combine_kernel(const D
   float mloc = mlr[0].x;
 #pragma unroll
   for (int k = 1; k < kMlPerThread; ++k) mloc = fmaxf(mloc, mlr[k].x);
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) mloc = fmaxf(mloc, __shfl_xor(mloc, off));
+  mloc = wave_max(mloc);
   if ((tid & 63) == 0) red_s[tid >> 6] = mloc;
   __syncthreads();
   float m = red_s[0];
