@@ -440,7 +440,10 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
   // Queries projected here: the projection's few words (basis pieces, raw queries) are waited for BEFORE the
   // tiles go out -- every workgroup of the launch starts at the same moment, and behind the whole chip's
   // first tiles those words took 3-5 us to arrive; the tiles then stream while the projection runs.
-  if (!from_workspace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#ifndef SKV_MMA_WORDS_FIRST
+#define SKV_MMA_WORDS_FIRST 1
+#endif
+  if (SKV_MMA_WORDS_FIRST && !from_workspace) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   auto clamped_tile = [&](int tile) { return tile < n_whole ? tile : n_whole - 1; };
 #if SKV_MMA_DEPTH == 2
   TileRegsM tb;
