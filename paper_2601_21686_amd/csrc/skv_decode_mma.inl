@@ -440,6 +440,8 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
   // Queries projected here: the projection's few words (basis pieces, raw queries) are waited for BEFORE the
   // tiles go out -- every workgroup of the launch starts at the same moment, and behind the whole chip's
   // first tiles those words took 3-5 us to arrive; the tiles then stream while the projection runs.
+  // (SKV_MMA_WORDS_FIRST = 0 sends the tiles after the words without waiting: 47.1 against 45.9 us per call at
+  // b4/32K 64/64, level over the quantised caches)
 #ifndef SKV_MMA_WORDS_FIRST
 #define SKV_MMA_WORDS_FIRST 1
 #endif
