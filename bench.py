@@ -10,7 +10,10 @@ HBM when the clock starts.
 
 Prints ONE JSON line.  `value` is algorithmic compressed-cache bytes per second
 for the whole step (GB/s); tokens/s is reported beside it.  `roofline` is the
-decode range kernel alone, timed with events on the launch stream.
+decode range kernel alone, timed with events on the launch stream; its
+`hbm_only` object (and `value_hbm_only`) repeat the launch and the step rotated
+over enough distinct copies of the layer's cache that no row is found in a cache
+again -- the rate a model whose layers together exceed the last-level cache sees.
 `cpu_baseline` is the float64 oracle timed on the host for one decode step of
 the same workload.
 """
