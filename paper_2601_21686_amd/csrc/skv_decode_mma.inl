@@ -38,7 +38,10 @@
 // multiply-add that also subtracts the softmax reference), and the softmax weights are kept 2^64 above
 // their usual size (the reference sits 64 below the running maximum; normaliser, zero sums and partial
 // results are all in that convention, which is as valid a partial result as any), the last 2^133 going
-// onto the mix once, before it is written.
+// onto the mix once, before it is written.  What this asks of the data: the products of the leading weights,
+// 2^64 .. 2^72 times a row's value scale times a code times 2^-133, must be normal float32 numbers, i.e. value
+// scales between about 2^-50 and 2^50 (ranges from 1e-13 to 1e17 at 8 bits) -- far outside what a projected
+// activation spans, and tested over 2^-20 .. 2^20 times the usual ranges.
 // ---------------------------------------------------------------------------------------------------
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));

@@ -170,6 +170,32 @@ def test_quantised_decode_matches_oracle_on_identical_cache_bytes(bits, r_k, r_v
 
 
 @pytest.mark.parametrize("bits", [8, 4])
+def test_value_ranges_over_many_orders_of_magnitude(bits):
+    """The matrix-core range kernel takes the codes as the bf16 numbers n * 2^-133 and carries the factor on the
+    weights; value ranges from 2^-20 to 2^20 times the usual ones (row by row, in both the oracle's layer and the
+    bytes uploaded) must come out as the definition says."""
+    _, attention_fn, _, _, _, _ = _fns(bits)
+    n, hq, hkv = 700, 8, 2
+    P = QPair(("qdec-ranges", bits), 2, hq, hkv, 64, 64, n, bits)
+    k, v = P.raw_kv(5, n)
+    P.oracle_append(k, v, 0)
+    shift = (((np.arange(n) * 7) % 41) - 20).astype(np.int32)          # exponent change per row
+    for arr in (P.ora.v_scale_bits, P.ora.v_zero_bits):
+        a = arr[:, :, :n].astype(np.int32)
+        nonzero = (a & 0x7f80) != 0                                     # a zero point of exactly 0 stays 0
+        a = np.where(nonzero, a + (shift[None, None, :, None] << 7), a)
+        assert ((a & 0x7f80) != 0x7f80).all() and (a >= 0).all() and (a <= 0xffff).all()
+        arr[:, :, :n] = a.astype(arr.dtype)
+    P.upload_oracle_cache(n)
+    q = P.queries(6)
+    out = torch.empty((2, hq, 128), dtype=torch.float32, device="cuda")
+    for n_ctx in (n, 33):
+        attention_fn(P.gpu, q, out, n_ctx)
+        torch.cuda.synchronize()
+        assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
+
+
+@pytest.mark.parametrize("bits", [8, 4])
 def test_quantised_decode_steps_end_to_end(bits):
     # Append through the library, then a few fused decode steps; both sides keep their own caches.  A code is
     # an integer decided by floating point: the library decides it in float32 on a float32 sum, the oracle in
