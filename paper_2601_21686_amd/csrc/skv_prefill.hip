@@ -42,7 +42,7 @@
 #include "skv_internal.h"
 
 #ifndef SKV_MINB3_SUM
-#define SKV_MINB3_SUM 128
+#define SKV_MINB3_SUM 112         // up to this r_K + r_V the staged-together schedule is held to three waves per SIMD
 #endif
 #ifndef SKV_PAGED
 #define SKV_PAGED 0                 // 1: the caches are page pools addressed through a block table
@@ -115,8 +115,10 @@ __device__ __forceinline__ int swap23(int c) { return (c & ~12) | ((c & 4) << 1)
 // one instruction every 8-10 cycles, so both the vector and the matrix pipe stay busy only with
 // several waves resident; 3 where the live state fits in 168 registers without spilling.
 constexpr int prefill_min_blocks(int rk, int rv, bool pipe) {
-  // (the paged build needs a few registers more: held to two waves per SIMD rather than left to drop to one)
-  return (!pipe && rk + rv <= SKV_MINB3_SUM) ? 3 : (SKV_PAGED ? 2 : 1);
+  // (every other build is held to two waves per SIMD rather than left to drop to one: at the large ranks the
+  // live state sits at the 256-register line, and a kernel allowed one wave takes a few accumulation
+  // registers beyond it and halves its residency -- 128/128 took 49 ms that way against 31)
+  return (!pipe && rk + rv <= SKV_MINB3_SUM) ? 3 : 2;
 }
 
 template <int RK, int RV, bool PIPE>
@@ -202,14 +204,18 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
   // Tiles that lie wholly inside every query's visible range are fetched with addresses that
   // are a per-thread constant plus a uniform tile base; the last few tiles (the causal
   // diagonal, the end of the cache) clamp their rows instead.
-  uint4 kreg[KPT];
+  // (named registers, not an array: as an array the key pieces were seen to stay in scratch memory in some
+  // instantiations -- every tile then went global -> wait -> scratch -> LDS, and the prefetch was gone)
+  static_assert(KPT <= 4, "a thread holds at most four key pieces");
+  uint4 kreg0 = {}, kreg1 = {}, kreg2 = {}, kreg3 = {};
+  auto each_key_piece = [&](auto&& f) {
+    f(0, kreg0);
+    if constexpr (KPT > 1) f(1, kreg1);
+    if constexpr (KPT > 2) f(2, kreg2);
+    if constexpr (KPT > 3) f(3, kreg3);
+  };
   uint32_t vreg[VPT][8];
-  int koff[KPT], voff[VPT];
-#pragma unroll
-  for (int u = 0; u < KPT; ++u) {
-    const int i = tid + u * NT;
-    koff[u] = (i / KC8) * RK + (i % KC8) * 8;
-  }
+  int voff[VPT];
 #pragma unroll
   for (int u = 0; u < VPT; ++u) {
     const int i = tid + u * NT;
@@ -221,19 +227,18 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
     const int j0 = tile * KT;
     const uint16_t* kc = paged ? p.k_cache + page_shift_rows(tile) * RK : kc_flat;
     const uint16_t* kt = kc + (int64_t)j0 * RK;
-#pragma unroll
-    for (int u = 0; u < KPT; ++u) {
+    each_key_piece([&](int u, uint4& piece) {
       const int i = tid + u * NT;
       if (KPIECES % NT == 0 || i < KPIECES) {
         if (decltype(inner_tag)::value) {
-          kreg[u] = *reinterpret_cast<const uint4*>(kt + koff[u]);
+          piece = *reinterpret_cast<const uint4*>(kt + (i / KC8) * RK + (i % KC8) * 8);
         } else {
           int row = j0 + i / KC8;
           row = row < last_row ? row : last_row;       // rows past the end re-read the last row; masked later
-          kreg[u] = *reinterpret_cast<const uint4*>(kc + (int64_t)row * RK + (i % KC8) * 8);
+          piece = *reinterpret_cast<const uint4*>(kc + (int64_t)row * RK + (i % KC8) * 8);
         }
       }
-    }
+    });
   };
   auto load_v = [&](auto inner_tag, int tile) {
     const int j0 = tile * KT;
@@ -260,14 +265,13 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
     }
   };
   auto store_k = [&](uint16_t* ks) {
-#pragma unroll
-    for (int u = 0; u < KPT; ++u) {
+    each_key_piece([&](int u, uint4& piece) {
       const int i = tid + u * NT;
       if (KPIECES % NT == 0 || i < KPIECES) {
         const int key = i / KC8, c8 = i % KC8;
-        *reinterpret_cast<uint4*>(ks + key * KP + c8 * 8) = kreg[u];
+        *reinterpret_cast<uint4*>(ks + key * KP + c8 * 8) = piece;
       }
-    }
+    });
   };
   auto store_v = [&](uint16_t* vt) {
 #pragma unroll
@@ -644,9 +648,11 @@ __global__ __launch_bounds__(NT, prefill_min_blocks(RK, RV, PIPE)) void prefill_
 // registers cost more than the overlap gains.
 constexpr bool pipe_default(int rk, int rv) {
   if (rk <= 32) return true;
-  if (rk <= 48) return rv >= 80 && rv <= 96;
-  if (rk <= 64) return rv >= 48 && rv <= 64;
-  if (rk <= 96) return rv >= 48 && rv <= 64;
+  if (rk <= 48) return rv >= 32 && rv <= 112;
+  if (rk <= 64) return rv <= 112;
+  if (rk <= 80) return rv >= 32 && rv <= 80;
+  if (rk <= 96) return rv <= 48;
+  if (rk <= 112) return rv == 16 || rv == 48;
   return false;
 }
 
