@@ -479,8 +479,16 @@ def main():
         outs_low = [torch.empty((n_steps_total, Bt, HQ, ranks_v[li]), dtype=torch.float32, device=dev)
                     for li in range(wl.n_layers)]
 
+    # a stack of plain bf16 layers goes through the library's own loop over layers (the same launches)
+    stack = B.LayerStack(layers) if (wl.n_layers > 1 and not (folded or q8 or paged)) else None
+
     def step(s: int):
         cur = n0 + s
+        if stack is not None:
+            B.skv_decode_step_layers(stack, [x[:, s:s + 1] for x in new_k], [x[:, s:s + 1] for x in new_v], cur,
+                                     [qs[s, li] for li in range(wl.n_layers)],
+                                     [outs[s, li] for li in range(wl.n_layers)], 0.0, ws)
+            return
         for li, L in enumerate(layers):
             if folded:
                 B.skv_decode_step_folded(L, nk_low[li][s], nv_low[li][s], cur, q_low[li][s], outs_low[li][s], 0.0, ws)

@@ -217,6 +217,33 @@ skv_status skv_decode_step(const skv_layer* layer,
                            void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * A stack of layers (Sec. 3.3: ranks differ from layer to layer, so every layer carries its own
+ * descriptor, bases and caches): skv_decode_attention, or skv_decode_step, for layers[0 .. n_layers) in
+ * order on one stream, exactly as the loop of single-layer calls would run them and with bit-identical
+ * results -- a convenience for callers that hold a layer's inputs ready for all layers (benchmarks, a
+ * model whose attention inputs are precomputed).  Every layer is checked before the first launch: an
+ * argument error in any layer returns its code with nothing enqueued.
+ *   layers        host array of n_layers descriptors (n_layers = 0 is a no-op)
+ *   q, out        host arrays of n_layers device pointers, each as for the single-layer call
+ *   k_new, v_new  likewise (ignored when T = 0); the strides, T and cur_len are shared by all layers
+ *   n_ctx         rows attended in every layer's cache
+ *   workspace     one scratch buffer used by each layer in turn: at least the largest
+ *                 skv_decode_workspace_bytes() over the layers
+ * Errors: as the single-layer call, plus NULL for a missing array and SHAPE for n_layers < 0.  A HIP launch
+ * failure at layer l leaves layers [0, l) enqueued.
+ */
+skv_status skv_decode_attention_layers(const skv_layer* layers, int32_t n_layers,
+                                       const void* const* q, void* const* out,
+                                       int64_t n_ctx, float scale,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+skv_status skv_decode_step_layers(const skv_layer* layers, int32_t n_layers,
+                                  const void* const* k_new, const void* const* v_new,
+                                  int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                                  int32_t T, int64_t cur_len,
+                                  const void* const* q, void* const* out, float scale,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The three stages of skv_decode_attention, exposed so that a caller can time
  * or schedule them separately; calling them back to back on one stream with
  * the same workspace and n_splits gives bit for bit the result of

@@ -36,6 +36,7 @@ EXPORTS = (
     "skv_project_append", "skv_decode_attention", "skv_decode_attention_static", "skv_decode_workspace_bytes",
     "skv_decode_default_splits", "skv_decode_range", "skv_decode_step", "skv_decode_project_query",
     "skv_decode_partial", "skv_decode_combine", "skv_decode_partial_q",
+    "skv_decode_attention_layers", "skv_decode_step_layers",
     "skv_layer_ranks", "skv_cache_bytes", "skv_status_string",
     "skv_q8_project_append", "skv_q8_decode_attention", "skv_q8_decode_step", "skv_q8_cache_bytes",
     "skv_q8_decode_project_query", "skv_q8_decode_partial", "skv_q8_decode_default_splits",
@@ -109,6 +110,11 @@ def lib() -> C.CDLL:
     L.skv_decode_range.restype = C.c_int
     L.skv_decode_step.argtypes = [LP, vp, vp, i64, i64, i64, i32, i64, vp, vp, C.c_float, vp, sz, vp]
     L.skv_decode_step.restype = C.c_int
+    pp = C.POINTER(C.c_void_p)
+    L.skv_decode_attention_layers.argtypes = [LP, i32, pp, pp, i64, C.c_float, vp, sz, vp]
+    L.skv_decode_attention_layers.restype = C.c_int
+    L.skv_decode_step_layers.argtypes = [LP, i32, pp, pp, i64, i64, i64, i32, i64, pp, pp, C.c_float, vp, sz, vp]
+    L.skv_decode_step_layers.restype = C.c_int
     L.skv_decode_project_query.argtypes = [LP, vp, C.c_float, vp, sz, vp]
     L.skv_decode_project_query.restype = C.c_int
     L.skv_decode_partial.argtypes = [LP, i64, i32, vp, sz, vp]
@@ -388,6 +394,55 @@ def skv_decode_step(layer, k_new: torch.Tensor, v_new: torch.Tensor, cur_len: in
                                  int(k_new.shape[1]), int(cur_len), q.data_ptr(), out.data_ptr(),
                                  float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
                                  _stream_ptr(stream)), "skv_decode_step")
+
+
+class LayerStack:
+    """The descriptors of several Layer objects as one C array, plus one workspace large enough for each of
+    them (argument marshalling for the *_layers calls; built once, reused every step)."""
+
+    def __init__(self, layers):
+        self.layers = list(layers)
+        self.c = (skv_layer * len(self.layers))(*[l.c for l in self.layers])
+        self._ws = None
+
+    def __len__(self):
+        return len(self.layers)
+
+    def workspace(self) -> torch.Tensor:
+        if self._ws is None:
+            n = max([skv_decode_workspace_bytes(l) for l in self.layers] + [16])
+            self._ws = torch.empty(n, dtype=torch.uint8, device=self.layers[0].p_k.device)
+        return self._ws
+
+
+def _ptr_array(tensors, n):
+    assert len(tensors) == n
+    return (C.c_void_p * n)(*[t.data_ptr() for t in tensors])
+
+
+def skv_decode_attention_layers(stack: LayerStack, q, out, n_ctx: int, scale: float = 0.0,
+                                workspace: torch.Tensor | None = None, stream=None) -> None:
+    """skv_decode_attention for every layer of the stack in order; q, out: one tensor per layer."""
+    n = len(stack)
+    ws = stack.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_attention_layers(stack.c, n, _ptr_array(q, n), _ptr_array(out, n), int(n_ctx),
+                                             float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                             _stream_ptr(stream)), "skv_decode_attention_layers")
+
+
+def skv_decode_step_layers(stack: LayerStack, k_new, v_new, cur_len: int, q, out, scale: float = 0.0,
+                           workspace: torch.Tensor | None = None, stream=None) -> None:
+    """skv_decode_step for every layer of the stack in order; k_new, v_new, q, out: one tensor per layer
+    (all k_new / v_new with the same shape and strides)."""
+    n = len(stack)
+    assert all(t.dtype == torch.bfloat16 and t.stride() == k_new[0].stride() and t.shape == k_new[0].shape
+               for t in list(k_new) + list(v_new)) and k_new[0].stride(3) == 1
+    sb, st, sh, _ = k_new[0].stride()
+    ws = stack.workspace() if workspace is None else workspace
+    _check(lib().skv_decode_step_layers(stack.c, n, _ptr_array(k_new, n), _ptr_array(v_new, n), sb, st, sh,
+                                        int(k_new[0].shape[1]), int(cur_len), _ptr_array(q, n), _ptr_array(out, n),
+                                        float(scale), ws.data_ptr(), ws.numel() * ws.element_size(),
+                                        _stream_ptr(stream)), "skv_decode_step_layers")
 
 
 def skv_decode_project_query(layer, q: torch.Tensor, scale: float = 0.0,

@@ -381,6 +381,48 @@ skv_status check_append(const skv_layer* L, const void* k_new, const void* v_new
   return SKV_OK;
 }
 
+// Everything skv_decode_attention needs checked before its first launch; *n_splits: the range plan.
+skv_status check_decode_attention(const skv_layer* L, const void* q, const void* out, int64_t n_ctx, float scale,
+                                  const void* workspace, size_t workspace_bytes, int32_t* n_splits) {
+  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
+  if (st != SKV_OK) return st;
+  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, n_splits);
+  if (st != SKV_OK) return st;
+  return check_combine_stage(L, out, *n_splits, workspace, workspace_bytes);
+}
+
+// How a decode step runs: fused (the new rows are projected, stored and attended by workgroups of the range
+// launch: two launches) or as append + attention; n_splits: partial results the merge reads.
+struct StepPlan {
+  bool fused = false;
+  int32_t n_splits = 0;
+};
+
+skv_status check_decode_step(const skv_layer* L, const void* k_new, const void* v_new, int64_t stride_b,
+                             int64_t stride_t, int64_t stride_h, int32_t T, int64_t cur_len, const void* q,
+                             const void* out, float scale, const void* workspace, size_t workspace_bytes,
+                             StepPlan* plan) {
+  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  if (st != SKV_OK) return st;
+  int32_t s = 0;
+  st = check_decode_attention(L, q, out, cur_len + T, scale, workspace, workspace_bytes, &s);
+  if (st != SKV_OK) return st;
+  plan->fused = false;
+  plan->n_splits = s;
+  const int gq = L->n_q_heads / L->n_kv_heads;
+  // (the fused launch adds up to one grid row per column: stay inside the grid's y limit)
+  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(L)) <= 65535;
+  if (T > 0 && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
+    int32_t s_old = 0;
+    if (!plan_splits(L, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
+    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
+    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
+    plan->fused = true;
+    plan->n_splits = s_old + 1;
+  }
+  return SKV_OK;
+}
+
 // ---- parameter blocks ---------------------------------------------------------------------
 
 void fill_query_params(const skv_layer* L, DecodeParams* p, const void* q, float scale, void* workspace) {
@@ -560,19 +602,33 @@ skv_status skv_decode_combine(const skv_layer* L, void* out, int32_t n_splits, v
 skv_status skv_decode_attention(const skv_layer* L, const void* q, void* out, int64_t n_ctx,
                                 float scale, void* workspace, size_t workspace_bytes,
                                 void* stream) {
-  // Check everything the three stages need before the first launch, so that an error
+  // Check everything the stages need before the first launch, so that an error
   // never leaves part of the work enqueued.
-  skv_status st = check_query_stage(L, q, scale, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
   int32_t s = 0;
-  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
-  if (st != SKV_OK) return st;
-  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
+  skv_status st = check_decode_attention(L, q, out, n_ctx, scale, workspace, workspace_bytes, &s);
   if (st != SKV_OK) return st;
   // two launches: the range kernel projects the queries itself
   st = run_partial_fused(L, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status skv_decode_attention_layers(const skv_layer* layers, int32_t n_layers, const void* const* q,
+                                       void* const* out, int64_t n_ctx, float scale, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  if (n_layers < 0) return SKV_ERR_SHAPE;
+  if (n_layers == 0) return SKV_OK;
+  if (!layers || !q || !out) return SKV_ERR_NULL;
+  for (int32_t l = 0; l < n_layers; ++l) {              // every layer is checked before the first launch
+    int32_t s = 0;
+    const skv_status st = check_decode_attention(&layers[l], q[l], out[l], n_ctx, scale, workspace, workspace_bytes, &s);
+    if (st != SKV_OK) return st;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const skv_status st = skv_decode_attention(&layers[l], q[l], out[l], n_ctx, scale, workspace, workspace_bytes, stream);
+    if (st != SKV_OK) return st;
+  }
+  return SKV_OK;
 }
 
 skv_status skv_project_append(const skv_layer* L, const void* k_new, const void* v_new,
@@ -590,32 +646,20 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
                            int64_t stride_b, int64_t stride_t, int64_t stride_h, int32_t T,
                            int64_t cur_len, const void* q, void* out, float scale, void* workspace,
                            size_t workspace_bytes, void* stream) {
-  skv_status st = check_append(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len);
+  StepPlan plan;
+  skv_status st = check_decode_step(L, k_new, v_new, stride_b, stride_t, stride_h, T, cur_len, q, out, scale,
+                                    workspace, workspace_bytes, &plan);
   if (st != SKV_OK) return st;
-  st = check_query_stage(L, q, scale, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-  const int64_t n_ctx = cur_len + T;
-  int32_t s = 0;
-  st = check_partial_stage(L, n_ctx, 0, workspace, workspace_bytes, &s);
-  if (st != SKV_OK) return st;
-  st = check_combine_stage(L, out, s, workspace, workspace_bytes);
-  if (st != SKV_OK) return st;
-
   hipStream_t hs = static_cast<hipStream_t>(stream);
-  const int gq = L->n_q_heads / L->n_kv_heads;
-  // (the fused launch adds up to one grid row per column: stay inside the grid's y limit)
-  const bool grid_ok = 2 * (int64_t)L->batch * L->n_kv_heads * (gq / decode_heads_per_pass(L)) <= 65535;
-  if (T > 0 && T <= kFusedStepMaxTokens && cur_len > 0 && grid_ok) {
+  const int64_t n_ctx = cur_len + T;
+  const int32_t s = plan.n_splits;
+  if (plan.fused) {
     // The usual decode step, two launches: context ranges over the rows already cached, plus one
     // workgroup per (sequence, KV head) that projects, stores and attends the new rows; then the merge.
-    int32_t s_old = 0;
-    if (!plan_splits(L, cur_len, 0, &s_old)) return SKV_ERR_SHAPE;
-    if (s_old + 1 > SKV_MAX_SPLITS) s_old = SKV_MAX_SPLITS - 1;
-    if (workspace_bytes < workspace_need(L, s_old + 1)) return SKV_ERR_WORKSPACE;   // one more partial than ranges
-    st = run_partial_fused(L, q, scale, cur_len, s_old, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
+    st = run_partial_fused(L, q, scale, cur_len, s - 1, k_new, v_new, stride_b, stride_t, stride_h, T, workspace,
                            stream);
     if (st != SKV_OK) return st;
-    return run_combine(L, out, s_old + 1, workspace, stream);
+    return run_combine(L, out, s, workspace, stream);
   }
   if (T > 0) {
     AppendParams ap;
@@ -625,6 +669,29 @@ skv_status skv_decode_step(const skv_layer* L, const void* k_new, const void* v_
   st = run_partial_fused(L, q, scale, n_ctx, s, nullptr, nullptr, 0, 0, 0, 0, workspace, stream);
   if (st != SKV_OK) return st;
   return run_combine(L, out, s, workspace, stream);
+}
+
+skv_status skv_decode_step_layers(const skv_layer* layers, int32_t n_layers, const void* const* k_new,
+                                  const void* const* v_new, int64_t stride_b, int64_t stride_t, int64_t stride_h,
+                                  int32_t T, int64_t cur_len, const void* const* q, void* const* out, float scale,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
+  if (n_layers < 0) return SKV_ERR_SHAPE;
+  if (n_layers == 0) return SKV_OK;
+  if (!layers || !q || !out || (T > 0 && (!k_new || !v_new))) return SKV_ERR_NULL;
+  for (int32_t l = 0; l < n_layers; ++l) {              // every layer is checked before the first launch
+    StepPlan plan;
+    const skv_status st = check_decode_step(&layers[l], T > 0 ? k_new[l] : nullptr, T > 0 ? v_new[l] : nullptr, stride_b,
+                                            stride_t, stride_h, T, cur_len, q[l], out[l], scale, workspace,
+                                            workspace_bytes, &plan);
+    if (st != SKV_OK) return st;
+  }
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const skv_status st = skv_decode_step(&layers[l], T > 0 ? k_new[l] : nullptr, T > 0 ? v_new[l] : nullptr, stride_b,
+                                          stride_t, stride_h, T, cur_len, q[l], out[l], scale, workspace,
+                                          workspace_bytes, stream);
+    if (st != SKV_OK) return st;
+  }
+  return SKV_OK;
 }
 
 }  // extern "C"

@@ -503,3 +503,36 @@ def test_paged_quantised_argument_checks():
     # chunk attention and the separate first launch are offered over bf16 pages only
     assert lib.skv_paged_prefill_attention(C.byref(paged(8)), FAKE, 8192, 4096, 128, FAKE, 16, 0, 0.0, 0, None) == B.SKV_ERR_SHAPE
     assert lib.skv_paged_decode_partial_q(C.byref(paged(8)), FAKE, None, 0.0, 100, 0, FAKE, big, None) == B.SKV_ERR_SHAPE
+
+
+def test_layer_stack_calls_check_every_layer_before_anything_else():
+    """skv_decode_attention_layers / skv_decode_step_layers (Sec. 3.3: one descriptor per layer): the arrays
+    and the count are checked, and an error in ANY layer is returned -- also in the last one, i.e. before
+    the first layer would have been launched (a launch here, without a GPU, would return SKV_ERR_HIP)."""
+    lib = B.lib()
+    n = 3
+    ptrs = (C.c_void_p * n)(FAKE, FAKE, FAKE)
+    good = (B.skv_layer * n)(_layer(), _layer(r_k=32, p_k_head_stride=128 * 32), _layer(r_v=96, p_v_head_stride=128 * 96))
+    att = lambda layers, cnt, q=ptrs, out=ptrs, n_ctx=16, ws=FAKE, nbytes=1 << 30: lib.skv_decode_attention_layers(
+        layers, cnt, q, out, n_ctx, 0.0, ws, nbytes, None)
+    step = lambda layers, cnt, k=ptrs, v=ptrs, q=ptrs, out=ptrs, T=1, cur=15, ws=FAKE, nbytes=1 << 30: \
+        lib.skv_decode_step_layers(layers, cnt, k, v, 8192, 1024, 128, T, cur, q, out, 0.0, ws, nbytes, None)
+    assert att(good, 0) == B.SKV_OK and step(good, 0) == B.SKV_OK
+    assert att(good, -1) == B.SKV_ERR_SHAPE and step(good, -1) == B.SKV_ERR_SHAPE
+    assert att(None, n) == B.SKV_ERR_NULL and att(good, n, q=None) == B.SKV_ERR_NULL and att(good, n, out=None) == B.SKV_ERR_NULL
+    assert step(None, n) == B.SKV_ERR_NULL and step(good, n, k=None) == B.SKV_ERR_NULL and step(good, n, v=None) == B.SKV_ERR_NULL
+    assert step(good, n, q=None) == B.SKV_ERR_NULL and step(good, n, out=None) == B.SKV_ERR_NULL
+    # the last layer is the bad one
+    bad_last = (B.skv_layer * n)(_layer(), _layer(), _layer(r_k=72))
+    assert att(bad_last, n) == B.SKV_ERR_RANK and step(bad_last, n) == B.SKV_ERR_RANK
+    # a pointer of the last layer is missing / misaligned
+    holes = (C.c_void_p * n)(FAKE, FAKE, None)
+    assert att(good, n, q=holes) == B.SKV_ERR_NULL and att(good, n, out=holes) == B.SKV_ERR_NULL
+    assert step(good, n, k=holes) == B.SKV_ERR_NULL and step(good, n, q=holes) == B.SKV_ERR_NULL
+    odd = (C.c_void_p * n)(FAKE, FAKE, FAKE + 4)
+    assert att(good, n, out=odd) == B.SKV_ERR_ALIGN and step(good, n, v=odd) == B.SKV_ERR_ALIGN
+    # context and capacity, shared by all layers; the workspace must serve the neediest layer
+    assert att(good, n, n_ctx=0) == B.SKV_ERR_CAPACITY and att(good, n, n_ctx=1025) == B.SKV_ERR_CAPACITY
+    assert step(good, n, cur=1024) == B.SKV_ERR_CAPACITY
+    assert att(good, n, nbytes=4096) == B.SKV_ERR_WORKSPACE and step(good, n, nbytes=4096) == B.SKV_ERR_WORKSPACE
+    assert att(good, n, ws=None) == B.SKV_ERR_NULL

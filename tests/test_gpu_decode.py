@@ -311,3 +311,72 @@ def test_ranges_around_the_early_request_depth(r, tile_rows, tiles, extra):
         B.skv_decode_combine(P.gpu, out, n_splits)
         torch.cuda.synchronize()
         assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
+
+
+STACK_RANKS = [(64, 64), (32, 96), (48, 80), (128, 16)]
+
+
+def _stack(tag, batch, hq, hkv, n0, extra, oracle):
+    pairs = [Pair((tag, l, rk, rv), batch, hq, hkv, rk, rv, n0 + extra, oracle=oracle) for l, (rk, rv) in enumerate(STACK_RANKS)]
+    for l, P in enumerate(pairs):
+        k0, v0 = P.raw_kv(("fill", l), n0)
+        B.skv_project_append(P.gpu, k0, v0, 0)
+        if oracle:
+            P.oracle_append(k0.cpu(), v0.cpu(), 0)
+    return pairs
+
+
+@pytest.mark.gpu
+def test_layer_stack_calls_equal_the_loop_of_single_layer_calls():
+    # Sec. 3.3: ranks differ per layer.  skv_decode_attention_layers / skv_decode_step_layers over four layers
+    # of different ranks: bit-identical to the loop of single-layer calls (outputs and caches), one shared
+    # workspace, and against the oracle layer by layer.
+    batch, hq, hkv, n0, T = 2, 8, 2, 700, 1
+    a = _stack("stack", batch, hq, hkv, n0, T, oracle=True)
+    b = _stack("stack", batch, hq, hkv, n0, T, oracle=False)
+    stack = B.LayerStack([P.gpu for P in a])
+    qs = [P.queries(("q", l)) for l, P in enumerate(a)]
+    new = lambda: [torch.full((batch, hq, 128), float("nan"), dtype=torch.float32, device="cuda") for _ in a]
+    # attention over the cached rows
+    out_stack, out_loop = new(), new()
+    B.skv_decode_attention_layers(stack, qs, out_stack, n0)
+    for l, P in enumerate(b):
+        B.skv_decode_attention(P.gpu, qs[l], out_loop[l], n0)
+    torch.cuda.synchronize()
+    for l, P in enumerate(a):
+        assert torch.equal(out_stack[l], out_loop[l]), l
+        assert vec_rel_err(out_stack[l].cpu().numpy(), P.oracle_decode(qs[l], n0)) <= TOL, l
+    # one whole step: append a token per layer, attend n0 + 1 rows
+    kv = [P.raw_kv(("new", l), T) for l, P in enumerate(a)]
+    out_stack, out_loop = new(), new()
+    B.skv_decode_step_layers(stack, [k for k, _ in kv], [v for _, v in kv], n0, qs, out_stack)
+    for l, P in enumerate(b):
+        B.skv_decode_step(P.gpu, kv[l][0], kv[l][1], n0, qs[l], out_loop[l])
+    torch.cuda.synchronize()
+    for l, P in enumerate(a):
+        assert torch.equal(out_stack[l], out_loop[l]), l
+        assert torch.equal(P.gpu.k_cache, b[l].gpu.k_cache) and torch.equal(P.gpu.v_cache, b[l].gpu.v_cache), l
+        P.oracle_append(kv[l][0].cpu(), kv[l][1].cpu(), n0)
+        assert vec_rel_err(out_stack[l].cpu().numpy(), P.oracle_decode(qs[l], n0 + T)) <= TOL, l
+
+
+@pytest.mark.gpu
+def test_layer_stack_call_with_a_bad_last_layer_launches_nothing():
+    batch, hq, hkv, n0 = 2, 8, 2, 300
+    a = _stack("stack-bad", batch, hq, hkv, n0, 1, oracle=False)
+    stack = B.LayerStack([P.gpu for P in a])
+    stack.c[len(a) - 1].r_k = 72                       # not a rank the library is built for
+    qs = [P.queries(("q", l)) for l, P in enumerate(a)]
+    outs = [torch.full((batch, hq, 128), 7.0, dtype=torch.float32, device="cuda") for _ in a]
+    caches = [P.gpu.k_cache.clone() for P in a]
+    kv = [P.raw_kv(("new", l), 1) for l, P in enumerate(a)]
+    with pytest.raises(B.SkvError) as e:
+        B.skv_decode_attention_layers(stack, qs, outs, n0)
+    assert e.value.code == B.SKV_ERR_RANK
+    with pytest.raises(B.SkvError) as e:
+        B.skv_decode_step_layers(stack, [k for k, _ in kv], [v for _, v in kv], n0, qs, outs)
+    assert e.value.code == B.SKV_ERR_RANK
+    torch.cuda.synchronize()
+    for l, P in enumerate(a):
+        assert bool((outs[l] == 7.0).all()), l
+        assert torch.equal(P.gpu.k_cache, caches[l]), l
