@@ -13,11 +13,6 @@ from _helpers import TOL, Pair, vec_rel_err
 
 pytestmark = pytest.mark.gpu
 
-# Fast mode feeds single bf16 operands to the matrix cores: projected queries, softmax weights
-# and the normalised mix each carry a relative rounding of 2^-9.  The weight and mix roundings
-# alone bound an output vector's error by 2 * 2^-9 of its scale; the query rounding adds
-# (2^-9 |s|) relative to each weight.  With the scores of these inputs (|s| of a few units)
-# 1.5e-2 is a safe bound; the observed error is a few 1e-3.
 
 
 def _filled_pair(seed, batch, hq, hkv, r_k, r_v, n, **kw):
