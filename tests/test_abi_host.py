@@ -536,3 +536,13 @@ def test_layer_stack_calls_check_every_layer_before_anything_else():
     assert step(good, n, cur=1024) == B.SKV_ERR_CAPACITY
     assert att(good, n, nbytes=4096) == B.SKV_ERR_WORKSPACE and step(good, n, nbytes=4096) == B.SKV_ERR_WORKSPACE
     assert att(good, n, ws=None) == B.SKV_ERR_NULL
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N > 1 ends with a message and a non-zero status before it touches a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
