@@ -361,6 +361,22 @@ def test_layer_stack_calls_equal_the_loop_of_single_layer_calls():
 
 
 @pytest.mark.gpu
+def test_layer_stack_step_without_new_tokens_is_the_attention_call():
+    batch, hq, hkv, n0 = 2, 8, 2, 450
+    a = _stack("stack-t0", batch, hq, hkv, n0, 0, oracle=False)
+    stack = B.LayerStack([P.gpu for P in a])
+    qs = [P.queries(("q", l)) for l, P in enumerate(a)]
+    new = lambda: [torch.full((batch, hq, 128), float("nan"), dtype=torch.float32, device="cuda") for _ in a]
+    none = [torch.empty((batch, 0, hkv, 128), dtype=torch.bfloat16, device="cuda") for _ in a]
+    out_step, out_att = new(), new()
+    B.skv_decode_step_layers(stack, none, none, n0, qs, out_step)
+    B.skv_decode_attention_layers(stack, qs, out_att, n0)
+    torch.cuda.synchronize()
+    for l in range(len(a)):
+        assert torch.equal(out_step[l], out_att[l]), l
+
+
+@pytest.mark.gpu
 def test_layer_stack_call_with_a_bad_last_layer_launches_nothing():
     batch, hq, hkv, n0 = 2, 8, 2, 300
     a = _stack("stack-bad", batch, hq, hkv, n0, 1, oracle=False)
