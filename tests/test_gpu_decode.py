@@ -86,6 +86,26 @@ def test_peaked_softmax_with_large_scores():
     assert vec_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("r_k,r_v,hq,hkv", [(64, 64, 8, 2), (48, 80, 8, 2), (128, 32, 4, 4), (32, 128, 16, 2)])
+def test_softmax_reference_moves_tile_after_tile(r_k, r_v, hq, hkv):
+    # Both range kernels keep a softmax reference that moves only when a score exceeds it by a margin, and
+    # rescale their accumulators then.  Keys that grow with their position (a ramp of 1 .. 9 over the context)
+    # under a scale 7 and 70 times the default make the largest score of many a tile exceed the previous
+    # reference by more than the margin (scores up to +-90 and +-900), in every context range.
+    from oracle import skv_oracle as O
+    n = 2900
+    P = _filled_pair(("ramp", r_k, r_v, hq), 2, hq, hkv, r_k, r_v, n)
+    ramp = 1.0 + 8.0 * np.arange(n, dtype=np.float64) / n
+    P.ora.k_cache[:, :, :n] = O.bf16_bits_to_f64(O.f64_to_bf16_bits(P.ora.k_cache[:, :, :n] * ramp[None, None, :, None]))
+    P.upload_oracle_cache(n)
+    q = P.queries(8)
+    for scale in (0.6, 6.0):
+        for n_ctx in (n, 777):
+            got = P.gpu_decode(q, n_ctx, scale)
+            assert np.all(np.isfinite(got))
+            assert vec_rel_err(got, P.oracle_decode(q, n_ctx, scale)) <= TOL, (scale, n_ctx)
+
+
 def test_decode_is_deterministic_and_stage_calls_equal_the_fused_call():
     n = 3000
     P = _filled_pair(("det",), 2, 8, 2, 64, 64, n)

@@ -109,6 +109,28 @@ def test_prefill_strided_queries_scale_and_shared_key_basis():
     assert vec_rel_err(got, want) <= TOL
 
 
+@pytest.mark.parametrize("r_k,r_v", [(48, 80), (64, 64), (128, 128), (96, 32)])
+def test_prefill_softmax_reference_moves_tile_after_tile(r_k, r_v):
+    """The kernel keeps a softmax reference that it moves only when a score exceeds it by 8 (log2 units) and
+    rescales its accumulators then.  Ordinary inputs move it once; here the cached keys grow with their position
+    (a ramp of 1 .. 9 over the context) and the scale is 7 and 70 times the default, so the largest score of many
+    a 64-key tile exceeds the previous reference by more than the threshold (counted on the CPU: up to 10 moves
+    per query row), and the early tiles end up far below the last."""
+    n_prev, T = 700, 140
+    n = n_prev + T
+    P = _filled_pair(("pf-ramp", r_k, r_v), 1, 8, 2, r_k, r_v, n)
+    ramp = 1.0 + 8.0 * np.arange(n, dtype=np.float64) / n
+    kb = O.f64_to_bf16_bits(P.ora.k_cache[:, :, :n] * ramp[None, None, :, None])
+    P.ora.k_cache[:, :, :n] = O.bf16_bits_to_f64(kb)            # the oracle holds what the bf16 cache holds
+    P.upload_oracle_cache(n)
+    q = _chunk_q(P, 12, T)
+    for scale in (0.6, 6.0):                           # scores up to +-90 and +-900: 3 .. 10 moves per query row
+        want = O.prefill_attention(P.ora, _f64(q), n_prev, scale=scale)
+        got = _gpu_prefill(P, q, n_prev, scale=scale)
+        assert np.all(np.isfinite(got))
+        assert vec_rel_err(got, want) <= TOL, scale
+
+
 def test_prefill_has_no_reduced_precision_mode():
     """Bit 0 of mode once selected single-term bf16 operands; it is rejected now (each operand fed as one
     bf16 term breaks the 2e-3 bound by itself, tests/test_prefill_operand_rounding.py)."""

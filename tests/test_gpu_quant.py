@@ -195,6 +195,27 @@ def test_value_ranges_over_many_orders_of_magnitude(bits):
         assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx)) <= TOL
 
 
+@pytest.mark.parametrize("bits,r_k,r_v", [(8, 64, 64), (8, 96, 128), (4, 64, 64), (4, 128, 128)])
+def test_large_scores_move_the_softmax_reference_often(bits, r_k, r_v):
+    """The matrix-core range kernel moves its softmax reference only when a score exceeds it by a margin and
+    carries a power-of-two bias on the weights; under a scale 7 and 70 times the default (scores up to several
+    hundred, in log2 units) the per-tile maxima differ by far more than that margin again and again."""
+    _, attention_fn, _, _, _, _ = _fns(bits)
+    n, hq, hkv = 2100, 8, 2
+    P = QPair(("qdec-scale", bits, r_k, r_v), 2, hq, hkv, r_k, r_v, n, bits)
+    k, v = P.raw_kv(7, n)
+    P.oracle_append(k, v, 0)
+    P.upload_oracle_cache(n)
+    q = P.queries(8)
+    out = torch.empty((2, hq, 128), dtype=torch.float32, device="cuda")
+    for scale in (0.6, 6.0):
+        for n_ctx in (n, 500):
+            attention_fn(P.gpu, q, out, n_ctx, scale)
+            torch.cuda.synchronize()
+            assert torch.isfinite(out).all()
+            assert vec_rel_err(out.cpu().numpy(), P.oracle_decode(q, n_ctx, scale)) <= TOL, (scale, n_ctx)
+
+
 @pytest.mark.parametrize("bits", [8, 4])
 def test_quantised_decode_steps_end_to_end(bits):
     # Append through the library, then a few fused decode steps; both sides keep their own caches.  A code is
