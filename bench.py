@@ -555,14 +555,18 @@ def main():
         splits = args.splits if args.splits > 0 else default_splits(Lr, n_roof)
         # the launch the decode step makes: every workgroup projects its head group's queries itself
         partial_fn = lambda L_, n_, s_, ws_: B.skv_decode_partial_q(L_, qs[0, li_big], n_, s_, 0.0, ws_)
-    for _ in range(10):
-        partial_fn(Lr, n_roof, splits, ws)
+    # Launches alternate between n_ctx and n_ctx - 1 rows, as consecutive decode steps do: the range kernels sweep
+    # a sequence front to back or back to front by the parity of its length (one row in 32768 less every other
+    # launch; the bytes below are those of n_ctx - 1/2 rows).
+    n_alt = (n_roof, max(1, n_roof - 1))
+    for i in range(10):
+        partial_fn(Lr, n_alt[i & 1], splits, ws)
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     e0.record()
-    for _ in range(args.kernel_iters):
-        partial_fn(Lr, n_roof, splits, ws)
+    for i in range(args.kernel_iters):
+        partial_fn(Lr, n_alt[i & 1], splits, ws)
     e1.record()
     torch.cuda.synchronize()
     kern_ms = e0.elapsed_time(e1) / args.kernel_iters
@@ -570,7 +574,7 @@ def main():
     # queries in, the per-range partial results out
     rk, rv = ranks_k[li_big], ranks_v[li_big]
     q_in = Bt * HQ * rk * 4 if (q8 or folded) else Bt * HQ * d * 2 + HKV * d * rk * 2   # projected queries, or queries + key bases
-    kern_bytes = Bt * HKV * n_roof * row_bytes(li_big) + q_in + Bt * HQ * splits * (rv + 2) * 4
+    kern_bytes = Bt * HKV * (n_alt[0] + n_alt[1]) * row_bytes(li_big) // 2 + q_in + Bt * HQ * splits * (rv + 2) * 4
     achieved = kern_bytes / (kern_ms * 1e-3) / 1e9
 
     # the yardstick: a kernel that only reads a buffer of the same size (same launch stream, same events)

@@ -129,7 +129,12 @@ skv_status skv_project_append(const skv_layer* layer,
  * over cache rows j in [0, n_ctx).  The library evaluates the algebraically
  * equal factored form ((q P_K) against K_down, mix V_down, lift with P_V^T)
  * with float32 arithmetic and a split of the context into independent ranges
- * merged in a fixed order, so results are deterministic run to run.
+ * merged in a fixed order, so results are deterministic run to run.  Inside a
+ * range the rows are swept front to back when the sequence holds an even
+ * number of rows and back to front when it holds an odd number: a decode loop
+ * adds a row per step, so consecutive steps meet first the rows the step before
+ * read last, which a last-level cache may still hold.  The direction only
+ * permutes the terms of sums; the same call gives the same bits.
  *
  *   q          device bf16 [batch][n_q_heads][head_dim]
  *   out        device float32 [batch][n_q_heads][head_dim]

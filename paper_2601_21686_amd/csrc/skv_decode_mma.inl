@@ -185,7 +185,12 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
     return;
   }
   int t0, t1;
-  range_of_split((int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add, p.n_stream, split, &t0, &t1);
+  const int seq_rows = (int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add;
+  range_of_split(seq_rows, p.n_stream, split, &t0, &t1);
+  // whole tiles front to back for an even number of rows in the sequence, back to front for an odd one: the
+  // same rule, for the same reason, as in the vector kernel (consecutive decode steps sweep the cache in
+  // opposite directions and meet first what a last-level cache still holds)
+  const bool backwards = (seq_rows & 1) != 0;
 
   float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
   float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;
@@ -226,7 +231,7 @@ __global__ __launch_bounds__(kDecodeThreads, mma_min_workgroups(RK, RV, GT)) voi
   // as the launch asks (NT).  Nothing here depends on a condition: the loop below relies on every request of a
   // tile being the same run of instructions (see there).
   auto issue_whole = [&](int tile, TileRegsM& tr) {
-    const int row0 = t0 + tile * kMmaTileRows;
+    const int row0 = t0 + (backwards ? n_whole - 1 - tile : tile) * kMmaTileRows;
     const int64_t base = tile_base(row0);
     {
       {

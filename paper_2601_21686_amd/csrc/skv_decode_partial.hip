@@ -457,7 +457,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   }
 #endif
   int t0, t1;
-  range_of_split((int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add, p.n_stream, split, &t0, &t1);
+  const int seq_rows = (int)clamped_len(p.seq_lens, b, p.n_ctx - p.len_add) + p.len_add;
+  range_of_split(seq_rows, p.n_stream, split, &t0, &t1);
 
   float* out_acc = p.part_acc + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * RV;
   float* out_ml = p.part_ml + (((int64_t)b * p.n_q_heads + hq0) * p.n_splits + split) * 2;
@@ -473,6 +474,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
 
   const int lane_row = wave * ROWS_PER_WAVE + oct;     // this lane's first row inside a tile
   const int n_full = (t1 - t0) / ROWS_PER_WG;         // tiles with every row valid
+  // The full tiles of a range are taken front to back when the sequence holds an even number of rows and back
+  // to front when it holds an odd number.  A decode loop adds a row per step, so consecutive steps sweep the
+  // cache in opposite directions and a step meets first the rows the step before read last -- the ones a
+  // last-level cache of about the cache's size still holds (a plain read of 256 MiB in 512 slices: 39.6 us per
+  // launch always front to back, 35.6 us in alternating directions).  The order only permutes the terms of
+  // sums; the same call gives the same bits.
+  const bool backwards = (seq_rows & 1) != 0;
+  auto row_of_tile = [&](int idx) { return t0 + (backwards ? n_full - 1 - idx : idx) * ROWS_PER_WG; };
   using Tile = TileRegs<RK, RV, U>;
   Tile ta;
 #if SKV_PAGED
@@ -491,8 +500,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
   auto issue_full = [&](int tile_row, Tile& t) {
     const int r = tile_row + wave_u * ROWS_PER_WAVE;           // this wave's first row: wave-uniform
     const int rel = (r >> p.pages.page_shift) - page_first;
-    while (rel - held_first >= 64) {
-      held_first += 64;
+    if (rel < held_first || rel - held_first >= 64) {          // (ranges are swept in either direction)
+      held_first = rel & ~63;
       held = held_first + lane < pages_in_range ? clamped_page(p.pages, b, page_first + held_first + lane) : 0;
     }
     const int page = __builtin_amdgcn_readlane(held, rel - held_first);
@@ -570,16 +579,16 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     pre = SKV_PIPELINE == 1 && n_full >= kEarlyFrom;
     pre2 = SKV_PIPELINE == 1 && !pre && n_full >= 3;
     if (pre) {
-      issue_full(t0, ta);
+      issue_full(row_of_tile(0), ta);
 #pragma unroll
-      for (int k = 1; k < kEarlyTiles; ++k) issue_full(t0 + k * ROWS_PER_WG, early[k - 1]);
+      for (int k = 1; k < kEarlyTiles; ++k) issue_full(row_of_tile(k), early[k - 1]);
       finish();
     } else if (pre2) {
-      issue_full(t0, ta);
-      issue_full(t0 + ROWS_PER_WG, early[0]);
+      issue_full(row_of_tile(0), ta);
+      issue_full(row_of_tile(1), early[0]);
       finish();
     } else if (n_full > 0) {
-      issue_full(t0, ta);
+      issue_full(row_of_tile(0), ta);
       finish();
     } else {
       finish();
@@ -598,7 +607,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
         qreg[g][i + 1] = v.y;
       }
     }
-    if (n_full > 0) issue_full(t0, ta);
+    if (n_full > 0) issue_full(row_of_tile(0), ta);
   }
 
   // ---- stream the range ---------------------------------------------------------------
@@ -630,20 +639,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     ring[0] = ta;                                   // tile 0 was requested before the projection
 #pragma unroll
     for (int k = 1; k < NBUF - 1; ++k)
-      if (k < n_full) issue_full(t0 + k * ROWS_PER_WG, ring[k]);
+      if (k < n_full) issue_full(row_of_tile(k), ring[k]);
     int i = 0;
     if constexpr (NBUF == 2) {
       if (pre) {                                    // tiles 0 .. kEarlyTiles-1 are on their way (n_full >= kEarlyFrom)
         consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
 #pragma unroll
         for (int k = 1; k < kEarlyTiles; ++k) {
-          if (k == kEarlyTiles - 1) issue_full(t0 + kEarlyTiles * ROWS_PER_WG, ring[0]);
+          if (k == kEarlyTiles - 1) issue_full(row_of_tile(kEarlyTiles), ring[0]);
           consume_rows<RK, RV, GT, U, false>(early[k - 1], 0, t1, qd, qreg, m, l, acc, zacc);
         }
         i = kEarlyTiles;                            // ring[0] holds that tile: the loop's invariant
       } else if (pre2) {                            // tiles 0 and 1 are on their way (n_full >= 3)
         consume_rows<RK, RV, GT, U, false>(ring[0], 0, t1, qd, qreg, m, l, acc, zacc);
-        issue_full(t0 + 2 * ROWS_PER_WG, ring[0]);
+        issue_full(row_of_tile(2), ring[0]);
         consume_rows<RK, RV, GT, U, false>(early[0], 0, t1, qd, qreg, m, l, acc, zacc);
         i = 2;
       }
@@ -652,7 +661,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
       while (i + 2 * NBUF - 2 < n_full) {           // ring[k] holds tile i+k for k < NBUF-1
 #pragma unroll
         for (int k = 0; k < NBUF; ++k) {
-          issue_full(t0 + (i + k + NBUF - 1) * ROWS_PER_WG, ring[(k + NBUF - 1) % NBUF]);
+          issue_full(row_of_tile((i + k + NBUF - 1)), ring[(k + NBUF - 1) % NBUF]);
           consume_rows<RK, RV, GT, U, false>(ring[k], 0, t1, qd, qreg, m, l, acc, zacc);
         }
         i += NBUF;
@@ -663,7 +672,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_partial_kernel(const De
     for (int k = 0; k < 2 * NBUF - 2 || k < 1; ++k) {
       if (i + k < n_full) {
         if (NBUF > 1 && i + k + NBUF - 1 < n_full)
-          issue_full(t0 + (i + k + NBUF - 1) * ROWS_PER_WG, ring[(k + NBUF - 1) % NBUF]);
+          issue_full(row_of_tile((i + k + NBUF - 1)), ring[(k + NBUF - 1) % NBUF]);
         consume_rows<RK, RV, GT, U, false>(ring[k % NBUF], 0, t1, qd, qreg, m, l, acc, zacc);
       }
     }
